@@ -1,0 +1,154 @@
+"""ctypes binding of the CPU oracle (``sedd_oracle.c``).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT: only ``tests/``, the smoke check and the
+benchmark's ``cpu_baseline`` leg import this package.  It takes and returns
+host numpy arrays and never touches the GPU library.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sedd_oracle.c")
+_LIB = os.path.join(_HERE, "libsedd_oracle.so")
+
+P61 = (1 << 61) - 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-shared", "-fPIC", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = C.CDLL(_LIB)
+        u64, i32, u32, vp = C.c_uint64, C.c_int32, C.c_uint32, C.c_void_p
+        lib.sedd_ref_mulmod.restype = u64
+        lib.sedd_ref_mulmod.argtypes = [u64, u64]
+        lib.sedd_ref_addmod.restype = u64
+        lib.sedd_ref_addmod.argtypes = [u64, u64]
+        lib.sedd_ref_powmod.restype = u64
+        lib.sedd_ref_powmod.argtypes = [u64, u64]
+        lib.sedd_ref_base_hash.restype = u64
+        lib.sedd_ref_base_hash.argtypes = [vp, u64]
+        lib.sedd_ref_coeffs.restype = C.c_int
+        lib.sedd_ref_coeffs.argtypes = [u64, i32, vp, vp]
+        lib.sedd_ref_doc_shingles.restype = u64
+        lib.sedd_ref_doc_shingles.argtypes = [vp, u64, i32, u32, vp, u64]
+        lib.sedd_ref_minhash_shingles.restype = C.c_int
+        lib.sedd_ref_minhash_shingles.argtypes = [vp, u64, i32, u64, vp]
+        lib.sedd_ref_minhash.restype = C.c_int
+        lib.sedd_ref_minhash.argtypes = [vp, vp, u64, i32, i32, u64, u32, vp]
+        lib.sedd_ref_lsh_keys.restype = C.c_int
+        lib.sedd_ref_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp]
+        lib.sedd_ref_cluster.restype = C.c_int
+        lib.sedd_ref_cluster.argtypes = [vp, u64, i32, vp]
+        _lib = lib
+    return _lib
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code):
+        super().__init__(f"oracle returned {code}")
+        self.code = code
+
+
+def _ptr(a):
+    return a.ctypes.data if a is not None and a.size else None
+
+
+def _as_bytes(data) -> np.ndarray:
+    if isinstance(data, (bytes, bytearray)):
+        return np.frombuffer(bytes(data), dtype=np.uint8)
+    return np.ascontiguousarray(data, dtype=np.uint8)
+
+
+def mulmod(a: int, b: int) -> int:
+    return _load().sedd_ref_mulmod(a, b)
+
+
+def addmod(a: int, b: int) -> int:
+    return _load().sedd_ref_addmod(a, b)
+
+
+def powmod(g: int, e: int) -> int:
+    return _load().sedd_ref_powmod(g, e)
+
+
+def base_hash(s) -> int:
+    s = _as_bytes(s)
+    return _load().sedd_ref_base_hash(_ptr(s), s.size)
+
+
+def coeffs(seed: int, K: int):
+    a = np.zeros(K, dtype=np.uint64)
+    b = np.zeros(K, dtype=np.uint64)
+    rc = _load().sedd_ref_coeffs(seed, K, a.ctypes.data, b.ctypes.data)
+    if rc:
+        raise OracleError(rc)
+    return a, b
+
+
+def doc_shingles(text, n: int, byte_mode: bool = False) -> np.ndarray:
+    """Base hashes (Eq. 1) of the shingles of one document, in order."""
+    t = _as_bytes(text)
+    lib = _load()
+    flags = 1 if byte_mode else 0
+    cnt = lib.sedd_ref_doc_shingles(_ptr(t), t.size, n, flags, None, 0)
+    out = np.zeros(cnt, dtype=np.uint64)
+    if cnt:
+        lib.sedd_ref_doc_shingles(_ptr(t), t.size, n, flags, out.ctypes.data, cnt)
+    return out
+
+
+def minhash_shingles(x, K: int, seed: int = 0) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    sig = np.zeros(K, dtype=np.uint32)
+    rc = _load().sedd_ref_minhash_shingles(_ptr(x), x.size, K, seed, sig.ctypes.data)
+    if rc:
+        raise OracleError(rc)
+    return sig
+
+
+def minhash(data, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags: int = 0) -> np.ndarray:
+    data = _as_bytes(data)
+    off = np.ascontiguousarray(doc_offsets, dtype=np.uint64)
+    n_docs = max(0, off.size - 1)
+    sig = np.zeros((n_docs, max(K, 0)), dtype=np.uint32)
+    rc = _load().sedd_ref_minhash(_ptr(data), _ptr(off), n_docs, shingle_n, K, seed, flags,
+                                  _ptr(sig))
+    if rc:
+        raise OracleError(rc)
+    return sig
+
+
+def lsh_keys(sig, b: int, r: int) -> np.ndarray:
+    sig = np.ascontiguousarray(sig, dtype=np.uint32)
+    n_docs, K = sig.shape
+    keys = np.zeros((n_docs, max(b, 0)), dtype=np.uint64)
+    rc = _load().sedd_ref_lsh_keys(_ptr(sig), n_docs, K, b, r, _ptr(keys))
+    if rc:
+        raise OracleError(rc)
+    return keys
+
+
+def cluster(keys) -> np.ndarray:
+    keys = np.ascontiguousarray(keys, dtype=np.uint64)
+    n_docs, b = keys.shape
+    cid = np.zeros(n_docs, dtype=np.int64)
+    rc = _load().sedd_ref_cluster(_ptr(keys), n_docs, b, _ptr(cid))
+    if rc:
+        raise OracleError(rc)
+    return cid

@@ -1,0 +1,262 @@
+/*
+ * CPU oracle for MinHash-LSH deduplication: signatures, band keys, clusters.
+ *
+ * TEST INFRASTRUCTURE, NOT THE PRODUCT.  Plain, slow, single-threaded C that
+ * writes the definitions out directly.  Only the test-suite, the smoke check
+ * and the benchmark's CPU-baseline leg may call it.  It shares no code with
+ * the HIP library and includes none of its headers.
+ *
+ * What it follows (SEDD paper):
+ *   - Section 2.2 "MinHash generation": shingle every document, apply H hash
+ *     functions to every shingle, keep the minimum per function.
+ *   - Section 3.2 Eq. 1: the shingle hash h(s) = (sum_i c_i q^(i-1)) mod p
+ *     with c_i the characters of the shingle.  It is evaluated here directly
+ *     from Eq. 1 for every shingle; the reuse of Eq. 2 is an optimisation
+ *     that yields the same integer and is deliberately not used.
+ *   - Section 2.3 / Appendix A.2: split the signature into b bands of r
+ *     values, hash each band; documents sharing a band hash in the same band
+ *     are linked.
+ *   - Section 2.2 "Constructing a union graph" and "Generating the final
+ *     list": connected components; the representative is the lowest index.
+ *
+ * Readings fixed where the paper leaves a choice (all integer, all exact):
+ *   p = 2^61 - 1, q = 257, characters are raw byte values 0..255.
+ *   H hash functions: h_k(s) = ((a_k * x(s) + b_k) mod p) mod 2^32, where
+ *   x(s) is Eq. 1's value; a_k = s0 * Ga^(k+1) mod p, b_k = s0 * Gb^(k+1)
+ *   mod p, s0 = (seed mod (p-1)) + 1.
+ *   Word shingles: tokens are maximal runs of bytes outside
+ *   {09,0A,0B,0C,0D,20}; a shingle is n consecutive tokens joined by one 20.
+ *   A document with 1..n-1 tokens has one shingle made of all of them; with
+ *   none it has no shingle and its signature is all 0xFFFFFFFF.
+ *   Byte shingles: every window of n bytes; a document of 1..n-1 bytes has
+ *   one shingle (the whole document).
+ *   Band key: Eq. 1's polynomial over the band's r values with base Q, mod p.
+ *
+ * Parity with the paper authors' released code is unpinned: the paper prints
+ * no hash value, signature or bucket id for any input.  The functions here
+ * are pinned by the CPU test-suite against closed forms, big-integer
+ * arithmetic, brute-force Jaccard / connected components and the LSH
+ * collision-probability curve.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define SEDD_REF_OK 0
+#define SEDD_REF_EINVAL (-1)
+#define SEDD_REF_ENOMEM (-2)
+
+typedef unsigned __int128 u128;
+
+static const uint64_t P61 = 2305843009213693951ULL;  /* 2^61 - 1 */
+static const uint64_t Q_CHAR = 257ULL;                /* Eq. 1 base, > 255 */
+static const uint64_t Q_BAND = 1687994237021934823ULL;
+static const uint64_t G_A = 1425089352415399810ULL;
+static const uint64_t G_B = 955111447119501601ULL;
+
+/* x mod (2^61-1) for x < 2^125, using 2^61 = 1 (mod p) */
+static uint64_t mod_p(u128 x) {
+  u128 y = (x & P61) + (x >> 61);          /* < 2^61 + 2^64 */
+  uint64_t z = (uint64_t)(y & P61) + (uint64_t)(y >> 61);
+  while (z >= P61) z -= P61;
+  return z;
+}
+
+uint64_t sedd_ref_mulmod(uint64_t a, uint64_t b) { return mod_p((u128)a * b); }
+uint64_t sedd_ref_addmod(uint64_t a, uint64_t b) { return mod_p((u128)a + b); }
+
+uint64_t sedd_ref_powmod(uint64_t g, uint64_t e) {
+  uint64_t r = 1;
+  for (uint64_t i = 0; i < e; i++) r = sedd_ref_mulmod(r, g);  /* plain repeated product */
+  return r;
+}
+
+/* Eq. 1: x(s) = sum_{i=1..len} s_i * q^(i-1) mod p, first character at q^0 */
+uint64_t sedd_ref_base_hash(const uint8_t *s, uint64_t len) {
+  uint64_t x = 0, pw = 1;
+  for (uint64_t i = 0; i < len; i++) {
+    x = sedd_ref_addmod(x, sedd_ref_mulmod((uint64_t)s[i], pw));
+    pw = sedd_ref_mulmod(pw, Q_CHAR);
+  }
+  return x;
+}
+
+/* coefficients of the K hash functions */
+int sedd_ref_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
+  if (K < 1 || !a || !b) return SEDD_REF_EINVAL;
+  uint64_t s0 = seed % (P61 - 1) + 1;
+  uint64_t ga = 1, gb = 1;
+  for (int32_t k = 0; k < K; k++) {
+    ga = sedd_ref_mulmod(ga, G_A);   /* Ga^(k+1) */
+    gb = sedd_ref_mulmod(gb, G_B);
+    a[k] = sedd_ref_mulmod(s0, ga);
+    b[k] = sedd_ref_mulmod(s0, gb);
+  }
+  return SEDD_REF_OK;
+}
+
+static int is_space(uint8_t c) { return c == 0x20 || (c >= 0x09 && c <= 0x0D); }
+
+/*
+ * Base hashes of the shingles of one document, in document order.
+ * Returns the number of shingles; writes at most cap of them to out
+ * (out may be NULL to count only).
+ */
+uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32_t flags,
+                               uint64_t *out, uint64_t cap) {
+  uint64_t count = 0;
+  if (n < 1) return 0;
+  if (flags & 1u) {                                   /* byte n-grams */
+    if (len == 0) return 0;
+    if (len < (uint64_t)n) { if (out && cap) out[0] = sedd_ref_base_hash(t, len); return 1; }
+    for (uint64_t i = 0; i + n <= len; i++) {
+      if (out && count < cap) out[count] = sedd_ref_base_hash(t + i, (uint64_t)n);
+      count++;
+    }
+    return count;
+  }
+  /* word n-grams: token list first */
+  uint64_t n_tok = 0, i = 0;
+  while (i < len) {
+    while (i < len && is_space(t[i])) i++;
+    if (i == len) break;
+    while (i < len && !is_space(t[i])) i++;
+    n_tok++;
+  }
+  if (n_tok == 0) return 0;
+  uint64_t *ts = (uint64_t *)malloc(n_tok * 8), *tl = (uint64_t *)malloc(n_tok * 8);
+  uint64_t k = 0; i = 0;
+  while (i < len) {
+    while (i < len && is_space(t[i])) i++;
+    if (i == len) break;
+    uint64_t s = i;
+    while (i < len && !is_space(t[i])) i++;
+    ts[k] = s; tl[k] = i - s; k++;
+  }
+  uint64_t per = n_tok < (uint64_t)n ? n_tok : (uint64_t)n;   /* tokens per shingle */
+  uint64_t n_sh = n_tok - per + 1;
+  uint8_t *buf = NULL; uint64_t bcap = 0;
+  for (uint64_t s = 0; s < n_sh; s++) {
+    uint64_t need = per - 1;
+    for (uint64_t j = 0; j < per; j++) need += tl[s + j];
+    if (need > bcap) { bcap = need * 2; buf = (uint8_t *)realloc(buf, bcap); }
+    uint64_t w = 0;
+    for (uint64_t j = 0; j < per; j++) {
+      if (j) buf[w++] = 0x20;
+      memcpy(buf + w, t + ts[s + j], tl[s + j]); w += tl[s + j];
+    }
+    if (out && count < cap) out[count] = sedd_ref_base_hash(buf, w);
+    count++;
+  }
+  free(buf); free(ts); free(tl);
+  return count;
+}
+
+/*
+ * Signature of a document given the base hashes of its shingles (a multiset;
+ * order and repetition do not matter).  sig holds K values.
+ */
+int sedd_ref_minhash_shingles(const uint64_t *x, uint64_t n_sh, int32_t K, uint64_t seed,
+                              uint32_t *sig) {
+  if (K < 1 || !sig || (n_sh && !x)) return SEDD_REF_EINVAL;
+  uint64_t *a = (uint64_t *)malloc((size_t)K * 8), *b = (uint64_t *)malloc((size_t)K * 8);
+  if (!a || !b) { free(a); free(b); return SEDD_REF_ENOMEM; }
+  sedd_ref_coeffs(seed, K, a, b);
+  for (int32_t k = 0; k < K; k++) {
+    uint32_t m = 0xFFFFFFFFu;
+    for (uint64_t s = 0; s < n_sh; s++) {
+      uint64_t h = sedd_ref_addmod(sedd_ref_mulmod(a[k], x[s]), b[k]);
+      uint32_t h32 = (uint32_t)(h & 0xFFFFFFFFu);
+      if (h32 < m) m = h32;
+    }
+    sig[k] = m;
+  }
+  free(a); free(b);
+  return SEDD_REF_OK;
+}
+
+/* sig[d*K + k] = min over the shingles s of document d of h_k(s) */
+int sedd_ref_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
+                     int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags,
+                     uint32_t *sig) {
+  if (shingle_n < 1 || K < 1 || (flags & ~1u)) return SEDD_REF_EINVAL;
+  if (n_docs == 0) return SEDD_REF_OK;
+  if (!doc_offsets || !sig) return SEDD_REF_EINVAL;
+  for (uint64_t d = 0; d < n_docs; d++)
+    if (doc_offsets[d + 1] < doc_offsets[d]) return SEDD_REF_EINVAL;
+  if (doc_offsets[n_docs] > doc_offsets[0] && !bytes) return SEDD_REF_EINVAL;
+  uint64_t *x = NULL, xcap = 0;
+  for (uint64_t d = 0; d < n_docs; d++) {
+    const uint8_t *t = bytes + doc_offsets[d];
+    uint64_t len = doc_offsets[d + 1] - doc_offsets[d];
+    uint64_t n_sh = sedd_ref_doc_shingles(t, len, shingle_n, flags, NULL, 0);
+    if (n_sh > xcap) { xcap = n_sh * 2; free(x); x = (uint64_t *)malloc(xcap * 8); if (!x) return SEDD_REF_ENOMEM; }
+    sedd_ref_doc_shingles(t, len, shingle_n, flags, x, n_sh);
+    int rc = sedd_ref_minhash_shingles(x, n_sh, K, seed, sig + d * (uint64_t)K);
+    if (rc) { free(x); return rc; }
+  }
+  free(x);
+  return SEDD_REF_OK;
+}
+
+/* key[d*b + j] = sum_{i<r} sig[d*K + j*r + i] * Q^i mod p */
+int sedd_ref_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, int32_t r,
+                      uint64_t *keys) {
+  if (K < 1 || b < 1 || r < 1 || (int64_t)b * r > K) return SEDD_REF_EINVAL;
+  if (n_docs == 0) return SEDD_REF_OK;
+  if (!sig || !keys) return SEDD_REF_EINVAL;
+  for (uint64_t d = 0; d < n_docs; d++)
+    for (int32_t j = 0; j < b; j++) {
+      uint64_t key = 0, pw = 1;
+      for (int32_t i = 0; i < r; i++) {
+        key = sedd_ref_addmod(key, sedd_ref_mulmod((uint64_t)sig[d * (uint64_t)K + (uint64_t)j * r + i], pw));
+        pw = sedd_ref_mulmod(pw, Q_BAND);
+      }
+      keys[d * (uint64_t)b + j] = key;
+    }
+  return SEDD_REF_OK;
+}
+
+/* ---- clusters: connected components of "shares a band key in the same band" ---- */
+
+typedef struct { uint64_t key; uint64_t doc; } kd_t;
+static int kd_cmp(const void *pa, const void *pb) {
+  const kd_t *a = (const kd_t *)pa, *b = (const kd_t *)pb;
+  if (a->key != b->key) return a->key < b->key ? -1 : 1;
+  if (a->doc != b->doc) return a->doc < b->doc ? -1 : 1;
+  return 0;
+}
+static uint64_t uf_find(uint64_t *parent, uint64_t v) {
+  uint64_t root = v;
+  while (parent[root] != root) root = parent[root];
+  while (parent[v] != root) { uint64_t nx = parent[v]; parent[v] = root; v = nx; }
+  return root;
+}
+
+int sedd_ref_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id) {
+  if (b < 1) return SEDD_REF_EINVAL;
+  if (n_docs == 0) return SEDD_REF_OK;
+  if (!keys || !cluster_id) return SEDD_REF_EINVAL;
+  uint64_t *parent = (uint64_t *)malloc(n_docs * 8);
+  kd_t *col = (kd_t *)malloc(n_docs * sizeof(kd_t));
+  uint64_t *lowest = (uint64_t *)malloc(n_docs * 8);
+  if (!parent || !col || !lowest) { free(parent); free(col); free(lowest); return SEDD_REF_ENOMEM; }
+  for (uint64_t d = 0; d < n_docs; d++) parent[d] = d;
+  for (int32_t j = 0; j < b; j++) {
+    for (uint64_t d = 0; d < n_docs; d++) { col[d].key = keys[d * (uint64_t)b + j]; col[d].doc = d; }
+    qsort(col, n_docs, sizeof(kd_t), kd_cmp);
+    for (uint64_t i = 1; i < n_docs; i++)
+      if (col[i].key == col[i - 1].key) {
+        uint64_t ra = uf_find(parent, col[i - 1].doc), rb = uf_find(parent, col[i].doc);
+        if (ra != rb) parent[rb] = ra;
+      }
+  }
+  for (uint64_t d = 0; d < n_docs; d++) lowest[d] = UINT64_MAX;
+  for (uint64_t d = 0; d < n_docs; d++) {
+    uint64_t rt = uf_find(parent, d);
+    if (d < lowest[rt]) lowest[rt] = d;
+  }
+  for (uint64_t d = 0; d < n_docs; d++) cluster_id[d] = (int64_t)lowest[uf_find(parent, d)];
+  free(parent); free(col); free(lowest);
+  return SEDD_REF_OK;
+}
