@@ -1,0 +1,114 @@
+/*
+ * libsedd: MinHash-LSH near-duplicate detection on one MI355X (gfx950).
+ *
+ * The three calls follow the pipeline of the SEDD paper (Sections 2.2, 2.3):
+ *   documents -> signature matrix -> per-band bucket keys -> union graph ->
+ *   lowest-index representative of each connected component.
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer to memory the caller owns.  The
+ *     library never frees or keeps a caller pointer.  Outputs are written only
+ *     by the work the call enqueues.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue their kernels on it and return; results are ready when the
+ *     stream has drained.  sedd_minhash additionally copies `doc_offsets` to
+ *     the host and waits for that copy before it enqueues anything, because
+ *     the host validates the offsets and plans bounded-size chunks from them.
+ *   - Return value: SEDD_OK (0) or a negative error code.  On SEDD_EINVAL
+ *     nothing is written and no device work is enqueued.  `n_docs == 0` is a
+ *     successful no-op that touches nothing.
+ *   - Device scratch (chunk work lists, sort buffers, the union-find forest)
+ *     lives in a grow-only allocation owned by the library, shared by all
+ *     calls of the process: calls must not overlap in time on different
+ *     streams.  sedd_release_scratch() frees it.
+ *   - All arithmetic is exact unsigned integer arithmetic; results do not
+ *     depend on launch shape, chunking or timing.
+ */
+#ifndef SEDD_H
+#define SEDD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SEDD_OK 0
+#define SEDD_EINVAL (-1)  /* bad argument (null pointer, K<1, b*r>K, offsets decreasing, ...) */
+#define SEDD_ENOMEM (-2)  /* device or pinned-host scratch allocation failed */
+#define SEDD_EDEVICE (-3) /* a HIP call failed; sedd_last_device_error() names it */
+
+/* flags of sedd_minhash */
+#define SEDD_FLAG_BYTE_SHINGLES 1u /* shingles are byte n-grams instead of word n-grams */
+
+/* largest K / shingle_n / b the kernels accept */
+#define SEDD_MAX_K 4096
+#define SEDD_MAX_SHINGLE_N 64
+#define SEDD_MAX_BANDS 4096
+
+/*
+ * MinHash signature generation (Section 2.2 "MinHash generation"; shingle hash of
+ * Section 3.2, Eq. 1).
+ *
+ * For every document d = bytes[doc_offsets[d] .. doc_offsets[d+1]):
+ *   1. shingles.  Word mode (default): tokens are the maximal runs of bytes outside
+ *      {0x09,0x0A,0x0B,0x0C,0x0D,0x20}; shingle i is tokens i..i+shingle_n-1 joined by a
+ *      single 0x20.  A document with 1..shingle_n-1 tokens has one shingle (all its
+ *      tokens); with none it has no shingle.  Byte mode (SEDD_FLAG_BYTE_SHINGLES): every
+ *      window of shingle_n bytes; a document of 1..shingle_n-1 bytes has one shingle.
+ *   2. x(s) = (sum_i s_i * 257^(i-1)) mod (2^61-1) over the bytes s_i of the shingle
+ *      (Eq. 1 with q = 257, p = 2^61-1).
+ *   3. h_k(s) = ((a_k * x(s) + b_k) mod p) mod 2^32 for k = 0..K-1, with
+ *      a_k = s0 * Ga^(k+1) mod p, b_k = s0 * Gb^(k+1) mod p, s0 = (seed mod (p-1)) + 1,
+ *      Ga = 1425089352415399810, Gb = 955111447119501601.
+ *   4. sig[d*K + k] = min over the document's shingles of h_k(s); 0xFFFFFFFF if none.
+ *
+ * bytes        device, uint8; read in [doc_offsets[0], doc_offsets[n_docs]).
+ * doc_offsets  device, uint64[n_docs+1], non-decreasing byte offsets into `bytes`.
+ * shingle_n    1..SEDD_MAX_SHINGLE_N.   K  1..SEDD_MAX_K.
+ * sig          device, uint32[n_docs*K], document-major; fully overwritten.
+ * A single document must be smaller than 2^32 - 2^20 bytes; n_docs < 2^31.
+ */
+int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
+                 int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,
+                 void *stream);
+
+/*
+ * LSH band keys (Section 2.3: the signature is cut into b bands of r rows and each band
+ * is hashed to a bucket).  key[d*b + j] = (sum_{i<r} sig[d*K + j*r + i] * Q^i) mod p with
+ * Q = 1687994237021934823: Eq. 1's polynomial over the band's values.  Equal bands give
+ * equal keys; unequal bands collide with probability about 2^-61.  Requires b*r <= K; the
+ * first b*r columns of sig are used.
+ *
+ * sig   device, uint32[n_docs*K].   keys  device, uint64[n_docs*b], document-major.
+ */
+int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, int32_t r,
+                  uint64_t *keys, void *stream);
+
+/*
+ * Bucket grouping into duplicate clusters (Section 2.2 "Constructing a union graph" and
+ * "Generating the final list of duplicates"; Appendix A.2: per-band graphs are merged).
+ * Documents u, v are linked when keys[u*b + j] == keys[v*b + j] for some band j (same j on
+ * both sides).  cluster_id[d] = the smallest document index in d's connected component.
+ *
+ * keys        device, uint64[n_docs*b], document-major, values < 2^61.
+ * cluster_id  device, int64[n_docs].       n_docs < 2^31, n_docs*b < 2^32.
+ */
+int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
+                 void *stream);
+
+/* Text for an error code (static storage). */
+const char *sedd_strerror(int code);
+/* Text of the HIP error behind the last SEDD_EDEVICE of this thread (static storage). */
+const char *sedd_last_device_error(void);
+/* Library version, major*10000 + minor*100 + patch. */
+int sedd_version(void);
+/* Free the library-owned device and pinned-host scratch (blocks until the device is idle). */
+int sedd_release_scratch(void);
+/* Bytes of device scratch currently held. */
+uint64_t sedd_scratch_bytes(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEDD_H */

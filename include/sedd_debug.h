@@ -1,0 +1,49 @@
+/*
+ * Stage-level entry points of libsedd, for parity tests of the intermediate results.
+ * Same conventions as sedd.h: device pointers owned by the caller, a hipStream_t as void*,
+ * SEDD_OK or a negative code.  They run the same kernels the three public calls run.
+ */
+#ifndef SEDD_DEBUG_H
+#define SEDD_DEBUG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Base hashes x(s) of every shingle (Section 3.2, Eq. 1), in document order.
+ *   shingle_offsets  device, uint64[n_docs+1]: document d owns x[shingle_offsets[d] ..
+ *                    shingle_offsets[d+1]).
+ *   x                device, uint64[x_cap]; entries beyond x_cap are not written (the
+ *                    offsets are still complete, so a first call may size the second).
+ */
+int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
+                              uint64_t n_docs, int32_t shingle_n, uint32_t flags, uint64_t *x,
+                              uint64_t x_cap, uint64_t *shingle_offsets, void *stream);
+
+/* Coefficients a_k, b_k of the K hash functions: device uint64[K] each. */
+int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream);
+
+/* Exclusive prefix sum of n uint32 values (device), out may alias in. */
+int sedd_debug_scan_u32(const uint32_t *in, uint32_t *out, uint64_t n, void *stream);
+
+/*
+ * The sort inside sedd_cluster: for every band j the (key, doc) records sorted by key,
+ * stable in doc.  keys_sorted uint64[b*n_docs] and docs_sorted uint32[b*n_docs] are
+ * band-major (band j occupies [j*n_docs, (j+1)*n_docs)).
+ */
+int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
+                          uint64_t *keys_sorted, uint32_t *docs_sorted, void *stream);
+
+/*
+ * Upper bound on the text bytes processed per internal chunk of sedd_minhash (0 restores
+ * the default).  Results never depend on it; tests use small values to cross chunk edges.
+ */
+int sedd_debug_set_chunk_bytes(uint64_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEDD_DEBUG_H */

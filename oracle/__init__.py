@@ -152,3 +152,39 @@ def cluster(keys) -> np.ndarray:
     if rc:
         raise OracleError(rc)
     return cid
+
+
+_shard_ctx = None   # inherited by forked workers; avoids pickling the corpus per job
+
+
+def _shard_worker(rng):
+    data, off, shingle_n, K, seed, flags = _shard_ctx
+    d0, d1 = rng
+    base = int(off[d0])
+    sub = data[base:int(off[d1])]
+    return d0, minhash(sub, off[d0:d1 + 1] - np.uint64(base), shingle_n, K, seed, flags)
+
+
+def minhash_sharded(data, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags: int = 0,
+                    procs: int = 1) -> np.ndarray:
+    """The single-threaded oracle run as `procs` processes over disjoint document ranges."""
+    global _shard_ctx
+    data = _as_bytes(data)
+    off = np.ascontiguousarray(doc_offsets, dtype=np.uint64)
+    n_docs = max(0, off.size - 1)
+    if procs <= 1 or n_docs < 2 * procs:
+        return minhash(data, off, shingle_n, K, seed, flags)
+    import multiprocessing as mp
+    _load()
+    n_sh = procs * 8
+    cuts = [n_docs * i // n_sh for i in range(n_sh + 1)]
+    jobs = [(cuts[i], cuts[i + 1]) for i in range(n_sh) if cuts[i + 1] > cuts[i]]
+    sig = np.zeros((n_docs, K), dtype=np.uint32)
+    _shard_ctx = (data, off, shingle_n, K, seed, flags)
+    try:
+        with mp.get_context("fork").Pool(procs) as pool:
+            for d0, part in pool.imap_unordered(_shard_worker, jobs):
+                sig[d0:d0 + part.shape[0]] = part
+    finally:
+        _shard_ctx = None
+    return sig

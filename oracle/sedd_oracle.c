@@ -62,12 +62,16 @@ static uint64_t mod_p(u128 x) {
   return z;
 }
 
-uint64_t sedd_ref_mulmod(uint64_t a, uint64_t b) { return mod_p((u128)a * b); }
-uint64_t sedd_ref_addmod(uint64_t a, uint64_t b) { return mod_p((u128)a + b); }
+static uint64_t mulmod(uint64_t a, uint64_t b) { return mod_p((u128)a * b); }
+static uint64_t addmod(uint64_t a, uint64_t b) { return mod_p((u128)a + b); }
+
+/* exported for the arithmetic pins */
+uint64_t sedd_ref_mulmod(uint64_t a, uint64_t b) { return mulmod(a, b); }
+uint64_t sedd_ref_addmod(uint64_t a, uint64_t b) { return addmod(a, b); }
 
 uint64_t sedd_ref_powmod(uint64_t g, uint64_t e) {
   uint64_t r = 1;
-  for (uint64_t i = 0; i < e; i++) r = sedd_ref_mulmod(r, g);  /* plain repeated product */
+  for (uint64_t i = 0; i < e; i++) r = mulmod(r, g);  /* plain repeated product */
   return r;
 }
 
@@ -75,8 +79,8 @@ uint64_t sedd_ref_powmod(uint64_t g, uint64_t e) {
 uint64_t sedd_ref_base_hash(const uint8_t *s, uint64_t len) {
   uint64_t x = 0, pw = 1;
   for (uint64_t i = 0; i < len; i++) {
-    x = sedd_ref_addmod(x, sedd_ref_mulmod((uint64_t)s[i], pw));
-    pw = sedd_ref_mulmod(pw, Q_CHAR);
+    x = addmod(x, mulmod((uint64_t)s[i], pw));
+    pw = mulmod(pw, Q_CHAR);
   }
   return x;
 }
@@ -87,10 +91,10 @@ int sedd_ref_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
   uint64_t s0 = seed % (P61 - 1) + 1;
   uint64_t ga = 1, gb = 1;
   for (int32_t k = 0; k < K; k++) {
-    ga = sedd_ref_mulmod(ga, G_A);   /* Ga^(k+1) */
-    gb = sedd_ref_mulmod(gb, G_B);
-    a[k] = sedd_ref_mulmod(s0, ga);
-    b[k] = sedd_ref_mulmod(s0, gb);
+    ga = mulmod(ga, G_A);   /* Ga^(k+1) */
+    gb = mulmod(gb, G_B);
+    a[k] = mulmod(s0, ga);
+    b[k] = mulmod(s0, gb);
   }
   return SEDD_REF_OK;
 }
@@ -165,7 +169,7 @@ int sedd_ref_minhash_shingles(const uint64_t *x, uint64_t n_sh, int32_t K, uint6
   for (int32_t k = 0; k < K; k++) {
     uint32_t m = 0xFFFFFFFFu;
     for (uint64_t s = 0; s < n_sh; s++) {
-      uint64_t h = sedd_ref_addmod(sedd_ref_mulmod(a[k], x[s]), b[k]);
+      uint64_t h = addmod(mulmod(a[k], x[s]), b[k]);
       uint32_t h32 = (uint32_t)(h & 0xFFFFFFFFu);
       if (h32 < m) m = h32;
     }
@@ -209,8 +213,8 @@ int sedd_ref_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b
     for (int32_t j = 0; j < b; j++) {
       uint64_t key = 0, pw = 1;
       for (int32_t i = 0; i < r; i++) {
-        key = sedd_ref_addmod(key, sedd_ref_mulmod((uint64_t)sig[d * (uint64_t)K + (uint64_t)j * r + i], pw));
-        pw = sedd_ref_mulmod(pw, Q_BAND);
+        key = addmod(key, mulmod((uint64_t)sig[d * (uint64_t)K + (uint64_t)j * r + i], pw));
+        pw = mulmod(pw, Q_BAND);
       }
       keys[d * (uint64_t)b + j] = key;
     }

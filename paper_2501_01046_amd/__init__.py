@@ -1,0 +1,227 @@
+"""MI355X-native MinHash-LSH deduplication hot path (SEDD paper, Sections 2.2-3.2).
+
+Thin binding over the C-ABI library ``libsedd.so`` (hand-written HIP for gfx950).  The
+functions here only marshal arguments: torch supplies device memory and the current HIP
+stream, every step of the path runs in the library's kernels.  There is no CPU fallback:
+if the library has not been built, or there is no GPU, the calls raise.
+
+    sig  = sedd_minhash(text_u8, doc_offsets_u64, shingle_n=5, K=128)   # uint32 [n_docs, K]
+    keys = sedd_lsh_keys(sig, b=16, r=8)                                  # uint64 [n_docs, b]
+    cid  = sedd_cluster(keys)                                             # int64  [n_docs]
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+__all__ = [
+    "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
+    "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
+    "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
+    "FLAG_BYTE_SHINGLES",
+]
+
+FLAG_BYTE_SHINGLES = 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsedd.so")
+_lib = None
+
+
+class SeddError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        msg = f"{where} failed with code {code}"
+        if detail:
+            msg += f": {detail}"
+        super().__init__(msg)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2501_01046_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        u64, i32, u32, vp = C.c_uint64, C.c_int32, C.c_uint32, C.c_void_p
+        L.sedd_minhash.restype = C.c_int
+        L.sedd_minhash.argtypes = [vp, vp, u64, i32, i32, u64, u32, vp, vp]
+        L.sedd_lsh_keys.restype = C.c_int
+        L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
+        L.sedd_cluster.restype = C.c_int
+        L.sedd_cluster.argtypes = [vp, u64, i32, vp, vp]
+        L.sedd_strerror.restype = C.c_char_p
+        L.sedd_strerror.argtypes = [C.c_int]
+        L.sedd_last_device_error.restype = C.c_char_p
+        L.sedd_version.restype = C.c_int
+        L.sedd_release_scratch.restype = C.c_int
+        L.sedd_scratch_bytes.restype = u64
+        L.sedd_debug_shingle_hashes.restype = C.c_int
+        L.sedd_debug_shingle_hashes.argtypes = [vp, vp, u64, i32, u32, vp, u64, vp, vp]
+        L.sedd_debug_coeffs.restype = C.c_int
+        L.sedd_debug_coeffs.argtypes = [u64, i32, vp, vp, vp]
+        L.sedd_debug_scan_u32.restype = C.c_int
+        L.sedd_debug_scan_u32.argtypes = [vp, vp, u64, vp]
+        L.sedd_debug_sort_bands.restype = C.c_int
+        L.sedd_debug_sort_bands.argtypes = [vp, u64, i32, vp, vp, vp]
+        L.sedd_debug_set_chunk_bytes.restype = C.c_int
+        L.sedd_debug_set_chunk_bytes.argtypes = [u64]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        L = lib()
+        detail = L.sedd_strerror(rc).decode()
+        if rc == -3:
+            detail += " / " + L.sedd_last_device_error().decode()
+        raise SeddError(rc, where, detail)
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: the sedd_* calls run only on a HIP device")
+    return torch
+
+
+def _dev(t, dtype, name):
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _ptr(t):
+    return t.data_ptr() if t.numel() else None
+
+
+def _stream(stream):
+    torch = _torch()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def sedd_minhash(text, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags: int = 0,
+                 out=None, stream=None):
+    """uint32 [n_docs, K] signatures of the documents text[doc_offsets[d]:doc_offsets[d+1]]."""
+    torch = _torch()
+    text = _dev(text, torch.uint8, "text")
+    doc_offsets = _dev(doc_offsets, torch.uint64, "doc_offsets")
+    n_docs = max(0, doc_offsets.numel() - 1)
+    if out is None:
+        out = torch.empty((n_docs, max(int(K), 0)), dtype=torch.uint32, device=text.device)
+    else:
+        out = _dev(out, torch.uint32, "out")
+        if out.numel() != n_docs * K:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_minhash(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, K, seed, flags,
+                              _ptr(out), _stream(stream)), "sedd_minhash")
+    return out
+
+
+def sedd_lsh_keys(sig, b: int, r: int, out=None, stream=None):
+    """uint64 [n_docs, b] band keys of uint32 [n_docs, K] signatures."""
+    torch = _torch()
+    sig = _dev(sig, torch.uint32, "sig")
+    n_docs, K = sig.shape
+    if out is None:
+        out = torch.empty((n_docs, max(int(b), 0)), dtype=torch.uint64, device=sig.device)
+    else:
+        out = _dev(out, torch.uint64, "out")
+        if out.numel() != n_docs * b:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_lsh_keys(_ptr(sig), n_docs, K, b, r, _ptr(out), _stream(stream)),
+           "sedd_lsh_keys")
+    return out
+
+
+def sedd_cluster(keys, out=None, stream=None):
+    """int64 [n_docs] smallest document index of each document's connected component."""
+    torch = _torch()
+    keys = _dev(keys, torch.uint64, "keys")
+    n_docs, b = keys.shape
+    if out is None:
+        out = torch.empty((n_docs,), dtype=torch.int64, device=keys.device)
+    else:
+        out = _dev(out, torch.int64, "out")
+        if out.numel() != n_docs:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_cluster(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)), "sedd_cluster")
+    return out
+
+
+def sedd_release_scratch():
+    _check(lib().sedd_release_scratch(), "sedd_release_scratch")
+
+
+def sedd_scratch_bytes() -> int:
+    return lib().sedd_scratch_bytes()
+
+
+def sedd_version() -> int:
+    return lib().sedd_version()
+
+
+# ---- stage-level entry points (parity tests of intermediate results) -----------------------
+
+def debug_shingle_hashes(text, doc_offsets, shingle_n: int, flags: int = 0, stream=None):
+    """(x uint64[n_shingles], shingle_offsets uint64[n_docs+1]) of Eq. 1 base hashes."""
+    torch = _torch()
+    text = _dev(text, torch.uint8, "text")
+    doc_offsets = _dev(doc_offsets, torch.uint64, "doc_offsets")
+    n_docs = max(0, doc_offsets.numel() - 1)
+    soff = torch.zeros(n_docs + 1, dtype=torch.uint64, device=text.device)
+    L = lib()
+    _check(L.sedd_debug_shingle_hashes(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, flags,
+                                       None, 0, _ptr(soff), _stream(stream)),
+           "sedd_debug_shingle_hashes")
+    total = int(soff[-1].item())
+    x = torch.zeros(total, dtype=torch.uint64, device=text.device)
+    _check(L.sedd_debug_shingle_hashes(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, flags,
+                                       _ptr(x), total, _ptr(soff), _stream(stream)),
+           "sedd_debug_shingle_hashes")
+    return x, soff
+
+
+def debug_coeffs(seed: int, K: int, stream=None):
+    torch = _torch()
+    a = torch.zeros(max(K, 0), dtype=torch.uint64, device="cuda")
+    b = torch.zeros(max(K, 0), dtype=torch.uint64, device="cuda")
+    _check(lib().sedd_debug_coeffs(seed, K, _ptr(a), _ptr(b), _stream(stream)), "sedd_debug_coeffs")
+    return a, b
+
+
+def debug_scan_u32(values, stream=None):
+    torch = _torch()
+    values = _dev(values, torch.uint32, "values")
+    out = torch.empty_like(values)
+    _check(lib().sedd_debug_scan_u32(_ptr(values), _ptr(out), values.numel(), _stream(stream)),
+           "sedd_debug_scan_u32")
+    return out
+
+
+def debug_sort_bands(keys, stream=None):
+    torch = _torch()
+    keys = _dev(keys, torch.uint64, "keys")
+    n_docs, b = keys.shape
+    ks = torch.empty((b, n_docs), dtype=torch.uint64, device=keys.device)
+    ds = torch.empty((b, n_docs), dtype=torch.uint32, device=keys.device)
+    _check(lib().sedd_debug_sort_bands(_ptr(keys), n_docs, b, _ptr(ks), _ptr(ds), _stream(stream)),
+           "sedd_debug_sort_bands")
+    return ks, ds
+
+
+def debug_set_chunk_bytes(n: int):
+    _check(lib().sedd_debug_set_chunk_bytes(n), "sedd_debug_set_chunk_bytes")

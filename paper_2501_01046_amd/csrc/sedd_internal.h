@@ -1,0 +1,115 @@
+// Internal declarations shared by the HIP translation units of libsedd.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sedd.h"
+#include "sedd_debug.h"
+
+namespace sedd {
+
+// ---- constants of the method (Section 3.2 Eq. 1; readings fixed in include/sedd.h) ----
+constexpr uint64_t P61 = 2305843009213693951ull;     // 2^61 - 1
+constexpr uint64_t Q_BAND = 1687994237021934823ull;  // base of the band-key polynomial
+constexpr uint64_t G_A = 1425089352415399810ull;
+constexpr uint64_t G_B = 955111447119501601ull;
+
+// ---- arithmetic mod 2^61-1 (device) ----------------------------------------------------
+
+// canonical residue of r < 2^63
+__device__ __forceinline__ uint64_t fold61(uint64_t r) {
+  r = (r & P61) + (r >> 61);
+  return r >= P61 ? r - P61 : r;
+}
+__device__ __forceinline__ uint64_t addmod(uint64_t a, uint64_t b) {
+  uint64_t r = a + b;  // < 2^62
+  return r >= P61 ? r - P61 : r;
+}
+// a, b < 2^61.  2^64 = 8 (mod p), so hi*2^64 + lo = (lo & p) + (lo >> 61) + 8*hi.
+__device__ __forceinline__ uint64_t mulmod(uint64_t a, uint64_t b) {
+  uint64_t lo = a * b;
+  uint64_t hi = __umul64hi(a, b);  // < 2^58
+  return fold61((lo & P61) + (lo >> 61) + (hi << 3));
+}
+// x * 257 for x < p: 257 = 2^8 + 1 and a shift by 8 is a rotation of the 61-bit residue
+__device__ __forceinline__ uint64_t mul257(uint64_t x) {
+  uint64_t rot = ((x << 8) & P61) | (x >> 53);
+  return fold61(rot + x);
+}
+__device__ __forceinline__ uint64_t powmod(uint64_t g, uint64_t e) {
+  uint64_t r = 1;
+  while (e) {
+    if (e & 1) r = mulmod(r, g);
+    g = mulmod(g, g);
+    e >>= 1;
+  }
+  return r;
+}
+__device__ __forceinline__ bool is_ws(uint32_t c) { return c == 0x20u || (c - 0x09u) <= 4u; }
+
+// ---- block-level scan (device) ------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    uint32_t o = __shfl_up(v, d, 64);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive scan across the block of one value per thread; returns the exclusive prefix and
+// the block total in *total.  Must be called by all THREADS threads of the block.
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *total) {
+  __shared__ uint32_t wave_sum[THREADS / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = wave_inclusive_scan(v);
+  __syncthreads();  // protects wave_sum across repeated calls
+  if (lane == 63) wave_sum[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; w++) {
+    uint32_t s = wave_sum[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// ---- host runtime ------------------------------------------------------------------------
+
+int set_device_error(hipError_t e, const char *what);
+#define SEDD_HIP(expr)                                            \
+  do {                                                            \
+    hipError_t _e = (expr);                                       \
+    if (_e != hipSuccess) return sedd::set_device_error(_e, #expr); \
+  } while (0)
+#define SEDD_LAUNCH_CHECK() SEDD_HIP(hipGetLastError())
+
+// Grow-only device arena.  ensure() may synchronise the device and reallocate.
+int scratch_ensure(uint64_t bytes, uint8_t **base);
+// Grow-only pinned host buffer.
+int pinned_ensure(uint64_t bytes, void **ptr);
+
+struct Carver {  // carves 256-byte aligned sub-buffers out of the arena
+  uint64_t off = 0;
+  template <typename T> uint64_t take(uint64_t count) {
+    uint64_t o = off;
+    off += (count * sizeof(T) + 255) & ~uint64_t(255);
+    return o;
+  }
+};
+
+// Exclusive prefix sum of n uint32 (out may alias in).  tmp must hold scan_tmp_count(n) uint32.
+uint64_t scan_tmp_count(uint64_t n);
+int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *tmp,
+                       hipStream_t s);
+
+static inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
+
+}  // namespace sedd

@@ -1,0 +1,184 @@
+// Host runtime of libsedd: error reporting, the grow-only scratch arena, and the
+// exclusive-scan primitive the work-list builders use.
+#include <stdio.h>
+#include <string.h>
+
+#include "sedd_internal.h"
+
+namespace sedd {
+
+static thread_local char g_dev_err[512] = "";
+
+int set_device_error(hipError_t e, const char *what) {
+  snprintf(g_dev_err, sizeof(g_dev_err), "%s: %s (%s)", hipGetErrorName(e), hipGetErrorString(e),
+           what);
+  (void)hipGetLastError();  // clear the sticky last-error slot
+  return e == hipErrorOutOfMemory ? SEDD_ENOMEM : SEDD_EDEVICE;
+}
+
+static uint8_t *g_arena = nullptr;
+static uint64_t g_arena_bytes = 0;
+static void *g_pinned = nullptr;
+static uint64_t g_pinned_bytes = 0;
+
+int scratch_ensure(uint64_t bytes, uint8_t **base) {
+  if (bytes > g_arena_bytes) {
+    // earlier calls may still be using the old arena
+    SEDD_HIP(hipDeviceSynchronize());
+    if (g_arena) {
+      SEDD_HIP(hipFree(g_arena));
+      g_arena = nullptr;
+      g_arena_bytes = 0;
+    }
+    uint64_t want = (bytes + (uint64_t(1) << 21)) & ~((uint64_t(1) << 21) - 1);
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+      set_device_error(e, "hipMalloc(scratch)");
+      return SEDD_ENOMEM;
+    }
+    g_arena = (uint8_t *)p;
+    g_arena_bytes = want;
+  }
+  *base = g_arena;
+  return SEDD_OK;
+}
+
+int pinned_ensure(uint64_t bytes, void **ptr) {
+  if (bytes > g_pinned_bytes) {
+    if (g_pinned) {
+      SEDD_HIP(hipHostFree(g_pinned));
+      g_pinned = nullptr;
+      g_pinned_bytes = 0;
+    }
+    uint64_t want = (bytes + 4095) & ~uint64_t(4095);
+    void *p = nullptr;
+    hipError_t e = hipHostMalloc(&p, want, hipHostMallocDefault);
+    if (e != hipSuccess) {
+      set_device_error(e, "hipHostMalloc(offsets)");
+      return SEDD_ENOMEM;
+    }
+    g_pinned = p;
+    g_pinned_bytes = want;
+  }
+  *ptr = g_pinned;
+  return SEDD_OK;
+}
+
+// ---- exclusive scan ----------------------------------------------------------------------
+//
+// Blocks of 256 threads x 4 values.  Level 0 reduces each block to one partial, the partials
+// are scanned recursively, then each block rescans its values on top of its partial.
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_PER_THREAD = 4;
+constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
+
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, uint64_t n) {
+  uint64_t i0 = (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < SCAN_PER_THREAD; j++)
+    if (i0 + j < n) s += in[i0 + j];
+  uint32_t tot;
+  block_exclusive_scan<SCAN_THREADS>(s, &tot);
+  if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_down(const uint32_t *in, uint32_t *out, uint64_t n, const uint32_t *__restrict__ partial) {
+  uint64_t i0 = (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
+  uint32_t v[SCAN_PER_THREAD];
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < SCAN_PER_THREAD; j++) {
+    v[j] = (i0 + j < n) ? in[i0 + j] : 0u;
+    s += v[j];
+  }
+  uint32_t tot;
+  uint32_t ex = block_exclusive_scan<SCAN_THREADS>(s, &tot) + (partial ? partial[blockIdx.x] : 0u);
+#pragma unroll
+  for (int j = 0; j < SCAN_PER_THREAD; j++) {
+    if (i0 + j < n) out[i0 + j] = ex;
+    ex += v[j];
+  }
+}
+
+uint64_t scan_tmp_count(uint64_t n) {
+  uint64_t total = 0;
+  while (n > SCAN_BLOCK) {
+    n = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+    total += (n + 63) & ~uint64_t(63);
+  }
+  return total + 64;
+}
+
+int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *tmp,
+                       hipStream_t s) {
+  if (n == 0) return SEDD_OK;
+  uint64_t nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
+  if (nb == 1) {
+    hipLaunchKernelGGL(k_scan_down, dim3(1), dim3(SCAN_THREADS), 0, s, in, out, n,
+                       (const uint32_t *)nullptr);
+    SEDD_LAUNCH_CHECK();
+    return SEDD_OK;
+  }
+  hipLaunchKernelGGL(k_scan_reduce, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, tmp, n);
+  SEDD_LAUNCH_CHECK();
+  uint32_t *next_tmp = tmp + ((nb + 63) & ~uint64_t(63));
+  int rc = scan_exclusive_u32(tmp, tmp, nb, next_tmp, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_scan_down, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, out, n,
+                     (const uint32_t *)tmp);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+}  // namespace sedd
+
+using namespace sedd;
+
+extern "C" {
+
+const char *sedd_strerror(int code) {
+  switch (code) {
+    case SEDD_OK: return "success";
+    case SEDD_EINVAL: return "invalid argument";
+    case SEDD_ENOMEM: return "scratch allocation failed";
+    case SEDD_EDEVICE: return "HIP call failed (see sedd_last_device_error)";
+    default: return "unknown error code";
+  }
+}
+
+const char *sedd_last_device_error(void) { return g_dev_err; }
+
+int sedd_version(void) { return 100; }
+
+int sedd_release_scratch(void) {
+  SEDD_HIP(hipDeviceSynchronize());
+  if (g_arena) {
+    SEDD_HIP(hipFree(g_arena));
+    g_arena = nullptr;
+    g_arena_bytes = 0;
+  }
+  if (g_pinned) {
+    SEDD_HIP(hipHostFree(g_pinned));
+    g_pinned = nullptr;
+    g_pinned_bytes = 0;
+  }
+  return SEDD_OK;
+}
+
+uint64_t sedd_scratch_bytes(void) { return g_arena_bytes; }
+
+int sedd_debug_scan_u32(const uint32_t *in, uint32_t *out, uint64_t n, void *stream) {
+  if (n == 0) return SEDD_OK;
+  if (!in || !out || n >= (uint64_t(1) << 32)) return SEDD_EINVAL;
+  uint8_t *base;
+  int rc = scratch_ensure(scan_tmp_count(n) * 4, &base);
+  if (rc) return rc;
+  return scan_exclusive_u32(in, out, n, (uint32_t *)base, (hipStream_t)stream);
+}
+
+}  // extern "C"
