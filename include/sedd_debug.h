@@ -38,6 +38,41 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
                           uint64_t *keys_sorted, uint32_t *docs_sorted, void *stream);
 
 /*
+ * The K-hash / minimum kernel alone, on caller-supplied shingle hashes: document d owns
+ * x[shingle_offsets[d] .. shingle_offsets[d+1]) (values < 2^61-1, any order, repeats allowed).
+ * n_shingles = shingle_offsets[n_docs] - shingle_offsets[0] < 2^32.  sig as in sedd_minhash.
+ */
+int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
+                              uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,
+                              void *stream);
+
+/*
+ * Device-side counters since the library was loaded, copied to the HOST array out[SEDD_STAT_N]
+ * (waits for the device to go idle first).
+ */
+#define SEDD_STAT_SLOW_TILES 0 /* shingle tiles the min-hash kernel recomputed on its exact path */
+#define SEDD_STAT_N 16
+int sedd_debug_stats(uint64_t *out);
+
+/*
+ * Per-stage timing with HIP events on the stream the kernels are launched on.  While enabled,
+ * every call records an event pair around each stage; sedd_profile_read waits for them, adds
+ * the elapsed milliseconds and the number of timed spans per stage into the HOST arrays
+ * ms[SEDD_PROF_N], spans[SEDD_PROF_N], and forgets them.
+ */
+#define SEDD_PROF_MINHASH 0      /* K hash functions + minimum (the dominant kernel) */
+#define SEDD_PROF_SHINGLE_HASH 1 /* Eq. 1 base hash per shingle */
+#define SEDD_PROF_TOKENIZE 2     /* token marking, counting and token records */
+#define SEDD_PROF_WORKLIST 3     /* tile lists and scans */
+#define SEDD_PROF_LSH_KEYS 4
+#define SEDD_PROF_SORT 5
+#define SEDD_PROF_UNION 6
+#define SEDD_PROF_N 8
+int sedd_profile_enable(int on);
+int sedd_profile_read(double *ms, uint64_t *spans);
+const char *sedd_profile_label(int label);
+
+/*
  * Upper bound on the text bytes processed per internal chunk of sedd_minhash (0 restores
  * the default).  Results never depend on it; tests use small values to cross chunk edges.
  */

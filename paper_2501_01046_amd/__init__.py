@@ -18,6 +18,7 @@ __all__ = [
     "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
+    "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
     "FLAG_BYTE_SHINGLES",
 ]
 
@@ -70,6 +71,16 @@ def lib():
         L.sedd_debug_scan_u32.argtypes = [vp, vp, u64, vp]
         L.sedd_debug_sort_bands.restype = C.c_int
         L.sedd_debug_sort_bands.argtypes = [vp, u64, i32, vp, vp, vp]
+        L.sedd_debug_minhash_from_x.restype = C.c_int
+        L.sedd_debug_minhash_from_x.argtypes = [vp, vp, u64, u64, i32, u64, vp, vp]
+        L.sedd_debug_stats.restype = C.c_int
+        L.sedd_debug_stats.argtypes = [vp]
+        L.sedd_profile_enable.restype = C.c_int
+        L.sedd_profile_enable.argtypes = [C.c_int]
+        L.sedd_profile_read.restype = C.c_int
+        L.sedd_profile_read.argtypes = [vp, vp]
+        L.sedd_profile_label.restype = C.c_char_p
+        L.sedd_profile_label.argtypes = [C.c_int]
         L.sedd_debug_set_chunk_bytes.restype = C.c_int
         L.sedd_debug_set_chunk_bytes.argtypes = [u64]
         _lib = L
@@ -225,3 +236,46 @@ def debug_sort_bands(keys, stream=None):
 
 def debug_set_chunk_bytes(n: int):
     _check(lib().sedd_debug_set_chunk_bytes(n), "sedd_debug_set_chunk_bytes")
+
+
+def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None):
+    """Signatures from caller-supplied shingle hashes (the K-hash / minimum kernel alone)."""
+    torch = _torch()
+    x = _dev(x, torch.uint64, "x")
+    shingle_offsets = _dev(shingle_offsets, torch.uint64, "shingle_offsets")
+    n_docs = max(0, shingle_offsets.numel() - 1)
+    sig = torch.empty((n_docs, max(K, 0)), dtype=torch.uint32, device=x.device)
+    _check(lib().sedd_debug_minhash_from_x(_ptr(x), _ptr(shingle_offsets), n_docs, x.numel(), K,
+                                           seed, _ptr(sig), _stream(stream)),
+           "sedd_debug_minhash_from_x")
+    return sig
+
+
+STAT_SLOW_TILES = 0
+_STAT_N = 16
+_PROF_N = 8
+
+
+def debug_stats():
+    """Device-side counters since the library was loaded (list of ints; waits for the device)."""
+    buf = (C.c_uint64 * _STAT_N)()
+    _check(lib().sedd_debug_stats(buf), "sedd_debug_stats")
+    return list(buf)
+
+
+def profile_enable(on: bool):
+    _check(lib().sedd_profile_enable(1 if on else 0), "sedd_profile_enable")
+
+
+def profile_read():
+    """{stage: (milliseconds, timed spans)} accumulated since the last read (waits for them)."""
+    ms = (C.c_double * _PROF_N)()
+    spans = (C.c_uint64 * _PROF_N)()
+    L = lib()
+    _check(L.sedd_profile_read(ms, spans), "sedd_profile_read")
+    out = {}
+    for i in range(_PROF_N):
+        name = L.sedd_profile_label(i).decode()
+        if name:
+            out[name] = (ms[i], int(spans[i]))
+    return out

@@ -96,6 +96,21 @@ int scratch_ensure(uint64_t bytes, uint8_t **base);
 // Grow-only pinned host buffer.
 int pinned_ensure(uint64_t bytes, void **ptr);
 
+// Device counters that persist for the life of the process (SEDD_STAT_* indices).
+int stats_ensure(unsigned long long **p);
+
+// Times the work enqueued during its lifetime under `label` when profiling is enabled.
+struct ProfScope {
+  ProfScope(int label, hipStream_t st);
+  ~ProfScope();
+  ProfScope(const ProfScope &) = delete;
+  ProfScope &operator=(const ProfScope &) = delete;
+
+ private:
+  hipStream_t st_;
+  int idx_;
+};
+
 struct Carver {  // carves 256-byte aligned sub-buffers out of the arena
   uint64_t off = 0;
   template <typename T> uint64_t take(uint64_t count) {

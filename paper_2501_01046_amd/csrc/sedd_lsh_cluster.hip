@@ -248,6 +248,7 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
   if (!sig || !keys || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   const uint64_t total = n_docs * (uint64_t)b;
   if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  ProfScope prof(SEDD_PROF_LSH_KEYS, (hipStream_t)stream);
   hipLaunchKernelGGL(k_lsh_keys, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0,
                      (hipStream_t)stream, sig, n_docs, (int)K, (int)b, (int)r, keys);
   SEDD_LAUNCH_CHECK();
@@ -271,8 +272,12 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
-  rc = sort_bands(keys, n_docs, (uint32_t)b, &sb, st);
-  if (rc) return rc;
+  {
+    ProfScope prof(SEDD_PROF_SORT, st);
+    rc = sort_bands(keys, n_docs, (uint32_t)b, &sb, st);
+    if (rc) return rc;
+  }
+  ProfScope prof(SEDD_PROF_UNION, st);
   const uint32_t n = (uint32_t)n_docs;
   hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
   SEDD_LAUNCH_CHECK();

@@ -25,6 +25,27 @@ constexpr uint32_t TB = TB_THREADS * 16;  // bytes per byte tile
 constexpr uint32_t TS = 1024;             // shingles per hash tile
 constexpr int QPOW_N = 256;
 
+// x(s) of Eq. 1 as the hot kernel wants it: x = x1 * 2^31 + x0 with x0 < 2^31, x1 < 2^30,
+// stored pre-scaled as lo2 = 2 x0 and hi4 = 4 x1 (both fit 32 bits).
+struct XSplit {
+  uint32_t lo2, hi4;
+};
+__device__ __forceinline__ XSplit x_split(uint64_t x) {
+  XSplit r;
+  r.lo2 = ((uint32_t)x & 0x7FFFFFFFu) << 1;
+  r.hi4 = (uint32_t)(x >> 31) << 2;
+  return r;
+}
+__device__ __forceinline__ uint64_t x_join(XSplit v) {
+  return ((uint64_t)(v.hi4 >> 2) << 31) | (v.lo2 >> 1);
+}
+
+// coefficients of one hash function in the same limb form: a = a1 * 2^31 + a0
+struct CoefSplit {
+  uint32_t a0;   // a mod 2^31
+  uint32_t a12;  // 2 * (a >> 31)
+};
+
 struct WordRec {
   uint64_t w;   // Eq. 1 hash of the token's bytes
   uint64_t pw;  // 257^len mod p
@@ -43,12 +64,20 @@ __global__ void k_fill_u32(uint32_t *p, uint64_t n, uint32_t v) {
 __global__ void k_zero_u64(uint64_t *p) { *p = 0; }
 
 // a_k = s0 * Ga^(k+1), b_k = s0 * Gb^(k+1) (mod p), s0 = (seed mod (p-1)) + 1; qpow[i] = 257^i
-__global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, uint64_t *qpow) {
+__global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, CoefSplit *split,
+                         uint64_t *qpow) {
   int k = blockIdx.x * blockDim.x + threadIdx.x;
   uint64_t s0 = seed % (P61 - 1) + 1;
   if (k < K) {
-    a[k] = mulmod(s0, powmod(G_A, (uint64_t)k + 1));
+    const uint64_t ak = mulmod(s0, powmod(G_A, (uint64_t)k + 1));
+    a[k] = ak;
     b[k] = mulmod(s0, powmod(G_B, (uint64_t)k + 1));
+    if (split) {
+      CoefSplit c;
+      c.a0 = (uint32_t)ak & 0x7FFFFFFFu;
+      c.a12 = (uint32_t)(ak >> 31) << 1;
+      split[k] = c;
+    }
   }
   if (qpow && k < QPOW_N) qpow[k] = powmod(257, (uint64_t)k);
 }
@@ -188,7 +217,7 @@ k_shingle_hash(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ d
                const uint32_t *__restrict__ docw, const WordRec *__restrict__ rec,
                const uint32_t *__restrict__ sbase, const uint32_t *__restrict__ htile_base,
                const uint32_t *__restrict__ htile_doc, uint32_t nd, uint32_t n, int byte_mode,
-               uint64_t *__restrict__ xs) {
+               XSplit *__restrict__ xs) {
   const uint32_t t = blockIdx.x;
   if (t >= htile_base[nd]) return;
   const uint32_t d = htile_doc[t];
@@ -202,7 +231,7 @@ k_shingle_hash(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ d
       const uint8_t *p = pbase + vs + i;
       uint64_t acc = 0;
       for (uint32_t j = per; j-- > 0;) acc = addmod(mul257(acc), (uint64_t)p[j]);
-      xs[s0 + i] = acc;
+      xs[s0 + i] = x_split(acc);
     }
   } else {
     const uint32_t w0 = docw[d], W = docw[d + 1] - w0;
@@ -213,21 +242,43 @@ k_shingle_hash(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ d
       // prepend "token 0x20": x = W + q^len * (32 + q * x_rest)
       for (uint32_t m = per - 1; m-- > 0;)
         acc = addmod(r[m].w, mulmod(r[m].pw, addmod(32, mul257(acc))));
-      xs[s0 + i] = acc;
+      xs[s0 + i] = x_split(acc);
     }
   }
 }
 
 // ---- the hot kernel ------------------------------------------------------------------------
+//
+// One wavefront per shingle tile; lane l evaluates hash functions k0+l, k0+64+l, ... (F of them),
+// the shingle value is wave-uniform (scalar registers).  Per (shingle, function) the kernel needs
+// h = ((a x + b) mod p) mod 2^32 with p = 2^61-1.
+//
+// 31-bit limbs: a = a1 2^31 + a0, x = x1 2^31 + x0.  With 2^61 = 1 and 2^62 = 2 (mod p):
+//   a x + b  =  a0 x0 + 2 a1 x1 + b  +  2^31 M,        M = a0 x1 + a1 x0  (< 2^62)
+//   2^31 M   =  mh + 2^31 ml,                           mh = M >> 30, ml = M mod 2^30
+// N = 4 M = a0 (4 x1) + (2 a1)(2 x0) is formed instead of M: its high word is mh and its low word
+// is 4 ml, so 2^31 ml = n_lo 2^29 needs no mask.  Everything is chained through the 64-bit addend
+// of the 32x32+64 multiply-add:
+//   N = a0*(4x1) + (2a1)*(2x0);  S = n_lo*2^29 + a0*x0 + (2a1)*x1 + b  (< 2^64);  Z = S + mh.
+// Z mod p has low word  s_lo + mh + (S >> 61)  unless bits 33..60 of S are all ones (then a carry
+// may cross bit 61 or the folded value may reach p).  That case has probability 2^-28 per
+// evaluation; the lane records it in `amb`, and a tile with any such lane is recomputed with the
+// plain 64-bit arithmetic.  The multipliers 2^29 and 8 are passed as kernel arguments so that they
+// stay multiplies (one instruction) instead of being expanded into 64-bit shift/add pairs.
 
-// One wavefront per shingle tile; lane l evaluates hash functions k0+l, k0+64+l, ... (F of them).
-// h = ((a x + b) mod p) mod 2^32, running minimum per function.
+struct HotConsts {
+  uint32_t two29;  // 1 << 29
+  uint32_t eight;  // 8
+};
+
 template <int F>
 __global__ void __launch_bounds__(64)
-k_minhash(const uint64_t *__restrict__ xs, const uint32_t *__restrict__ sbase,
+k_minhash(const XSplit *__restrict__ xs, const uint32_t *__restrict__ sbase,
           const uint32_t *__restrict__ htile_base, const uint32_t *__restrict__ htile_doc,
           uint32_t nd, const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
-          int K, uint32_t *__restrict__ sig /* first document of the chunk */) {
+          const CoefSplit *__restrict__ coef_split, int K,
+          uint32_t *__restrict__ sig /* first document of the chunk */, HotConsts hc,
+          unsigned long long *__restrict__ slow_tiles) {
   const uint32_t t = blockIdx.x;
   if (t >= htile_base[nd]) return;
   const uint32_t d = htile_doc[t];
@@ -235,26 +286,50 @@ k_minhash(const uint64_t *__restrict__ xs, const uint32_t *__restrict__ sbase,
   const uint32_t s0 = sbase[d], S = sbase[d + 1] - s0;
   const uint32_t i0 = (t - tb) * TS;
   const uint32_t cnt = min(TS, S - i0);
-  const uint64_t *__restrict__ xp = xs + s0 + i0;
+  const XSplit *__restrict__ xp = xs + s0 + i0;
 
   const int kbase = blockIdx.y * (64 * F) + threadIdx.x;
   uint64_t a[F], b[F];
-  uint32_t m[F];
+  uint32_t a0[F], a12[F], m[F];
 #pragma unroll
   for (int j = 0; j < F; j++) {
     int k = kbase + 64 * j;
-    a[j] = k < K ? coef_a[k] : 1;
-    b[j] = k < K ? coef_b[k] : 0;
+    const int kk = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
+    a[j] = coef_a[kk];
+    b[j] = coef_b[kk];
+    const CoefSplit c = coef_split[kk];
+    a0[j] = c.a0;
+    a12[j] = c.a12;
     m[j] = 0xFFFFFFFFu;
   }
+  uint32_t amb = 0;
+#pragma unroll 4
   for (uint32_t s = 0; s < cnt; s++) {
-    const uint64_t x = xp[s];
+    const XSplit xv = xp[s];
+    const uint32_t x0_2 = xv.lo2, x1_4 = xv.hi4;
+    const uint32_t x0 = x0_2 >> 1, x1 = x1_4 >> 2;
 #pragma unroll
     for (int j = 0; j < F; j++) {
-      uint64_t lo = a[j] * x;
-      uint64_t hi = __umul64hi(a[j], x);
-      uint64_t h = fold61((lo & P61) + (lo >> 61) + (hi << 3) + b[j]);
-      m[j] = min(m[j], (uint32_t)h);
+      uint64_t N = (uint64_t)a0[j] * x1_4;
+      N += (uint64_t)a12[j] * x0_2;
+      uint64_t U = (uint64_t)a12[j] * x1 + b[j];
+      U += (uint64_t)a0[j] * x0;
+      const uint64_t Sv = (uint64_t)(uint32_t)N * hc.two29 + U;
+      const uint64_t W = (uint64_t)(uint32_t)(Sv >> 32) * hc.eight;  // hi: S >> 61, lo: bits 32..60
+      const uint32_t h = (uint32_t)Sv + (uint32_t)(N >> 32) + (uint32_t)(W >> 32);
+      amb = max(amb, (uint32_t)W);
+      m[j] = min(m[j], h);
+    }
+  }
+  if (__any(amb >= 0xFFFFFFF0u)) {
+    // rare: some evaluation sat within reach of a carry across bit 61; redo the tile exactly
+    if (threadIdx.x == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+    for (uint32_t s = 0; s < cnt; s++) {
+      const uint64_t x = x_join(xp[s]);
+#pragma unroll
+      for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)addmod(mulmod(a[j], x), b[j]));
     }
   }
   uint32_t *out = sig + (uint64_t)d * K;
@@ -270,7 +345,7 @@ k_minhash(const uint64_t *__restrict__ xs, const uint32_t *__restrict__ sbase,
 
 // ---- debug copies ------------------------------------------------------------------------
 
-__global__ void k_debug_copy_x(const uint64_t *__restrict__ xs, const uint32_t *__restrict__ sbase,
+__global__ void k_debug_copy_x(const XSplit *__restrict__ xs, const uint32_t *__restrict__ sbase,
                                uint32_t nd, const uint64_t *__restrict__ total,
                                uint64_t *__restrict__ out_x, uint64_t cap,
                                uint64_t *__restrict__ out_off) {
@@ -279,11 +354,50 @@ __global__ void k_debug_copy_x(const uint64_t *__restrict__ xs, const uint32_t *
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   const uint32_t ns = sbase[nd];
   for (uint64_t j = i; j < ns; j += stride)
-    if (base + j < cap) out_x[base + j] = xs[j];
+    if (base + j < cap) out_x[base + j] = x_join(xs[j]);
   for (uint64_t j = i; j <= nd; j += stride) out_off[j] = base + sbase[j];
 }
 __global__ void k_debug_add_total(uint64_t *total, const uint32_t *sbase_last) {
   *total += *sbase_last;
+}
+
+// launches the hot kernel over nht candidate tiles (tiles beyond the device-side count exit)
+static int launch_minhash(const XSplit *xs, const uint32_t *sbase, const uint32_t *htb,
+                          const uint32_t *htd, uint32_t nd, uint64_t nht, const uint64_t *coef_a,
+                          const uint64_t *coef_b, const CoefSplit *coef_s, int K, uint32_t *csig,
+                          hipStream_t st) {
+  unsigned long long *stats = nullptr;
+  int rc = stats_ensure(&stats);
+  if (rc) return rc;
+  const int F = K <= 64 ? 1 : (K <= 128 ? 2 : 4);
+  const uint32_t ky = (uint32_t)((K + 64 * F - 1) / (64 * F));
+  const HotConsts hc = {1u << 29, 8u};
+  dim3 grid((uint32_t)nht, ky);
+  ProfScope prof(SEDD_PROF_MINHASH, st);
+  if (F == 1)
+    hipLaunchKernelGGL(k_minhash<1>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
+  else if (F == 2)
+    hipLaunchKernelGGL(k_minhash<2>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
+  else
+    hipLaunchKernelGGL(k_minhash<4>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+// shingle_offsets (uint64, absolute) -> sbase (uint32), tile counts; x (uint64) -> split form
+__global__ void k_from_x_prepare(const uint64_t *__restrict__ soff, uint32_t nd,
+                                 uint32_t *__restrict__ sbase, uint32_t *__restrict__ hcnt) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > nd) return;
+  sbase[i] = (uint32_t)(soff[i] - soff[0]);
+  hcnt[i] = i < nd ? (uint32_t)((soff[i + 1] - soff[i] + TS - 1) / TS) : 0u;
+}
+__global__ void k_from_x_split(const uint64_t *__restrict__ x, uint64_t n, XSplit *__restrict__ xs) {
+  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) xs[i] = x_split(x[i]);
 }
 
 // ---- host driver ---------------------------------------------------------------------------
@@ -339,6 +453,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
 
   Carver cv;
   const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
+  const uint64_t o_cs = cv.take<CoefSplit>(K);
   const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
   const uint64_t o_total = cv.take<uint64_t>(1);
   const uint64_t o_dv = cv.take<uint32_t>(max_nd + 1);
@@ -350,25 +465,26 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_sbase = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_htb = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_htd = cv.take<uint32_t>(NHT);
-  const uint64_t o_xs = cv.take<uint64_t>(NS);
+  const uint64_t o_xs = cv.take<XSplit>(NS);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(std::max(NBT + 1, max_nd + 1)));
   uint8_t *A = nullptr;
   rc = scratch_ensure(cv.off, &A);
   if (rc) return rc;
   uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
+  CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   uint64_t *qpow = (uint64_t *)(A + o_qpow), *total = (uint64_t *)(A + o_total);
   uint32_t *dv = (uint32_t *)(A + o_dv), *btb = (uint32_t *)(A + o_btb);
   uint32_t *btd = (uint32_t *)(A + o_btd), *wbase = (uint32_t *)(A + o_wbase);
   WordRec *rec = (WordRec *)(A + o_rec);
   uint32_t *docw = (uint32_t *)(A + o_docw), *sbase = (uint32_t *)(A + o_sbase);
   uint32_t *htb = (uint32_t *)(A + o_htb), *htd = (uint32_t *)(A + o_htd);
-  uint64_t *xs = (uint64_t *)(A + o_xs);
+  XSplit *xs = (XSplit *)(A + o_xs);
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
 
   {
     int nthr = std::max(K, QPOW_N);
     hipLaunchKernelGGL(k_coeffs, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
-                       coef_b, qpow);
+                       coef_b, coef_s, qpow);
     SEDD_LAUNCH_CHECK();
   }
   if (debug) {
@@ -383,8 +499,6 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
 
   const uint64_t align = (uint64_t)(uintptr_t)bytes & 15;
   const uint8_t *bytes16 = bytes - align;
-  const int F = K <= 64 ? 1 : (K <= 128 ? 2 : 4);
-  const uint32_t ky = (uint32_t)((K + 64 * F - 1) / (64 * F));
 
   for (const Chunk &c : chunks) {
     const uint32_t nd = (uint32_t)(c.d1 - c.d0);
@@ -397,13 +511,19 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
     const uint64_t *coff = doc_offsets + c.d0;
     const uint32_t gdoc = (nd + 1 + 255) / 256;
 
-    hipLaunchKernelGGL(k_doc_btiles, dim3(gdoc), dim3(256), 0, st, coff, shift, nd, dv, btb);
-    SEDD_LAUNCH_CHECK();
-    if (!byte_mode) {
-      rc = scan_exclusive_u32(btb, btb, (uint64_t)nd + 1, tmp, st);
-      if (rc) return rc;
-      hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, btb, nd, btd);
+    {
+      ProfScope prof(SEDD_PROF_WORKLIST, st);
+      hipLaunchKernelGGL(k_doc_btiles, dim3(gdoc), dim3(256), 0, st, coff, shift, nd, dv, btb);
       SEDD_LAUNCH_CHECK();
+      if (!byte_mode) {
+        rc = scan_exclusive_u32(btb, btb, (uint64_t)nd + 1, tmp, st);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, btb, nd, btd);
+        SEDD_LAUNCH_CHECK();
+      }
+    }
+    if (!byte_mode) {
+      ProfScope prof(SEDD_PROF_TOKENIZE, st);
       hipLaunchKernelGGL(k_count_words, dim3((uint32_t)nbt + 1), dim3(TB_THREADS), 0, st, pbase, dv,
                          btb, btd, nd, wbase);
       SEDD_LAUNCH_CHECK();
@@ -413,18 +533,24 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
                          btd, nd, wbase, qpow, rec);
       SEDD_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(k_doc_shingles, dim3(gdoc), dim3(256), 0, st, dv, btb, wbase, nd,
-                       (uint32_t)n, byte_mode, docw, sbase, htb);
-    SEDD_LAUNCH_CHECK();
-    rc = scan_exclusive_u32(sbase, sbase, (uint64_t)nd + 1, tmp, st);
-    if (rc) return rc;
-    rc = scan_exclusive_u32(htb, htb, (uint64_t)nd + 1, tmp, st);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, htb, nd, htd);
-    SEDD_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_shingle_hash, dim3((uint32_t)nht), dim3(256), 0, st, pbase, dv, docw, rec,
-                       sbase, htb, htd, nd, (uint32_t)n, byte_mode, xs);
-    SEDD_LAUNCH_CHECK();
+    {
+      ProfScope prof(SEDD_PROF_WORKLIST, st);
+      hipLaunchKernelGGL(k_doc_shingles, dim3(gdoc), dim3(256), 0, st, dv, btb, wbase, nd,
+                         (uint32_t)n, byte_mode, docw, sbase, htb);
+      SEDD_LAUNCH_CHECK();
+      rc = scan_exclusive_u32(sbase, sbase, (uint64_t)nd + 1, tmp, st);
+      if (rc) return rc;
+      rc = scan_exclusive_u32(htb, htb, (uint64_t)nd + 1, tmp, st);
+      if (rc) return rc;
+      hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, htb, nd, htd);
+      SEDD_LAUNCH_CHECK();
+    }
+    {
+      ProfScope prof(SEDD_PROF_SHINGLE_HASH, st);
+      hipLaunchKernelGGL(k_shingle_hash, dim3((uint32_t)nht), dim3(256), 0, st, pbase, dv, docw,
+                         rec, sbase, htb, htd, nd, (uint32_t)n, byte_mode, xs);
+      SEDD_LAUNCH_CHECK();
+    }
     if (debug) {
       hipLaunchKernelGGL(k_debug_copy_x, dim3(1024), dim3(256), 0, st, xs, sbase, nd, total, dbg_x,
                          dbg_cap, dbg_off + c.d0);
@@ -432,18 +558,9 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
     } else {
-      uint32_t *csig = sig + c.d0 * (uint64_t)K;
-      dim3 grid((uint32_t)nht, ky);
-      if (F == 1)
-        hipLaunchKernelGGL(k_minhash<1>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
-                           coef_b, (int)K, csig);
-      else if (F == 2)
-        hipLaunchKernelGGL(k_minhash<2>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
-                           coef_b, (int)K, csig);
-      else
-        hipLaunchKernelGGL(k_minhash<4>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
-                           coef_b, (int)K, csig);
-      SEDD_LAUNCH_CHECK();
+      rc = launch_minhash(xs, sbase, htb, htd, nd, nht, coef_a, coef_b, coef_s, (int)K,
+                          sig + c.d0 * (uint64_t)K, st);
+      if (rc) return rc;
     }
   }
   return SEDD_OK;
@@ -486,9 +603,55 @@ int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
 int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream) {
   if (K < 1 || K > SEDD_MAX_K || !a || !b) return SEDD_EINVAL;
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, (hipStream_t)stream, seed,
-                     (int)K, a, b, (uint64_t *)nullptr);
+                     (int)K, a, b, (CoefSplit *)nullptr, (uint64_t *)nullptr);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
+}
+
+int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
+                              uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,
+                              void *stream) {
+  if (K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
+  if (n_docs == 0) return SEDD_OK;
+  if (!shingle_offsets || !sig || (n_shingles && !x)) return SEDD_EINVAL;
+  if (n_docs >= (uint64_t(1) << 31) || n_shingles >= (uint64_t(1) << 32)) return SEDD_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t nd = (uint32_t)n_docs;
+  const uint64_t nht = n_docs + n_shingles / TS + 2;
+  Carver cv;
+  const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
+  const uint64_t o_cs = cv.take<CoefSplit>(K);
+  const uint64_t o_sbase = cv.take<uint32_t>(n_docs + 1), o_htb = cv.take<uint32_t>(n_docs + 1);
+  const uint64_t o_htd = cv.take<uint32_t>(nht), o_xs = cv.take<XSplit>(n_shingles + 1);
+  const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(n_docs + 1));
+  uint8_t *A = nullptr;
+  int rc = scratch_ensure(cv.off, &A);
+  if (rc) return rc;
+  uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
+  uint32_t *sbase = (uint32_t *)(A + o_sbase), *htb = (uint32_t *)(A + o_htb);
+  uint32_t *htd = (uint32_t *)(A + o_htd), *tmp = (uint32_t *)(A + o_tmp);
+  XSplit *xs = (XSplit *)(A + o_xs);
+  CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
+  hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
+                     coef_b, coef_s, (uint64_t *)nullptr);
+  SEDD_LAUNCH_CHECK();
+  const uint64_t nsig = n_docs * (uint64_t)K;
+  hipLaunchKernelGGL(k_fill_u32, dim3((uint32_t)std::min<uint64_t>((nsig + 255) / 256, 65536)),
+                     dim3(256), 0, st, sig, nsig, 0xFFFFFFFFu);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_from_x_prepare, dim3((nd + 1 + 255) / 256), dim3(256), 0, st,
+                     shingle_offsets, nd, sbase, htb);
+  SEDD_LAUNCH_CHECK();
+  rc = scan_exclusive_u32(htb, htb, n_docs + 1, tmp, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_fill_tile_doc, dim3((nd + 255) / 256), dim3(256), 0, st, htb, nd, htd);
+  SEDD_LAUNCH_CHECK();
+  if (n_shingles) {
+    hipLaunchKernelGGL(k_from_x_split, dim3((uint32_t)((n_shingles + 255) / 256)), dim3(256), 0, st,
+                       x, n_shingles, xs);
+    SEDD_LAUNCH_CHECK();
+  }
+  return launch_minhash(xs, sbase, htb, htd, nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
 }
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {

@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "sedd_internal.h"
 
 namespace sedd {
@@ -63,6 +65,58 @@ int pinned_ensure(uint64_t bytes, void **ptr) {
   }
   *ptr = g_pinned;
   return SEDD_OK;
+}
+
+// ---- persistent device counters ------------------------------------------------------------
+
+static unsigned long long *g_stats = nullptr;
+
+int stats_ensure(unsigned long long **p) {
+  if (!g_stats) {
+    void *q = nullptr;
+    hipError_t e = hipMalloc(&q, SEDD_STAT_N * sizeof(unsigned long long));
+    if (e != hipSuccess) {
+      set_device_error(e, "hipMalloc(stats)");
+      return SEDD_ENOMEM;
+    }
+    SEDD_HIP(hipMemset(q, 0, SEDD_STAT_N * sizeof(unsigned long long)));
+    g_stats = (unsigned long long *)q;
+  }
+  *p = g_stats;
+  return SEDD_OK;
+}
+
+// ---- per-stage timing with HIP events (off unless enabled) -------------------------------
+
+struct ProfSpan {
+  int label;
+  hipEvent_t e0, e1;
+};
+static bool g_prof_on = false;
+static std::vector<ProfSpan> g_spans;
+static std::vector<hipEvent_t> g_event_pool;
+
+static hipEvent_t prof_event() {
+  if (!g_event_pool.empty()) {
+    hipEvent_t e = g_event_pool.back();
+    g_event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+ProfScope::ProfScope(int label, hipStream_t st) : st_(st), idx_(-1) {
+  if (!g_prof_on) return;
+  ProfSpan sp{label, prof_event(), prof_event()};
+  if (!sp.e0 || !sp.e1) return;
+  (void)hipEventRecord(sp.e0, st);
+  g_spans.push_back(sp);
+  idx_ = (int)g_spans.size() - 1;
+}
+ProfScope::~ProfScope() {
+  if (idx_ >= 0) (void)hipEventRecord(g_spans[idx_].e1, st_);
 }
 
 // ---- exclusive scan ----------------------------------------------------------------------
@@ -171,6 +225,55 @@ int sedd_release_scratch(void) {
 }
 
 uint64_t sedd_scratch_bytes(void) { return g_arena_bytes; }
+
+int sedd_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return SEDD_OK;
+}
+
+int sedd_profile_read(double *ms, uint64_t *spans) {
+  if (!ms || !spans) return SEDD_EINVAL;
+  for (int i = 0; i < SEDD_PROF_N; i++) {
+    ms[i] = 0.0;
+    spans[i] = 0;
+  }
+  for (ProfSpan &sp : g_spans) {
+    SEDD_HIP(hipEventSynchronize(sp.e1));
+    float t = 0.f;
+    SEDD_HIP(hipEventElapsedTime(&t, sp.e0, sp.e1));
+    if (sp.label >= 0 && sp.label < SEDD_PROF_N) {
+      ms[sp.label] += t;
+      spans[sp.label] += 1;
+    }
+    g_event_pool.push_back(sp.e0);
+    g_event_pool.push_back(sp.e1);
+  }
+  g_spans.clear();
+  return SEDD_OK;
+}
+
+const char *sedd_profile_label(int label) {
+  switch (label) {
+    case SEDD_PROF_MINHASH: return "minhash";
+    case SEDD_PROF_SHINGLE_HASH: return "shingle_hash";
+    case SEDD_PROF_TOKENIZE: return "tokenize";
+    case SEDD_PROF_WORKLIST: return "worklist";
+    case SEDD_PROF_LSH_KEYS: return "lsh_keys";
+    case SEDD_PROF_SORT: return "sort";
+    case SEDD_PROF_UNION: return "union_find";
+    default: return "";
+  }
+}
+
+int sedd_debug_stats(uint64_t *out) {
+  if (!out) return SEDD_EINVAL;
+  unsigned long long *p = nullptr;
+  int rc = stats_ensure(&p);
+  if (rc) return rc;
+  SEDD_HIP(hipDeviceSynchronize());
+  SEDD_HIP(hipMemcpy(out, p, SEDD_STAT_N * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  return SEDD_OK;
+}
 
 int sedd_debug_scan_u32(const uint32_t *in, uint32_t *out, uint64_t n, void *stream) {
   if (n == 0) return SEDD_OK;

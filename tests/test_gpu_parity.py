@@ -26,7 +26,10 @@ def sedd():
 
 
 def dev(a):
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    a = np.ascontiguousarray(a)
+    if not a.flags.writeable:
+        a = a.copy()
+    return torch.from_numpy(a).cuda()
 
 
 def host(t):
@@ -209,6 +212,53 @@ def test_minhash_rejects_decreasing_offsets(sedd):
     assert (out.view(torch.int32) == 7).all().item()          # nothing written
 
 
+def test_minhash_from_x_random_and_structured(sedd):
+    say("minhash from x")
+    rng = np.random.default_rng(5)
+    P = (1 << 61) - 1
+    lens = [0, 1, 2, 1023, 1024, 1025, 5000, 0, 3]
+    parts = [rng.integers(0, P, size=l, dtype=np.uint64) for l in lens]
+    # limb edge values: all-ones / zero limbs, values around 2^31 and 2^60
+    edge = np.array([0, 1, 2, (1 << 31) - 1, 1 << 31, (1 << 31) + 1, (1 << 32) - 1, 1 << 32,
+                     (1 << 60) - 1, 1 << 60, P - 2, P - 1, 0x1FFFFFFF80000000, 0x7FFFFFFF,
+                     0x1FFFFFFFFFFFFFFE, 0x1555555555555555, 0x0AAAAAAAAAAAAAAA], dtype=np.uint64)
+    parts.append(edge)
+    x = np.concatenate(parts)
+    off = np.cumsum([0] + [p.size for p in parts]).astype(np.uint64)
+    for K, seed in [(128, 0), (64, 3), (256, 9), (100, 1)]:
+        got = host(sedd.debug_minhash_from_x(dev(x), dev(off), K, seed))
+        for d, p in enumerate(parts):
+            assert np.array_equal(got[d], oracle.minhash_shingles(p, K, seed)), (K, seed, d)
+
+
+def test_minhash_exact_path_for_values_next_to_the_modulus(sedd):
+    """Shingle values chosen so that (a_k x + b_k) mod p lands within a few units of 0 or p:
+    the kernel's fast evaluation cannot decide those and must take its exact path."""
+    say("minhash near-modulus values")
+    P = (1 << 61) - 1
+    K, seed = 128, 0
+    a, b = oracle.coeffs(seed, K)
+    targets = [0, 1, 2, 5, 7, P - 1, P - 2, P - 5, P - (1 << 32), P - (1 << 32) - 1,
+               P - (1 << 33), (1 << 32) - 1, 1 << 32]
+    docs = []
+    for k in (0, 1, 63, 64, 127):
+        inv = pow(int(a[k]), -1, P)
+        xs = [((t - int(b[k])) * inv) % P for t in targets]
+        for t, xv in zip(targets, xs):
+            assert (int(a[k]) * xv + int(b[k])) % P == t
+        filler = np.random.default_rng(k).integers(0, P, size=200, dtype=np.uint64)
+        docs.append(np.concatenate([np.array(xs, dtype=np.uint64), filler]))
+        docs.append(np.array(xs[:3], dtype=np.uint64))
+    x = np.concatenate(docs)
+    off = np.cumsum([0] + [d.size for d in docs]).astype(np.uint64)
+    before = sedd.debug_stats()[sedd.STAT_SLOW_TILES]
+    got = host(sedd.debug_minhash_from_x(dev(x), dev(off), K, seed))
+    after = sedd.debug_stats()[sedd.STAT_SLOW_TILES]
+    for d, p in enumerate(docs):
+        assert np.array_equal(got[d], oracle.minhash_shingles(p, K, seed)), d
+    assert after > before, "the exact path was never taken"
+
+
 # ---- band keys -----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("K,b,r", [(128, 16, 8), (128, 8, 16), (256, 32, 8), (256, 64, 4), (64, 64, 1),
@@ -287,7 +337,9 @@ def test_config1_whole_path(sedd):
     say("config 1 whole path")
     cid = _full_path(sedd, corpus.config(1), NPROC)
     dups = int((cid != np.arange(cid.size)).sum())
-    assert 300 <= dups <= 700          # about 10 % planted near-duplicates at a 5 % edit rate
+    # 10 % planted near-duplicates at a 5 % word edit rate: Jaccard of 5-grams is about 0.6,
+    # where the (16, 8) collision curve catches a bit under half of them
+    assert 100 <= dups <= 500
 
 
 def test_config3_shape_small(sedd):
