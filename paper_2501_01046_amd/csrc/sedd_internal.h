@@ -32,6 +32,17 @@ __device__ __forceinline__ uint64_t mulmod(uint64_t a, uint64_t b) {
   uint64_t hi = __umul64hi(a, b);  // < 2^58
   return fold61((lo & P61) + (lo >> 61) + (hi << 3));
 }
+// Same product through 31-bit limbs and the 32x32+64 multiply-add (fewer instructions than the
+// 64x64 high/low pair): a = a1 2^31 + a0, x = x1 2^31 + x0, 2^61 = 1, 2^62 = 2 (mod p):
+//   a x = a0 x0 + 2 a1 x1 + 2^31 M,  M = a0 x1 + a1 x0,  2^31 M = (M >> 30) + 2^31 (M mod 2^30).
+// N = 4M keeps M >> 30 in its high word and 4 (M mod 2^30) in its low word.
+__device__ __forceinline__ uint64_t mulmod31(uint64_t a, uint64_t x) {
+  const uint32_t a0 = (uint32_t)a & 0x7FFFFFFFu, a12 = (uint32_t)(a >> 31) << 1;
+  const uint32_t x0 = (uint32_t)x & 0x7FFFFFFFu, x1 = (uint32_t)(x >> 31);
+  const uint64_t N = (uint64_t)a0 * (x1 << 2) + (uint64_t)a12 * (x0 << 1);
+  const uint64_t U = (uint64_t)a12 * x1 + (uint64_t)a0 * x0;           // < 2^61 + 2^62
+  return fold61(((uint64_t)(uint32_t)N << 29) + U + (N >> 32));         // < 2^63 + 2^33
+}
 // x * 257 for x < p: 257 = 2^8 + 1 and a shift by 8 is a rotation of the 61-bit residue
 __device__ __forceinline__ uint64_t mul257(uint64_t x) {
   uint64_t rot = ((x << 8) & P61) | (x >> 53);

@@ -17,7 +17,7 @@ k_lsh_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int 
   uint32_t j = (uint32_t)(idx - d * (uint32_t)b);
   const uint32_t *src = sig + d * (uint64_t)K + (uint64_t)j * r;
   uint64_t acc = src[r - 1];
-  for (int i = r - 2; i >= 0; i--) acc = addmod(mulmod(acc, Q_BAND), (uint64_t)src[i]);
+  for (int i = r - 2; i >= 0; i--) acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)src[i]);
   keys[idx] = acc;
 }
 

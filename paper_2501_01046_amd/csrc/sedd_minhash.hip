@@ -46,10 +46,29 @@ struct CoefSplit {
   uint32_t a12;  // 2 * (a >> 31)
 };
 
-struct WordRec {
-  uint64_t w;   // Eq. 1 hash of the token's bytes
-  uint64_t pw;  // 257^len mod p
+// Token records, structure of arrays: tok_v[i] = Eq. 1 hash of "token 0x20" = W + 32 * 257^len,
+// tok_len[i] = min(len, 255); a token of 255 bytes or more keeps its length in tok_long[i]
+// (written and read only for such tokens).
+struct TokenRecs {
+  uint64_t *v;
+  uint8_t *len;
+  uint32_t *long_len;
 };
+constexpr uint32_t LONG_TOKEN = 255;
+
+// 257^e with the first QPOW_N powers from a table in LDS
+__device__ __forceinline__ uint64_t qpow_lookup(const uint64_t *sm_qpow, uint32_t e) {
+  return e < (uint32_t)QPOW_N ? sm_qpow[e] : powmod(257, e);
+}
+__device__ __forceinline__ void store_token(const TokenRecs &tr, uint32_t idx, uint64_t w,
+                                            uint32_t len, const uint64_t *sm_qpow) {
+  // 32 * 257^len: a shift by 5 is a rotation of the 61-bit residue
+  const uint64_t pw = qpow_lookup(sm_qpow, len);
+  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
+  tr.v[idx] = addmod(w, sp == P61 ? 0 : sp);
+  tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
+  if (len >= LONG_TOKEN) tr.long_len[idx] = len;
+}
 
 static uint64_t g_chunk_bytes_override = 0;
 
@@ -98,31 +117,110 @@ __global__ void k_doc_btiles(const uint64_t *__restrict__ off, uint64_t shift, u
   cnt[i] = c;
 }
 
-// tile_doc[t] = d for every tile t of document d
-__global__ void k_fill_tile_doc(const uint32_t *__restrict__ tbase, uint32_t nd,
-                                uint32_t *__restrict__ tile_doc) {
+// Work-list entries.  One load tells a block everything about its tile, so no block walks a
+// chain of dependent index loads before it can touch its data.
+struct BTile {      // 4 KiB byte tile of one document
+  uint32_t vs, ve;  // the document's bytes [vs, ve) in the chunk frame
+  uint32_t tile0;   // first byte of the tile (16-aligned)
+  uint32_t pad;
+};
+struct HTile {       // tile of up to TS shingles of one document
+  uint32_t doc;      // document index within the chunk
+  uint32_t x_off;    // index of the tile's first shingle in the chunk's shingle stream
+  uint32_t cnt;      // shingles in the tile
+  uint32_t single;   // 1 if the document has no other tile
+  uint32_t tok0;     // (word mode) index of the first token of the tile's first shingle
+  uint32_t per;      // (word mode) tokens per shingle: min(n, tokens in the document)
+  uint32_t pad[2];
+};
+
+__global__ void k_fill_btiles(const uint32_t *__restrict__ dv, const uint32_t *__restrict__ tbase,
+                              uint32_t nd, BTile *__restrict__ tiles) {
   uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
   if (d >= nd) return;
-  uint32_t t1 = tbase[d + 1];
-  for (uint32_t t = tbase[d]; t < t1; t++) tile_doc[t] = d;
+  const uint32_t t0 = tbase[d], t1 = tbase[d + 1];
+  BTile bt;
+  bt.vs = dv[d];
+  bt.ve = dv[d + 1];
+  bt.pad = 0;
+  for (uint32_t t = t0; t < t1; t++) {
+    bt.tile0 = (bt.vs & ~15u) + (t - t0) * TB;
+    tiles[t] = bt;
+  }
+}
+
+__global__ void k_fill_htiles(const uint32_t *__restrict__ sbase, const uint32_t *__restrict__ tbase,
+                              const uint32_t *__restrict__ docw, uint32_t nd, uint32_t n,
+                              HTile *__restrict__ tiles) {
+  uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
+  if (d >= nd) return;
+  const uint32_t t0 = tbase[d], t1 = tbase[d + 1];
+  const uint32_t s0 = sbase[d], S = sbase[d + 1] - s0;
+  HTile ht;
+  ht.doc = d;
+  ht.single = (t1 - t0 == 1) ? 1u : 0u;
+  ht.pad[0] = ht.pad[1] = 0;
+  const uint32_t w0 = docw ? docw[d] : 0u;
+  ht.per = docw ? min(n, docw[d + 1] - w0) : 0u;
+  for (uint32_t t = t0; t < t1; t++) {
+    const uint32_t i0 = (t - t0) * TS;
+    ht.x_off = s0 + i0;
+    ht.cnt = min(TS, S - i0);
+    ht.tok0 = w0 + i0;
+    tiles[t] = ht;
+  }
 }
 
 // ---- tokenisation ------------------------------------------------------------------------
 
-// Bit i of the result: byte seg+i starts a token of the document [vs, ve).  seg is 16-aligned.
-__device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pbase, uint32_t seg,
-                                                 uint32_t vs, uint32_t ve, uint32_t *sm_last) {
-  uint32_t wm = 0;
+// The 16 bytes of one thread's segment and the mask of its token bytes (bit i: byte seg+i lies
+// inside the document [vs, ve) and is not whitespace).  seg is 16-aligned; the load is issued
+// only if the segment holds at least one byte of the document.
+struct Segment {
+  uint32_t w[4];
+  uint32_t wm;
+};
+__device__ __forceinline__ uint32_t seg_byte(const Segment &sg, int i) {
+  return (sg.w[i >> 2] >> (8 * (i & 3))) & 0xFFu;
+}
+// 4-bit mask of the bytes of w that are NOT whitespace {09..0D, 20}, by SWAR on the word
+__device__ __forceinline__ uint32_t nonspace_mask4(uint32_t w) {
+  const uint32_t lo7 = w & 0x7F7F7F7Fu;
+  // byte == 0x20
+  const uint32_t t = w ^ 0x20202020u;
+  const uint32_t eq20 = ~(((t & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | t) & 0x80808080u;
+  // 0x09 <= byte <= 0x0D (bytes >= 0x80 excluded by ~w)
+  const uint32_t ge9 = lo7 + (0x80808080u - 0x09090909u);  // bit 7 set iff low7 >= 9
+  const uint32_t le13 = ~(lo7 + (0x80808080u - 0x0E0E0E0Eu));  // bit 7 set iff low7 <= 13
+  const uint32_t ws = (eq20 | (ge9 & le13 & ~w)) & 0x80808080u;
+  const uint32_t ns = ~ws & 0x80808080u;
+  // gather bits 7, 15, 23, 31 into bits 0..3
+  return ((ns >> 7) * 0x00204081u >> 21) & 0xFu;
+}
+__device__ __forceinline__ Segment load_segment(const uint8_t *__restrict__ pbase, uint32_t seg,
+                                                uint32_t vs, uint32_t ve) {
+  Segment sg;
+  sg.w[0] = sg.w[1] = sg.w[2] = sg.w[3] = 0;
+  sg.wm = 0;
   if (seg < ve && seg + 16 > vs) {
     const uint4 q = *reinterpret_cast<const uint4 *>(pbase + seg);
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int i = 0; i < 16; i++) {
-      uint32_t c = (w[i >> 2] >> (8 * (i & 3))) & 0xFFu;
-      uint32_t pos = seg + i;
-      if (pos >= vs && pos < ve && !is_ws(c)) wm |= 1u << i;
-    }
+    sg.w[0] = q.x; sg.w[1] = q.y; sg.w[2] = q.z; sg.w[3] = q.w;
+    const uint32_t m = nonspace_mask4(q.x) | (nonspace_mask4(q.y) << 4) |
+                       (nonspace_mask4(q.z) << 8) | (nonspace_mask4(q.w) << 12);
+    // bytes of the segment inside the document: [lo, hi)
+    const uint32_t lo = vs > seg ? vs - seg : 0u;
+    const uint32_t hi = ve - seg < 16u ? ve - seg : 16u;
+    const uint32_t valid = ((1u << hi) - 1u) & ~((1u << lo) - 1u);
+    sg.wm = m & valid;
   }
+  return sg;
+}
+
+// Bit i of the result: byte seg+i starts a token.  Needs the token-byte bit of the byte before
+// the segment: the previous thread's last bit, or for thread 0 the byte before the tile.
+__device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pbase, uint32_t seg,
+                                                 uint32_t vs, uint32_t ve, uint32_t wm,
+                                                 uint32_t *sm_last) {
   sm_last[threadIdx.x] = wm >> 15;
   __syncthreads();
   uint32_t prev;
@@ -135,51 +233,131 @@ __device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pba
   return wm & ~((wm << 1) | prev) & 0xFFFFu;
 }
 
-__global__ void __launch_bounds__(TB_THREADS)
-k_count_words(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ dv,
-              const uint32_t *__restrict__ btile_base, const uint32_t *__restrict__ tile_doc,
-              uint32_t nd, uint32_t *__restrict__ wcnt) {
-  __shared__ uint32_t sm_last[TB_THREADS];
-  const uint32_t t = blockIdx.x;
-  if (t >= btile_base[nd]) {
-    if (threadIdx.x == 0) wcnt[t] = 0;
+// Token starts per 4 KiB byte tile.  One wavefront per tile, 64 bytes per lane (four aligned
+// 16-byte loads), no LDS: the bit before a lane's bytes comes from the lane below by shuffle.
+__global__ void __launch_bounds__(256)
+k_count_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
+              const uint32_t *__restrict__ n_tiles, uint32_t n_slots,
+              uint32_t *__restrict__ wcnt) {
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const uint32_t lane = threadIdx.x & 63;
+  if (t >= n_slots) return;
+  if (t >= *n_tiles) {
+    if (lane == 0) wcnt[t] = 0;
     return;
   }
-  const uint32_t d = tile_doc[t];
-  const uint32_t vs = dv[d], ve = dv[d + 1];
-  const uint32_t seg = (vs & ~15u) + (t - btile_base[d]) * TB + threadIdx.x * 16;
-  uint32_t starts = token_starts(pbase, seg, vs, ve, sm_last);
-  uint32_t tot;
-  block_exclusive_scan<TB_THREADS>(__popc(starts), &tot);
-  if (threadIdx.x == 0) wcnt[t] = tot;
+  const BTile bt = tiles[t];
+  const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
+  const uint32_t base = tile0 + lane * 64;
+  uint64_t wm = 0;
+#pragma unroll
+  for (int k = 0; k < 4; k++) {
+    const Segment sg = load_segment(pbase, base + 16 * k, vs, ve);
+    wm |= (uint64_t)sg.wm << (16 * k);
+  }
+  uint32_t prev = __shfl_up((uint32_t)(wm >> 63), 1, 64);
+  if (lane == 0) prev = (tile0 > vs && tile0 <= ve) ? (is_ws(pbase[tile0 - 1]) ? 0u : 1u) : 0u;
+  const uint64_t starts = wm & ~((wm << 1) | prev);
+  uint32_t cnt = __popcll(starts);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if (lane == 0) wcnt[t] = cnt;
 }
 
+// acc * 257 + c without full reduction: result < 2^61 + 2^10 for acc < 2^61 + 2^10
+__device__ __forceinline__ uint64_t horner257_lazy(uint64_t acc, uint32_t c) {
+  const uint64_t lo = (uint64_t)(uint32_t)acc * 257u + c;              // < 2^41
+  const uint64_t hi = (uint64_t)(uint32_t)(acc >> 32) * 257u + (lo >> 32);  // < 2^39
+  // value = hi * 2^32 + lo32; bits 61.. of it are hi >> 29, and 2^61 = 1 (mod p)
+  return (((hi & 0x1FFFFFFFu) << 32) | (uint32_t)lo) + (hi >> 29);
+}
+
+// One block per 4 KiB byte tile, one thread per 16 bytes.  Each thread walks its 16 bytes from
+// the last to the first in registers (Horner for Eq. 1), writing a record for every token that
+// starts and ends inside its segment.  A token that runs up to the end of the segment is
+// completed from the following threads' head fragments (the token bytes each segment begins
+// with), exchanged through LDS; a token that runs past the tile is finished from global memory.
 __global__ void __launch_bounds__(TB_THREADS)
-k_emit_words(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ dv,
-             const uint32_t *__restrict__ btile_base, const uint32_t *__restrict__ tile_doc,
-             uint32_t nd, const uint32_t *__restrict__ wbase, const uint64_t *__restrict__ qpow,
-             WordRec *__restrict__ rec) {
+k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
+             const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
+             const uint64_t *__restrict__ qpow, TokenRecs rec) {
   __shared__ uint32_t sm_last[TB_THREADS];
+  __shared__ uint64_t sm_head[TB_THREADS];     // Eq. 1 hash of the segment's head fragment
+  __shared__ uint32_t sm_head_len[TB_THREADS]; // its length, 0..16 (16: the whole segment)
+  __shared__ uint64_t sm_qpow[QPOW_N];
   const uint32_t t = blockIdx.x;
-  if (t >= btile_base[nd]) return;
-  const uint32_t d = tile_doc[t];
-  const uint32_t vs = dv[d], ve = dv[d + 1];
-  const uint32_t seg = (vs & ~15u) + (t - btile_base[d]) * TB + threadIdx.x * 16;
-  uint32_t starts = token_starts(pbase, seg, vs, ve, sm_last);
+  if (t >= *n_tiles) return;
+  sm_qpow[threadIdx.x] = qpow[threadIdx.x];
+  const BTile bt = tiles[t];
+  const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
+  const uint32_t seg = tile0 + threadIdx.x * 16;
+  const Segment sg = load_segment(pbase, seg, vs, ve);
+  const uint32_t starts = token_starts(pbase, seg, vs, ve, sg.wm, sm_last);
   uint32_t tot;
-  uint32_t rank = wbase[t] + block_exclusive_scan<TB_THREADS>(__popc(starts), &tot);
-  while (starts) {
-    const uint32_t s = seg + (uint32_t)__ffs(starts) - 1;
-    starts &= starts - 1;
-    uint32_t e = s + 1;
-    while (e < ve && !is_ws(pbase[e])) e++;
-    uint64_t acc = 0;  // Horner from the last byte: W = c_0 + q (c_1 + q (...))
-    for (uint32_t j = e; j-- > s;) acc = addmod(mul257(acc), (uint64_t)pbase[j]);
-    const uint32_t len = e - s;
-    WordRec r;
-    r.w = acc;
-    r.pw = len < (uint32_t)QPOW_N ? qpow[len] : powmod(257, len);
-    rec[rank++] = r;
+  const uint32_t rank = wbase[t] + block_exclusive_scan<TB_THREADS>(__popc(starts), &tot);
+
+  uint64_t acc = 0;
+  uint32_t len = 0;
+  uint64_t tail_acc = 0;
+  uint32_t tail_len = 0, tail_idx = 0xFFFFFFFFu;
+#pragma unroll
+  for (int i = 15; i >= 0; i--) {
+    const uint32_t bit = 1u << i;
+    if (sg.wm & bit) {
+      acc = horner257_lazy(acc, seg_byte(sg, i));
+      len++;
+      if (starts & bit) {
+        const uint32_t idx = rank + __popc(starts & (bit - 1));
+        if (i + len == 16) {  // reaches the end of the segment: may continue in the next one
+          tail_acc = acc;
+          tail_len = len;
+          tail_idx = idx;
+        } else {
+          // sm_qpow was filled before the barrier inside token_starts
+          store_token(rec, idx, fold61(acc), len, sm_qpow);
+        }
+        acc = 0;
+        len = 0;
+      }
+    } else {
+      acc = 0;
+      len = 0;
+    }
+  }
+  // what is left is the head fragment: token bytes at the start of the segment that belong to a
+  // token begun earlier (len = 0 if the segment starts with whitespace or with a token start)
+  sm_head[threadIdx.x] = fold61(acc);
+  sm_head_len[threadIdx.x] = len;
+  __syncthreads();
+  if (tail_idx != 0xFFFFFFFFu) {
+    uint64_t w = fold61(tail_acc);
+    uint32_t l = tail_len;
+    uint32_t t2 = threadIdx.x + 1;
+    for (;;) {
+      if (t2 == TB_THREADS) {
+        // past the tile: finish the token byte by byte (forward: w += c * 257^l)
+        uint32_t pos = tile0 + TB;
+        if (pos < ve && !is_ws(pbase[pos])) {
+          uint64_t pw = qpow_lookup(sm_qpow, l);
+          while (pos < ve) {
+            const uint32_t c = pbase[pos];
+            if (is_ws(c)) break;
+            w = addmod(w, mulmod(pw, (uint64_t)c));
+            pw = mul257(pw);
+            pos++;
+            l++;
+          }
+        }
+        break;
+      }
+      const uint32_t hl = sm_head_len[t2];
+      if (hl == 0) break;
+      w = addmod(w, mulmod31(qpow_lookup(sm_qpow, l), sm_head[t2]));
+      l += hl;
+      if (hl < 16) break;
+      t2++;
+    }
+    store_token(rec, tail_idx, w, l, sm_qpow);
   }
 }
 
@@ -212,38 +390,68 @@ __global__ void k_doc_shingles(const uint32_t *__restrict__ dv,
 }
 
 // x(s) of Eq. 1 for every shingle of the chunk: block per shingle tile, thread per shingle.
+// Word mode: with V_m = hash of "token_m 0x20" and P_m = 257^(len_m + 1),
+//   x = V_0 + P_0 (V_1 + P_1 (... (V_{n-2} + P_{n-2} W_{n-1}))),   W_{n-1} = V_{n-1} - 32 * 257^len.
+// The tile's token records are staged in LDS once (V, W and P in limb form), so every shingle is
+// n-1 multiply-adds on LDS operands.
 __global__ void __launch_bounds__(256)
 k_shingle_hash(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ dv,
-               const uint32_t *__restrict__ docw, const WordRec *__restrict__ rec,
-               const uint32_t *__restrict__ sbase, const uint32_t *__restrict__ htile_base,
-               const uint32_t *__restrict__ htile_doc, uint32_t nd, uint32_t n, int byte_mode,
+               TokenRecs rec, const uint64_t *__restrict__ qpow,
+               const uint32_t *__restrict__ sbase, const HTile *__restrict__ tiles,
+               const uint32_t *__restrict__ n_tiles, uint32_t n, int byte_mode,
                XSplit *__restrict__ xs) {
+  __shared__ uint64_t sm_qpow[QPOW_N];
+  __shared__ uint64_t sm_v[TS + SEDD_MAX_SHINGLE_N];
+  __shared__ uint64_t sm_w[TS + SEDD_MAX_SHINGLE_N];
+  __shared__ CoefSplit sm_p[TS + SEDD_MAX_SHINGLE_N];
   const uint32_t t = blockIdx.x;
-  if (t >= htile_base[nd]) return;
-  const uint32_t d = htile_doc[t];
-  const uint32_t s0 = sbase[d], S = sbase[d + 1] - s0;
-  const uint32_t i0 = (t - htile_base[d]) * TS;
-  const uint32_t i1 = min(i0 + TS, S);
+  if (t >= *n_tiles) return;
+  const HTile ht = tiles[t];
+  const uint32_t cnt = ht.cnt;
+  XSplit *__restrict__ out = xs + ht.x_off;
   if (byte_mode) {
+    const uint32_t d = ht.doc;
     const uint32_t vs = dv[d], len = dv[d + 1] - vs;
     const uint32_t per = min(len, n);
-    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
-      const uint8_t *p = pbase + vs + i;
+    const uint32_t i0 = ht.x_off - sbase[d];
+    for (uint32_t i = threadIdx.x; i < cnt; i += blockDim.x) {
+      const uint8_t *p = pbase + vs + i0 + i;
       uint64_t acc = 0;
-      for (uint32_t j = per; j-- > 0;) acc = addmod(mul257(acc), (uint64_t)p[j]);
-      xs[s0 + i] = x_split(acc);
+      for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, p[j]);
+      out[i] = x_split(fold61(acc));
     }
-  } else {
-    const uint32_t w0 = docw[d], W = docw[d + 1] - w0;
-    const uint32_t per = min(W, n);
-    for (uint32_t i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
-      const WordRec *r = rec + w0 + i;
-      uint64_t acc = r[per - 1].w;
-      // prepend "token 0x20": x = W + q^len * (32 + q * x_rest)
-      for (uint32_t m = per - 1; m-- > 0;)
-        acc = addmod(r[m].w, mulmod(r[m].pw, addmod(32, mul257(acc))));
-      xs[s0 + i] = x_split(acc);
+    return;
+  }
+  sm_qpow[threadIdx.x] = qpow[threadIdx.x];
+  const uint32_t per = ht.per;
+  const uint32_t tok0 = ht.tok0, ntok = cnt + per - 1;
+  __syncthreads();
+  for (uint32_t j = threadIdx.x; j < ntok; j += blockDim.x) {
+    uint32_t l = rec.len[tok0 + j];
+    if (l == LONG_TOKEN) l = rec.long_len[tok0 + j];
+    const uint64_t v = rec.v[tok0 + j];
+    const uint64_t pw = qpow_lookup(sm_qpow, l);
+    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len
+    const uint64_t p1 = mul257(pw);                      // 257^(len+1)
+    sm_v[j] = v;
+    sm_w[j] = v >= sp ? v - sp : v + P61 - sp;
+    CoefSplit c;
+    c.a0 = (uint32_t)p1 & 0x7FFFFFFFu;
+    c.a12 = (uint32_t)(p1 >> 31) << 1;
+    sm_p[j] = c;
+  }
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < cnt; i += blockDim.x) {
+    uint64_t acc = sm_w[i + per - 1];
+    for (uint32_t m = i + per - 1; m-- > i;) {
+      const CoefSplit c = sm_p[m];
+      const uint32_t x0 = (uint32_t)acc & 0x7FFFFFFFu, x1 = (uint32_t)(acc >> 31);
+      const uint64_t N = (uint64_t)c.a0 * (x1 << 2) + (uint64_t)c.a12 * (x0 << 1);
+      const uint64_t U = (uint64_t)c.a12 * x1 + (uint64_t)c.a0 * x0;
+      // P*acc = (N_lo << 29) + U + N_hi (mod p); add V before the single reduction
+      acc = fold61(((uint64_t)(uint32_t)N << 29) + U + (N >> 32) + sm_v[m]);
     }
+    out[i] = x_split(acc);
   }
 }
 
@@ -273,20 +481,17 @@ struct HotConsts {
 
 template <int F>
 __global__ void __launch_bounds__(64)
-k_minhash(const XSplit *__restrict__ xs, const uint32_t *__restrict__ sbase,
-          const uint32_t *__restrict__ htile_base, const uint32_t *__restrict__ htile_doc,
-          uint32_t nd, const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
+k_minhash(const XSplit *__restrict__ xs, const HTile *__restrict__ tiles,
+          const uint32_t *__restrict__ n_tiles, const uint64_t *__restrict__ coef_a,
+          const uint64_t *__restrict__ coef_b,
           const CoefSplit *__restrict__ coef_split, int K,
           uint32_t *__restrict__ sig /* first document of the chunk */, HotConsts hc,
           unsigned long long *__restrict__ slow_tiles) {
   const uint32_t t = blockIdx.x;
-  if (t >= htile_base[nd]) return;
-  const uint32_t d = htile_doc[t];
-  const uint32_t tb = htile_base[d], ntile = htile_base[d + 1] - tb;
-  const uint32_t s0 = sbase[d], S = sbase[d + 1] - s0;
-  const uint32_t i0 = (t - tb) * TS;
-  const uint32_t cnt = min(TS, S - i0);
-  const XSplit *__restrict__ xp = xs + s0 + i0;
+  if (t >= *n_tiles) return;
+  const HTile ht = tiles[t];
+  const uint32_t d = ht.doc, cnt = ht.cnt;
+  const XSplit *__restrict__ xp = xs + ht.x_off;
 
   const int kbase = blockIdx.y * (64 * F) + threadIdx.x;
   uint64_t a[F], b[F];
@@ -337,7 +542,7 @@ k_minhash(const XSplit *__restrict__ xs, const uint32_t *__restrict__ sbase,
   for (int j = 0; j < F; j++) {
     int k = kbase + 64 * j;
     if (k < K) {
-      if (ntile == 1) out[k] = m[j];
+      if (ht.single) out[k] = m[j];
       else atomicMin(out + k, m[j]);
     }
   }
@@ -362,8 +567,8 @@ __global__ void k_debug_add_total(uint64_t *total, const uint32_t *sbase_last) {
 }
 
 // launches the hot kernel over nht candidate tiles (tiles beyond the device-side count exit)
-static int launch_minhash(const XSplit *xs, const uint32_t *sbase, const uint32_t *htb,
-                          const uint32_t *htd, uint32_t nd, uint64_t nht, const uint64_t *coef_a,
+static int launch_minhash(const XSplit *xs, const HTile *tiles, const uint32_t *n_tiles,
+                          uint64_t nht, const uint64_t *coef_a,
                           const uint64_t *coef_b, const CoefSplit *coef_s, int K, uint32_t *csig,
                           hipStream_t st) {
   unsigned long long *stats = nullptr;
@@ -375,13 +580,13 @@ static int launch_minhash(const XSplit *xs, const uint32_t *sbase, const uint32_
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
   if (F == 1)
-    hipLaunchKernelGGL(k_minhash<1>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+    hipLaunchKernelGGL(k_minhash<1>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
                        coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
   else if (F == 2)
-    hipLaunchKernelGGL(k_minhash<2>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+    hipLaunchKernelGGL(k_minhash<2>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
                        coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
   else
-    hipLaunchKernelGGL(k_minhash<4>, grid, dim3(64), 0, st, xs, sbase, htb, htd, nd, coef_a,
+    hipLaunchKernelGGL(k_minhash<4>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
                        coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
@@ -458,13 +663,15 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_total = cv.take<uint64_t>(1);
   const uint64_t o_dv = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_btb = cv.take<uint32_t>(max_nd + 1);
-  const uint64_t o_btd = cv.take<uint32_t>(byte_mode ? 1 : NBT);
+  const uint64_t o_btd = cv.take<BTile>(byte_mode ? 1 : NBT);
   const uint64_t o_wbase = cv.take<uint32_t>(byte_mode ? 1 : NBT + 1);
-  const uint64_t o_rec = cv.take<WordRec>(byte_mode ? 1 : NW);
+  const uint64_t o_tv = cv.take<uint64_t>(byte_mode ? 1 : NW);
+  const uint64_t o_tl = cv.take<uint8_t>(byte_mode ? 1 : NW);
+  const uint64_t o_tx = cv.take<uint32_t>(byte_mode ? 1 : NW);
   const uint64_t o_docw = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_sbase = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_htb = cv.take<uint32_t>(max_nd + 1);
-  const uint64_t o_htd = cv.take<uint32_t>(NHT);
+  const uint64_t o_htd = cv.take<HTile>(NHT);
   const uint64_t o_xs = cv.take<XSplit>(NS);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(std::max(NBT + 1, max_nd + 1)));
   uint8_t *A = nullptr;
@@ -474,10 +681,15 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   uint64_t *qpow = (uint64_t *)(A + o_qpow), *total = (uint64_t *)(A + o_total);
   uint32_t *dv = (uint32_t *)(A + o_dv), *btb = (uint32_t *)(A + o_btb);
-  uint32_t *btd = (uint32_t *)(A + o_btd), *wbase = (uint32_t *)(A + o_wbase);
-  WordRec *rec = (WordRec *)(A + o_rec);
+  BTile *btd = (BTile *)(A + o_btd);
+  uint32_t *wbase = (uint32_t *)(A + o_wbase);
+  TokenRecs rec;
+  rec.v = (uint64_t *)(A + o_tv);
+  rec.len = (uint8_t *)(A + o_tl);
+  rec.long_len = (uint32_t *)(A + o_tx);
   uint32_t *docw = (uint32_t *)(A + o_docw), *sbase = (uint32_t *)(A + o_sbase);
-  uint32_t *htb = (uint32_t *)(A + o_htb), *htd = (uint32_t *)(A + o_htd);
+  uint32_t *htb = (uint32_t *)(A + o_htb);
+  HTile *htd = (HTile *)(A + o_htd);
   XSplit *xs = (XSplit *)(A + o_xs);
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
 
@@ -518,19 +730,19 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       if (!byte_mode) {
         rc = scan_exclusive_u32(btb, btb, (uint64_t)nd + 1, tmp, st);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, btb, nd, btd);
+        hipLaunchKernelGGL(k_fill_btiles, dim3(gdoc), dim3(256), 0, st, dv, btb, nd, btd);
         SEDD_LAUNCH_CHECK();
       }
     }
     if (!byte_mode) {
       ProfScope prof(SEDD_PROF_TOKENIZE, st);
-      hipLaunchKernelGGL(k_count_words, dim3((uint32_t)nbt + 1), dim3(TB_THREADS), 0, st, pbase, dv,
-                         btb, btd, nd, wbase);
+      hipLaunchKernelGGL(k_count_words, dim3((uint32_t)((nbt + 1 + 3) / 4)), dim3(256), 0, st,
+                         pbase, btd, btb + nd, (uint32_t)(nbt + 1), wbase);
       SEDD_LAUNCH_CHECK();
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
-      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_THREADS), 0, st, pbase, dv, btb,
-                         btd, nd, wbase, qpow, rec);
+      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_THREADS), 0, st, pbase, btd,
+                         btb + nd, wbase, qpow, rec);
       SEDD_LAUNCH_CHECK();
     }
     {
@@ -542,13 +754,14 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       if (rc) return rc;
       rc = scan_exclusive_u32(htb, htb, (uint64_t)nd + 1, tmp, st);
       if (rc) return rc;
-      hipLaunchKernelGGL(k_fill_tile_doc, dim3(gdoc), dim3(256), 0, st, htb, nd, htd);
+      hipLaunchKernelGGL(k_fill_htiles, dim3(gdoc), dim3(256), 0, st, sbase, htb,
+                         byte_mode ? (const uint32_t *)nullptr : docw, nd, (uint32_t)n, htd);
       SEDD_LAUNCH_CHECK();
     }
     {
       ProfScope prof(SEDD_PROF_SHINGLE_HASH, st);
-      hipLaunchKernelGGL(k_shingle_hash, dim3((uint32_t)nht), dim3(256), 0, st, pbase, dv, docw,
-                         rec, sbase, htb, htd, nd, (uint32_t)n, byte_mode, xs);
+      hipLaunchKernelGGL(k_shingle_hash, dim3((uint32_t)nht), dim3(256), 0, st, pbase, dv, rec,
+                         qpow, sbase, htd, htb + nd, (uint32_t)n, byte_mode, xs);
       SEDD_LAUNCH_CHECK();
     }
     if (debug) {
@@ -558,7 +771,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
     } else {
-      rc = launch_minhash(xs, sbase, htb, htd, nd, nht, coef_a, coef_b, coef_s, (int)K,
+      rc = launch_minhash(xs, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K,
                           sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
     }
@@ -622,14 +835,15 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
   const uint64_t o_cs = cv.take<CoefSplit>(K);
   const uint64_t o_sbase = cv.take<uint32_t>(n_docs + 1), o_htb = cv.take<uint32_t>(n_docs + 1);
-  const uint64_t o_htd = cv.take<uint32_t>(nht), o_xs = cv.take<XSplit>(n_shingles + 1);
+  const uint64_t o_htd = cv.take<HTile>(nht), o_xs = cv.take<XSplit>(n_shingles + 1);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(n_docs + 1));
   uint8_t *A = nullptr;
   int rc = scratch_ensure(cv.off, &A);
   if (rc) return rc;
   uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
   uint32_t *sbase = (uint32_t *)(A + o_sbase), *htb = (uint32_t *)(A + o_htb);
-  uint32_t *htd = (uint32_t *)(A + o_htd), *tmp = (uint32_t *)(A + o_tmp);
+  HTile *htd = (HTile *)(A + o_htd);
+  uint32_t *tmp = (uint32_t *)(A + o_tmp);
   XSplit *xs = (XSplit *)(A + o_xs);
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
@@ -644,14 +858,15 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   SEDD_LAUNCH_CHECK();
   rc = scan_exclusive_u32(htb, htb, n_docs + 1, tmp, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_fill_tile_doc, dim3((nd + 255) / 256), dim3(256), 0, st, htb, nd, htd);
+  hipLaunchKernelGGL(k_fill_htiles, dim3((nd + 255) / 256), dim3(256), 0, st, sbase, htb,
+                     (const uint32_t *)nullptr, nd, 0u, htd);
   SEDD_LAUNCH_CHECK();
   if (n_shingles) {
     hipLaunchKernelGGL(k_from_x_split, dim3((uint32_t)((n_shingles + 255) / 256)), dim3(256), 0, st,
                        x, n_shingles, xs);
     SEDD_LAUNCH_CHECK();
   }
-  return launch_minhash(xs, sbase, htb, htd, nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
+  return launch_minhash(xs, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
 }
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {
