@@ -40,7 +40,8 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
 /*
  * The K-hash / minimum kernel alone, on caller-supplied shingle hashes: document d owns
  * x[shingle_offsets[d] .. shingle_offsets[d+1]) (values < 2^61-1, any order, repeats allowed).
- * n_shingles = shingle_offsets[n_docs] - shingle_offsets[0] < 2^32.  sig as in sedd_minhash.
+ * n_shingles = the length of x; shingle_offsets[n_docs] <= n_shingles < 2^32.  sig as in
+ * sedd_minhash.
  */
 int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
                               uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,

@@ -22,22 +22,21 @@ namespace sedd {
 
 constexpr int TB_THREADS = 256;
 constexpr uint32_t TB = TB_THREADS * 16;  // bytes per byte tile
-constexpr uint32_t TS = 1024;             // shingles per hash tile
+constexpr uint32_t TS = 512;              // shingles per hash tile
 constexpr int QPOW_N = 256;
 
-// x(s) of Eq. 1 as the hot kernel wants it: x = x1 * 2^31 + x0 with x0 < 2^31, x1 < 2^30,
-// stored pre-scaled as lo2 = 2 x0 and hi4 = 4 x1 (both fit 32 bits).
-struct XSplit {
-  uint32_t lo2, hi4;
+// x(s) of Eq. 1 as the hot kernel multiplies by it: x = x1 * 2^31 + x0 with x0 < 2^31,
+// x1 < 2^30, together with the pre-scaled limbs 2 x0 and 4 x1 (both fit 32 bits).
+struct XLimbs {
+  uint32_t x0, x1, x0_2, x1_4;
 };
-__device__ __forceinline__ XSplit x_split(uint64_t x) {
-  XSplit r;
-  r.lo2 = ((uint32_t)x & 0x7FFFFFFFu) << 1;
-  r.hi4 = (uint32_t)(x >> 31) << 2;
+__device__ __forceinline__ XLimbs x_limbs(uint64_t x) {
+  XLimbs r;
+  r.x0 = (uint32_t)x & 0x7FFFFFFFu;
+  r.x1 = (uint32_t)(x >> 31);
+  r.x0_2 = r.x0 << 1;
+  r.x1_4 = r.x1 << 2;
   return r;
-}
-__device__ __forceinline__ uint64_t x_join(XSplit v) {
-  return ((uint64_t)(v.hi4 >> 2) << 31) | (v.lo2 >> 1);
 }
 
 // coefficients of one hash function in the same limb form: a = a1 * 2^31 + a0
@@ -389,77 +388,71 @@ __global__ void k_doc_shingles(const uint32_t *__restrict__ dv,
   hcnt[i] = (S + TS - 1) / TS;
 }
 
-// x(s) of Eq. 1 for every shingle of the chunk: block per shingle tile, thread per shingle.
+// ---- shingle hashes (Eq. 1) ----------------------------------------------------------------
+
+// Where a tile's shingle hashes come from.
+struct XSource {
+  const uint8_t *pbase;   // chunk text frame (byte mode)
+  const uint32_t *dv;     // document frame positions (byte mode)
+  const uint32_t *sbase;  // shingle offsets per document (byte mode)
+  TokenRecs rec;          // token records (word mode)
+  const uint64_t *qpow;   // 257^i, i < QPOW_N
+  const uint64_t *given;  // caller-supplied hashes (debug entry), indexed like the shingle stream
+  uint32_t n;             // shingle length
+};
+enum { X_WORDS = 0, X_BYTES = 1, X_GIVEN = 2 };
+
+__device__ __forceinline__ uint32_t token_len(const TokenRecs &rec, uint32_t i) {
+  uint32_t l = rec.len[i];
+  if (l == LONG_TOKEN) l = rec.long_len[i];
+  return l;
+}
+__device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpow, uint32_t e) {
+  return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
+}
+
+// x of shingle i of tile ht.
 // Word mode: with V_m = hash of "token_m 0x20" and P_m = 257^(len_m + 1),
 //   x = V_0 + P_0 (V_1 + P_1 (... (V_{n-2} + P_{n-2} W_{n-1}))),   W_{n-1} = V_{n-1} - 32 * 257^len.
-// The tile's token records are staged in LDS once (V, W and P in limb form), so every shingle is
-// n-1 multiply-adds on LDS operands.
-__global__ void __launch_bounds__(256)
-k_shingle_hash(const uint8_t *__restrict__ pbase, const uint32_t *__restrict__ dv,
-               TokenRecs rec, const uint64_t *__restrict__ qpow,
-               const uint32_t *__restrict__ sbase, const HTile *__restrict__ tiles,
-               const uint32_t *__restrict__ n_tiles, uint32_t n, int byte_mode,
-               XSplit *__restrict__ xs) {
-  __shared__ uint64_t sm_qpow[QPOW_N];
-  __shared__ uint64_t sm_v[TS + SEDD_MAX_SHINGLE_N];
-  __shared__ uint64_t sm_w[TS + SEDD_MAX_SHINGLE_N];
-  __shared__ CoefSplit sm_p[TS + SEDD_MAX_SHINGLE_N];
-  const uint32_t t = blockIdx.x;
-  if (t >= *n_tiles) return;
-  const HTile ht = tiles[t];
-  const uint32_t cnt = ht.cnt;
-  XSplit *__restrict__ out = xs + ht.x_off;
-  if (byte_mode) {
+// Byte mode: Horner over the window's bytes from the last to the first.
+template <int MODE>
+__device__ __forceinline__ uint64_t shingle_x(const XSource &xsrc, const HTile &ht, uint32_t i) {
+  if (MODE == X_GIVEN) return xsrc.given[ht.x_off + i];
+  if (MODE == X_BYTES) {
     const uint32_t d = ht.doc;
-    const uint32_t vs = dv[d], len = dv[d + 1] - vs;
-    const uint32_t per = min(len, n);
-    const uint32_t i0 = ht.x_off - sbase[d];
-    for (uint32_t i = threadIdx.x; i < cnt; i += blockDim.x) {
-      const uint8_t *p = pbase + vs + i0 + i;
-      uint64_t acc = 0;
-      for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, p[j]);
-      out[i] = x_split(fold61(acc));
-    }
-    return;
+    const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
+    const uint32_t per = min(len, xsrc.n);
+    const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
+    uint64_t acc = 0;
+    for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, p[j]);
+    return fold61(acc);
   }
-  sm_qpow[threadIdx.x] = qpow[threadIdx.x];
-  const uint32_t per = ht.per;
-  const uint32_t tok0 = ht.tok0, ntok = cnt + per - 1;
-  __syncthreads();
-  for (uint32_t j = threadIdx.x; j < ntok; j += blockDim.x) {
-    uint32_t l = rec.len[tok0 + j];
-    if (l == LONG_TOKEN) l = rec.long_len[tok0 + j];
-    const uint64_t v = rec.v[tok0 + j];
-    const uint64_t pw = qpow_lookup(sm_qpow, l);
-    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len
-    const uint64_t p1 = mul257(pw);                      // 257^(len+1)
-    sm_v[j] = v;
-    sm_w[j] = v >= sp ? v - sp : v + P61 - sp;
-    CoefSplit c;
-    c.a0 = (uint32_t)p1 & 0x7FFFFFFFu;
-    c.a12 = (uint32_t)(p1 >> 31) << 1;
-    sm_p[j] = c;
+  const TokenRecs &rec = xsrc.rec;
+  const uint32_t first = ht.tok0 + i, last = first + ht.per - 1;
+  const uint64_t pw = qpow_global(xsrc.qpow, token_len(rec, last));
+  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
+  const uint64_t v_last = rec.v[last];
+  uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;
+  for (uint32_t m = last; m-- > first;) {
+    const uint64_t P = qpow_global(xsrc.qpow, token_len(rec, m) + 1);
+    const uint32_t a0 = (uint32_t)P & 0x7FFFFFFFu, a12 = (uint32_t)(P >> 31) << 1;
+    const uint32_t x0 = (uint32_t)acc & 0x7FFFFFFFu, x1 = (uint32_t)(acc >> 31);
+    const uint64_t N = (uint64_t)a0 * (x1 << 2) + (uint64_t)a12 * (x0 << 1);
+    const uint64_t U = (uint64_t)a12 * x1 + (uint64_t)a0 * x0;
+    // P*acc = (N_lo << 29) + U + N_hi (mod p); V is added before the single reduction
+    acc = fold61(((uint64_t)(uint32_t)N << 29) + U + (N >> 32) + rec.v[m]);
   }
-  __syncthreads();
-  for (uint32_t i = threadIdx.x; i < cnt; i += blockDim.x) {
-    uint64_t acc = sm_w[i + per - 1];
-    for (uint32_t m = i + per - 1; m-- > i;) {
-      const CoefSplit c = sm_p[m];
-      const uint32_t x0 = (uint32_t)acc & 0x7FFFFFFFu, x1 = (uint32_t)(acc >> 31);
-      const uint64_t N = (uint64_t)c.a0 * (x1 << 2) + (uint64_t)c.a12 * (x0 << 1);
-      const uint64_t U = (uint64_t)c.a12 * x1 + (uint64_t)c.a0 * x0;
-      // P*acc = (N_lo << 29) + U + N_hi (mod p); add V before the single reduction
-      acc = fold61(((uint64_t)(uint32_t)N << 29) + U + (N >> 32) + sm_v[m]);
-    }
-    out[i] = x_split(acc);
-  }
+  return acc;
 }
 
 // ---- the hot kernel ------------------------------------------------------------------------
 //
-// One wavefront per shingle tile; lane l evaluates hash functions k0+l, k0+64+l, ... (F of them),
-// the shingle value is wave-uniform (scalar registers).  Per (shingle, function) the kernel needs
-// h = ((a x + b) mod p) mod 2^32 with p = 2^61-1.
+// One wavefront per shingle tile (up to TS shingles of one document).
+//
+// Phase A: the 64 lanes compute the tile's Eq. 1 hashes (lane = shingle) into LDS in limb form.
+// Phase B: lane l evaluates hash functions k0+l, k0+64+l, ... (F of them) over the tile; the
+// shingle limbs are read from LDS at a wave-uniform address (a broadcast).  Per (shingle,
+// function) the kernel needs h = ((a x + b) mod p) mod 2^32 with p = 2^61-1.
 //
 // 31-bit limbs: a = a1 2^31 + a0, x = x1 2^31 + x0.  With 2^61 = 1 and 2^62 = 2 (mod p):
 //   a x + b  =  a0 x0 + 2 a1 x1 + b  +  2^31 M,        M = a0 x1 + a1 x0  (< 2^62)
@@ -479,19 +472,20 @@ struct HotConsts {
   uint32_t eight;  // 8
 };
 
-template <int F>
+template <int F, int MODE>
 __global__ void __launch_bounds__(64)
-k_minhash(const XSplit *__restrict__ xs, const HTile *__restrict__ tiles,
-          const uint32_t *__restrict__ n_tiles, const uint64_t *__restrict__ coef_a,
-          const uint64_t *__restrict__ coef_b,
+k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
+          const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
           const CoefSplit *__restrict__ coef_split, int K,
           uint32_t *__restrict__ sig /* first document of the chunk */, HotConsts hc,
           unsigned long long *__restrict__ slow_tiles) {
+  __shared__ XLimbs sx[TS];
   const uint32_t t = blockIdx.x;
   if (t >= *n_tiles) return;
   const HTile ht = tiles[t];
   const uint32_t d = ht.doc, cnt = ht.cnt;
-  const XSplit *__restrict__ xp = xs + ht.x_off;
+
+  for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
 
   const int kbase = blockIdx.y * (64 * F) + threadIdx.x;
   uint64_t a[F], b[F];
@@ -507,18 +501,18 @@ k_minhash(const XSplit *__restrict__ xs, const HTile *__restrict__ tiles,
     a12[j] = c.a12;
     m[j] = 0xFFFFFFFFu;
   }
+  __syncthreads();
+
   uint32_t amb = 0;
 #pragma unroll 4
   for (uint32_t s = 0; s < cnt; s++) {
-    const XSplit xv = xp[s];
-    const uint32_t x0_2 = xv.lo2, x1_4 = xv.hi4;
-    const uint32_t x0 = x0_2 >> 1, x1 = x1_4 >> 2;
+    const XLimbs xv = sx[s];
 #pragma unroll
     for (int j = 0; j < F; j++) {
-      uint64_t N = (uint64_t)a0[j] * x1_4;
-      N += (uint64_t)a12[j] * x0_2;
-      uint64_t U = (uint64_t)a12[j] * x1 + b[j];
-      U += (uint64_t)a0[j] * x0;
+      uint64_t N = (uint64_t)a0[j] * xv.x1_4;
+      N += (uint64_t)a12[j] * xv.x0_2;
+      uint64_t U = (uint64_t)a12[j] * xv.x1 + b[j];
+      U += (uint64_t)a0[j] * xv.x0;
       const uint64_t Sv = (uint64_t)(uint32_t)N * hc.two29 + U;
       const uint64_t W = (uint64_t)(uint32_t)(Sv >> 32) * hc.eight;  // hi: S >> 61, lo: bits 32..60
       const uint32_t h = (uint32_t)Sv + (uint32_t)(N >> 32) + (uint32_t)(W >> 32);
@@ -532,7 +526,8 @@ k_minhash(const XSplit *__restrict__ xs, const HTile *__restrict__ tiles,
 #pragma unroll
     for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
     for (uint32_t s = 0; s < cnt; s++) {
-      const uint64_t x = x_join(xp[s]);
+      const XLimbs xv = sx[s];
+      const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
 #pragma unroll
       for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)addmod(mulmod(a[j], x), b[j]));
     }
@@ -548,27 +543,35 @@ k_minhash(const XSplit *__restrict__ xs, const HTile *__restrict__ tiles,
   }
 }
 
-// ---- debug copies ------------------------------------------------------------------------
+// ---- stage-level output of the shingle hashes (debug entry) ----------------------------------
 
-__global__ void k_debug_copy_x(const XSplit *__restrict__ xs, const uint32_t *__restrict__ sbase,
-                               uint32_t nd, const uint64_t *__restrict__ total,
-                               uint64_t *__restrict__ out_x, uint64_t cap,
-                               uint64_t *__restrict__ out_off) {
-  const uint64_t base = *total;
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-  const uint32_t ns = sbase[nd];
-  for (uint64_t j = i; j < ns; j += stride)
-    if (base + j < cap) out_x[base + j] = x_join(xs[j]);
-  for (uint64_t j = i; j <= nd; j += stride) out_off[j] = base + sbase[j];
+template <int MODE>
+__global__ void __launch_bounds__(64)
+k_debug_write_x(XSource xsrc, const HTile *__restrict__ tiles,
+                const uint32_t *__restrict__ n_tiles, const uint64_t *__restrict__ total,
+                uint64_t *__restrict__ out_x, uint64_t cap) {
+  const uint32_t t = blockIdx.x;
+  if (t >= *n_tiles) return;
+  const HTile ht = tiles[t];
+  const uint64_t base = *total + ht.x_off;
+  for (uint32_t i = threadIdx.x; i < ht.cnt; i += 64) {
+    const uint64_t x = shingle_x<MODE>(xsrc, ht, i);
+    if (base + i < cap) out_x[base + i] = x;
+  }
+}
+__global__ void k_debug_write_offsets(const uint32_t *__restrict__ sbase, uint32_t nd,
+                                      const uint64_t *__restrict__ total,
+                                      uint64_t *__restrict__ out_off) {
+  uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i <= nd) out_off[i] = *total + sbase[i];
 }
 __global__ void k_debug_add_total(uint64_t *total, const uint32_t *sbase_last) {
   *total += *sbase_last;
 }
 
 // launches the hot kernel over nht candidate tiles (tiles beyond the device-side count exit)
-static int launch_minhash(const XSplit *xs, const HTile *tiles, const uint32_t *n_tiles,
-                          uint64_t nht, const uint64_t *coef_a,
+static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
+                          const uint32_t *n_tiles, uint64_t nht, const uint64_t *coef_a,
                           const uint64_t *coef_b, const CoefSplit *coef_s, int K, uint32_t *csig,
                           hipStream_t st) {
   unsigned long long *stats = nullptr;
@@ -579,30 +582,31 @@ static int launch_minhash(const XSplit *xs, const HTile *tiles, const uint32_t *
   const HotConsts hc = {1u << 29, 8u};
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
-  if (F == 1)
-    hipLaunchKernelGGL(k_minhash<1>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
-                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
-  else if (F == 2)
-    hipLaunchKernelGGL(k_minhash<2>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
-                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
-  else
-    hipLaunchKernelGGL(k_minhash<4>, grid, dim3(64), 0, st, xs, tiles, n_tiles, coef_a,
-                       coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);
+#define SEDD_LAUNCH_MH(FF, MM)                                                                  \
+  hipLaunchKernelGGL((k_minhash<FF, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, coef_a, \
+                     coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
+#define SEDD_LAUNCH_MH_F(MM)                  \
+  do {                                        \
+    if (F == 1) SEDD_LAUNCH_MH(1, MM);        \
+    else if (F == 2) SEDD_LAUNCH_MH(2, MM);   \
+    else SEDD_LAUNCH_MH(4, MM);               \
+  } while (0)
+  if (mode == X_WORDS) SEDD_LAUNCH_MH_F(X_WORDS);
+  else if (mode == X_BYTES) SEDD_LAUNCH_MH_F(X_BYTES);
+  else SEDD_LAUNCH_MH_F(X_GIVEN);
+#undef SEDD_LAUNCH_MH_F
+#undef SEDD_LAUNCH_MH
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
 
-// shingle_offsets (uint64, absolute) -> sbase (uint32), tile counts; x (uint64) -> split form
+// shingle_offsets (uint64) -> sbase (uint32, same values) and tile counts
 __global__ void k_from_x_prepare(const uint64_t *__restrict__ soff, uint32_t nd,
                                  uint32_t *__restrict__ sbase, uint32_t *__restrict__ hcnt) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i > nd) return;
-  sbase[i] = (uint32_t)(soff[i] - soff[0]);
+  sbase[i] = (uint32_t)soff[i];
   hcnt[i] = i < nd ? (uint32_t)((soff[i + 1] - soff[i] + TS - 1) / TS) : 0u;
-}
-__global__ void k_from_x_split(const uint64_t *__restrict__ x, uint64_t n, XSplit *__restrict__ xs) {
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) xs[i] = x_split(x[i]);
 }
 
 // ---- host driver ---------------------------------------------------------------------------
@@ -672,7 +676,6 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_sbase = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_htb = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_htd = cv.take<HTile>(NHT);
-  const uint64_t o_xs = cv.take<XSplit>(NS);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(std::max(NBT + 1, max_nd + 1)));
   uint8_t *A = nullptr;
   rc = scratch_ensure(cv.off, &A);
@@ -690,8 +693,15 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   uint32_t *docw = (uint32_t *)(A + o_docw), *sbase = (uint32_t *)(A + o_sbase);
   uint32_t *htb = (uint32_t *)(A + o_htb);
   HTile *htd = (HTile *)(A + o_htd);
-  XSplit *xs = (XSplit *)(A + o_xs);
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
+  XSource xsrc;
+  xsrc.dv = dv;
+  xsrc.sbase = sbase;
+  xsrc.rec = rec;
+  xsrc.qpow = qpow;
+  xsrc.given = nullptr;
+  xsrc.n = (uint32_t)n;
+  const int mode = byte_mode ? X_BYTES : X_WORDS;
 
   {
     int nthr = std::max(K, QPOW_N);
@@ -758,20 +768,22 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
                          byte_mode ? (const uint32_t *)nullptr : docw, nd, (uint32_t)n, htd);
       SEDD_LAUNCH_CHECK();
     }
-    {
-      ProfScope prof(SEDD_PROF_SHINGLE_HASH, st);
-      hipLaunchKernelGGL(k_shingle_hash, dim3((uint32_t)nht), dim3(256), 0, st, pbase, dv, rec,
-                         qpow, sbase, htd, htb + nd, (uint32_t)n, byte_mode, xs);
-      SEDD_LAUNCH_CHECK();
-    }
+    xsrc.pbase = pbase;
     if (debug) {
-      hipLaunchKernelGGL(k_debug_copy_x, dim3(1024), dim3(256), 0, st, xs, sbase, nd, total, dbg_x,
-                         dbg_cap, dbg_off + c.d0);
+      if (byte_mode)
+        hipLaunchKernelGGL(k_debug_write_x<X_BYTES>, dim3((uint32_t)nht), dim3(64), 0, st, xsrc, htd,
+                           htb + nd, total, dbg_x, dbg_cap);
+      else
+        hipLaunchKernelGGL(k_debug_write_x<X_WORDS>, dim3((uint32_t)nht), dim3(64), 0, st, xsrc, htd,
+                           htb + nd, total, dbg_x, dbg_cap);
+      SEDD_LAUNCH_CHECK();
+      hipLaunchKernelGGL(k_debug_write_offsets, dim3(gdoc), dim3(256), 0, st, sbase, nd, total,
+                         dbg_off + c.d0);
       SEDD_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
     } else {
-      rc = launch_minhash(xs, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K,
+      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K,
                           sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
     }
@@ -835,7 +847,7 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
   const uint64_t o_cs = cv.take<CoefSplit>(K);
   const uint64_t o_sbase = cv.take<uint32_t>(n_docs + 1), o_htb = cv.take<uint32_t>(n_docs + 1);
-  const uint64_t o_htd = cv.take<HTile>(nht), o_xs = cv.take<XSplit>(n_shingles + 1);
+  const uint64_t o_htd = cv.take<HTile>(nht);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(n_docs + 1));
   uint8_t *A = nullptr;
   int rc = scratch_ensure(cv.off, &A);
@@ -844,7 +856,6 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   uint32_t *sbase = (uint32_t *)(A + o_sbase), *htb = (uint32_t *)(A + o_htb);
   HTile *htd = (HTile *)(A + o_htd);
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
-  XSplit *xs = (XSplit *)(A + o_xs);
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
                      coef_b, coef_s, (uint64_t *)nullptr);
@@ -861,12 +872,9 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   hipLaunchKernelGGL(k_fill_htiles, dim3((nd + 255) / 256), dim3(256), 0, st, sbase, htb,
                      (const uint32_t *)nullptr, nd, 0u, htd);
   SEDD_LAUNCH_CHECK();
-  if (n_shingles) {
-    hipLaunchKernelGGL(k_from_x_split, dim3((uint32_t)((n_shingles + 255) / 256)), dim3(256), 0, st,
-                       x, n_shingles, xs);
-    SEDD_LAUNCH_CHECK();
-  }
-  return launch_minhash(xs, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
+  XSource xsrc = {};
+  xsrc.given = x;  // tiles index it by shingle offset
+  return launch_minhash(X_GIVEN, xsrc, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
 }
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {
