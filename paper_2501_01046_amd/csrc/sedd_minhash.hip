@@ -20,8 +20,8 @@
 
 namespace sedd {
 
-constexpr int TB_THREADS = 256;
-constexpr uint32_t TB = TB_THREADS * 16;  // bytes per byte tile
+constexpr int TB_LANES = 64;
+constexpr uint32_t TB = TB_LANES * 16;    // bytes per byte tile: one wavefront, 16 bytes per lane
 constexpr uint32_t TS = 512;              // shingles per hash tile
 constexpr int QPOW_N = 256;
 
@@ -55,14 +55,14 @@ struct TokenRecs {
 };
 constexpr uint32_t LONG_TOKEN = 255;
 
-// 257^e with the first QPOW_N powers from a table in LDS
-__device__ __forceinline__ uint64_t qpow_lookup(const uint64_t *sm_qpow, uint32_t e) {
-  return e < (uint32_t)QPOW_N ? sm_qpow[e] : powmod(257, e);
+// 257^e with the first QPOW_N powers from a table (a few cache lines, shared by every lane)
+__device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpow, uint32_t e) {
+  return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
 }
 __device__ __forceinline__ void store_token(const TokenRecs &tr, uint32_t idx, uint64_t w,
-                                            uint32_t len, const uint64_t *sm_qpow) {
+                                            uint32_t len, const uint64_t *__restrict__ qpow) {
   // 32 * 257^len: a shift by 5 is a rotation of the 61-bit residue
-  const uint64_t pw = qpow_lookup(sm_qpow, len);
+  const uint64_t pw = qpow_global(qpow, len);
   const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
   tr.v[idx] = addmod(w, sp == P61 ? 0 : sp);
   tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
@@ -118,7 +118,7 @@ __global__ void k_doc_btiles(const uint64_t *__restrict__ off, uint64_t shift, u
 
 // Work-list entries.  One load tells a block everything about its tile, so no block walks a
 // chain of dependent index loads before it can touch its data.
-struct BTile {      // 4 KiB byte tile of one document
+struct BTile {      // 1 KiB byte tile of one document
   uint32_t vs, ve;  // the document's bytes [vs, ve) in the chunk frame
   uint32_t tile0;   // first byte of the tile (16-aligned)
   uint32_t pad;
@@ -216,24 +216,17 @@ __device__ __forceinline__ Segment load_segment(const uint8_t *__restrict__ pbas
 }
 
 // Bit i of the result: byte seg+i starts a token.  Needs the token-byte bit of the byte before
-// the segment: the previous thread's last bit, or for thread 0 the byte before the tile.
-__device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pbase, uint32_t seg,
-                                                 uint32_t vs, uint32_t ve, uint32_t wm,
-                                                 uint32_t *sm_last) {
-  sm_last[threadIdx.x] = wm >> 15;
-  __syncthreads();
-  uint32_t prev;
-  if (threadIdx.x > 0) {
-    prev = sm_last[threadIdx.x - 1];
-  } else {
-    // byte before the tile: inside the document only if seg > vs
-    prev = (seg > vs && seg <= ve) ? (is_ws(pbase[seg - 1]) ? 0u : 1u) : 0u;
-  }
+// the segment: the lane below's last bit (by shuffle), or for lane 0 the byte before the tile.
+// Must be called by all 64 lanes of the tile's wavefront.
+__device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pbase, uint32_t lane,
+                                                 uint32_t tile0, uint32_t vs, uint32_t ve,
+                                                 uint32_t wm) {
+  uint32_t prev = __shfl_up(wm >> 15, 1, 64);
+  if (lane == 0) prev = (tile0 > vs && tile0 <= ve) ? (is_ws(pbase[tile0 - 1]) ? 0u : 1u) : 0u;
   return wm & ~((wm << 1) | prev) & 0xFFFFu;
 }
 
-// Token starts per 4 KiB byte tile.  One wavefront per tile, 64 bytes per lane (four aligned
-// 16-byte loads), no LDS: the bit before a lane's bytes comes from the lane below by shuffle.
+// Token starts per byte tile: one wavefront per tile, 16 bytes per lane, no LDS.
 __global__ void __launch_bounds__(256)
 k_count_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
               const uint32_t *__restrict__ n_tiles, uint32_t n_slots,
@@ -241,23 +234,14 @@ k_count_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles
   const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
   const uint32_t lane = threadIdx.x & 63;
   if (t >= n_slots) return;
+  const BTile bt = tiles[t < n_slots - 1 ? t : 0];  // entry n_slots-1 only pads the scan
   if (t >= *n_tiles) {
     if (lane == 0) wcnt[t] = 0;
     return;
   }
-  const BTile bt = tiles[t];
-  const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
-  const uint32_t base = tile0 + lane * 64;
-  uint64_t wm = 0;
-#pragma unroll
-  for (int k = 0; k < 4; k++) {
-    const Segment sg = load_segment(pbase, base + 16 * k, vs, ve);
-    wm |= (uint64_t)sg.wm << (16 * k);
-  }
-  uint32_t prev = __shfl_up((uint32_t)(wm >> 63), 1, 64);
-  if (lane == 0) prev = (tile0 > vs && tile0 <= ve) ? (is_ws(pbase[tile0 - 1]) ? 0u : 1u) : 0u;
-  const uint64_t starts = wm & ~((wm << 1) | prev);
-  uint32_t cnt = __popcll(starts);
+  const Segment sg = load_segment(pbase, bt.tile0 + lane * 16, bt.vs, bt.ve);
+  const uint32_t starts = token_starts(pbase, lane, bt.tile0, bt.vs, bt.ve, sg.wm);
+  uint32_t cnt = __popc(starts);
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
   if (lane == 0) wcnt[t] = cnt;
@@ -271,34 +255,41 @@ __device__ __forceinline__ uint64_t horner257_lazy(uint64_t acc, uint32_t c) {
   return (((hi & 0x1FFFFFFFu) << 32) | (uint32_t)lo) + (hi >> 29);
 }
 
-// One block per 4 KiB byte tile, one thread per 16 bytes.  Each thread walks its 16 bytes from
-// the last to the first in registers (Horner for Eq. 1), writing a record for every token that
-// starts and ends inside its segment.  A token that runs up to the end of the segment is
-// completed from the following threads' head fragments (the token bytes each segment begins
-// with), exchanged through LDS; a token that runs past the tile is finished from global memory.
-__global__ void __launch_bounds__(TB_THREADS)
+// One wavefront per byte tile, one lane per 16 bytes.
+// Pass 1 (lane = 16-byte segment): each lane walks its bytes from the last to the first in
+// registers (Horner for Eq. 1) and drops the partial hash and length of every token that starts
+// in its segment into LDS at the token's rank within the tile; what is left over at byte 0 is
+// the segment's head fragment (token bytes that continue a token begun earlier).
+// Pass 2 (lane = token): finish the token (a token that ran up to the end of its segment is
+// completed from the following segments' head fragments, or from global memory past the tile),
+// form V = W + 32 * 257^len and store the record; consecutive lanes store consecutive records.
+constexpr uint32_t MAX_TILE_TOKENS = TB / 2 + 2;
+
+__global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
              const uint64_t *__restrict__ qpow, TokenRecs rec) {
-  __shared__ uint32_t sm_last[TB_THREADS];
-  __shared__ uint64_t sm_head[TB_THREADS];     // Eq. 1 hash of the segment's head fragment
-  __shared__ uint32_t sm_head_len[TB_THREADS]; // its length, 0..16 (16: the whole segment)
-  __shared__ uint64_t sm_qpow[QPOW_N];
+  __shared__ uint64_t sm_head[TB_LANES];      // Eq. 1 hash of the segment's head fragment
+  __shared__ uint32_t sm_head_len[TB_LANES];  // its length, 0..16 (16: the whole segment)
+  __shared__ uint64_t sm_tok_acc[MAX_TILE_TOKENS];   // unreduced in-segment hash per token
+  __shared__ uint16_t sm_tok_meta[MAX_TILE_TOKENS];  // len | 0x80 if it reaches the segment end | lane << 8
   const uint32_t t = blockIdx.x;
-  if (t >= *n_tiles) return;
-  sm_qpow[threadIdx.x] = qpow[threadIdx.x];
+  const uint32_t lane = threadIdx.x;
+  // independent loads first (the work list is allocated for the launch bound, so reading an
+  // entry past the device-side count is harmless); the count decides afterwards
   const BTile bt = tiles[t];
+  const uint32_t first_idx = wbase[t];
+  if (t >= *n_tiles) return;
   const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
-  const uint32_t seg = tile0 + threadIdx.x * 16;
-  const Segment sg = load_segment(pbase, seg, vs, ve);
-  const uint32_t starts = token_starts(pbase, seg, vs, ve, sg.wm, sm_last);
-  uint32_t tot;
-  const uint32_t rank = wbase[t] + block_exclusive_scan<TB_THREADS>(__popc(starts), &tot);
+  const Segment sg = load_segment(pbase, tile0 + lane * 16, vs, ve);
+  const uint32_t starts = token_starts(pbase, lane, tile0, vs, ve, sg.wm);
+  const uint32_t cnt = __popc(starts);
+  const uint32_t inc = wave_inclusive_scan(cnt);
+  const uint32_t local_rank = inc - cnt;
+  const uint32_t tot = __shfl(inc, 63, 64);
 
   uint64_t acc = 0;
   uint32_t len = 0;
-  uint64_t tail_acc = 0;
-  uint32_t tail_len = 0, tail_idx = 0xFFFFFFFFu;
 #pragma unroll
   for (int i = 15; i >= 0; i--) {
     const uint32_t bit = 1u << i;
@@ -306,15 +297,9 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
       acc = horner257_lazy(acc, seg_byte(sg, i));
       len++;
       if (starts & bit) {
-        const uint32_t idx = rank + __popc(starts & (bit - 1));
-        if (i + len == 16) {  // reaches the end of the segment: may continue in the next one
-          tail_acc = acc;
-          tail_len = len;
-          tail_idx = idx;
-        } else {
-          // sm_qpow was filled before the barrier inside token_starts
-          store_token(rec, idx, fold61(acc), len, sm_qpow);
-        }
+        const uint32_t j = local_rank + __popc(starts & (bit - 1));
+        sm_tok_acc[j] = acc;
+        sm_tok_meta[j] = (uint16_t)(len | ((i + len == 16) ? 0x80u : 0u) | (lane << 8));
         acc = 0;
         len = 0;
       }
@@ -323,40 +308,42 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
       len = 0;
     }
   }
-  // what is left is the head fragment: token bytes at the start of the segment that belong to a
-  // token begun earlier (len = 0 if the segment starts with whitespace or with a token start)
-  sm_head[threadIdx.x] = fold61(acc);
-  sm_head_len[threadIdx.x] = len;
+  sm_head[lane] = fold61(acc);
+  sm_head_len[lane] = len;
   __syncthreads();
-  if (tail_idx != 0xFFFFFFFFu) {
-    uint64_t w = fold61(tail_acc);
-    uint32_t l = tail_len;
-    uint32_t t2 = threadIdx.x + 1;
-    for (;;) {
-      if (t2 == TB_THREADS) {
-        // past the tile: finish the token byte by byte (forward: w += c * 257^l)
-        uint32_t pos = tile0 + TB;
-        if (pos < ve && !is_ws(pbase[pos])) {
-          uint64_t pw = qpow_lookup(sm_qpow, l);
-          while (pos < ve) {
-            const uint32_t c = pbase[pos];
-            if (is_ws(c)) break;
-            w = addmod(w, mulmod(pw, (uint64_t)c));
-            pw = mul257(pw);
-            pos++;
-            l++;
+
+  for (uint32_t j = lane; j < tot; j += TB_LANES) {
+    uint64_t w = fold61(sm_tok_acc[j]);
+    const uint32_t meta = sm_tok_meta[j];
+    uint32_t l = meta & 0x7Fu;
+    if (meta & 0x80u) {
+      uint32_t t2 = (meta >> 8) + 1;
+      for (;;) {
+        if (t2 == TB_LANES) {
+          // past the tile: finish the token byte by byte (forward: w += c * 257^l)
+          uint32_t pos = tile0 + TB;
+          if (pos < ve && !is_ws(pbase[pos])) {
+            uint64_t pw = qpow_global(qpow, l);
+            while (pos < ve) {
+              const uint32_t c = pbase[pos];
+              if (is_ws(c)) break;
+              w = addmod(w, mulmod(pw, (uint64_t)c));
+              pw = mul257(pw);
+              pos++;
+              l++;
+            }
           }
+          break;
         }
-        break;
+        const uint32_t hl = sm_head_len[t2];
+        if (hl == 0) break;
+        w = addmod(w, mulmod31(qpow_global(qpow, l), sm_head[t2]));
+        l += hl;
+        if (hl < 16) break;
+        t2++;
       }
-      const uint32_t hl = sm_head_len[t2];
-      if (hl == 0) break;
-      w = addmod(w, mulmod31(qpow_lookup(sm_qpow, l), sm_head[t2]));
-      l += hl;
-      if (hl < 16) break;
-      t2++;
     }
-    store_token(rec, tail_idx, w, l, sm_qpow);
+    store_token(rec, first_idx + j, w, l, qpow);
   }
 }
 
@@ -406,9 +393,6 @@ __device__ __forceinline__ uint32_t token_len(const TokenRecs &rec, uint32_t i) 
   uint32_t l = rec.len[i];
   if (l == LONG_TOKEN) l = rec.long_len[i];
   return l;
-}
-__device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpow, uint32_t e) {
-  return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
 }
 
 // x of shingle i of tile ht.
@@ -481,8 +465,8 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
           unsigned long long *__restrict__ slow_tiles) {
   __shared__ XLimbs sx[TS];
   const uint32_t t = blockIdx.x;
+  const HTile ht = tiles[t];  // the list is allocated for the launch bound: safe past the count
   if (t >= *n_tiles) return;
-  const HTile ht = tiles[t];
   const uint32_t d = ht.doc, cnt = ht.cnt;
 
   for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
@@ -751,7 +735,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       SEDD_LAUNCH_CHECK();
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
-      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_THREADS), 0, st, pbase, btd,
+      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase, btd,
                          btb + nd, wbase, qpow, rec);
       SEDD_LAUNCH_CHECK();
     }
