@@ -1,14 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the MinHash-LSH hot path on one MI355X.
 
-A step is one pass of the whole path (sedd_minhash -> sedd_lsh_keys -> sedd_cluster) over the
-medium workload: 1M synthetic web-text-shaped documents, 5-word shingles, K=128, 16 bands of 8
-rows, with the text and offsets already resident in HBM.  Prints one JSON line.
+A step is one pass of the whole path (sedd_minhash -> sedd_lsh_keys -> sedd_cluster) over one
+batch of synthetic input that is already resident in HBM.  The default workload is the medium
+one the headline metric is quoted on: 1M web-text-shaped documents, 5-word shingles, K=128,
+16 bands of 8 rows.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--docs N] [--config 2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--docs N]
+                    [--sweep] [--no-cpu-baseline]
 
-The CPU oracle is timed on a bounded sample of the same corpus and reported beside it as
-`cpu_baseline`; it is a reported baseline, not the target.
+--config 3 keeps the whole text resident and feeds sedd_minhash 2 GB at a time; --config 5
+--sweep runs the K x (b, r) x n grid and adds the planted-pair S-curve fit per setting.
+The CPU oracle is timed on a bounded sample of the same corpus and reported beside the GPU
+figure as `cpu_baseline`; it is a reported baseline, not the target.
 """
 from __future__ import annotations
 
@@ -22,12 +26,64 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Algorithmic work of the dominant kernel: per (shingle, hash function) one 61-bit modular
-# multiply-add, truncation and minimum = 8 integer VALU lane-operations in the best sequence
-# known here (six 32x32+64 multiply-adds, one 3-input add, one minimum).
+# Algorithmic work of the dominant kernel, in 32-bit integer VALU lane-operations:
+#   per (shingle, hash function): one 61-bit multiply-add mod 2^61-1, truncation, minimum
+#     = 8 operations in the best sequence known here (six 32x32+64 multiply-adds, one 3-input
+#       add, one minimum);
+#   per shingle: its Eq. 1 base hash from n token records (word mode) = n-1 modular
+#     multiply-adds of 8 operations, or n byte steps of 4 operations (byte mode).
 OPS_PER_PAIR = 8
+OPS_PER_BASE_STEP_WORD = 8
+OPS_PER_BASE_STEP_BYTE = 4
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one 32-bit integer lane-operation per lane per clock
 PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+STREAM_CHUNK_BYTES = 2 << 30
+
+
+def ops_per_shingle(recipe, K):
+    if recipe.byte_mode:
+        base = recipe.shingle_n * OPS_PER_BASE_STEP_BYTE
+    else:
+        base = (recipe.shingle_n - 1) * OPS_PER_BASE_STEP_WORD
+    return K * OPS_PER_PAIR + base
+
+
+def load_corpus(torch, corpus, recipe, stream_chunk=None):
+    """Generate the corpus and place it in HBM.  Returns a list of (text, offsets, d0, d1)
+    device pieces (one piece unless stream_chunk is given), total bytes, and the host arrays of
+    the first piece (for the oracle sample)."""
+    gen = corpus.Corpus(recipe)
+    pieces = []
+    total = 0
+    first_host = None
+    if stream_chunk is None:
+        data, off = gen.generate()
+        pieces.append((torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(), 0, recipe.n_docs))
+        return pieces, int(data.size), (data, off)
+    # documents per generation batch sized from the recipe's mean length (about 6 bytes a word)
+    mean_words = recipe.len_median * 2.0
+    docs_per = max(1000, int(stream_chunk / (mean_words * 6.5)))
+    d0 = 0
+    while d0 < recipe.n_docs:
+        d1 = min(recipe.n_docs, d0 + docs_per)
+        data, off = gen.generate(d0, d1)
+        while data.size > stream_chunk and d1 - d0 > 1:      # keep each piece within the chunk size
+            d1 = d0 + (d1 - d0) * 3 // 4
+            data, off = gen.generate(d0, d1)
+        if first_host is None:
+            first_host = (data, off)
+        pieces.append((torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(), d0, d1))
+        total += int(data.size)
+        d0 = d1
+    return pieces, total, first_host
+
+
+def jaccard_of_pair(oracle, a: bytes, b: bytes, n: int, byte_mode: bool) -> float:
+    sa = set(oracle.doc_shingles(a, n, byte_mode).tolist())
+    sb = set(oracle.doc_shingles(b, n, byte_mode).tolist())
+    if not sa and not sb:
+        return 1.0
+    return len(sa & sb) / len(sa | sb)
 
 
 def main() -> int:
@@ -37,6 +93,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--docs", type=int, default=0, help="override the document count")
     ap.add_argument("--config", type=int, default=2, help="workload number 1..5")
+    ap.add_argument("--K", type=int, default=0)
+    ap.add_argument("--b", type=int, default=0)
+    ap.add_argument("--r", type=int, default=0)
+    ap.add_argument("--shingle-n", type=int, default=0)
+    ap.add_argument("--sweep", action="store_true", help="config 5 parameter grid")
     ap.add_argument("--cpu-sample-docs", type=int, default=20000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
@@ -59,59 +120,80 @@ def main() -> int:
     sedd.lib()
 
     recipe = corpus.config(args.config)
-    if args.docs:
-        recipe = recipe.scaled(args.docs)
+    over = {}
+    if args.K:
+        over["K"] = args.K
+    if args.b:
+        over["b"] = args.b
+    if args.r:
+        over["r"] = args.r
+    if args.shingle_n:
+        over["shingle_n"] = args.shingle_n
+    recipe = recipe.scaled(args.docs or recipe.n_docs, **over)
     flags = sedd.FLAG_BYTE_SHINGLES if recipe.byte_mode else 0
+    streamed = args.config == 3
 
     t0 = time.time()
-    data, off = corpus.generate(recipe)
+    pieces, n_bytes, (h_data, h_off) = load_corpus(torch, corpus, recipe,
+                                                   STREAM_CHUNK_BYTES if streamed else None)
     t_gen = time.time() - t0
-    n_docs, n_bytes = recipe.n_docs, int(data.size)
-    d_data = torch.from_numpy(data).cuda()
-    d_off = torch.from_numpy(off).cuda()
-    sig = torch.empty((n_docs, recipe.K), dtype=torch.uint32, device="cuda")
-    keys = torch.empty((n_docs, recipe.b), dtype=torch.uint64, device="cuda")
-    cid = torch.empty((n_docs,), dtype=torch.int64, device="cuda")
+    n_docs = recipe.n_docs
 
-    def step():
-        sedd.sedd_minhash(d_data, d_off, recipe.shingle_n, recipe.K, 0, flags, out=sig)
-        sedd.sedd_lsh_keys(sig, recipe.b, recipe.r, out=keys)
+    def run_path(K, b, r, n, sig, keys, cid):
+        for text, off, d0, d1 in pieces:
+            sedd.sedd_minhash(text, off, n, K, 0, flags, out=sig[d0:d1])
+        sedd.sedd_lsh_keys(sig, b, r, out=keys)
         sedd.sedd_cluster(keys, out=cid)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    def measure(K, b, r, n, steps, warmup):
+        sig = torch.empty((n_docs, K), dtype=torch.uint32, device="cuda")
+        keys = torch.empty((n_docs, b), dtype=torch.uint64, device="cuda")
+        cid = torch.empty((n_docs,), dtype=torch.int64, device="cuda")
+        for _ in range(warmup):
+            run_path(K, b, r, n, sig, keys, cid)
+        torch.cuda.synchronize()
+        sedd.profile_enable(True)
+        sedd.profile_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run_path(K, b, r, n, sig, keys, cid)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        sedd.profile_enable(False)
+        return elapsed, sedd.profile_read(), sig, keys, cid
 
-    sedd.profile_enable(True)
-    sedd.profile_read()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    sedd.profile_enable(False)
-    stages = sedd.profile_read()
+    def shingle_count(n):
+        tot = 0
+        for text, off, d0, d1 in pieces:
+            _, soff = sedd.debug_shingle_hashes_offsets(text, off, n, flags)
+            tot += int(soff[-1])
+        return tot
 
+    if args.sweep:
+        return sweep(args, recipe, pieces, measure, shingle_count, sedd, corpus, np, torch,
+                     n_docs, n_bytes, flags)
+
+    K, b, r, n = recipe.K, recipe.b, recipe.r, recipe.shingle_n
+    elapsed, stages, sig, keys, cid = measure(K, b, r, n, args.steps, args.warmup)
     ms_per_step = 1e3 * elapsed / args.steps
     docs_per_s = n_docs * args.steps / elapsed
     text_gbps = n_bytes * args.steps / elapsed / 1e9
 
-    # shingle count of the corpus (outside the timed region)
-    _, soff = sedd.debug_shingle_hashes(d_data, d_off, recipe.shingle_n, flags)
-    n_shingles = int(soff.cpu().numpy()[-1])
+    n_shingles = shingle_count(n)          # outside the timed region
     mh_ms, mh_spans = stages["minhash"]
-    pairs_per_step = n_shingles * recipe.K
+    ops_per_step = n_shingles * ops_per_shingle(recipe, K)
     launches_per_step = max(1, mh_spans // max(1, args.steps))
     avg_launch_ms = mh_ms / max(1, mh_spans)
-    achieved = pairs_per_step * args.steps * OPS_PER_PAIR / (mh_ms * 1e-3) / 1e12 if mh_ms else 0.0
+    achieved = ops_per_step * args.steps / (mh_ms * 1e-3) / 1e12 if mh_ms else 0.0
     roofline = {
         "kernel": "k_minhash", "bound": "alu", "achieved": round(achieved, 3),
         "peak": round(PEAK_TOPS, 3), "unit": "TOP/s (int32 VALU lane-ops)",
         "frac": round(achieved / PEAK_TOPS, 4), "traffic": None,
-        "ops_per_hash_eval": OPS_PER_PAIR, "hash_evals_per_step": pairs_per_step,
+        "ops_per_shingle": ops_per_shingle(recipe, K), "shingles_per_step": n_shingles,
+        "ops_per_launch": ops_per_step // launches_per_step,
         "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_launch_ms, 4),
-        "hash_evals_per_s": round(pairs_per_step * args.steps / (mh_ms * 1e-3), 1) if mh_ms else 0,
+        "hash_evals_per_s": round(n_shingles * K * args.steps / (mh_ms * 1e-3), 1) if mh_ms else 0,
     }
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
 
@@ -119,12 +201,12 @@ def main() -> int:
     parity = None
     if not args.no_cpu_baseline:
         import oracle
-        ns = min(args.cpu_sample_docs, n_docs)
-        sub_off = off[: ns + 1]
-        sub = data[: int(sub_off[-1])]
+        ns = min(args.cpu_sample_docs, h_off.size - 1)
+        sub_off = h_off[: ns + 1]
+        sub = h_data[: int(sub_off[-1])]
         t0 = time.perf_counter()
-        o_sig = oracle.minhash(sub, sub_off, recipe.shingle_n, recipe.K, 0, flags)
-        o_keys = oracle.lsh_keys(o_sig, recipe.b, recipe.r)
+        o_sig = oracle.minhash(sub, sub_off, n, K, 0, flags)
+        o_keys = oracle.lsh_keys(o_sig, b, r)
         oracle.cluster(o_keys)
         t_cpu = time.perf_counter() - t0
         cpu_baseline = {
@@ -144,9 +226,9 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "u64 (61-bit modular) / u32",
         "data": "synthetic",
         "config": {"workload": recipe.name, "n_docs": n_docs, "text_bytes": n_bytes,
-                   "shingles": n_shingles, "shingle_n": recipe.shingle_n,
-                   "byte_shingles": bool(recipe.byte_mode), "K": recipe.K, "b": recipe.b,
-                   "r": recipe.r, "corpus_seed": recipe.seed, "hash_seed": 0},
+                   "shingles": n_shingles, "shingle_n": n, "byte_shingles": bool(recipe.byte_mode),
+                   "K": K, "b": b, "r": r, "corpus_seed": recipe.seed, "hash_seed": 0,
+                   "minhash_calls_per_step": len(pieces)},
         "text_GB_per_s": round(text_gbps, 3),
         "stage_ms_per_step": stage_ms,
         "duplicates_found": int((cid.cpu().numpy() != np.arange(n_docs)).sum()),
@@ -158,6 +240,75 @@ def main() -> int:
         "parity_sample_ok": parity,
     }
     print(json.dumps(out))
+    return 0
+
+
+def sweep(args, recipe, pieces, measure, shingle_count, sedd, corpus, np, torch, n_docs, n_bytes,
+          flags):
+    """Config 5: K x (b, r) x shingle length grid; throughput and the S-curve fit per setting."""
+    import oracle
+    gen = corpus.Corpus(recipe)
+    text, off, _, _ = pieces[0]
+    h_off = off.cpu().numpy()
+    # planted pairs: near-duplicates and their sources, exact Jaccard from brute-force shingle sets
+    rng = np.random.default_rng(0)
+    cand = rng.choice(n_docs, size=min(n_docs, 60000), replace=False)
+    pairs = []
+    for dnum in cand:
+        kind, src, _ = gen.meta(int(dnum))
+        if kind == 1:
+            pairs.append((int(dnum), int(src)))
+        if len(pairs) >= 3000:
+            break
+    h_text = text.cpu().numpy()
+
+    def doc(i):
+        return h_text[int(h_off[i]):int(h_off[i + 1])].tobytes()
+
+    results = []
+    for n in (3, 5):
+        J = np.array([jaccard_of_pair(oracle, doc(a), doc(b_), n, recipe.byte_mode)
+                      for a, b_ in pairs])
+        n_sh = shingle_count(n)
+        for K in (64, 128, 256, 512):
+            sig_time = None
+            for (b, r) in ((8, 16), (16, 8), (32, 8), (64, 4)):
+                if b * r > K:
+                    results.append({"n": n, "K": K, "b": b, "r": r, "skipped": "b*r > K"})
+                    continue
+                elapsed, stages, sig, keys, cid = measure(K, b, r, n, args.steps, 1)
+                k_host = keys.cpu().numpy()
+                ia = np.array([p[0] for p in pairs])
+                ib = np.array([p[1] for p in pairs])
+                hit = (k_host[ia] == k_host[ib]).any(axis=1)
+                # binned recall against 1-(1-s^r)^b
+                bins = np.linspace(0.0, 1.0, 11)
+                dev2, used = 0.0, 0
+                for lo, hi in zip(bins[:-1], bins[1:]):
+                    msk = (J >= lo) & (J < hi if hi < 1.0 else J <= hi)
+                    if msk.sum() >= 30:
+                        want = (1 - (1 - J[msk] ** r) ** b).mean()
+                        dev2 += (hit[msk].mean() - want) ** 2
+                        used += 1
+                mh_ms = stages["minhash"][0] / args.steps
+                results.append({
+                    "n": n, "K": K, "b": b, "r": r,
+                    "docs_per_s": round(n_docs * args.steps / elapsed, 1),
+                    "text_GB_per_s": round(n_bytes * args.steps / elapsed / 1e9, 3),
+                    "minhash_ms": round(mh_ms, 3),
+                    "minhash_frac_of_alu_peak": round(
+                        n_sh * ops_per_shingle(recipe.scaled(n_docs, shingle_n=n), K)
+                        / (mh_ms * 1e-3) / 1e12 / PEAK_TOPS, 4),
+                    "keys_cluster_ms": round((stages["lsh_keys"][0] + stages["sort"][0]
+                                              + stages["union_find"][0]) / args.steps, 3),
+                    "scurve_rms": round(float(np.sqrt(dev2 / max(1, used))), 4),
+                    "scurve_bins": used, "planted_pairs": len(pairs),
+                    "duplicates_found": int((cid.cpu().numpy() != np.arange(n_docs)).sum()),
+                })
+                del sig, keys, cid
+    print(json.dumps({"metric": "config 5 parameter sweep", "workload": recipe.name,
+                      "n_docs": n_docs, "text_bytes": n_bytes, "steps": args.steps,
+                      "results": results}))
     return 0
 
 

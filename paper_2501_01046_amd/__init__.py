@@ -19,6 +19,7 @@ __all__ = [
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
+    "debug_shingle_hashes_offsets",
     "FLAG_BYTE_SHINGLES",
 ]
 
@@ -204,6 +205,19 @@ def debug_shingle_hashes(text, doc_offsets, shingle_n: int, flags: int = 0, stre
                                        _ptr(x), total, _ptr(soff), _stream(stream)),
            "sedd_debug_shingle_hashes")
     return x, soff
+
+
+def debug_shingle_hashes_offsets(text, doc_offsets, shingle_n: int, flags: int = 0, stream=None):
+    """(None, shingle_offsets as a host numpy array): the counting half of debug_shingle_hashes."""
+    torch = _torch()
+    text = _dev(text, torch.uint8, "text")
+    doc_offsets = _dev(doc_offsets, torch.uint64, "doc_offsets")
+    n_docs = max(0, doc_offsets.numel() - 1)
+    soff = torch.zeros(n_docs + 1, dtype=torch.uint64, device=text.device)
+    _check(lib().sedd_debug_shingle_hashes(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, flags,
+                                           None, 0, _ptr(soff), _stream(stream)),
+           "sedd_debug_shingle_hashes")
+    return None, soff.cpu().numpy()
 
 
 def debug_coeffs(seed: int, K: int, stream=None):

@@ -133,41 +133,52 @@ struct HTile {       // tile of up to TS shingles of one document
   uint32_t pad[2];
 };
 
+// document owning tile t: the d with tbase[d] <= t < tbase[d+1] (documents without tiles repeat
+// their neighbour's base and are skipped by the search)
+__device__ __forceinline__ uint32_t tile_owner(const uint32_t *__restrict__ tbase, uint32_t nd,
+                                               uint32_t t) {
+  uint32_t lo = 0, hi = nd;  // invariant: tbase[lo] <= t < tbase[hi]
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (tbase[mid] <= t) lo = mid;
+    else hi = mid;
+  }
+  return lo;
+}
+
+// one thread per tile (a document can own thousands of tiles)
 __global__ void k_fill_btiles(const uint32_t *__restrict__ dv, const uint32_t *__restrict__ tbase,
-                              uint32_t nd, BTile *__restrict__ tiles) {
-  uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
-  if (d >= nd) return;
-  const uint32_t t0 = tbase[d], t1 = tbase[d + 1];
+                              uint32_t nd, uint32_t n_slots, BTile *__restrict__ tiles) {
+  const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_slots || t >= tbase[nd]) return;
+  const uint32_t d = tile_owner(tbase, nd, t);
   BTile bt;
   bt.vs = dv[d];
   bt.ve = dv[d + 1];
+  bt.tile0 = (bt.vs & ~15u) + (t - tbase[d]) * TB;
   bt.pad = 0;
-  for (uint32_t t = t0; t < t1; t++) {
-    bt.tile0 = (bt.vs & ~15u) + (t - t0) * TB;
-    tiles[t] = bt;
-  }
+  tiles[t] = bt;
 }
 
 __global__ void k_fill_htiles(const uint32_t *__restrict__ sbase, const uint32_t *__restrict__ tbase,
                               const uint32_t *__restrict__ docw, uint32_t nd, uint32_t n,
-                              HTile *__restrict__ tiles) {
-  uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
-  if (d >= nd) return;
+                              uint32_t n_slots, HTile *__restrict__ tiles) {
+  const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_slots || t >= tbase[nd]) return;
+  const uint32_t d = tile_owner(tbase, nd, t);
   const uint32_t t0 = tbase[d], t1 = tbase[d + 1];
   const uint32_t s0 = sbase[d], S = sbase[d + 1] - s0;
+  const uint32_t i0 = (t - t0) * TS;
+  const uint32_t w0 = docw ? docw[d] : 0u;
   HTile ht;
   ht.doc = d;
+  ht.x_off = s0 + i0;
+  ht.cnt = min(TS, S - i0);
   ht.single = (t1 - t0 == 1) ? 1u : 0u;
-  ht.pad[0] = ht.pad[1] = 0;
-  const uint32_t w0 = docw ? docw[d] : 0u;
+  ht.tok0 = w0 + i0;
   ht.per = docw ? min(n, docw[d + 1] - w0) : 0u;
-  for (uint32_t t = t0; t < t1; t++) {
-    const uint32_t i0 = (t - t0) * TS;
-    ht.x_off = s0 + i0;
-    ht.cnt = min(TS, S - i0);
-    ht.tok0 = w0 + i0;
-    tiles[t] = ht;
-  }
+  ht.pad[0] = ht.pad[1] = 0;
+  tiles[t] = ht;
 }
 
 // ---- tokenisation ------------------------------------------------------------------------
@@ -724,7 +735,8 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       if (!byte_mode) {
         rc = scan_exclusive_u32(btb, btb, (uint64_t)nd + 1, tmp, st);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_fill_btiles, dim3(gdoc), dim3(256), 0, st, dv, btb, nd, btd);
+        hipLaunchKernelGGL(k_fill_btiles, dim3((uint32_t)((nbt + 255) / 256)), dim3(256), 0, st, dv,
+                           btb, nd, (uint32_t)nbt, btd);
         SEDD_LAUNCH_CHECK();
       }
     }
@@ -748,8 +760,9 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       if (rc) return rc;
       rc = scan_exclusive_u32(htb, htb, (uint64_t)nd + 1, tmp, st);
       if (rc) return rc;
-      hipLaunchKernelGGL(k_fill_htiles, dim3(gdoc), dim3(256), 0, st, sbase, htb,
-                         byte_mode ? (const uint32_t *)nullptr : docw, nd, (uint32_t)n, htd);
+      hipLaunchKernelGGL(k_fill_htiles, dim3((uint32_t)((nht + 255) / 256)), dim3(256), 0, st, sbase,
+                         htb, byte_mode ? (const uint32_t *)nullptr : docw, nd, (uint32_t)n,
+                         (uint32_t)nht, htd);
       SEDD_LAUNCH_CHECK();
     }
     xsrc.pbase = pbase;
@@ -853,8 +866,8 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   SEDD_LAUNCH_CHECK();
   rc = scan_exclusive_u32(htb, htb, n_docs + 1, tmp, st);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_fill_htiles, dim3((nd + 255) / 256), dim3(256), 0, st, sbase, htb,
-                     (const uint32_t *)nullptr, nd, 0u, htd);
+  hipLaunchKernelGGL(k_fill_htiles, dim3((uint32_t)((nht + 255) / 256)), dim3(256), 0, st, sbase,
+                     htb, (const uint32_t *)nullptr, nd, 0u, (uint32_t)nht, htd);
   SEDD_LAUNCH_CHECK();
   XSource xsrc = {};
   xsrc.given = x;  // tiles index it by shingle offset

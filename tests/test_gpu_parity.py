@@ -358,3 +358,32 @@ def test_config4_shape_small(sedd):
 def test_config5_sweep_points_small(sedd, K, b, r, n):
     say("config 5 point", K, b, r, n)
     _full_path(sedd, corpus.config(5).scaled(1500, K=K, b=b, r=r, shingle_n=n), NPROC)
+
+
+# ---- full-size workload, in the launch configuration bench.py times -------------------------
+
+def test_config2_full_size_whole_path(sedd):
+    """1M documents, 2.6 GB of text: every signature, band key and cluster id against the
+    oracle (run as NPROC processes over disjoint document ranges)."""
+    say("config 2 at full size: generating")
+    r = corpus.config(2)
+    data, off = corpus.generate(r)
+    say("config 2: oracle on", NPROC, "processes")
+    wsig = oracle.minhash_sharded(data, off, r.shingle_n, r.K, 0, 0, procs=NPROC)
+    wkeys = oracle.lsh_keys(wsig, r.b, r.r)
+    wcid = oracle.cluster(wkeys)
+    say("config 2: GPU")
+    d_data, d_off = dev(data), dev(off)
+    sig = sedd.sedd_minhash(d_data, d_off, r.shingle_n, r.K, 0, 0)
+    keys = sedd.sedd_lsh_keys(sig, r.b, r.r)
+    cid = sedd.sedd_cluster(keys)
+    bad = np.nonzero((host(sig) != wsig).any(axis=1))[0]
+    assert bad.size == 0, f"{bad.size} signatures differ, first {bad[:5]}"
+    assert np.array_equal(host(keys), wkeys)
+    assert np.array_equal(host(cid), wcid)
+    # second call on the same buffers: identical bytes (scratch reuse, atomics, exact path)
+    sig2 = sedd.sedd_minhash(d_data, d_off, r.shingle_n, r.K, 0, 0)
+    assert torch.equal(sig.view(torch.int32), sig2.view(torch.int32))
+    dups = int((wcid != np.arange(wcid.size)).sum())
+    say("config 2: duplicates found", dups)
+    assert 20_000 <= dups <= 150_000
