@@ -480,7 +480,44 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   if (t >= *n_tiles) return;
   const uint32_t d = ht.doc, cnt = ht.cnt;
 
-  for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
+  if (MODE == X_WORDS) {
+    // Straight-line evaluation for tokens shorter than LONG_TOKEN bytes (table powers, lazily
+    // reduced accumulator); a lane that meets a longer token redoes its shingle the general way.
+    const TokenRecs &rec = xsrc.rec;
+    const uint64_t *__restrict__ qpow = xsrc.qpow;
+    const uint32_t per = ht.per;
+    for (uint32_t i = threadIdx.x; i < cnt; i += 64) {
+      const uint32_t first = ht.tok0 + i, last = first + per - 1;
+      const uint32_t l_last = rec.len[last];
+      bool long_tok = l_last == LONG_TOKEN;
+      const uint64_t pw = qpow[l_last];
+      const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
+      const uint64_t v_last = rec.v[last];
+      uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;  // W of the last token
+      for (uint32_t m = last; m-- > first;) {
+        const uint32_t lm = rec.len[m];
+        long_tok |= lm == LONG_TOKEN;
+        const uint64_t Pm = qpow[lm + 1];  // lm + 1 <= 255 stays inside the table
+        const uint64_t V = rec.v[m];
+        // acc <- Pm * acc + V (mod p), acc kept below 2^61 + 8 rather than canonical
+        const uint32_t p_lo = (uint32_t)Pm, a0 = p_lo & 0x7FFFFFFFu, a0_2 = p_lo << 1;
+        const uint32_t a12 = (uint32_t)(Pm >> 31) << 1;
+        const uint32_t c_lo = (uint32_t)acc, x0 = c_lo & 0x7FFFFFFFu, x0_2 = c_lo << 1;
+        const uint32_t x1 = (uint32_t)(acc >> 31), x1_2 = x1 << 1;
+        uint64_t N = (uint64_t)a0_2 * x1_2;
+        N += (uint64_t)a12 * x0_2;
+        uint64_t U = (uint64_t)a12 * x1 + V;
+        U += (uint64_t)a0 * x0;
+        const uint64_t Z = (uint64_t)(uint32_t)N * hc.two29 + U + (N >> 32);
+        acc = (Z & P61) + (Z >> 61);
+      }
+      acc = fold61(acc);
+      if (long_tok) acc = shingle_x<MODE>(xsrc, ht, i);
+      sx[i] = x_limbs(acc);
+    }
+  } else {
+    for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
+  }
 
   const int kbase = blockIdx.y * (64 * F) + threadIdx.x;
   uint64_t a[F], b[F];
