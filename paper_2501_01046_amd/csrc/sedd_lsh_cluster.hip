@@ -23,10 +23,16 @@ k_lsh_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int 
 
 // ---- radix sort of (key, doc) per band ---------------------------------------------------
 //
-// Records of band j live in [j*n, (j+1)*n) of band-major arrays.  Eight stable passes over
-// 8-bit digits (61-bit keys).  Per pass: per-block digit histograms, one exclusive scan over
-// [band][digit][block] (every band holds exactly n records, so the scan of the whole array
-// already yields band-major positions), then a stable scatter.
+// Records of band j live in [j*n, (j+1)*n) of band-major arrays.  Stable passes over 8-bit
+// digits of the low `key_bits` bits of the key.  Per pass: per-block digit histograms, one
+// exclusive scan over [band][digit][block] (every band holds exactly n records, so the scan of
+// the whole array already yields band-major positions), then a stable scatter.
+//
+// Grouping does not need a full sort.  Band keys are residues of a polynomial hash, so their low
+// bits are uniform: sorting by the low B bits with 2^B >= 16 n leaves, on average, less than 1/16
+// foreign record inside a group of records that agree in those bits.  sedd_cluster therefore
+// sorts by B = 24 or 32 bits (3 or 4 passes instead of 8) and the linking kernel walks back over
+// the records that share the low B bits until it meets one with the same full key.
 
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_ITEMS = 16;
@@ -153,15 +159,24 @@ __global__ void k_iota_u32(uint32_t *p, uint32_t n) {
   if (i < n) p[i] = i;
 }
 
-// neighbours in sorted order with equal keys are in the same bucket of that band
+// Records sorted by the low bits selected by `mask`: every record is linked to the nearest
+// earlier record of its band with the same full key; the walk stops at the first record that
+// differs in the sorted bits.  (With a full sort the walk is one step.)
 __global__ void __launch_bounds__(256)
 k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
-            uint32_t b, uint32_t *parent) {
+            uint32_t b, uint64_t mask, uint32_t *parent) {
   uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (uint64_t)n * b) return;
-  uint32_t i = (uint32_t)(idx % n);
-  if (i == 0) return;
-  if (bk[idx] == bk[idx - 1]) uf_unite(parent, bd[idx - 1], bd[idx]);
+  const uint32_t i = (uint32_t)(idx % n);
+  const uint64_t key = bk[idx];
+  for (uint32_t back = 1; back <= i; back++) {
+    const uint64_t other = bk[idx - back];
+    if ((other ^ key) & mask) break;
+    if (other == key) {
+      uf_unite(parent, bd[idx - back], bd[idx]);
+      break;
+    }
+  }
 }
 
 __global__ void k_write_roots(uint32_t *parent, uint32_t n, int64_t *__restrict__ cluster_id) {
@@ -208,8 +223,17 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
   return SEDD_OK;
 }
 
-// leaves the sorted records in sb->ka / sb->da
-static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, SortBufs *sb,
+// number of low key bits sedd_cluster sorts by: a multiple of 16 (an even number of passes, so
+// the result lands in the first buffer) with 2^bits >= 16 n where that is possible
+static int grouping_bits(uint64_t n_docs) {
+  int bits = 16;
+  while (bits < 48 && (uint64_t(1) << bits) < 16 * n_docs) bits += 16;
+  return bits;
+}
+
+// leaves the records, sorted by the low key_bits bits (a multiple of 16, or KEY_BITS for a full
+// sort), in sb->ka / sb->da
+static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key_bits, SortBufs *sb,
                       hipStream_t st) {
   const uint32_t n = (uint32_t)n_docs;
   hipLaunchKernelGGL(k_to_band_major, dim3((n + 255) / 256), dim3(256), 0, st, keys, n, b, sb->ka,
@@ -219,7 +243,7 @@ static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, SortBuf
   uint64_t *src_k = sb->ka, *dst_k = sb->kb;
   uint32_t *src_d = sb->da, *dst_d = sb->db;
   static_assert(((KEY_BITS + RADIX_BITS - 1) / RADIX_BITS) % 2 == 0, "even pass count");
-  for (int shift = 0; shift < KEY_BITS; shift += RADIX_BITS) {
+  for (int shift = 0; shift < key_bits; shift += RADIX_BITS) {
     dim3 grid(sb->nblk, b);
     hipLaunchKernelGGL(k_radix_hist, grid, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
                        sb->hist);
@@ -272,9 +296,10 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
+  const int bits = grouping_bits(n_docs);
   {
     ProfScope prof(SEDD_PROF_SORT, st);
-    rc = sort_bands(keys, n_docs, (uint32_t)b, &sb, st);
+    rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
     if (rc) return rc;
   }
   ProfScope prof(SEDD_PROF_UNION, st);
@@ -283,7 +308,7 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   SEDD_LAUNCH_CHECK();
   const uint64_t total = n_docs * (uint64_t)b;
   hipLaunchKernelGGL(k_link_runs, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,
-                     sb.da, n, (uint32_t)b, sb.parent);
+                     sb.da, n, (uint32_t)b, (uint64_t(1) << bits) - 1, sb.parent);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
                      cluster_id);
@@ -300,7 +325,7 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
-  rc = sort_bands(keys, n_docs, (uint32_t)b, &sb, st);
+  rc = sort_bands(keys, n_docs, (uint32_t)b, KEY_BITS, &sb, st);
   if (rc) return rc;
   const uint64_t total = n_docs * (uint64_t)b;
   hipLaunchKernelGGL(k_copy_sorted, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,

@@ -301,6 +301,23 @@ def test_cluster_random_keys(sedd, n, b, span, seed):
     assert np.array_equal(got, oracle.cluster(keys))
 
 
+@pytest.mark.parametrize("n,b", [(3000, 3), (70_000, 2)])
+def test_cluster_keys_that_agree_in_their_low_bits(sedd, n, b):
+    """Few distinct low words, several high words: records with different keys interleave
+    inside every group of equal low bits, which is what the grouping sort leaves to the linker."""
+    say("cluster low-bit collisions", n, b)
+    rng = np.random.default_rng(n)
+    lo = rng.integers(0, 40, size=(n, b), dtype=np.uint64)
+    hi = rng.integers(0, 6, size=(n, b), dtype=np.uint64)
+    keys = (hi << np.uint64(45)) | (lo << np.uint64(3)) | (hi & np.uint64(1))
+    assert np.array_equal(host(sedd.sedd_cluster(dev(keys))), oracle.cluster(keys))
+    # and spread out so that most keys are singletons but some collide only in the low 32 bits
+    base = rng.integers(0, 1 << 32, size=(n, b), dtype=np.uint64)
+    keys = base | (rng.integers(0, 3, size=(n, b), dtype=np.uint64) << np.uint64(50))
+    keys[n // 2:] = keys[: n - n // 2] ^ (rng.integers(0, 2, size=(n - n // 2, b), dtype=np.uint64) << np.uint64(50))
+    assert np.array_equal(host(sedd.sedd_cluster(dev(keys))), oracle.cluster(keys))
+
+
 def test_cluster_long_chain_across_bands(sedd):
     say("cluster chain")
     # doc i shares band (i % 2) with doc i+1: one component threaded through two bands
