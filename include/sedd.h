@@ -11,9 +11,9 @@
  *     by the work the call enqueues.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue their kernels on it and return; results are ready when the
- *     stream has drained.  sedd_minhash additionally copies `doc_offsets` to
- *     the host and waits for that copy before it enqueues anything, because
- *     the host validates the offsets and plans bounded-size chunks from them.
+ *     stream has drained.  sedd_minhash first validates `doc_offsets` and plans
+ *     bounded-size chunks with two small kernels and waits (twice) for a few
+ *     numbers from them; everything after that is enqueued without host waits.
  *   - Return value: SEDD_OK (0) or a negative error code.  On SEDD_EINVAL
  *     nothing is written and no device work is enqueued.  `n_docs == 0` is a
  *     successful no-op that touches nothing.
@@ -67,7 +67,7 @@ extern "C" {
  * doc_offsets  device, uint64[n_docs+1], non-decreasing byte offsets into `bytes`.
  * shingle_n    1..SEDD_MAX_SHINGLE_N.   K  1..SEDD_MAX_K.
  * sig          device, uint32[n_docs*K], document-major; fully overwritten.
- * A single document must be smaller than 2^32 - 2^20 bytes; n_docs < 2^31.
+ * A single document must be smaller than 2^32 - 2^29 bytes; n_docs < 2^31.
  */
 int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
                  int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,

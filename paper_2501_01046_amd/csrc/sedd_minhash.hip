@@ -641,10 +641,61 @@ __global__ void k_from_x_prepare(const uint64_t *__restrict__ soff, uint32_t nd,
   hcnt[i] = i < nd ? (uint32_t)((soff[i + 1] - soff[i] + TS - 1) / TS) : 0u;
 }
 
+// ---- chunk planning on the device ------------------------------------------------------------
+//
+// The host never reads the offsets array: two tiny kernels give it the first and last offset,
+// a validity flag, and the chunk boundaries (document index and byte offset at every multiple of
+// the chunk size in bytes and of the chunk size in documents).
+
+struct PlanEntry {
+  uint64_t doc;
+  uint64_t off;
+};
+
+__global__ void k_plan_probe(const uint64_t *__restrict__ off, uint64_t n, uint64_t *__restrict__ out) {
+  out[0] = off[0];
+  out[1] = off[n];
+}
+
+// entries [0, n_byte): first document whose offset is >= first + k * chunk_bytes;
+// entries [n_byte, n_byte + n_cnt): document (j + 1) * chunk_docs
+__global__ void k_plan(const uint64_t *__restrict__ off, uint64_t n, uint64_t first,
+                       uint64_t chunk_bytes, uint64_t n_byte, uint64_t chunk_docs, uint64_t n_cnt,
+                       PlanEntry *__restrict__ out) {
+  const uint64_t k = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= n_byte + n_cnt) return;
+  uint64_t d;
+  if (k < n_byte) {
+    const uint64_t target = first + k * chunk_bytes;
+    uint64_t lo = 0, hi = n;  // smallest d in [0, n] with off[d] >= target (n if none)
+    while (lo < hi) {
+      const uint64_t mid = (lo + hi) >> 1;
+      if (off[mid] >= target) hi = mid;
+      else lo = mid + 1;
+    }
+    d = lo;
+  } else {
+    d = (k - n_byte + 1) * chunk_docs;
+  }
+  out[k].doc = d;
+  out[k].off = off[d];
+}
+
+__global__ void k_validate_offsets(const uint64_t *__restrict__ off, uint64_t n, uint64_t max_doc,
+                                   uint32_t *__restrict__ bad) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint64_t a = off[i], b = off[i + 1];
+  if (b < a || b - a >= max_doc) atomicOr(bad, 1u);
+}
+
+__global__ void k_zero_u32(uint32_t *p) { *p = 0; }
+
 // ---- host driver ---------------------------------------------------------------------------
 
 struct Chunk {
-  uint64_t d0, d1;
+  uint64_t d0, d1;  // documents [d0, d1)
+  uint64_t o0, o1;  // their byte range
 };
 
 static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
@@ -653,33 +704,71 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const bool debug = dbg_off != nullptr;
   const int byte_mode = (flags & SEDD_FLAG_BYTE_SHINGLES) ? 1 : 0;
 
-  // host copy of the offsets: validation and chunk planning
-  void *pin = nullptr;
-  int rc = pinned_ensure((n_docs + 1) * 8, &pin);
-  if (rc) return rc;
-  uint64_t *off = (uint64_t *)pin;
-  SEDD_HIP(hipMemcpyAsync(off, doc_offsets, (n_docs + 1) * 8, hipMemcpyDeviceToHost, st));
-  SEDD_HIP(hipStreamSynchronize(st));
-  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 20);
-  for (uint64_t d = 0; d < n_docs; d++) {
-    if (off[d + 1] < off[d]) return SEDD_EINVAL;
-    if (off[d + 1] - off[d] >= max_doc) return SEDD_EINVAL;
-  }
-  if (off[n_docs] > off[0] && !bytes) return SEDD_EINVAL;
-
-  const uint64_t chunk_bytes = g_chunk_bytes_override
-                                   ? g_chunk_bytes_override
-                                   : (byte_mode ? (uint64_t(128) << 20) : (uint64_t(256) << 20));
+  // validation and chunk planning on the device; the host sees a handful of numbers
+  const uint64_t chunk_bytes =
+      g_chunk_bytes_override ? std::min<uint64_t>(g_chunk_bytes_override, uint64_t(1) << 28)
+                             : (byte_mode ? (uint64_t(128) << 20) : (uint64_t(256) << 20));
   const uint64_t chunk_docs = uint64_t(1) << 22;
+  // chunk positions are 32-bit: a chunk is at most chunk_bytes (<= 2^28) plus one document
+  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 29);
+  const uint64_t plan_cap = uint64_t(1) << 20;  // boundaries per call
+  int rc;
+  uint64_t h_probe[2];
+  std::vector<PlanEntry> bnd;
+  {
+    void *pin = nullptr;
+    rc = pinned_ensure((plan_cap + 16) * sizeof(PlanEntry), &pin);
+    if (rc) return rc;
+    uint8_t *A0 = nullptr;
+    rc = scratch_ensure((plan_cap + 16) * sizeof(PlanEntry) + 512, &A0);
+    if (rc) return rc;
+    uint64_t *d_probe = (uint64_t *)A0;
+    uint32_t *d_bad = (uint32_t *)(A0 + 64);
+    PlanEntry *d_plan = (PlanEntry *)(A0 + 256);
+    hipLaunchKernelGGL(k_plan_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, d_probe);
+    SEDD_LAUNCH_CHECK();
+    SEDD_HIP(hipMemcpyAsync(pin, d_probe, 16, hipMemcpyDeviceToHost, st));
+    SEDD_HIP(hipStreamSynchronize(st));
+    h_probe[0] = ((uint64_t *)pin)[0];
+    h_probe[1] = ((uint64_t *)pin)[1];
+    if (h_probe[1] < h_probe[0]) return SEDD_EINVAL;
+    if (h_probe[1] > h_probe[0] && !bytes) return SEDD_EINVAL;
+    const uint64_t total = h_probe[1] - h_probe[0];
+    const uint64_t n_byte = total / chunk_bytes + 1, n_cnt = (n_docs - 1) / chunk_docs;
+    if (n_byte + n_cnt > plan_cap) return SEDD_EINVAL;
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(1), 0, st, d_bad);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
+                       doc_offsets, n_docs, max_doc, d_bad);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_plan, dim3((uint32_t)((n_byte + n_cnt + 255) / 256)), dim3(256), 0, st,
+                       doc_offsets, n_docs, h_probe[0], chunk_bytes, n_byte, chunk_docs, n_cnt,
+                       d_plan);
+    SEDD_LAUNCH_CHECK();
+    uint8_t *hp = (uint8_t *)pin;
+    SEDD_HIP(hipMemcpyAsync(hp, d_bad, 4, hipMemcpyDeviceToHost, st));
+    SEDD_HIP(hipMemcpyAsync(hp + 64, d_plan, (n_byte + n_cnt) * sizeof(PlanEntry),
+                            hipMemcpyDeviceToHost, st));
+    SEDD_HIP(hipStreamSynchronize(st));
+    if (*(uint32_t *)hp) return SEDD_EINVAL;
+    const PlanEntry *hpl = (const PlanEntry *)(hp + 64);
+    bnd.assign(hpl, hpl + n_byte + n_cnt);
+    bnd.push_back({n_docs, h_probe[1]});
+    std::sort(bnd.begin(), bnd.end(),
+              [](const PlanEntry &x, const PlanEntry &y) { return x.doc < y.doc; });
+  }
   std::vector<Chunk> chunks;
   uint64_t max_cv = 0, max_nd = 0;
-  for (uint64_t d0 = 0; d0 < n_docs;) {
-    uint64_t d1 = d0 + 1;
-    while (d1 < n_docs && d1 - d0 < chunk_docs && off[d1 + 1] - off[d0] <= chunk_bytes) d1++;
-    chunks.push_back({d0, d1});
-    max_cv = std::max(max_cv, off[d1] - off[d0] + 16);
-    max_nd = std::max(max_nd, d1 - d0);
-    d0 = d1;
+  {
+    uint64_t d0 = 0, o0 = h_probe[0];
+    for (const PlanEntry &e : bnd) {
+      if (e.doc <= d0) continue;
+      chunks.push_back({d0, e.doc, o0, e.off});
+      max_cv = std::max(max_cv, e.off - o0 + 16);
+      max_nd = std::max(max_nd, e.doc - d0);
+      d0 = e.doc;
+      o0 = e.off;
+    }
   }
 
   auto bounds = [&](uint64_t cv, uint64_t nd, uint64_t *nbt, uint64_t *nw, uint64_t *ns,
@@ -756,10 +845,10 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
 
   for (const Chunk &c : chunks) {
     const uint32_t nd = (uint32_t)(c.d1 - c.d0);
-    const uint64_t origin = (align + off[c.d0]) & ~uint64_t(15);
+    const uint64_t origin = (align + c.o0) & ~uint64_t(15);
     const uint64_t shift = align - origin;  // wraps; off[i] + shift is the aligned-frame position
     const uint8_t *pbase = bytes16 + origin;
-    const uint64_t cvb = off[c.d1] - off[c.d0] + 16;
+    const uint64_t cvb = c.o1 - c.o0 + 16;
     uint64_t nbt, nw, ns, nht;
     bounds(cvb, nd, &nbt, &nw, &ns, &nht);
     const uint64_t *coff = doc_offsets + c.d0;
