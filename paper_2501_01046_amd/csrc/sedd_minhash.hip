@@ -467,7 +467,7 @@ struct HotConsts {
   uint32_t eight;  // 8
 };
 
-template <int F, int MODE>
+template <int F, int P, int MODE>
 __global__ void __launch_bounds__(64)
 k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
           const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
@@ -519,12 +519,16 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
     for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
   }
 
-  const int kbase = blockIdx.y * (64 * F) + threadIdx.x;
+  // P = 2: the two half-waves take alternate shingles and each lane evaluates F functions of
+  // the 32*F this block covers (one LDS instruction then serves two shingles)
+  constexpr int LW = 64 / P;
+  const uint32_t grp = threadIdx.x / LW;
+  const int kbase = blockIdx.y * (LW * F) + (threadIdx.x % LW);
   uint64_t a[F], b[F];
   uint32_t a0[F], a12[F], m[F];
 #pragma unroll
   for (int j = 0; j < F; j++) {
-    int k = kbase + 64 * j;
+    int k = kbase + LW * j;
     const int kk = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
     a[j] = coef_a[kk];
     b[j] = coef_b[kk];
@@ -536,9 +540,7 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   __syncthreads();
 
   uint32_t amb = 0;
-#pragma unroll 4
-  for (uint32_t s = 0; s < cnt; s++) {
-    const XLimbs xv = sx[s];
+  auto eval = [&](const XLimbs &xv) {
 #pragma unroll
     for (int j = 0; j < F; j++) {
       uint64_t N = (uint64_t)a0[j] * xv.x1_4;
@@ -551,24 +553,33 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
       amb = max(amb, (uint32_t)W);
       m[j] = min(m[j], h);
     }
-  }
+  };
+  const XLimbs *sxg = sx + grp;  // this half-wave's first shingle
+  const uint32_t steps = cnt / P;
+#pragma unroll(F >= 4 ? 2 : 4)
+  for (uint32_t s = 0; s < steps; s++) eval(sxg[s * P]);
+  if (P == 2 && (cnt & 1)) eval(sx[cnt - 1]);  // both halves: a repeat cannot change a minimum
   if (__any(amb >= 0xFFFFFFF0u)) {
     // rare: some evaluation sat within reach of a carry across bit 61; redo the tile exactly
     if (threadIdx.x == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
 #pragma unroll
     for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
-    for (uint32_t s = 0; s < cnt; s++) {
+    for (uint32_t s = grp; s < cnt; s += P) {
       const XLimbs xv = sx[s];
       const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
 #pragma unroll
       for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)addmod(mulmod(a[j], x), b[j]));
     }
   }
+  if (P == 2) {
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)__shfl_xor(m[j], 32, 64));
+  }
   uint32_t *out = sig + (uint64_t)d * K;
 #pragma unroll
   for (int j = 0; j < F; j++) {
-    int k = kbase + 64 * j;
-    if (k < K) {
+    int k = kbase + LW * j;
+    if (grp == 0 && k < K) {
       if (ht.single) out[k] = m[j];
       else atomicMin(out + k, m[j]);
     }
@@ -609,19 +620,24 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   unsigned long long *stats = nullptr;
   int rc = stats_ensure(&stats);
   if (rc) return rc;
-  const int F = K <= 64 ? 1 : (K <= 128 ? 2 : 4);
-  const uint32_t ky = (uint32_t)((K + 64 * F - 1) / (64 * F));
+  // functions per lane F and half-wave split P: K <= 32: (1,2), <= 64: (2,2), <= 128: (4,2),
+  // larger: (4,1) with one grid row per 256 functions
+  const int P = K <= 128 ? 2 : 1;
+  const int F = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
+  const int per_block = (64 / P) * F;
+  const uint32_t ky = (uint32_t)((K + per_block - 1) / per_block);
   const HotConsts hc = {1u << 29, 8u};
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
-#define SEDD_LAUNCH_MH(FF, MM)                                                                  \
-  hipLaunchKernelGGL((k_minhash<FF, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, coef_a, \
-                     coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
-#define SEDD_LAUNCH_MH_F(MM)                  \
-  do {                                        \
-    if (F == 1) SEDD_LAUNCH_MH(1, MM);        \
-    else if (F == 2) SEDD_LAUNCH_MH(2, MM);   \
-    else SEDD_LAUNCH_MH(4, MM);               \
+#define SEDD_LAUNCH_MH(FF, PP, MM)                                                          \
+  hipLaunchKernelGGL((k_minhash<FF, PP, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
+                     coef_a, coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
+#define SEDD_LAUNCH_MH_F(MM)                       \
+  do {                                             \
+    if (P == 1) SEDD_LAUNCH_MH(4, 1, MM);          \
+    else if (F == 1) SEDD_LAUNCH_MH(1, 2, MM);     \
+    else if (F == 2) SEDD_LAUNCH_MH(2, 2, MM);     \
+    else SEDD_LAUNCH_MH(4, 2, MM);                 \
   } while (0)
   if (mode == X_WORDS) SEDD_LAUNCH_MH_F(X_WORDS);
   else if (mode == X_BYTES) SEDD_LAUNCH_MH_F(X_BYTES);
