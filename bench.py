@@ -38,6 +38,11 @@ OPS_PER_BASE_STEP_BYTE = 4
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one 32-bit integer lane-operation per lane per clock
 PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 STREAM_CHUNK_BYTES = 2 << 30
+# HBM bytes one k_minhash launch moves on the default workload (one 256 MB chunk), from the two
+# rocprofv3 --pmc runs summarised in profiles/hbm_traffic_cfg2_medium_1M.txt (FETCH_SIZE x 2 KiB
+# + WRITE_SIZE x 1 KiB, both scaled by a 1 GiB copy).  It is a recorded measurement, not
+# collected by this script; it only applies to the default workload.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH_CFG2 = 492.1e6
 
 
 def ops_per_shingle(recipe, K):
@@ -100,6 +105,9 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="config 5 parameter grid")
     ap.add_argument("--cpu-sample-docs", type=int, default=20000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference point for HBM "
+                         "byte counters collected with rocprofv3 --pmc)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -175,6 +183,13 @@ def main() -> int:
                      n_docs, n_bytes, flags)
 
     K, b, r, n = recipe.K, recipe.b, recipe.r, recipe.shingle_n
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     elapsed, stages, sig, keys, cid = measure(K, b, r, n, args.steps, args.warmup)
     ms_per_step = 1e3 * elapsed / args.steps
     docs_per_s = n_docs * args.steps / elapsed
@@ -189,7 +204,9 @@ def main() -> int:
     roofline = {
         "kernel": "k_minhash", "bound": "alu", "achieved": round(achieved, 3),
         "peak": round(PEAK_TOPS, 3), "unit": "TOP/s (int32 VALU lane-ops)",
-        "frac": round(achieved / PEAK_TOPS, 4), "traffic": None,
+        "frac": round(achieved / PEAK_TOPS, 4),
+        "traffic": (MEASURED_TRAFFIC_BYTES_PER_LAUNCH_CFG2
+                    if args.config == 2 and not args.docs and not over else None),
         "ops_per_shingle": ops_per_shingle(recipe, K), "shingles_per_step": n_shingles,
         "ops_per_launch": ops_per_step // launches_per_step,
         "launches_per_step": launches_per_step, "avg_launch_ms": round(avg_launch_ms, 4),
