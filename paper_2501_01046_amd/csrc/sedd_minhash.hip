@@ -55,6 +55,14 @@ struct TokenRecs {
 };
 constexpr uint32_t LONG_TOKEN = 255;
 
+// Per token length l < QPOW_N, what one Horner step over token records multiplies by:
+// P = 257^(l+1) as a0 = P mod 2^31, a0_2 = 2 a0, a12 = 2 (P >> 31); and nsp = p - 32 * 257^l,
+// which turns the hash of "token 0x20" into the hash of the bare token by one addition.
+struct PowSplit {
+  uint32_t a0, a0_2, a12, pad;
+  uint64_t nsp, pad2;
+};
+
 // 257^e with the first QPOW_N powers from a table (a few cache lines, shared by every lane)
 __device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpow, uint32_t e) {
   return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
@@ -83,7 +91,7 @@ __global__ void k_zero_u64(uint64_t *p) { *p = 0; }
 
 // a_k = s0 * Ga^(k+1), b_k = s0 * Gb^(k+1) (mod p), s0 = (seed mod (p-1)) + 1; qpow[i] = 257^i
 __global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, CoefSplit *split,
-                         uint64_t *qpow) {
+                         uint64_t *qpow, PowSplit *ptab) {
   int k = blockIdx.x * blockDim.x + threadIdx.x;
   uint64_t s0 = seed % (P61 - 1) + 1;
   if (k < K) {
@@ -97,7 +105,20 @@ __global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, CoefSpl
       split[k] = c;
     }
   }
-  if (qpow && k < QPOW_N) qpow[k] = powmod(257, (uint64_t)k);
+  if (qpow && k < QPOW_N) {
+    const uint64_t pw = powmod(257, (uint64_t)k);
+    qpow[k] = pw;
+    const uint64_t P = mul257(pw);
+    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^k (a rotation, never p)
+    PowSplit e;
+    e.a0 = (uint32_t)P & 0x7FFFFFFFu;
+    e.a0_2 = e.a0 << 1;
+    e.a12 = (uint32_t)(P >> 31) << 1;
+    e.pad = 0;
+    e.nsp = P61 - sp;
+    e.pad2 = 0;
+    ptab[k] = e;
+  }
 }
 
 // dv[i] = position of document i's first byte in the chunk's 16-byte aligned frame;
@@ -395,6 +416,7 @@ struct XSource {
   const uint32_t *sbase;  // shingle offsets per document (byte mode)
   TokenRecs rec;          // token records (word mode)
   const uint64_t *qpow;   // 257^i, i < QPOW_N
+  const PowSplit *ptab;   // Horner multipliers per token length, QPOW_N entries
   const uint64_t *given;  // caller-supplied hashes (debug entry), indexed like the shingle stream
   uint32_t n;             // shingle length
 };
@@ -465,7 +487,52 @@ __device__ __forceinline__ uint64_t shingle_x(const XSource &xsrc, const HTile &
 struct HotConsts {
   uint32_t two29;  // 1 << 29
   uint32_t eight;  // 8
+  uint32_t one;    // 1
 };
+
+// acc <- P acc + V (mod p) for acc < 2^61 + 8, P given as (a0, a0_2, a12), V < p; the result is
+// again below 2^61 + 8 (not canonical).  Same limb scheme as the hot loop, 4 multiply-adds.
+__device__ __forceinline__ uint64_t horner_step_lazy(uint64_t acc, uint32_t a0, uint32_t a0_2,
+                                                     uint32_t a12, uint64_t V, const HotConsts &hc) {
+  const uint32_t c_lo = (uint32_t)acc, x0 = c_lo & 0x7FFFFFFFu, x0_2 = c_lo << 1;
+  const uint32_t x1 = (uint32_t)(acc >> 31), x1_2 = x1 << 1;
+  uint64_t N = (uint64_t)a0_2 * x1_2;
+  N += (uint64_t)a12 * x0_2;
+  uint64_t U = (uint64_t)a12 * x1 + V;
+  U += (uint64_t)a0 * x0;
+  uint64_t Z = (uint64_t)(uint32_t)N * hc.two29 + U;
+  Z = (uint64_t)(uint32_t)(N >> 32) * hc.one + Z;
+  return (uint64_t)(uint32_t)(Z >> 61) * hc.one + (Z & P61);
+}
+
+// x of the shingle made of the PER tokens first .. first+PER-1, all loads issued up front.
+// Valid only if every token is shorter than LONG_TOKEN bytes; *long_tok says whether one is not.
+template <int PER>
+__device__ __forceinline__ uint64_t words_x_unrolled(const TokenRecs &rec,
+                                                     const PowSplit *__restrict__ ptab,
+                                                     uint32_t first, const HotConsts &hc,
+                                                     bool *long_tok) {
+  uint32_t len[PER];
+  uint64_t V[PER];
+#pragma unroll
+  for (int m = 0; m < PER; m++) {
+    len[m] = rec.len[first + m];
+    V[m] = rec.v[first + m];
+  }
+  uint4 e[PER];
+#pragma unroll
+  for (int m = 0; m < PER - 1; m++) e[m] = *reinterpret_cast<const uint4 *>(ptab + len[m]);
+  const uint64_t nsp = ptab[len[PER - 1]].nsp;
+  bool lt = false;
+#pragma unroll
+  for (int m = 0; m < PER; m++) lt |= len[m] == LONG_TOKEN;
+  *long_tok = lt;
+  uint64_t acc = V[PER - 1] + nsp;  // bare last token, < 2^62
+  acc = (acc & P61) + (acc >> 61);
+#pragma unroll
+  for (int m = PER - 2; m >= 0; m--) acc = horner_step_lazy(acc, e[m].x, e[m].y, e[m].z, V[m], hc);
+  return fold61(acc);
+}
 
 template <int F, int P, int MODE>
 __global__ void __launch_bounds__(64)
@@ -481,37 +548,35 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   const uint32_t d = ht.doc, cnt = ht.cnt;
 
   if (MODE == X_WORDS) {
-    // Straight-line evaluation for tokens shorter than LONG_TOKEN bytes (table powers, lazily
-    // reduced accumulator); a lane that meets a longer token redoes its shingle the general way.
+    // Straight-line evaluation for tokens shorter than LONG_TOKEN bytes (table multipliers,
+    // lazily reduced accumulator, unrolled for the usual shingle lengths); a lane that meets a
+    // longer token redoes its shingle the general way.
     const TokenRecs &rec = xsrc.rec;
-    const uint64_t *__restrict__ qpow = xsrc.qpow;
+    const PowSplit *__restrict__ ptab = xsrc.ptab;
     const uint32_t per = ht.per;
     for (uint32_t i = threadIdx.x; i < cnt; i += 64) {
-      const uint32_t first = ht.tok0 + i, last = first + per - 1;
-      const uint32_t l_last = rec.len[last];
-      bool long_tok = l_last == LONG_TOKEN;
-      const uint64_t pw = qpow[l_last];
-      const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
-      const uint64_t v_last = rec.v[last];
-      uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;  // W of the last token
-      for (uint32_t m = last; m-- > first;) {
-        const uint32_t lm = rec.len[m];
-        long_tok |= lm == LONG_TOKEN;
-        const uint64_t Pm = qpow[lm + 1];  // lm + 1 <= 255 stays inside the table
-        const uint64_t V = rec.v[m];
-        // acc <- Pm * acc + V (mod p), acc kept below 2^61 + 8 rather than canonical
-        const uint32_t p_lo = (uint32_t)Pm, a0 = p_lo & 0x7FFFFFFFu, a0_2 = p_lo << 1;
-        const uint32_t a12 = (uint32_t)(Pm >> 31) << 1;
-        const uint32_t c_lo = (uint32_t)acc, x0 = c_lo & 0x7FFFFFFFu, x0_2 = c_lo << 1;
-        const uint32_t x1 = (uint32_t)(acc >> 31), x1_2 = x1 << 1;
-        uint64_t N = (uint64_t)a0_2 * x1_2;
-        N += (uint64_t)a12 * x0_2;
-        uint64_t U = (uint64_t)a12 * x1 + V;
-        U += (uint64_t)a0 * x0;
-        const uint64_t Z = (uint64_t)(uint32_t)N * hc.two29 + U + (N >> 32);
-        acc = (Z & P61) + (Z >> 61);
+      const uint32_t first = ht.tok0 + i;
+      bool long_tok = false;
+      uint64_t acc;
+      if (per == 5) acc = words_x_unrolled<5>(rec, ptab, first, hc, &long_tok);
+      else if (per == 3) acc = words_x_unrolled<3>(rec, ptab, first, hc, &long_tok);
+      else if (per == 4) acc = words_x_unrolled<4>(rec, ptab, first, hc, &long_tok);
+      else if (per == 2) acc = words_x_unrolled<2>(rec, ptab, first, hc, &long_tok);
+      else if (per == 1) acc = words_x_unrolled<1>(rec, ptab, first, hc, &long_tok);
+      else {
+        const uint32_t last = first + per - 1;
+        const uint32_t l_last = rec.len[last];
+        long_tok = l_last == LONG_TOKEN;
+        acc = rec.v[last] + ptab[l_last].nsp;
+        acc = (acc & P61) + (acc >> 61);
+        for (uint32_t m = last; m-- > first;) {
+          const uint32_t lm = rec.len[m];
+          long_tok |= lm == LONG_TOKEN;
+          const uint4 e = *reinterpret_cast<const uint4 *>(ptab + lm);
+          acc = horner_step_lazy(acc, e.x, e.y, e.z, rec.v[m], hc);
+        }
+        acc = fold61(acc);
       }
-      acc = fold61(acc);
       if (long_tok) acc = shingle_x<MODE>(xsrc, ht, i);
       sx[i] = x_limbs(acc);
     }
@@ -626,7 +691,7 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   const int F = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
   const int per_block = (64 / P) * F;
   const uint32_t ky = (uint32_t)((K + per_block - 1) / per_block);
-  const HotConsts hc = {1u << 29, 8u};
+  const HotConsts hc = {1u << 29, 8u, 1u};
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
 #define SEDD_LAUNCH_MH(FF, PP, MM)                                                          \
@@ -801,6 +866,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
   const uint64_t o_cs = cv.take<CoefSplit>(K);
   const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
+  const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
   const uint64_t o_total = cv.take<uint64_t>(1);
   const uint64_t o_dv = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_btb = cv.take<uint32_t>(max_nd + 1);
@@ -820,6 +886,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   uint64_t *qpow = (uint64_t *)(A + o_qpow), *total = (uint64_t *)(A + o_total);
+  PowSplit *ptab = (PowSplit *)(A + o_ptab);
   uint32_t *dv = (uint32_t *)(A + o_dv), *btb = (uint32_t *)(A + o_btb);
   BTile *btd = (BTile *)(A + o_btd);
   uint32_t *wbase = (uint32_t *)(A + o_wbase);
@@ -836,6 +903,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   xsrc.sbase = sbase;
   xsrc.rec = rec;
   xsrc.qpow = qpow;
+  xsrc.ptab = ptab;
   xsrc.given = nullptr;
   xsrc.n = (uint32_t)n;
   const int mode = byte_mode ? X_BYTES : X_WORDS;
@@ -843,7 +911,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   {
     int nthr = std::max(K, QPOW_N);
     hipLaunchKernelGGL(k_coeffs, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
-                       coef_b, coef_s, qpow);
+                       coef_b, coef_s, qpow, ptab);
     SEDD_LAUNCH_CHECK();
   }
   if (debug) {
@@ -967,7 +1035,7 @@ int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
 int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream) {
   if (K < 1 || K > SEDD_MAX_K || !a || !b) return SEDD_EINVAL;
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, (hipStream_t)stream, seed,
-                     (int)K, a, b, (CoefSplit *)nullptr, (uint64_t *)nullptr);
+                     (int)K, a, b, (CoefSplit *)nullptr, (uint64_t *)nullptr, (PowSplit *)nullptr);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
@@ -997,7 +1065,7 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
-                     coef_b, coef_s, (uint64_t *)nullptr);
+                     coef_b, coef_s, (uint64_t *)nullptr, (PowSplit *)nullptr);
   SEDD_LAUNCH_CHECK();
   const uint64_t nsig = n_docs * (uint64_t)K;
   hipLaunchKernelGGL(k_fill_u32, dim3((uint32_t)std::min<uint64_t>((nsig + 255) / 256, 65536)),
