@@ -67,7 +67,7 @@ extern "C" {
  * doc_offsets  device, uint64[n_docs+1], non-decreasing byte offsets into `bytes`.
  * shingle_n    1..SEDD_MAX_SHINGLE_N.   K  1..SEDD_MAX_K.
  * sig          device, uint32[n_docs*K], document-major; fully overwritten.
- * A single document must be smaller than 2^32 - 2^29 bytes; n_docs < 2^31.
+ * A single document must be smaller than 2^32 - 2^30 - 2^16 bytes; n_docs < 2^31.
  */
 int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
                  int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,

@@ -22,7 +22,7 @@ namespace sedd {
 
 constexpr int TB_LANES = 64;
 constexpr uint32_t TB = TB_LANES * 16;    // bytes per byte tile: one wavefront, 16 bytes per lane
-constexpr uint32_t TS = 512;              // shingles per hash tile
+constexpr uint32_t TS = 256;              // shingles per hash tile
 constexpr int QPOW_N = 256;
 
 // x(s) of Eq. 1 as the hot kernel multiplies by it: x = x1 * 2^31 + x0 with x0 < 2^31,
@@ -535,7 +535,7 @@ __device__ __forceinline__ uint64_t words_x_unrolled(const TokenRecs &rec,
 }
 
 template <int F, int P, int MODE>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
           const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
           const CoefSplit *__restrict__ coef_split, int K,
@@ -787,11 +787,11 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
 
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
-      g_chunk_bytes_override ? std::min<uint64_t>(g_chunk_bytes_override, uint64_t(1) << 28)
+      g_chunk_bytes_override ? std::min<uint64_t>(g_chunk_bytes_override, uint64_t(1) << 30)
                              : (byte_mode ? (uint64_t(128) << 20) : (uint64_t(256) << 20));
   const uint64_t chunk_docs = uint64_t(1) << 22;
-  // chunk positions are 32-bit: a chunk is at most chunk_bytes (<= 2^28) plus one document
-  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 29);
+  // chunk positions are 32-bit: a chunk is at most chunk_bytes (<= 2^30) plus one document
+  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
   const uint64_t plan_cap = uint64_t(1) << 20;  // boundaries per call
   int rc;
   uint64_t h_probe[2];
