@@ -287,24 +287,61 @@ __device__ __forceinline__ uint64_t horner257_lazy(uint64_t acc, uint32_t c) {
   return (((hi & 0x1FFFFFFFu) << 32) | (uint32_t)lo) + (hi >> 29);
 }
 
-// One wavefront per byte tile, one lane per 16 bytes.
-// Pass 1 (lane = 16-byte segment): each lane walks its bytes from the last to the first in
-// registers (Horner for Eq. 1) and drops the partial hash and length of every token that starts
-// in its segment into LDS at the token's rank within the tile; what is left over at byte 0 is
-// the segment's head fragment (token bytes that continue a token begun earlier).
-// Pass 2 (lane = token): finish the token (a token that ran up to the end of its segment is
-// completed from the following segments' head fragments, or from global memory past the tile),
-// form V = W + 32 * 257^len and store the record; consecutive lanes store consecutive records.
+// acc * 257^3 + D without full reduction, for acc < 2^61 + 2^26 and D < 2^25; the result is
+// again below 2^61 + 2^26.  (257^3 fits 25 bits: one step consumes three bytes.)
+constexpr uint32_t R3 = 257u * 257u * 257u;
+__device__ __forceinline__ uint64_t horner3_lazy(uint64_t acc, uint32_t D) {
+  const uint64_t lo = (uint64_t)(uint32_t)acc * R3 + D;                        // < 2^58
+  const uint64_t hi = (uint64_t)(uint32_t)(acc >> 32) * R3 + (lo >> 32);       // < 2^55
+  // value = hi * 2^32 + lo32; bits 61.. of it are hi >> 29, and 2^61 = 1 (mod p)
+  return (((hi & 0x1FFFFFFFull) << 32) | (uint32_t)lo) + (hi >> 29);
+}
+
+// A token that the tile's wavefront cannot finish from LDS (64 bytes or more, or running past
+// the look-ahead): Eq. 1 byte by byte from global memory, w = sum c_i 257^i.
+struct WalkedToken {
+  uint64_t w;
+  uint32_t len;
+};
+__device__ __noinline__ WalkedToken walk_token(const uint8_t *__restrict__ pbase, uint32_t p0,
+                                               uint32_t ve) {
+  uint64_t w = 0, pw = 1;
+  uint32_t l = 0;
+  for (uint32_t p = p0; p < ve; p++) {
+    const uint32_t c = pbase[p];
+    if (is_ws(c)) break;
+    w = addmod(w, mulmod(pw, (uint64_t)c));
+    pw = mul257(pw);
+    l++;
+  }
+  WalkedToken r;
+  r.w = w;
+  r.len = l;
+  return r;
+}
+
+// One wavefront per byte tile.
+// Pass 1 (lane = 16-byte segment): the tile's bytes, plus LOOK bytes of look-ahead, go to LDS
+// together with the bitmap of token bytes; every lane drops the positions of the tokens that
+// start in its segment into LDS at their rank within the tile.
+// Pass 2 (lane = token): the token's length is the run of ones in the bitmap from its position;
+// its Eq. 1 hash is a Horner chain over 3-byte digits read from the LDS copy, last digit first,
+// the same number of steps for the whole wavefront (lanes with shorter tokens feed zero digits
+// first, which leave the accumulator at zero).  Then V = W + 32 * 257^len and the record is
+// stored; consecutive lanes store consecutive records.
+constexpr uint32_t LOOK = 16;
 constexpr uint32_t MAX_TILE_TOKENS = TB / 2 + 2;
+constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from LDS
 
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
              const uint64_t *__restrict__ qpow, TokenRecs rec) {
-  __shared__ uint64_t sm_head[TB_LANES];      // Eq. 1 hash of the segment's head fragment
-  __shared__ uint32_t sm_head_len[TB_LANES];  // its length, 0..16 (16: the whole segment)
-  __shared__ uint64_t sm_tok_acc[MAX_TILE_TOKENS];   // unreduced in-segment hash per token
-  __shared__ uint16_t sm_tok_meta[MAX_TILE_TOKENS];  // len | 0x80 if it reaches the segment end | lane << 8
+  // text: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
+  // than the wavefront's longest
+  __shared__ uint32_t sm_text[(TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2];
+  __shared__ uint32_t sm_bits[TB / 32 + 4];  // token-byte bitmap: tile, look-ahead, zero pad
+  __shared__ uint16_t sm_pos[MAX_TILE_TOKENS];
   const uint32_t t = blockIdx.x;
   const uint32_t lane = threadIdx.x;
   // independent loads first (the work list is allocated for the launch bound, so reading an
@@ -314,68 +351,80 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
   if (t >= *n_tiles) return;
   const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
   const Segment sg = load_segment(pbase, tile0 + lane * 16, vs, ve);
-  const uint32_t starts = token_starts(pbase, lane, tile0, vs, ve, sg.wm);
-  const uint32_t cnt = __popc(starts);
-  const uint32_t inc = wave_inclusive_scan(cnt);
-  const uint32_t local_rank = inc - cnt;
-  const uint32_t tot = __shfl(inc, 63, 64);
+  Segment la;
+  la.w[0] = la.w[1] = la.w[2] = la.w[3] = 0;
+  la.wm = 0;
+  if (lane == 0) la = load_segment(pbase, tile0 + TB, vs, ve);
+  const uint32_t starts0 = token_starts(pbase, lane, tile0, vs, ve, sg.wm);
 
-  uint64_t acc = 0;
-  uint32_t len = 0;
-#pragma unroll
-  for (int i = 15; i >= 0; i--) {
-    const uint32_t bit = 1u << i;
-    if (sg.wm & bit) {
-      acc = horner257_lazy(acc, seg_byte(sg, i));
-      len++;
-      if (starts & bit) {
-        const uint32_t j = local_rank + __popc(starts & (bit - 1));
-        sm_tok_acc[j] = acc;
-        sm_tok_meta[j] = (uint16_t)(len | ((i + len == 16) ? 0x80u : 0u) | (lane << 8));
-        acc = 0;
-        len = 0;
-      }
-    } else {
-      acc = 0;
-      len = 0;
+  *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = make_uint4(sg.w[0], sg.w[1], sg.w[2], sg.w[3]);
+  const uint32_t wm_up = __shfl_down(sg.wm, 1, 64);
+  if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
+  if (lane == 0) {
+    *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = make_uint4(la.w[0], la.w[1], la.w[2], la.w[3]);
+    sm_bits[TB / 32] = la.wm;
+    sm_bits[TB / 32 + 1] = 0;
+    sm_bits[TB / 32 + 2] = 0;
+  }
+  const uint32_t cnt = __popc(starts0);
+  const uint32_t inc = wave_inclusive_scan(cnt);
+  const uint32_t tot = __shfl(inc, 63, 64);
+  {
+    uint32_t st = starts0, j = inc - cnt;
+    while (st) {
+      const uint32_t bit = __ffs(st) - 1;
+      sm_pos[j++] = (uint16_t)(lane * 16 + bit);
+      st &= st - 1;
     }
   }
-  sm_head[lane] = fold61(acc);
-  sm_head_len[lane] = len;
   __syncthreads();
 
-  for (uint32_t j = lane; j < tot; j += TB_LANES) {
-    uint64_t w = fold61(sm_tok_acc[j]);
-    const uint32_t meta = sm_tok_meta[j];
-    uint32_t l = meta & 0x7Fu;
-    if (meta & 0x80u) {
-      uint32_t t2 = (meta >> 8) + 1;
-      for (;;) {
-        if (t2 == TB_LANES) {
-          // past the tile: finish the token byte by byte (forward: w += c * 257^l)
-          uint32_t pos = tile0 + TB;
-          if (pos < ve && !is_ws(pbase[pos])) {
-            uint64_t pw = qpow_global(qpow, l);
-            while (pos < ve) {
-              const uint32_t c = pbase[pos];
-              if (is_ws(c)) break;
-              w = addmod(w, mulmod(pw, (uint64_t)c));
-              pw = mul257(pw);
-              pos++;
-              l++;
-            }
-          }
-          break;
-        }
-        const uint32_t hl = sm_head_len[t2];
-        if (hl == 0) break;
-        w = addmod(w, mulmod31(qpow_global(qpow, l), sm_head[t2]));
-        l += hl;
-        if (hl < 16) break;
-        t2++;
-      }
+  // does the document end inside what the LDS copy covers?
+  const bool doc_ends_in_view = tile0 + TB + LOOK >= ve;
+  for (uint32_t base = 0; base < tot; base += TB_LANES) {
+    const uint32_t j = base + lane;
+    const bool active = j < tot;
+    const uint32_t pos = active ? sm_pos[j] : 0u;
+    // 64 bitmap bits from the token's first byte on
+    const uint32_t dw = pos >> 5, sh = pos & 31;
+    const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
+    const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
+    const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
+    const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
+    const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
+    // the run ends at a real non-token byte (or at the document's end) inside the LDS copy
+    const bool fast = active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
+    const uint32_t flen = fast ? run : 0u;
+    const uint32_t nd = (flen + 2) / 3;
+    uint32_t maxnd;
+    if (!__any(flen > 12)) {
+      maxnd = 1u + (__any(flen > 3) ? 1u : 0u) + (__any(flen > 6) ? 1u : 0u) + (__any(flen > 9) ? 1u : 0u);
+    } else {
+      maxnd = nd;
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
+      maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
     }
-    store_token(rec, first_idx + j, w, l, qpow);
+    uint64_t acc = 0;
+    for (uint32_t k = maxnd; k-- > 0;) {
+      const int rem = (int)flen - (int)(3 * k);        // bytes of the token from digit k on
+      const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
+      const uint32_t m = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
+      const uint32_t off = pos + 3 * k;
+      const uint32_t lo = sm_text[off >> 2], hi = sm_text[(off >> 2) + 1];
+      const uint32_t d = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & m;
+      // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
+      const uint32_t D = d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
+      acc = horner3_lazy(acc, D);
+    }
+    uint64_t w = fold61(acc);
+    uint32_t len = flen;
+    if (active && !fast) {
+      const WalkedToken wt = walk_token(pbase, tile0 + pos, ve);
+      w = wt.w;
+      len = wt.len;
+    }
+    if (active) store_token(rec, first_idx + j, w, len, qpow);
   }
 }
 
