@@ -55,6 +55,7 @@ struct TokenRecs {
 };
 constexpr uint32_t LONG_TOKEN = 255;
 
+
 // Per token length l < QPOW_N, what one Horner step over token records multiplies by:
 // P = 257^(l+1) as a0 = P mod 2^31, a0_2 = 2 a0, a12 = 2 (P >> 31); and nsp = p - 32 * 257^l,
 // which turns the hash of "token 0x20" into the hash of the bare token by one addition.
@@ -68,11 +69,20 @@ __device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpo
   return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
 }
 __device__ __forceinline__ void store_token(const TokenRecs &tr, uint32_t idx, uint64_t w,
-                                            uint32_t len, const uint64_t *__restrict__ qpow) {
-  // 32 * 257^len: a shift by 5 is a rotation of the 61-bit residue
-  const uint64_t pw = qpow_global(qpow, len);
-  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
-  tr.v[idx] = addmod(w, sp == P61 ? 0 : sp);
+                                            uint32_t len, const uint64_t *__restrict__ qpow,
+                                            const PowSplit *__restrict__ ptab) {
+  uint64_t v;
+  if (len < (uint32_t)QPOW_N) {
+    // w + 32 * 257^len = w - nsp (mod p)
+    const uint64_t nsp = ptab[len].nsp;
+    v = w >= nsp ? w - nsp : w + (P61 - nsp);
+  } else {
+    // 32 * 257^len: a shift by 5 is a rotation of the 61-bit residue
+    const uint64_t pw = powmod(257, len);
+    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
+    v = addmod(w, sp == P61 ? 0 : sp);
+  }
+  tr.v[idx] = v;
   tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
   if (len >= LONG_TOKEN) tr.long_len[idx] = len;
 }
@@ -228,55 +238,78 @@ __device__ __forceinline__ uint32_t nonspace_mask4(uint32_t w) {
   // gather bits 7, 15, 23, 31 into bits 0..3
   return ((ns >> 7) * 0x00204081u >> 21) & 0xFu;
 }
-__device__ __forceinline__ Segment load_segment(const uint8_t *__restrict__ pbase, uint32_t seg,
-                                                uint32_t vs, uint32_t ve) {
+// The 16 bytes at seg (16-aligned) if the segment holds at least one byte of the document
+// [vs, ve); zeros otherwise (no load is issued then).
+__device__ __forceinline__ uint4 load_raw16(const uint8_t *__restrict__ pbase, uint32_t seg,
+                                            uint32_t vs, uint32_t ve) {
+  uint4 q = make_uint4(0, 0, 0, 0);
+  if (seg < ve && seg + 16 > vs) q = *reinterpret_cast<const uint4 *>(pbase + seg);
+  return q;
+}
+__device__ __forceinline__ Segment make_segment(const uint4 q, uint32_t seg, uint32_t vs,
+                                                uint32_t ve) {
   Segment sg;
-  sg.w[0] = sg.w[1] = sg.w[2] = sg.w[3] = 0;
-  sg.wm = 0;
-  if (seg < ve && seg + 16 > vs) {
-    const uint4 q = *reinterpret_cast<const uint4 *>(pbase + seg);
-    sg.w[0] = q.x; sg.w[1] = q.y; sg.w[2] = q.z; sg.w[3] = q.w;
-    const uint32_t m = nonspace_mask4(q.x) | (nonspace_mask4(q.y) << 4) |
-                       (nonspace_mask4(q.z) << 8) | (nonspace_mask4(q.w) << 12);
-    // bytes of the segment inside the document: [lo, hi)
-    const uint32_t lo = vs > seg ? vs - seg : 0u;
-    const uint32_t hi = ve - seg < 16u ? ve - seg : 16u;
-    const uint32_t valid = ((1u << hi) - 1u) & ~((1u << lo) - 1u);
-    sg.wm = m & valid;
-  }
+  sg.w[0] = q.x; sg.w[1] = q.y; sg.w[2] = q.z; sg.w[3] = q.w;
+  const uint32_t m = nonspace_mask4(q.x) | (nonspace_mask4(q.y) << 4) |
+                     (nonspace_mask4(q.z) << 8) | (nonspace_mask4(q.w) << 12);
+  // bytes of the segment inside the document: [lo, hi)
+  const bool inside = seg < ve && seg + 16 > vs;
+  const uint32_t lo = vs > seg ? vs - seg : 0u;
+  const uint32_t hi = ve - seg < 16u ? ve - seg : 16u;
+  const uint32_t valid = ((1u << hi) - 1u) & ~((1u << lo) - 1u);
+  sg.wm = inside ? (m & valid) : 0u;
   return sg;
+}
+// The byte before the tile if it belongs to the document, a space otherwise.
+__device__ __forceinline__ uint32_t load_prev_byte(const uint8_t *__restrict__ pbase,
+                                                   uint32_t tile0, uint32_t vs, uint32_t ve) {
+  return (tile0 > vs && tile0 <= ve) ? (uint32_t)pbase[tile0 - 1] : 0x20u;
 }
 
 // Bit i of the result: byte seg+i starts a token.  Needs the token-byte bit of the byte before
 // the segment: the lane below's last bit (by shuffle), or for lane 0 the byte before the tile.
 // Must be called by all 64 lanes of the tile's wavefront.
-__device__ __forceinline__ uint32_t token_starts(const uint8_t *__restrict__ pbase, uint32_t lane,
-                                                 uint32_t tile0, uint32_t vs, uint32_t ve,
-                                                 uint32_t wm) {
+__device__ __forceinline__ uint32_t token_starts(uint32_t lane, uint32_t prev_byte, uint32_t wm) {
   uint32_t prev = __shfl_up(wm >> 15, 1, 64);
-  if (lane == 0) prev = (tile0 > vs && tile0 <= ve) ? (is_ws(pbase[tile0 - 1]) ? 0u : 1u) : 0u;
+  if (lane == 0) prev = is_ws(prev_byte) ? 0u : 1u;
   return wm & ~((wm << 1) | prev) & 0xFFFFu;
 }
 
-// Token starts per byte tile: one wavefront per tile, 16 bytes per lane, no LDS.
+// Token starts per byte tile: one wavefront per COUNT_TILES consecutive tiles (all loads issued
+// before the first is used), 16 bytes per lane, no LDS.
+constexpr int COUNT_TILES = 4;
 __global__ void __launch_bounds__(256)
 k_count_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
               const uint32_t *__restrict__ n_tiles, uint32_t n_slots,
               uint32_t *__restrict__ wcnt) {
-  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t t0 = (blockIdx.x * 4 + wave) * COUNT_TILES;
   const uint32_t lane = threadIdx.x & 63;
-  if (t >= n_slots) return;
-  const BTile bt = tiles[t < n_slots - 1 ? t : 0];  // entry n_slots-1 only pads the scan
-  if (t >= *n_tiles) {
-    if (lane == 0) wcnt[t] = 0;
-    return;
-  }
-  const Segment sg = load_segment(pbase, bt.tile0 + lane * 16, bt.vs, bt.ve);
-  const uint32_t starts = token_starts(pbase, lane, bt.tile0, bt.vs, bt.ve, sg.wm);
-  uint32_t cnt = __popc(starts);
+  const uint32_t nt = *n_tiles;
+  BTile bt[COUNT_TILES];
+  uint4 q[COUNT_TILES];
+  uint32_t pv[COUNT_TILES];
 #pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
-  if (lane == 0) wcnt[t] = cnt;
+  for (int i = 0; i < COUNT_TILES; i++) {
+    bt[i].vs = bt[i].ve = bt[i].tile0 = bt[i].pad = 0;
+    if (t0 + i < nt) bt[i] = tiles[t0 + i];
+  }
+#pragma unroll
+  for (int i = 0; i < COUNT_TILES; i++) {
+    q[i] = load_raw16(pbase, bt[i].tile0 + lane * 16, bt[i].vs, bt[i].ve);
+    pv[i] = load_prev_byte(pbase, bt[i].tile0, bt[i].vs, bt[i].ve);
+  }
+#pragma unroll
+  for (int i = 0; i < COUNT_TILES; i++) {
+    const uint32_t t = t0 + i;
+    if (t >= n_slots) break;
+    const Segment sg = make_segment(q[i], bt[i].tile0 + lane * 16, bt[i].vs, bt[i].ve);
+    const uint32_t starts = token_starts(lane, pv[i], sg.wm);
+    uint32_t cnt = __popc(starts);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    if (lane == 0) wcnt[t] = cnt;  // 0 for the slots past the tile count (they pad the scan)
+  }
 }
 
 // acc * 257 + c without full reduction: result < 2^61 + 2^10 for acc < 2^61 + 2^10
@@ -333,98 +366,116 @@ constexpr uint32_t LOOK = 16;
 constexpr uint32_t MAX_TILE_TOKENS = TB / 2 + 2;
 constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from LDS
 
+constexpr uint32_t SM_TEXT_WORDS = (TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2;
+
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
-             const uint64_t *__restrict__ qpow, TokenRecs rec) {
+             const uint64_t *__restrict__ qpow, const PowSplit *__restrict__ ptab,
+             TokenRecs rec) {
   // text: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
   // than the wavefront's longest
-  __shared__ uint32_t sm_text[(TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2];
+  __shared__ uint32_t sm_text[SM_TEXT_WORDS];
   __shared__ uint32_t sm_bits[TB / 32 + 4];  // token-byte bitmap: tile, look-ahead, zero pad
   __shared__ uint16_t sm_pos[MAX_TILE_TOKENS];
-  const uint32_t t = blockIdx.x;
   const uint32_t lane = threadIdx.x;
+  const uint32_t t = blockIdx.x;
   // independent loads first (the work list is allocated for the launch bound, so reading an
   // entry past the device-side count is harmless); the count decides afterwards
   const BTile bt = tiles[t];
   const uint32_t first_idx = wbase[t];
   if (t >= *n_tiles) return;
-  const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
-  const Segment sg = load_segment(pbase, tile0 + lane * 16, vs, ve);
-  Segment la;
-  la.w[0] = la.w[1] = la.w[2] = la.w[3] = 0;
-  la.wm = 0;
-  if (lane == 0) la = load_segment(pbase, tile0 + TB, vs, ve);
-  const uint32_t starts0 = token_starts(pbase, lane, tile0, vs, ve, sg.wm);
-
-  *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = make_uint4(sg.w[0], sg.w[1], sg.w[2], sg.w[3]);
-  const uint32_t wm_up = __shfl_down(sg.wm, 1, 64);
-  if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
-  if (lane == 0) {
-    *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = make_uint4(la.w[0], la.w[1], la.w[2], la.w[3]);
-    sm_bits[TB / 32] = la.wm;
-    sm_bits[TB / 32 + 1] = 0;
-    sm_bits[TB / 32 + 2] = 0;
-  }
-  const uint32_t cnt = __popc(starts0);
-  const uint32_t inc = wave_inclusive_scan(cnt);
-  const uint32_t tot = __shfl(inc, 63, 64);
   {
-    uint32_t st = starts0, j = inc - cnt;
-    while (st) {
-      const uint32_t bit = __ffs(st) - 1;
-      sm_pos[j++] = (uint16_t)(lane * 16 + bit);
-      st &= st - 1;
-    }
-  }
-  __syncthreads();
+    const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
+    const uint4 q_own = load_raw16(pbase, tile0 + lane * 16, vs, ve);
+    const uint4 q_la = load_raw16(pbase, tile0 + TB, vs, ve);  // wave-uniform: scalar loads
+    const uint32_t prev_byte = load_prev_byte(pbase, tile0, vs, ve);
+    const Segment sg = make_segment(q_own, tile0 + lane * 16, vs, ve);
+    const Segment la = make_segment(q_la, tile0 + TB, vs, ve);
+    const uint32_t starts0 = token_starts(lane, prev_byte, sg.wm);
 
-  // does the document end inside what the LDS copy covers?
-  const bool doc_ends_in_view = tile0 + TB + LOOK >= ve;
-  for (uint32_t base = 0; base < tot; base += TB_LANES) {
-    const uint32_t j = base + lane;
-    const bool active = j < tot;
-    const uint32_t pos = active ? sm_pos[j] : 0u;
-    // 64 bitmap bits from the token's first byte on
-    const uint32_t dw = pos >> 5, sh = pos & 31;
-    const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
-    const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
-    const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
-    const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
-    const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
-    // the run ends at a real non-token byte (or at the document's end) inside the LDS copy
-    const bool fast = active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
-    const uint32_t flen = fast ? run : 0u;
-    const uint32_t nd = (flen + 2) / 3;
-    uint32_t maxnd;
-    if (!__any(flen > 12)) {
-      maxnd = 1u + (__any(flen > 3) ? 1u : 0u) + (__any(flen > 6) ? 1u : 0u) + (__any(flen > 9) ? 1u : 0u);
-    } else {
-      maxnd = nd;
+    *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = q_own;
+    const uint32_t wm_up = __shfl_down(sg.wm, 1, 64);
+    if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
+    if (lane == 0) {
+      *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = q_la;
+      sm_bits[TB / 32] = la.wm;
+      sm_bits[TB / 32 + 1] = 0;
+      sm_bits[TB / 32 + 2] = 0;
+    }
+    const uint32_t cnt = __popc(starts0);
+    const uint32_t inc = wave_inclusive_scan(cnt);
+    const uint32_t tot = __shfl(inc, 63, 64);
+    {
+      uint32_t st = starts0, j = inc - cnt;
+      while (st) {
+        const uint32_t bit = __ffs(st) - 1;
+        sm_pos[j++] = (uint16_t)(lane * 16 + bit);
+        st &= st - 1;
+      }
+    }
+    __syncthreads();
+
+    // does the document end inside what the LDS copy covers?
+    const bool doc_ends_in_view = tile0 + TB + LOOK >= ve;
+    for (uint32_t base = 0; base < tot; base += TB_LANES) {
+      const uint32_t j = base + lane;
+      const bool active = j < tot;
+      const uint32_t pos = active ? sm_pos[j] : 0u;
+      // 64 bitmap bits from the token's first byte on
+      const uint32_t dw = pos >> 5, sh = pos & 31;
+      const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
+      const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
+      const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
+      const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
+      const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
+      // the run ends at a real non-token byte (or at the document's end) inside the LDS copy
+      const bool fast =
+          active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
+      const uint32_t flen = fast ? run : 0u;
+      uint64_t acc = 0;
+      if (!__any(flen > 8)) {
+        // every token of this pass has at most 8 bytes: one 12-byte read, three digits
+        const uint32_t wd = pos >> 2;
+        const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2];
+        const uint64_t keep = ~0ull >> ((64u - 8u * flen) & 63u);  // flen >= 1 where it matters
+        const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, pos & 3u) & (uint32_t)keep;
+        const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, pos & 3u) & (uint32_t)(keep >> 32);
+        const uint32_t d0 = a0 & 0xFFFFFFu;
+        const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
+        const uint32_t d2 = a1 >> 16;
+        const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
+        const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
+        const uint32_t D2 = d2 + (d2 >> 8);
+        acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
+        acc = horner3_lazy(acc, D0);
+      } else {
+        const uint32_t nd = (flen + 2) / 3;
+        uint32_t maxnd = nd;
 #pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
-      maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
+        for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
+        maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
+        for (uint32_t k = maxnd; k-- > 0;) {
+          const int rem = (int)flen - (int)(3 * k);  // bytes of the token from digit k on
+          const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
+          const uint32_t m = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
+          const uint32_t off = pos + 3 * k;
+          const uint32_t lo = sm_text[off >> 2], hi = sm_text[(off >> 2) + 1];
+          const uint32_t d = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & m;
+          // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
+          const uint32_t D = d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
+          acc = horner3_lazy(acc, D);
+        }
+      }
+      uint64_t w = fold61(acc);
+      uint32_t len = flen;
+      if (active && !fast) {
+        const WalkedToken wt = walk_token(pbase, tile0 + pos, ve);
+        w = wt.w;
+        len = wt.len;
+      }
+      if (active) store_token(rec, first_idx + j, w, len, qpow, ptab);
     }
-    uint64_t acc = 0;
-    for (uint32_t k = maxnd; k-- > 0;) {
-      const int rem = (int)flen - (int)(3 * k);        // bytes of the token from digit k on
-      const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
-      const uint32_t m = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
-      const uint32_t off = pos + 3 * k;
-      const uint32_t lo = sm_text[off >> 2], hi = sm_text[(off >> 2) + 1];
-      const uint32_t d = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & m;
-      // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
-      const uint32_t D = d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
-      acc = horner3_lazy(acc, D);
-    }
-    uint64_t w = fold61(acc);
-    uint32_t len = flen;
-    if (active && !fast) {
-      const WalkedToken wt = walk_token(pbase, tile0 + pos, ve);
-      w = wt.w;
-      len = wt.len;
-    }
-    if (active) store_token(rec, first_idx + j, w, len, qpow);
   }
 }
 
@@ -1001,13 +1052,15 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
     }
     if (!byte_mode) {
       ProfScope prof(SEDD_PROF_TOKENIZE, st);
-      hipLaunchKernelGGL(k_count_words, dim3((uint32_t)((nbt + 1 + 3) / 4)), dim3(256), 0, st,
+      hipLaunchKernelGGL(k_count_words,
+                         dim3((uint32_t)((nbt + 1 + 4 * COUNT_TILES - 1) / (4 * COUNT_TILES))),
+                         dim3(256), 0, st,
                          pbase, btd, btb + nd, (uint32_t)(nbt + 1), wbase);
       SEDD_LAUNCH_CHECK();
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
       hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase, btd,
-                         btb + nd, wbase, qpow, rec);
+                         btb + nd, wbase, qpow, ptab, rec);
       SEDD_LAUNCH_CHECK();
     }
     {
