@@ -1,0 +1,227 @@
+"""GPU parity at the full sizes of workloads 3, 4 and 5, in the launch configuration bench.py
+times (workload 3 streamed through sedd_minhash in 2 GB pieces).
+
+The CPU oracle cannot process these corpora whole in test time, so:
+  * signatures and band keys are compared bit for bit on sampled documents the oracle computes
+    one by one (random documents, the first and last of every streamed piece, the longest
+    documents, exact copies and their sources);
+  * cluster ids are checked over ALL documents against the defining property: they must equal
+    the minimum-index labelling of the connected components of the graph "same key in the same
+    band", recomputed here from the band keys with library sorts and scipy (no code shared with
+    the HIP path or the oracle);
+  * for workload 5 the signatures of every K of the sweep must be the leading columns of the
+    K = 512 signatures (prefix property of the hash family), so one sampled comparison at K = 512
+    covers all of them.
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2501_01046_amd import corpus
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+NPROC = min(16, os.cpu_count() or 1)
+STREAM_CHUNK_BYTES = 2 << 30
+_PROGRESS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+def say(*a):
+    """Progress line on stdout and, where the folder exists, in a file a watcher can see."""
+    line = " ".join(str(x) for x in a)
+    print(line, flush=True)
+    if os.path.isdir(_PROGRESS):
+        with open(os.path.join(_PROGRESS, "gpu_tests_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {line}\n")
+
+
+@pytest.fixture(scope="module")
+def sedd():
+    import paper_2501_01046_amd as m
+    m.lib()
+    yield m
+    m.sedd_release_scratch()
+
+
+def _stream_minhash(sedd, gen, recipe, n, K, flags, chunk_bytes):
+    """sedd_minhash over the whole corpus, piece by piece (pieces of about chunk_bytes).
+    Returns the device signatures, the piece boundaries and the per-document byte lengths."""
+    n_docs = recipe.n_docs
+    sig = torch.empty((n_docs, K), dtype=torch.uint32, device="cuda")
+    lengths = np.zeros(n_docs, dtype=np.uint64)
+    docs_per = max(1000, int(chunk_bytes / (recipe.len_median * 2.0 * 6.5)))
+    bounds = []
+    d0, total = 0, 0
+    while d0 < n_docs:
+        d1 = min(n_docs, d0 + docs_per)
+        data, off = gen.generate(d0, d1)
+        while data.size > chunk_bytes and d1 - d0 > 1:
+            d1 = d0 + (d1 - d0) * 3 // 4
+            data, off = gen.generate(d0, d1)
+        lengths[d0:d1] = np.diff(off)
+        t_data, t_off = torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda()
+        sedd.sedd_minhash(t_data, t_off, n, K, 0, flags, out=sig[d0:d1])
+        torch.cuda.synchronize()
+        del t_data, t_off
+        bounds.append((d0, d1))
+        total += int(data.size)
+        say(f"  piece docs [{d0}, {d1}) {data.size / 1e9:.2f} GB")
+        d0 = d1
+    return sig, bounds, lengths, total
+
+
+def _sample_docs(gen, recipe, bounds, lengths, n_random, n_longest, n_copies, seed):
+    rng = np.random.default_rng(seed)
+    n_docs = recipe.n_docs
+    picks = set(int(x) for x in rng.choice(n_docs, size=min(n_random, n_docs), replace=False))
+    for d0, d1 in bounds:
+        picks.update((d0, d1 - 1))
+    picks.update(int(x) for x in np.argsort(lengths)[::-1][:n_longest])
+    picks.update(int(x) for x in np.argsort(lengths)[:3])
+    copies = []
+    if recipe.exact_frac > 0:
+        for d in rng.choice(n_docs, size=min(n_docs, 40 * n_copies), replace=False):
+            kind, src, _ = gen.meta(int(d))
+            if kind == 2:
+                copies.append((int(d), int(src)))
+                picks.update((int(d), int(src)))
+                if len(copies) >= n_copies:
+                    break
+    return np.array(sorted(picks), dtype=np.int64), copies
+
+
+def _oracle_on_sample(gen, ids, n, K, flags):
+    """The oracle's signatures of the sampled documents (each regenerated from its id)."""
+    parts, lens = [], []
+    for d in ids:
+        data, off = gen.generate(int(d), int(d) + 1, threads=1)
+        parts.append(data)
+        lens.append(int(off[1]))
+    data = np.concatenate(parts) if parts else np.zeros(0, np.uint8)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+    return oracle.minhash_sharded(data, off, n, K, 0, flags, procs=NPROC)
+
+
+def _components_min_label(keys_dev, n_docs, b):
+    """cluster ids implied by the band keys: connected components of "same key in the same
+    band", labelled by their smallest member.  torch sorts + scipy, independent of libsedd."""
+    from scipy.sparse import coo_matrix
+    from scipy.sparse.csgraph import connected_components
+    k_signed = keys_dev.view(torch.int64)            # keys < 2^61: order is preserved
+    src, dst = [], []
+    for j in range(b):
+        vals, order = torch.sort(k_signed[:, j])
+        same = vals[1:] == vals[:-1]
+        idx = torch.nonzero(same).flatten()
+        src.append(order[idx].cpu().numpy())
+        dst.append(order[idx + 1].cpu().numpy())
+        del vals, order, same, idx
+    src = np.concatenate(src)
+    dst = np.concatenate(dst)
+    g = coo_matrix((np.ones(src.size, dtype=np.int8), (src, dst)), shape=(n_docs, n_docs))
+    _, lab = connected_components(g, directed=False)
+    _, first = np.unique(lab, return_index=True)      # first occurrence = smallest member
+    return first[lab].astype(np.int64), int(src.size)
+
+
+def _check_keys_and_clusters(sedd, sig, ids, want_sig, K, b, r, copies, label):
+    n_docs = sig.shape[0]
+    keys = sedd.sedd_lsh_keys(sig, b, r)
+    cid = sedd.sedd_cluster(keys)
+    torch.cuda.synchronize()
+    want_keys = oracle.lsh_keys(np.ascontiguousarray(want_sig[:, :K]), b, r)
+    t_ids = torch.from_numpy(ids).cuda()
+    got_keys = keys.view(torch.int64)[t_ids].cpu().numpy().view(np.uint64)
+    assert np.array_equal(got_keys, want_keys), f"{label}: sampled band keys differ"
+    want_cid, n_edges = _components_min_label(keys, n_docs, b)
+    got_cid = cid.cpu().numpy()
+    bad = np.nonzero(got_cid != want_cid)[0]
+    assert bad.size == 0, f"{label}: {bad.size} cluster ids differ, first {bad[:5]}"
+    for d, s in copies:
+        assert got_cid[d] == got_cid[s], f"{label}: exact copy {d} of {s} not co-clustered"
+    dups = int((got_cid != np.arange(n_docs)).sum())
+    say(f"  {label}: keys ok on {ids.size} sampled docs, clusters ok on all {n_docs} "
+        f"({n_edges} equal-key neighbours, {dups} duplicates)")
+    del keys, cid
+    return dups
+
+
+def _check_sampled_signatures(sig, ids, want_sig, K, label):
+    got = sig.view(torch.int32)[torch.from_numpy(ids).cuda()].cpu().numpy().view(np.uint32)
+    bad = np.nonzero((got != want_sig[:, :K]).any(axis=1))[0]
+    assert bad.size == 0, f"{label}: {bad.size} sampled signatures differ, first docs {ids[bad[:5]]}"
+
+
+def test_config3_full_size_streamed(sedd):
+    """10M documents, about 62 GB of text, K=256, 32x8 bands, streamed in 2 GB pieces."""
+    r = corpus.config(3)
+    gen = corpus.Corpus(r)
+    say("config 3 at full size: streaming", r.n_docs, "documents")
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 0,
+                                                  STREAM_CHUNK_BYTES)
+    say(f"  {total / 1e9:.1f} GB in {len(bounds)} pieces; sampling")
+    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1500, n_longest=6, n_copies=50,
+                               seed=3)
+    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 0)
+    _check_sampled_signatures(sig, ids, want, r.K, "config 3")
+    for d, s in copies:                                   # exact copies: identical signatures
+        assert torch.equal(sig[d].view(torch.int32), sig[s].view(torch.int32))
+    say(f"  signatures ok on {ids.size} sampled docs ({len(copies)} exact copies)")
+    dups = _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 3")
+    assert dups >= int(0.03 * r.n_docs * 0.9)             # at least the exact copies
+
+
+def test_config4_full_size_long_documents(sedd):
+    """200k documents, 1 % of them 1-14 MB: byte 13-grams, split-document minimum."""
+    r = corpus.config(4)
+    gen = corpus.Corpus(r)
+    say("config 4 at full size:", r.n_docs, "documents")
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 1, 1 << 62)
+    say(f"  {total / 1e9:.1f} GB; longest document {int(lengths.max())} bytes; sampling")
+    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1200, n_longest=1, n_copies=0,
+                               seed=4)
+    # a few more long documents, taken from the short end of the long ones to bound oracle time
+    long_ids = np.nonzero(lengths > 1_000_000)[0]
+    extra = long_ids[np.argsort(lengths[long_ids])[:3]]
+    ids = np.array(sorted(set(ids.tolist()) | set(int(x) for x in extra)), dtype=np.int64)
+    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 1)
+    _check_sampled_signatures(sig, ids, want, r.K, "config 4")
+    say(f"  signatures ok on {ids.size} sampled docs")
+    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 4")
+
+
+def test_config5_full_size_sweep(sedd):
+    """2M documents; K in {64,128,256,512} x (b,r) in {(8,16),(16,8),(32,8),(64,4)} x n in {3,5}."""
+    r = corpus.config(5)
+    gen = corpus.Corpus(r)
+    say("config 5 at full size:", r.n_docs, "documents")
+    data, off = gen.generate()
+    lengths = np.diff(off)
+    t_data, t_off = torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda()
+    bounds = [(0, r.n_docs)]
+    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1500, n_longest=4, n_copies=0,
+                               seed=5)
+    for n in (3, 5):
+        want = _oracle_on_sample(gen, ids, n, 512, 0)
+        sig512 = sedd.sedd_minhash(t_data, t_off, n, 512)
+        _check_sampled_signatures(sig512, ids, want, 512, f"config 5 n={n} K=512")
+        say(f"  n={n}: K=512 signatures ok on {ids.size} sampled docs")
+        for K in (64, 128, 256, 512):
+            if K == 512:
+                sig = sig512
+            else:
+                sig = sedd.sedd_minhash(t_data, t_off, n, K)
+                assert torch.equal(sig.view(torch.int32), sig512[:, :K].contiguous().view(torch.int32)), \
+                    f"n={n} K={K}: not the leading columns of the K=512 signatures"
+            for b, rr in ((8, 16), (16, 8), (32, 8), (64, 4)):
+                if b * rr > K:
+                    continue
+                _check_keys_and_clusters(sedd, sig, ids, want, K, b, rr, copies,
+                                         f"config 5 n={n} K={K} b={b} r={rr}")
+            if K != 512:
+                del sig
+        del sig512
