@@ -55,6 +55,8 @@ def _load():
         lib.sedd_ref_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp]
         lib.sedd_ref_cluster.restype = C.c_int
         lib.sedd_ref_cluster.argtypes = [vp, u64, i32, vp]
+        lib.sedd_ref_cluster_verified.restype = C.c_int
+        lib.sedd_ref_cluster_verified.argtypes = [vp, vp, u64, i32, i32, i32, vp]
         _lib = lib
     return _lib
 
@@ -149,6 +151,29 @@ def cluster(keys) -> np.ndarray:
     n_docs, b = keys.shape
     cid = np.zeros(n_docs, dtype=np.int64)
     rc = _load().sedd_ref_cluster(_ptr(keys), n_docs, b, _ptr(cid))
+    if rc:
+        raise OracleError(rc)
+    return cid
+
+
+def min_match_for(theta: float, K: int) -> int:
+    """Smallest integer m with m >= theta * K (the threshold test of Section 3.3 on integers).
+    theta is taken as the decimal fraction it prints as, so 0.8 * 125 is exactly 100."""
+    from fractions import Fraction
+    t = Fraction(str(theta)) * K
+    return int(-((-t.numerator) // t.denominator))
+
+
+def cluster_verified(keys, sig, min_match: int) -> np.ndarray:
+    """Clusters from duplicate pairs verified on the full signatures (Section 3.3)."""
+    keys = np.ascontiguousarray(keys, dtype=np.uint64)
+    sig = np.ascontiguousarray(sig, dtype=np.uint32)
+    n_docs, b = keys.shape
+    K = sig.shape[1]
+    assert sig.shape[0] == n_docs
+    cid = np.zeros(n_docs, dtype=np.int64)
+    rc = _load().sedd_ref_cluster_verified(_ptr(keys), _ptr(sig), n_docs, K, b, int(min_match),
+                                           _ptr(cid))
     if rc:
         raise OracleError(rc)
     return cid

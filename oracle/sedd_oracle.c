@@ -264,3 +264,52 @@ int sedd_ref_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *
   free(parent); free(col); free(lowest);
   return SEDD_REF_OK;
 }
+
+/*
+ * Verified clusters (Section 2.3 last step; Section 3.3, the count-match matrix M_ij).
+ * A bucket is the set of documents with the same key in the same band.  Inside every bucket all
+ * pairs i < j are compared (the paper's exhaustive O(D^2) comparison, Section 3.1): the pair is
+ * a duplicate iff the number of positions k < K with sig[i][k] == sig[j][k] is at least
+ * min_match (min_match = the smallest integer >= theta * K; the caller takes that ceiling once,
+ * so no floating point is involved here).  Duplicate pairs are the edges of the union graph;
+ * cluster_id[d] = lowest index of d's connected component.
+ */
+int sedd_ref_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs,
+                              int32_t K, int32_t b, int32_t min_match, int64_t *cluster_id) {
+  if (b < 1 || K < 1 || min_match < 0) return SEDD_REF_EINVAL;
+  if (n_docs == 0) return SEDD_REF_OK;
+  if (!keys || !sig || !cluster_id) return SEDD_REF_EINVAL;
+  uint64_t *parent = (uint64_t *)malloc(n_docs * 8);
+  kd_t *col = (kd_t *)malloc(n_docs * sizeof(kd_t));
+  uint64_t *lowest = (uint64_t *)malloc(n_docs * 8);
+  if (!parent || !col || !lowest) { free(parent); free(col); free(lowest); return SEDD_REF_ENOMEM; }
+  for (uint64_t d = 0; d < n_docs; d++) parent[d] = d;
+  for (int32_t j = 0; j < b; j++) {
+    for (uint64_t d = 0; d < n_docs; d++) { col[d].key = keys[d * (uint64_t)b + j]; col[d].doc = d; }
+    qsort(col, n_docs, sizeof(kd_t), kd_cmp);
+    uint64_t s = 0;
+    while (s < n_docs) {                               /* bucket = run [s, e) of one key */
+      uint64_t e = s + 1;
+      while (e < n_docs && col[e].key == col[s].key) e++;
+      for (uint64_t x = s; x < e; x++)
+        for (uint64_t y = x + 1; y < e; y++) {         /* upper triangle of M */
+          const uint32_t *sx = sig + col[x].doc * (uint64_t)K, *sy = sig + col[y].doc * (uint64_t)K;
+          int32_t same = 0;
+          for (int32_t k = 0; k < K; k++) same += sx[k] == sy[k];
+          if (same >= min_match) {
+            uint64_t ra = uf_find(parent, col[x].doc), rb = uf_find(parent, col[y].doc);
+            if (ra != rb) parent[rb] = ra;
+          }
+        }
+      s = e;
+    }
+  }
+  for (uint64_t d = 0; d < n_docs; d++) lowest[d] = UINT64_MAX;
+  for (uint64_t d = 0; d < n_docs; d++) {
+    uint64_t rt = uf_find(parent, d);
+    if (d < lowest[rt]) lowest[rt] = d;
+  }
+  for (uint64_t d = 0; d < n_docs; d++) cluster_id[d] = (int64_t)lowest[uf_find(parent, d)];
+  free(parent); free(col); free(lowest);
+  return SEDD_REF_OK;
+}
