@@ -97,6 +97,23 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
 int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
                  void *stream);
 
+/*
+ * Verified duplicate clusters (Section 2.3, last step; Section 3.3: inside every bucket all
+ * document pairs are compared on their full signatures).  Documents u, v are linked when they
+ * share a key in some band AND the number of positions k < K with sig[u*K + k] == sig[v*K + k]
+ * is at least min_match; cluster_id[d] = the smallest document index in d's connected component
+ * of that graph.  min_match is the smallest integer >= theta * K for the paper's similarity
+ * threshold theta (theta = 0.8, K = 128: 103); the caller takes that ceiling, so the test is on
+ * integers.  min_match = 0 gives the clusters of sedd_cluster.
+ *
+ * keys, cluster_id as in sedd_cluster; sig device, uint32[n_docs*K], all K columns are compared.
+ * Cost: every document of a bucket is compared with the bucket's first document, and only those
+ * that fail with the rest of the bucket, which yields the components of the exhaustive
+ * comparison without its quadratic cost on buckets of alike documents.
+ */
+int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                          int32_t b, int32_t min_match, int64_t *cluster_id, void *stream);
+
 /* Text for an error code (static storage). */
 const char *sedd_strerror(int code);
 /* Text of the HIP error behind the last SEDD_EDEVICE of this thread (static storage). */

@@ -52,6 +52,9 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
  * (waits for the device to go idle first).
  */
 #define SEDD_STAT_SLOW_TILES 0 /* shingle tiles the min-hash kernel recomputed on its exact path */
+#define SEDD_STAT_VERIFY_COUNTS 1 /* sedd_cluster_verified of the last call: low word = records
+                                     compared with their bucket's first record, high word = records
+                                     then compared with their whole bucket */
 #define SEDD_STAT_N 16
 int sedd_debug_stats(uint64_t *out);
 
@@ -68,6 +71,7 @@ int sedd_debug_stats(uint64_t *out);
 #define SEDD_PROF_LSH_KEYS 4
 #define SEDD_PROF_SORT 5
 #define SEDD_PROF_UNION 6
+#define SEDD_PROF_VERIFY 7       /* pairwise signature comparison inside buckets + union-find */
 #define SEDD_PROF_N 8
 int sedd_profile_enable(int on);
 int sedd_profile_read(double *ms, uint64_t *spans);

@@ -8,6 +8,7 @@ if the library has not been built, or there is no GPU, the calls raise.
     sig  = sedd_minhash(text_u8, doc_offsets_u64, shingle_n=5, K=128)   # uint32 [n_docs, K]
     keys = sedd_lsh_keys(sig, b=16, r=8)                                  # uint64 [n_docs, b]
     cid  = sedd_cluster(keys)                                             # int64  [n_docs]
+    cid  = sedd_cluster_verified(keys, sig, min_match_for(0.8, 128))      # Section 3.3 clusters
 """
 from __future__ import annotations
 
@@ -16,6 +17,7 @@ import os
 
 __all__ = [
     "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
+    "sedd_cluster_verified", "min_match_for",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
@@ -58,6 +60,8 @@ def lib():
         L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
         L.sedd_cluster.restype = C.c_int
         L.sedd_cluster.argtypes = [vp, u64, i32, vp, vp]
+        L.sedd_cluster_verified.restype = C.c_int
+        L.sedd_cluster_verified.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
         L.sedd_strerror.restype = C.c_char_p
         L.sedd_strerror.argtypes = [C.c_int]
         L.sedd_last_device_error.restype = C.c_char_p
@@ -171,6 +175,35 @@ def sedd_cluster(keys, out=None, stream=None):
         if out.numel() != n_docs:
             raise ValueError("out has the wrong size")
     _check(lib().sedd_cluster(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)), "sedd_cluster")
+    return out
+
+
+def min_match_for(theta: float, K: int) -> int:
+    """Smallest integer m with m >= theta * K: the count the threshold test of Section 3.3 needs.
+    theta is read as the decimal fraction it prints as (0.8 * 125 is exactly 100)."""
+    from fractions import Fraction
+    t = Fraction(str(theta)) * K
+    return int(-((-t.numerator) // t.denominator))
+
+
+def sedd_cluster_verified(keys, sig, min_match: int, out=None, stream=None):
+    """int64 [n_docs] clusters of document pairs that share a band key and agree on at least
+    min_match signature entries (min_match = min_match_for(theta, K))."""
+    torch = _torch()
+    keys = _dev(keys, torch.uint64, "keys")
+    sig = _dev(sig, torch.uint32, "sig")
+    n_docs, b = keys.shape
+    if sig.shape[0] != n_docs:
+        raise ValueError("sig and keys describe different numbers of documents")
+    K = sig.shape[1]
+    if out is None:
+        out = torch.empty((n_docs,), dtype=torch.int64, device=keys.device)
+    else:
+        out = _dev(out, torch.int64, "out")
+        if out.numel() != n_docs:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_cluster_verified(_ptr(keys), _ptr(sig), n_docs, K, b, int(min_match),
+                                       _ptr(out), _stream(stream)), "sedd_cluster_verified")
     return out
 
 

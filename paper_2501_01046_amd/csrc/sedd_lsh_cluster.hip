@@ -154,6 +154,10 @@ __device__ __forceinline__ void uf_unite(uint32_t *parent, uint32_t a, uint32_t 
   }
 }
 
+__global__ void k_fill_small_u32(uint32_t *p, uint32_t n, uint32_t v) {
+  if (threadIdx.x < n) p[threadIdx.x] = v;
+}
+
 __global__ void k_iota_u32(uint32_t *p, uint32_t n) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = i;
@@ -175,6 +179,156 @@ k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, ui
     if (other == key) {
       uf_unite(parent, bd[idx - back], bd[idx]);
       break;
+    }
+  }
+}
+
+// ---- verified clusters (Section 3.3) --------------------------------------------------------
+//
+// A bucket is a run of records with the same key inside one band.  The grouping sort orders the
+// records by their low key bits only, so a group (run of equal low bits) is a bucket or, rarely,
+// a few interleaved buckets; every pair test below therefore also compares the full keys.
+//
+// The union graph of "pair in the same bucket with at least min_match equal signature entries"
+// is built without enumerating all pairs of a large bucket whose members are alike:
+//   1. every record that is not the first of its group is compared with the group's first
+//      record (its head); a verified pair is united, a record that fails becomes an outsider;
+//   2. every outsider is compared with all other records of its group.
+// A pair of two non-outsiders is never compared: both are already in the head's component, so
+// the edge could not change any component.  Likewise any pair found in one component is skipped.
+// The components, and so the cluster ids, are exactly those of the exhaustive comparison.
+
+constexpr int TEAM = 16;  // lanes that compare one pair of signatures
+
+// slot for every lane with pred set, taken from *counter by one atomic per wavefront
+__device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
+  const uint64_t m = __ballot(pred);
+  if (m == 0) return 0xFFFFFFFFu;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  base = __shfl(base, leader, 64);
+  return pred ? base + (uint32_t)__popcll(m & ((uint64_t(1) << lane) - 1)) : 0xFFFFFFFFu;
+}
+
+// records that are not the first of their group
+__global__ void __launch_bounds__(256)
+k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t total, uint64_t mask,
+         uint32_t *__restrict__ list1, uint32_t *__restrict__ counts) {
+  const uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  bool follower = false;
+  if (idx < total && idx % n != 0) follower = ((bk[idx] ^ bk[idx - 1]) & mask) == 0;
+  const uint32_t slot = wave_append(follower, counts);
+  if (follower) list1[slot] = (uint32_t)idx;
+}
+
+// number of equal entries of two signatures, computed by the TEAM lanes of one team; every
+// lane of the team returns the total
+__device__ __forceinline__ uint32_t team_matches(const uint32_t *__restrict__ su,
+                                                 const uint32_t *__restrict__ sv, int K,
+                                                 int tl) {
+  uint32_t c = 0;
+  if ((K & 3) == 0 && (((uintptr_t)su | (uintptr_t)sv) & 15) == 0) {
+    for (int k = tl * 4; k < K; k += TEAM * 4) {
+      const uint4 a = *reinterpret_cast<const uint4 *>(su + k);
+      const uint4 d = *reinterpret_cast<const uint4 *>(sv + k);
+      c += (a.x == d.x) + (a.y == d.y) + (a.z == d.z) + (a.w == d.w);
+    }
+  } else {
+    for (int k = tl; k < K; k += TEAM) c += su[k] == sv[k];
+  }
+#pragma unroll
+  for (int o = TEAM / 2; o >= 1; o >>= 1) c += __shfl_xor(c, o, TEAM);
+  return c;
+}
+
+// first index in [lo, hi] whose masked key is not below `want` (the masked keys are sorted)
+__device__ __forceinline__ uint32_t group_lower_bound(const uint64_t *__restrict__ bk, uint64_t mask,
+                                                      uint32_t lo, uint32_t hi, uint64_t want) {
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if ((bk[mid] & mask) >= want) hi = mid;
+    else lo = mid + 1;
+  }
+  return lo;
+}
+// first index in [lo, hi) whose masked key is above `want`, or hi
+__device__ __forceinline__ uint32_t group_upper_bound(const uint64_t *__restrict__ bk, uint64_t mask,
+                                                      uint32_t lo, uint32_t hi, uint64_t want) {
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if ((bk[mid] & mask) > want) hi = mid;
+    else lo = mid + 1;
+  }
+  return lo;
+}
+
+// the TEAM lanes decide one candidate pair (documents u, v of one bucket); lane 0 of the team
+// unites them if they verify.  Returns whether u and v are in one component afterwards.
+__device__ __forceinline__ bool team_verify_pair(const uint32_t *__restrict__ sig, int K,
+                                                 int min_match, uint32_t *parent, uint32_t u,
+                                                 uint32_t v, int tl) {
+  uint32_t same = 0;
+  if (tl == 0) same = uf_find(parent, u) == uf_find(parent, v) ? 1u : 0u;
+  same = __shfl(same, 0, TEAM);
+  if (same) return true;
+  const uint32_t m = team_matches(sig + (uint64_t)u * K, sig + (uint64_t)v * K, K, tl);
+  if ((int)m < min_match) return false;
+  if (tl == 0) uf_unite(parent, u, v);
+  return true;
+}
+
+// step 1: one team per follower record, against the head of its group
+__global__ void __launch_bounds__(256)
+k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
+               uint64_t mask, const uint32_t *__restrict__ sig, int K, int min_match,
+               uint32_t *parent, const uint32_t *__restrict__ list1, uint32_t *counts,
+               uint32_t *__restrict__ list2) {
+  const uint32_t n1 = counts[0];
+  const int tl = threadIdx.x & (TEAM - 1);
+  const uint32_t teams = gridDim.x * (blockDim.x / TEAM);
+  // every lane of a wavefront runs the same number of rounds (wave_append is a wave operation)
+  const uint32_t rounds = (n1 + teams - 1) / teams;
+  uint32_t e = blockIdx.x * (blockDim.x / TEAM) + threadIdx.x / TEAM;
+  for (uint32_t it = 0; it < rounds; it++, e += teams) {
+    bool outsider = false;
+    uint32_t i = 0;
+    if (e < n1) {
+      i = list1[e];
+      const uint64_t key = bk[i];
+      const uint32_t band0 = (i / n) * n;
+      const uint32_t gs = group_lower_bound(bk, mask, band0, i, key & mask);
+      bool joined = false;
+      if (bk[gs] == key) joined = team_verify_pair(sig, K, min_match, parent, bd[gs], bd[i], tl);
+      outsider = !joined && tl == 0;
+    }
+    const uint32_t slot = wave_append(outsider, counts + 1);
+    if (outsider) list2[slot] = i;
+  }
+}
+
+// step 2: one wavefront per outsider, against every other record of its group
+__global__ void __launch_bounds__(256)
+k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
+                   uint64_t mask, const uint32_t *__restrict__ sig, int K, int min_match,
+                   uint32_t *parent, const uint32_t *__restrict__ list2,
+                   const uint32_t *__restrict__ counts) {
+  const uint32_t n2 = counts[1];
+  const int tl = threadIdx.x & (TEAM - 1);
+  const uint32_t team = (threadIdx.x & 63) / TEAM;
+  const uint32_t waves = gridDim.x * (blockDim.x / 64);
+  for (uint32_t e = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64; e < n2; e += waves) {
+    const uint32_t o = list2[e];
+    const uint64_t key = bk[o];
+    const uint32_t band0 = (o / n) * n;
+    const uint32_t gs = group_lower_bound(bk, mask, band0, o, key & mask);
+    const uint32_t ge = group_upper_bound(bk, mask, o + 1, band0 + n, key & mask);
+    const uint32_t v = bd[o];
+    // the head (gs) was this record's partner in step 1
+    for (uint32_t j = gs + 1 + team; j < ge; j += 64 / TEAM) {
+      if (j == o || bk[j] != key) continue;
+      team_verify_pair(sig, K, min_match, parent, bd[j], v, tl);
     }
   }
 }
@@ -309,6 +463,54 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   const uint64_t total = n_docs * (uint64_t)b;
   hipLaunchKernelGGL(k_link_runs, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,
                      sb.da, n, (uint32_t)b, (uint64_t(1) << bits) - 1, sb.parent);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
+                     cluster_id);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                          int32_t b, int32_t min_match, int64_t *cluster_id, void *stream) {
+  if (K < 1 || K > SEDD_MAX_K || min_match < 0) return SEDD_EINVAL;
+  int rc = check_cluster_args(keys, n_docs, b, cluster_id);
+  if (rc || n_docs == 0) return rc;
+  if (!sig) return SEDD_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  SortBufs sb;
+  rc = sort_layout(n_docs, (uint32_t)b, &sb);
+  if (rc) return rc;
+  unsigned long long *stats = nullptr;
+  rc = stats_ensure(&stats);
+  if (rc) return rc;
+  // two list lengths, kept beside the device counters (cleared by every call)
+  uint32_t *counts = (uint32_t *)(stats + SEDD_STAT_VERIFY_COUNTS);
+  const int bits = grouping_bits(n_docs);
+  {
+    ProfScope prof(SEDD_PROF_SORT, st);
+    rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
+    if (rc) return rc;
+  }
+  ProfScope prof(SEDD_PROF_VERIFY, st);
+  const uint32_t n = (uint32_t)n_docs;
+  const uint64_t total = n_docs * (uint64_t)b;
+  const uint64_t mask = (uint64_t(1) << bits) - 1;
+  // the sort leaves its result in the first buffer pair; the second pair holds the two lists
+  uint32_t *list1 = (uint32_t *)sb.kb, *list2 = sb.db;
+  hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 2u, 0u);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_v_mark, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka, n,
+                     total, mask, list1, counts);
+  SEDD_LAUNCH_CHECK();
+  // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
+  const uint32_t grid = 256 * 8;
+  hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,
+                     (int)K, (int)min_match, sb.parent, list1, counts, list2);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_v_outsider_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,
+                     (int)K, (int)min_match, sb.parent, list2, counts);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
                      cluster_id);

@@ -261,6 +261,7 @@ const char *sedd_profile_label(int label) {
     case SEDD_PROF_LSH_KEYS: return "lsh_keys";
     case SEDD_PROF_SORT: return "sort";
     case SEDD_PROF_UNION: return "union_find";
+    case SEDD_PROF_VERIFY: return "verify";
     default: return "";
   }
 }

@@ -9,6 +9,9 @@ The CPU oracle cannot process these corpora whole in test time, so:
     the minimum-index labelling of the connected components of the graph "same key in the same
     band", recomputed here from the band keys with library sorts and scipy (no code shared with
     the HIP path or the oracle);
+  * verified cluster ids (Section 3.3) are checked over ALL documents the same way: every pair
+    of documents inside a bucket is enumerated with torch, its equal signature entries counted,
+    and the components of the pairs at or above the threshold recomputed with scipy;
   * for workload 5 the signatures of every K of the sweep must be the leading columns of the
     K = 512 signatures (prefix property of the hash family), so one sampled comparison at K = 512
     covers all of them.
@@ -128,7 +131,61 @@ def _components_min_label(keys_dev, n_docs, b):
     return first[lab].astype(np.int64), int(src.size)
 
 
-def _check_keys_and_clusters(sedd, sig, ids, want_sig, K, b, r, copies, label):
+def _verified_components_min_label(keys_dev, sig_dev, n_docs, b, min_match, max_bucket=2048):
+    """cluster ids implied by keys and signatures under the count-match threshold: all pairs of
+    every bucket, match counts by torch, components by scipy.  Independent of libsedd."""
+    from scipy.sparse import coo_matrix
+    from scipy.sparse.csgraph import connected_components
+    k_signed = keys_dev.view(torch.int64)
+    s32 = sig_dev.view(torch.int32)
+    packed = []
+    for j in range(b):
+        vals, order = torch.sort(k_signed[:, j])
+        d = 1
+        while True:
+            same = vals[d:] == vals[:-d]
+            idx = torch.nonzero(same).flatten()
+            if idx.numel() == 0:
+                break
+            assert d < max_bucket, "a bucket is too large for the exhaustive check"
+            u, v = order[idx], order[idx + d]
+            packed.append((torch.minimum(u, v) << 32) | torch.maximum(u, v))
+            d += 1
+        del vals, order
+    if packed:
+        pairs = torch.unique(torch.cat(packed))
+    else:
+        pairs = torch.zeros(0, dtype=torch.int64, device=keys_dev.device)
+    u, v = pairs >> 32, pairs & 0xFFFFFFFF
+    keep = []
+    step = 1 << 20
+    for i in range(0, pairs.numel(), step):
+        m = (s32[u[i:i + step]] == s32[v[i:i + step]]).sum(dim=1)
+        keep.append(m >= min_match)
+    keep = torch.cat(keep) if keep else torch.zeros(0, dtype=torch.bool, device=keys_dev.device)
+    src, dst = u[keep].cpu().numpy(), v[keep].cpu().numpy()
+    g = coo_matrix((np.ones(src.size, dtype=np.int8), (src, dst)), shape=(n_docs, n_docs))
+    _, lab = connected_components(g, directed=False)
+    _, first = np.unique(lab, return_index=True)
+    return first[lab].astype(np.int64), int(pairs.numel()), int(src.size)
+
+
+def _check_verified(sedd, sig, keys, K, b, label, theta=0.8):
+    n_docs = sig.shape[0]
+    mm = sedd.min_match_for(theta, K)
+    cid = sedd.sedd_cluster_verified(keys, sig, mm)
+    torch.cuda.synchronize()
+    want, n_pairs, n_edges = _verified_components_min_label(keys, sig, n_docs, b, mm)
+    got = cid.cpu().numpy()
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, f"{label}: {bad.size} verified cluster ids differ, first {bad[:5]}"
+    dups = int((got != np.arange(n_docs)).sum())
+    say(f"  {label}: verified clusters (>= {mm} of {K}) ok on all {n_docs} "
+        f"({n_pairs} candidate pairs, {n_edges} verified, {dups} duplicates)")
+    return got
+
+
+def _check_keys_and_clusters(sedd, sig, ids, want_sig, K, b, r, copies, label, verified=False):
     n_docs = sig.shape[0]
     keys = sedd.sedd_lsh_keys(sig, b, r)
     cid = sedd.sedd_cluster(keys)
@@ -146,6 +203,11 @@ def _check_keys_and_clusters(sedd, sig, ids, want_sig, K, b, r, copies, label):
     dups = int((got_cid != np.arange(n_docs)).sum())
     say(f"  {label}: keys ok on {ids.size} sampled docs, clusters ok on all {n_docs} "
         f"({n_edges} equal-key neighbours, {dups} duplicates)")
+    if verified:
+        vcid = _check_verified(sedd, sig, keys, K, b, label)
+        assert (got_cid[vcid] == got_cid).all(), f"{label}: verified clusters do not refine"
+        for d, s in copies:
+            assert vcid[d] == vcid[s], f"{label}: exact copy {d} of {s} not co-clustered (verified)"
     del keys, cid
     return dups
 
@@ -171,7 +233,8 @@ def test_config3_full_size_streamed(sedd):
     for d, s in copies:                                   # exact copies: identical signatures
         assert torch.equal(sig[d].view(torch.int32), sig[s].view(torch.int32))
     say(f"  signatures ok on {ids.size} sampled docs ({len(copies)} exact copies)")
-    dups = _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 3")
+    dups = _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 3",
+                                    verified=True)
     assert dups >= int(0.03 * r.n_docs * 0.9)             # at least the exact copies
 
 
@@ -191,7 +254,8 @@ def test_config4_full_size_long_documents(sedd):
     want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 1)
     _check_sampled_signatures(sig, ids, want, r.K, "config 4")
     say(f"  signatures ok on {ids.size} sampled docs")
-    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 4")
+    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 4",
+                             verified=True)
 
 
 def test_config5_full_size_sweep(sedd):
@@ -221,7 +285,8 @@ def test_config5_full_size_sweep(sedd):
                 if b * rr > K:
                     continue
                 _check_keys_and_clusters(sedd, sig, ids, want, K, b, rr, copies,
-                                         f"config 5 n={n} K={K} b={b} r={rr}")
+                                         f"config 5 n={n} K={K} b={b} r={rr}",
+                                         verified=(K, b) in ((128, 16), (256, 64), (512, 8)))
             if K != 512:
                 del sig
         del sig512

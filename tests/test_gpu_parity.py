@@ -398,9 +398,107 @@ def test_config2_full_size_whole_path(sedd):
     assert bad.size == 0, f"{bad.size} signatures differ, first {bad[:5]}"
     assert np.array_equal(host(keys), wkeys)
     assert np.array_equal(host(cid), wcid)
+    say("config 2: verified clusters")
+    mm = oracle.min_match_for(0.8, r.K)
+    wv = oracle.cluster_verified(wkeys, wsig, mm)
+    assert np.array_equal(host(sedd.sedd_cluster_verified(keys, sig, mm)), wv)
+    say("config 2: verified duplicates", int((wv != np.arange(wv.size)).sum()))
     # second call on the same buffers: identical bytes (scratch reuse, atomics, exact path)
     sig2 = sedd.sedd_minhash(d_data, d_off, r.shingle_n, r.K, 0, 0)
     assert torch.equal(sig.view(torch.int32), sig2.view(torch.int32))
     dups = int((wcid != np.arange(wcid.size)).sum())
     say("config 2: duplicates found", dups)
     assert 20_000 <= dups <= 150_000
+
+
+# ---- verified clusters (Section 3.3) ---------------------------------------------------------
+
+def _proto_case(seed, n, K, b, span, groups, noise=0.6):
+    """Signatures scattered around a few prototypes (match counts spread over 0..K) and keys
+    from a small range (buckets of several documents, unrelated to the signatures)."""
+    rng = np.random.default_rng(seed)
+    proto = rng.integers(0, 1 << 32, size=(groups, K), dtype=np.uint64).astype(np.uint32)
+    sig = proto[rng.integers(0, groups, size=n)].copy()
+    flip = rng.random((n, K)) < rng.random((n, 1)) * noise
+    sig[flip] = rng.integers(0, 1 << 32, size=int(flip.sum()), dtype=np.uint64).astype(np.uint32)
+    keys = rng.integers(0, span, size=(n, b), dtype=np.uint64)
+    return keys, sig
+
+
+@pytest.mark.parametrize("seed,n,K,b,span,groups", [
+    (0, 1, 8, 1, 1, 1), (1, 2, 8, 1, 1, 1), (2, 500, 16, 3, 60, 4), (3, 3000, 32, 4, 400, 6),
+    (4, 2000, 128, 16, 700, 5), (5, 1500, 7, 2, 30, 2), (6, 4000, 130, 5, 500, 8),
+    (7, 5000, 256, 32, 3000, 10)])
+def test_cluster_verified_random_buckets(sedd, seed, n, K, b, span, groups):
+    say("verified random", seed, n, K, b)
+    keys, sig = _proto_case(seed, n, K, b, span, groups)
+    d_keys, d_sig = dev(keys), dev(sig)
+    for mm in sorted({0, 1, K // 2, oracle.min_match_for(0.8, K), K, K + 1}):
+        got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+        assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
+    assert np.array_equal(host(sedd.sedd_cluster_verified(d_keys, d_sig, 0)),
+                          host(sedd.sedd_cluster(d_keys)))
+
+
+def test_cluster_verified_large_buckets(sedd):
+    """One bucket holding every document: identical signatures (no second step needed), two
+    interleaved groups, and unrelated signatures (every record ends up compared with all)."""
+    say("verified large buckets")
+    rng = np.random.default_rng(1)
+    n, K = 1200, 64
+    keys = np.zeros((n, 2), dtype=np.uint64)
+    keys[:, 1] = np.arange(n)
+    same = np.tile(rng.integers(0, 1 << 32, size=K, dtype=np.uint64).astype(np.uint32), (n, 1))
+    two = same.copy()
+    two[1::2] = rng.integers(0, 1 << 32, size=K, dtype=np.uint64).astype(np.uint32)
+    rand = rng.integers(0, 1 << 32, size=(n, K), dtype=np.uint64).astype(np.uint32)
+    chain = np.zeros((n, K), dtype=np.uint32)
+    for i in range(n):                      # document i agrees with i-1 on K-1 entries only
+        chain[i] = np.arange(K) + 1000 * ((i + np.arange(K)) // K)
+    for name, sig, mm in (("same", same, K), ("two", two, K), ("rand", rand, 1),
+                          ("chain", chain, K - 1), ("chain", chain, K - 8)):
+        want = oracle.cluster_verified(keys, sig, mm)
+        got = host(sedd.sedd_cluster_verified(dev(keys), dev(sig), mm))
+        assert np.array_equal(got, want), (name, mm)
+    assert oracle.cluster_verified(keys, two, K).tolist()[:4] == [0, 1, 0, 1]
+
+
+def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
+    """Buckets whose keys differ only above the sorted bits share one sorted group."""
+    say("verified low-bit collisions")
+    rng = np.random.default_rng(2)
+    n, K, b = 4000, 32, 3
+    lo = rng.integers(0, 50, size=(n, b), dtype=np.uint64)
+    hi = rng.integers(0, 4, size=(n, b), dtype=np.uint64)
+    keys = (hi << np.uint64(45)) | lo
+    _, sig = _proto_case(3, n, K, b, 10, 5, noise=0.3)
+    for mm in (0, 20, 26, 32):
+        got = host(sedd.sedd_cluster_verified(dev(keys), dev(sig), mm))
+        assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
+
+
+@pytest.mark.parametrize("cfg,docs", [(1, 5000), (3, 3000), (4, 1500)])
+def test_cluster_verified_on_corpora(sedd, cfg, docs):
+    say("verified on corpus", cfg)
+    r = corpus.config(cfg).scaled(docs) if cfg != 4 else \
+        corpus.config(4).scaled(docs, long_lo=20_000, long_hi=100_000)
+    data, off = corpus.generate(r)
+    flags = int(r.byte_mode)
+    wsig = oracle.minhash_sharded(data, off, r.shingle_n, r.K, 0, flags, procs=NPROC)
+    wkeys = oracle.lsh_keys(wsig, r.b, r.r)
+    sig = sedd.sedd_minhash(dev(data), dev(off), r.shingle_n, r.K, 0, flags)
+    keys = sedd.sedd_lsh_keys(sig, r.b, r.r)
+    for theta in (0.5, 0.8, 0.95):
+        mm = sedd.min_match_for(theta, r.K)
+        assert mm == oracle.min_match_for(theta, r.K)
+        got = host(sedd.sedd_cluster_verified(keys, sig, mm))
+        assert np.array_equal(got, oracle.cluster_verified(wkeys, wsig, mm)), theta
+
+
+def test_cluster_verified_rejects_bad_arguments(sedd):
+    keys = dev(np.zeros((4, 2), np.uint64))
+    sig = dev(np.zeros((4, 8), np.uint32))
+    with pytest.raises(sedd.SeddError):
+        sedd.sedd_cluster_verified(keys, sig, -1)
+    with pytest.raises(ValueError):
+        sedd.sedd_cluster_verified(keys, sig[:3], 1)
