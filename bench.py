@@ -105,6 +105,8 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="config 5 parameter grid")
     ap.add_argument("--cpu-sample-docs", type=int, default=20000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--theta", type=float, default=0.8,
+                    help="similarity threshold of the verified-cluster measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM "
                          "byte counters collected with rocprofv3 --pmc)")
@@ -214,6 +216,27 @@ def main() -> int:
     }
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
 
+    # Verified clusters (the paper's count-match step, theta = 0.8): outside the timed steps, on
+    # the signatures and keys the last step left in HBM.
+    min_match = sedd.min_match_for(args.theta, K)
+    vcid = torch.empty((n_docs,), dtype=torch.int64, device="cuda")
+    sedd.sedd_cluster_verified(keys, sig, min_match, out=vcid)
+    torch.cuda.synchronize()
+    sedd.profile_enable(True)
+    sedd.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(3):
+        sedd.sedd_cluster_verified(keys, sig, min_match, out=vcid)
+    torch.cuda.synchronize()
+    v_ms = 1e3 * (time.perf_counter() - t0) / 3
+    sedd.profile_enable(False)
+    v_stages = sedd.profile_read()
+    verified = {
+        "theta": args.theta, "min_match": min_match, "ms_per_call": round(v_ms, 3),
+        "stage_ms": {k: round(v[0] / 3, 4) for k, v in v_stages.items() if v[0]},
+        "duplicates_found": int((vcid.cpu().numpy() != np.arange(n_docs)).sum()),
+    }
+
     cpu_baseline = None
     parity = None
     if not args.no_cpu_baseline:
@@ -224,7 +247,7 @@ def main() -> int:
         t0 = time.perf_counter()
         o_sig = oracle.minhash(sub, sub_off, n, K, 0, flags)
         o_keys = oracle.lsh_keys(o_sig, b, r)
-        oracle.cluster(o_keys)
+        o_cid = oracle.cluster(o_keys)
         t_cpu = time.perf_counter() - t0
         cpu_baseline = {
             "value": round(ns / t_cpu, 2), "unit": "docs/s", "cores": 1, "kind": "oracle",
@@ -233,8 +256,13 @@ def main() -> int:
                       f"minhash + band keys + clusters, single thread, {t_cpu:.1f} s",
         }
         # the sample doubles as a parity spot check of the timed configuration
+        o_vcid = oracle.cluster_verified(o_keys, o_sig, min_match)
+        s_vcid = sedd.sedd_cluster_verified(keys[:ns].contiguous(), sig[:ns].contiguous(), min_match)
         parity = bool(np.array_equal(sig[:ns].cpu().numpy(), o_sig)
-                      and np.array_equal(keys[:ns].cpu().numpy(), o_keys))
+                      and np.array_equal(keys[:ns].cpu().numpy(), o_keys)
+                      and np.array_equal(
+                          sedd.sedd_cluster(keys[:ns].contiguous()).cpu().numpy(), o_cid)
+                      and np.array_equal(s_vcid.cpu().numpy(), o_vcid))
 
     out = {
         "metric": "MinHash+LSH docs/sec on 1 MI355X (minhash + band keys + clustering)",
@@ -252,6 +280,7 @@ def main() -> int:
         "corpus_generation_s": round(t_gen, 2),
         "scratch_bytes": sedd.sedd_scratch_bytes(),
         "exact_path_tiles": sedd.debug_stats()[sedd.STAT_SLOW_TILES],
+        "verified_clusters": verified,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity_sample_ok": parity,

@@ -212,15 +212,29 @@ __device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
   return pred ? base + (uint32_t)__popcll(m & ((uint64_t(1) << lane) - 1)) : 0xFFFFFFFFu;
 }
 
-// records that are not the first of their group
-__global__ void __launch_bounds__(256)
-k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t total, uint64_t mask,
+// records that are not the first of their group: one list entry each, one atomic per block of
+// SORT_TILE records
+__global__ void __launch_bounds__(SORT_THREADS)
+k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
          uint32_t *__restrict__ list1, uint32_t *__restrict__ counts) {
-  const uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool follower = false;
-  if (idx < total && idx % n != 0) follower = ((bk[idx] ^ bk[idx - 1]) & mask) == 0;
-  const uint32_t slot = wave_append(follower, counts);
-  if (follower) list1[slot] = (uint32_t)idx;
+  __shared__ uint32_t s_base;
+  const uint32_t blk = blockIdx.x, band = blockIdx.y;
+  const uint64_t *src = bk + (uint64_t)band * n;
+  uint32_t flags = 0;
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
+    if (e < n && e > 0 && ((src[e] ^ src[e - 1]) & mask) == 0) flags |= 1u << it;
+  }
+  uint32_t tot;
+  const uint32_t pre = block_exclusive_scan<SORT_THREADS>(__popc(flags), &tot);
+  if (threadIdx.x == 0) s_base = tot ? atomicAdd(counts, tot) : 0u;
+  __syncthreads();
+  uint32_t o = s_base + pre;
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++)
+    if (flags & (1u << it))
+      list1[o++] = band * n + blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
 }
 
 // number of equal entries of two signatures, computed by the TEAM lanes of one team; every
@@ -243,9 +257,14 @@ __device__ __forceinline__ uint32_t team_matches(const uint32_t *__restrict__ su
   return c;
 }
 
-// first index in [lo, hi] whose masked key is not below `want` (the masked keys are sorted)
+// first index in [lo, hi] whose masked key is not below `want` (the masked keys are sorted and
+// bk[hi] has the masked key `want`); most groups are a few records long, so walk first
 __device__ __forceinline__ uint32_t group_lower_bound(const uint64_t *__restrict__ bk, uint64_t mask,
                                                       uint32_t lo, uint32_t hi, uint64_t want) {
+  for (int step = 0; step < 4; step++) {
+    if (hi == lo || (bk[hi - 1] & mask) != want) return hi;
+    hi--;
+  }
   while (lo < hi) {
     const uint32_t mid = lo + ((hi - lo) >> 1);
     if ((bk[mid] & mask) >= want) hi = mid;
@@ -256,6 +275,10 @@ __device__ __forceinline__ uint32_t group_lower_bound(const uint64_t *__restrict
 // first index in [lo, hi) whose masked key is above `want`, or hi
 __device__ __forceinline__ uint32_t group_upper_bound(const uint64_t *__restrict__ bk, uint64_t mask,
                                                       uint32_t lo, uint32_t hi, uint64_t want) {
+  for (int step = 0; step < 4; step++) {
+    if (lo == hi || (bk[lo] & mask) != want) return lo;
+    lo++;
+  }
   while (lo < hi) {
     const uint32_t mid = lo + ((hi - lo) >> 1);
     if ((bk[mid] & mask) > want) hi = mid;
@@ -501,11 +524,11 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 2u, 0u);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_v_mark, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka, n,
-                     total, mask, list1, counts);
+  hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
+                     list1, counts);
   SEDD_LAUNCH_CHECK();
   // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
-  const uint32_t grid = 256 * 8;
+  const uint32_t grid = 256 * 16;
   hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,
                      (int)K, (int)min_match, sb.parent, list1, counts, list2);
   SEDD_LAUNCH_CHECK();
