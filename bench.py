@@ -216,6 +216,32 @@ def main() -> int:
     }
     stage_ms = {k: round(v[0] / args.steps, 4) for k, v in stages.items()}
 
+    # Ceiling of the hot loop on this chip, measured in the same job: the same kernel on full
+    # tiles of caller-supplied shingle hashes (no tokenisation, no Eq. 1 work, no short tiles).
+    def alu_ceiling():
+        per, nd = 4096, 10000
+        g = torch.Generator(device="cuda").manual_seed(0)
+        xs = torch.randint(0, (1 << 61) - 1, (per * nd,), dtype=torch.int64, device="cuda",
+                           generator=g).view(torch.uint64)
+        soff = (torch.arange(nd + 1, dtype=torch.int64, device="cuda") * per).view(torch.uint64)
+        out = torch.empty((nd, K), dtype=torch.uint32, device="cuda")
+        for _ in range(40):                                   # clocks settle within ~50 ms
+            sedd.debug_minhash_from_x(xs, soff, K, 0, out=out)
+        torch.cuda.synchronize()
+        sedd.profile_enable(True)
+        sedd.profile_read()
+        for _ in range(10):
+            sedd.debug_minhash_from_x(xs, soff, K, 0, out=out)
+        torch.cuda.synchronize()
+        sedd.profile_enable(False)
+        ms = sedd.profile_read()["minhash"][0] / 10
+        return per * nd * K * OPS_PER_PAIR / (ms * 1e-3) / 1e12
+
+    ceiling = alu_ceiling()
+    roofline["hot_loop_ceiling"] = {
+        "achieved": round(ceiling, 3), "frac": round(ceiling / PEAK_TOPS, 4),
+        "what": "k_minhash on full tiles of given shingle hashes (same launch shape, same K)"}
+
     # Verified clusters (the paper's count-match step, theta = 0.8): outside the timed steps, on
     # the signatures and keys the last step left in HBM.
     min_match = sedd.min_match_for(args.theta, K)

@@ -285,13 +285,18 @@ def debug_set_chunk_bytes(n: int):
     _check(lib().sedd_debug_set_chunk_bytes(n), "sedd_debug_set_chunk_bytes")
 
 
-def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None):
+def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None, out=None):
     """Signatures from caller-supplied shingle hashes (the K-hash / minimum kernel alone)."""
     torch = _torch()
     x = _dev(x, torch.uint64, "x")
     shingle_offsets = _dev(shingle_offsets, torch.uint64, "shingle_offsets")
     n_docs = max(0, shingle_offsets.numel() - 1)
-    sig = torch.empty((n_docs, max(K, 0)), dtype=torch.uint32, device=x.device)
+    if out is None:
+        sig = torch.empty((n_docs, max(K, 0)), dtype=torch.uint32, device=x.device)
+    else:
+        sig = _dev(out, torch.uint32, "out")
+        if sig.numel() != n_docs * K:
+            raise ValueError("out has the wrong size")
     _check(lib().sedd_debug_minhash_from_x(_ptr(x), _ptr(shingle_offsets), n_docs, x.numel(), K,
                                            seed, _ptr(sig), _stream(stream)),
            "sedd_debug_minhash_from_x")
