@@ -680,6 +680,48 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
       if (long_tok) acc = shingle_x<MODE>(xsrc, ht, i);
       sx[i] = x_limbs(acc);
     }
+  } else if (MODE == X_BYTES) {
+    // Byte windows.  The tile's bytes are staged in LDS; lane l owns the windows 4l .. 4l+3: it
+    // evaluates the last of them by Horner over its bytes and derives the others with the reuse
+    // form of Eq. 1 (Eq. 2 read backwards, so that the step multiplies by q instead of dividing):
+    //   x(i-1) = q (x(i) - c[i+per-1] q^(per-1)) + c[i-1]      (mod p).
+    // The windows of row j = i mod 4 are stored from slot off_j on, consecutive lanes in
+    // consecutive slots; the slots [0, cnt) then hold every window once, in an order that does
+    // not matter to a minimum.
+    __shared__ uint32_t sm_b[MODE == X_BYTES ? (TS + SEDD_MAX_SHINGLE_N + 8) / 4 + 1 : 1];
+    const uint32_t vs = xsrc.dv[d], dlen = xsrc.dv[d + 1] - vs;
+    const uint32_t per = min(dlen, xsrc.n);
+    const uint32_t b0 = vs + (ht.x_off - xsrc.sbase[d]);  // frame position of the first window
+    const uint32_t o = b0 & 3u;
+    const uint32_t ndw = (o + cnt + per - 1 + 3) >> 2;    // aligned words that hold >= 1 byte of it
+    for (uint32_t w = threadIdx.x; w < ndw; w += 64)
+      sm_b[w] = *reinterpret_cast<const uint32_t *>(xsrc.pbase + (b0 - o) + 4 * w);
+    __syncthreads();
+    const uint8_t *tb = reinterpret_cast<const uint8_t *>(sm_b) + o;  // tb[i] = byte i of the tile
+    const uint32_t l = threadIdx.x;
+    if (4 * l < cnt) {
+      const uint32_t m = min(4u, cnt - 4 * l);
+      const uint32_t top = 4 * l + m - 1;
+      uint64_t acc = 0;
+      for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, tb[top + j]);
+      const uint64_t Q = xsrc.qpow[per - 1];  // per <= SEDD_MAX_SHINGLE_N < QPOW_N
+      const uint32_t q_lo = (uint32_t)Q, q_hi = (uint32_t)(Q >> 32);
+      for (uint32_t i = top;; i--) {
+        const uint32_t j = i & 3u;
+        uint32_t slot = l;  // off_j + l, off_j = sum over rows before j of ceil((cnt - row) / 4)
+        for (uint32_t row = 0; row < j; row++) slot += (cnt - row + 3) >> 2;
+        sx[slot] = x_limbs(fold61(acc));
+        if (i == 4 * l) break;
+        // x(i-1) from x(i)
+        const uint32_t c_hi = tb[i + per - 1], c_lo = tb[i - 1];
+        const uint64_t lo = (uint64_t)q_lo * c_hi;
+        const uint64_t hi = (uint64_t)q_hi * c_hi + (lo >> 32);
+        const uint64_t tq = (((hi & 0x1FFFFFFFull) << 32) | (uint32_t)lo) + (hi >> 29);  // c_hi Q
+        uint64_t dd = acc + (2 * P61 - tq);  // below 2^63
+        dd = (dd & P61) + (dd >> 61);
+        acc = horner257_lazy(dd, c_lo);
+      }
+    }
   } else {
     for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i] = x_limbs(shingle_x<MODE>(xsrc, ht, i));
   }
@@ -745,8 +787,14 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   for (int j = 0; j < F; j++) {
     int k = kbase + LW * j;
     if (grp == 0 && k < K) {
-      if (ht.single) out[k] = m[j];
-      else atomicMin(out + k, m[j]);
+      if (ht.single) {
+        out[k] = m[j];
+      } else {
+        // values only ever decrease, so a (possibly stale) read that is not above m[j] settles
+        // it without an atomic; a long document's tiles would otherwise queue on 4 cache lines
+        const uint32_t cur = __hip_atomic_load(out + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (m[j] < cur) atomicMin(out + k, m[j]);
+      }
     }
   }
 }
