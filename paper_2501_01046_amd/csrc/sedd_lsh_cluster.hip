@@ -70,31 +70,43 @@ k_radix_hist(const uint64_t *__restrict__ bk, uint32_t n, uint32_t nblk, int shi
   hist[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk] = h[threadIdx.x];
 }
 
+// Stable scatter of one tile.  Wavefront w owns the tile's records [w*1024, (w+1)*1024), 16 per
+// lane, all loaded before the first is used.  Ranking needs no block barrier: the lanes of a
+// wavefront that hold the same digit find each other with ballots, the first of them advances the
+// wavefront's own counter of that digit in LDS.  Two barriers follow: one before the per-digit
+// prefix over the four wavefronts, one before the stores.
 __global__ void __launch_bounds__(SORT_THREADS)
 k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
                 uint32_t nblk, int shift, const uint32_t *__restrict__ pos,
                 uint64_t *__restrict__ ok, uint32_t *__restrict__ od) {
-  __shared__ uint32_t running[RADIX];
-  __shared__ uint32_t wcnt[SORT_THREADS / 64][RADIX];
+  constexpr int WAVES = SORT_THREADS / 64;
+  __shared__ uint32_t wc[WAVES][RADIX];  // per wavefront: digit count, later the global offset
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  running[threadIdx.x] = pos[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk];
   const uint64_t *sk = bk + (uint64_t)band * n;
   const uint32_t *sd = bd + (uint64_t)band * n;
-  for (int it = 0; it < SORT_ITEMS; it++) {
 #pragma unroll
-    for (int w = 0; w < SORT_THREADS / 64; w++) wcnt[w][threadIdx.x] = 0;
-    __syncthreads();
-    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
-    const bool valid = e < n;
-    uint64_t key = 0;
-    uint32_t doc = 0, digit = 0;
-    if (valid) {
-      key = sk[e];
-      doc = sd[e];
-      digit = (uint32_t)(key >> shift) & (RADIX - 1);
+  for (int w = 0; w < WAVES; w++) wc[w][threadIdx.x] = 0;
+  uint64_t key[SORT_ITEMS];
+  uint32_t doc[SORT_ITEMS];
+  const uint32_t e0 = blk * SORT_TILE + wave * (SORT_TILE / WAVES) + lane;
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const uint32_t e = e0 + it * 64;
+    key[it] = 0;
+    doc[it] = 0;
+    if (e < n) {
+      key[it] = sk[e];
+      doc[it] = sd[e];
     }
-    // lanes of this wavefront holding the same digit
+  }
+  __syncthreads();  // counters cleared
+  uint32_t rank[SORT_ITEMS];  // rank among the wavefront's records of the same digit
+  const uint64_t lt_mask = (uint64_t(1) << lane) - 1;
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const bool valid = e0 + it * 64 < n;
+    const uint32_t digit = (uint32_t)(key[it] >> shift) & (RADIX - 1);
     uint64_t peers = __ballot(valid);
 #pragma unroll
     for (int bit = 0; bit < RADIX_BITS; bit++) {
@@ -102,21 +114,33 @@ k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd
       const uint64_t bb = __ballot(valid && set);
       peers &= set ? bb : ~bb;
     }
-    const uint32_t below = __popcll(peers & ((uint64_t(1) << lane) - 1));
-    if (valid && below == 0) wcnt[wave][digit] = __popcll(peers);
-    __syncthreads();
-    if (valid) {
-      uint32_t o = running[digit] + below;
-      for (int w = 0; w < wave; w++) o += wcnt[w][digit];
-      ok[o] = key;
-      od[o] = doc;
-    }
-    __syncthreads();
-    uint32_t add = 0;
+    const uint32_t below = __popcll(peers & lt_mask);
+    volatile uint32_t *ctr = &wc[wave][digit];
+    uint32_t old = 0;
+    if (valid) old = *ctr;                                  // every peer reads the count ...
+    if (valid && below == 0) *ctr = old + __popcll(peers);  // ... before the first one advances it
+    rank[it] = old + below;
+  }
+  __syncthreads();
+  {
+    // this thread's digit: global start of the block's run, then one sub-run per wavefront
+    uint32_t base = pos[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk];
 #pragma unroll
-    for (int w = 0; w < SORT_THREADS / 64; w++) add += wcnt[w][threadIdx.x];
-    running[threadIdx.x] += add;
-    __syncthreads();
+    for (int w = 0; w < WAVES; w++) {
+      const uint32_t c = wc[w][threadIdx.x];
+      wc[w][threadIdx.x] = base;
+      base += c;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    if (e0 + it * 64 < n) {
+      const uint32_t digit = (uint32_t)(key[it] >> shift) & (RADIX - 1);
+      const uint32_t o = wc[wave][digit] + rank[it];
+      ok[o] = key[it];
+      od[o] = doc[it];
+    }
   }
 }
 
@@ -400,16 +424,16 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
   return SEDD_OK;
 }
 
-// number of low key bits sedd_cluster sorts by: a multiple of 16 (an even number of passes, so
-// the result lands in the first buffer) with 2^bits >= 16 n where that is possible
+// number of low key bits sedd_cluster sorts by: whole digits with 2^bits >= 16 n where that is
+// possible
 static int grouping_bits(uint64_t n_docs) {
-  int bits = 16;
-  while (bits < 48 && (uint64_t(1) << bits) < 16 * n_docs) bits += 16;
+  int bits = 2 * RADIX_BITS;
+  while (bits < 48 && (uint64_t(1) << bits) < 16 * n_docs) bits += RADIX_BITS;
   return bits;
 }
 
-// leaves the records, sorted by the low key_bits bits (a multiple of 16, or KEY_BITS for a full
-// sort), in sb->ka / sb->da
+// leaves the records, sorted by the low key_bits bits (whole digits, or KEY_BITS for a full
+// sort), in sb->ka / sb->da; sb->kb / sb->db are free afterwards
 static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key_bits, SortBufs *sb,
                       hipStream_t st) {
   const uint32_t n = (uint32_t)n_docs;
@@ -419,7 +443,6 @@ static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key
   const uint64_t nh = (uint64_t)b * RADIX * sb->nblk;
   uint64_t *src_k = sb->ka, *dst_k = sb->kb;
   uint32_t *src_d = sb->da, *dst_d = sb->db;
-  static_assert(((KEY_BITS + RADIX_BITS - 1) / RADIX_BITS) % 2 == 0, "even pass count");
   for (int shift = 0; shift < key_bits; shift += RADIX_BITS) {
     dim3 grid(sb->nblk, b);
     hipLaunchKernelGGL(k_radix_hist, grid, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
@@ -433,6 +456,11 @@ static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key
     std::swap(src_k, dst_k);
     std::swap(src_d, dst_d);
   }
+  // after an odd number of passes the result sits in the second pair: rename the pairs
+  sb->kb = dst_k;
+  sb->db = dst_d;
+  sb->ka = src_k;
+  sb->da = src_d;
   return SEDD_OK;
 }
 
