@@ -424,11 +424,13 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
   return SEDD_OK;
 }
 
-// number of low key bits sedd_cluster sorts by: whole digits with 2^bits >= 16 n where that is
-// possible
-static int grouping_bits(uint64_t n_docs) {
+// number of low key bits the grouping sort orders by: whole digits with 2^bits >= slack * n where
+// that is possible.  A group of equal low bits then holds about 1 / slack records of other keys.
+// sedd_cluster takes slack 16 (its linker walks over the few strangers); the verified path takes
+// 4096 so that a group is, almost always, exactly one bucket.
+static int grouping_bits(uint64_t n_docs, uint64_t slack) {
   int bits = 2 * RADIX_BITS;
-  while (bits < 48 && (uint64_t(1) << bits) < 16 * n_docs) bits += RADIX_BITS;
+  while (bits < 56 && (uint64_t(1) << bits) < slack * n_docs) bits += RADIX_BITS;
   return bits;
 }
 
@@ -501,7 +503,7 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
-  const int bits = grouping_bits(n_docs);
+  const int bits = grouping_bits(n_docs, 16);
   {
     ProfScope prof(SEDD_PROF_SORT, st);
     rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
@@ -536,7 +538,7 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   if (rc) return rc;
   // two list lengths, kept beside the device counters (cleared by every call)
   uint32_t *counts = (uint32_t *)(stats + SEDD_STAT_VERIFY_COUNTS);
-  const int bits = grouping_bits(n_docs);
+  const int bits = grouping_bits(n_docs, 4096);
   {
     ProfScope prof(SEDD_PROF_SORT, st);
     rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
