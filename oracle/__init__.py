@@ -55,6 +55,8 @@ def _load():
         lib.sedd_ref_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp]
         lib.sedd_ref_cluster.restype = C.c_int
         lib.sedd_ref_cluster.argtypes = [vp, u64, i32, vp]
+        lib.sedd_ref_lsh_dense_keys.restype = C.c_int
+        lib.sedd_ref_lsh_dense_keys.argtypes = [vp, u64, i32, i32, i32, u64, vp]
         lib.sedd_ref_cluster_verified.restype = C.c_int
         lib.sedd_ref_cluster_verified.argtypes = [vp, vp, u64, i32, i32, i32, vp]
         _lib = lib
@@ -154,6 +156,24 @@ def cluster(keys) -> np.ndarray:
     if rc:
         raise OracleError(rc)
     return cid
+
+
+def dense_bucket_count(n_docs: int, k: int = 4) -> int:
+    """The paper's number of buckets, k * sqrt(N) with k = 4 (Section 3.2), as the integer
+    floor(sqrt(k^2 N)), at least 1."""
+    import math
+    return max(1, math.isqrt(k * k * int(n_docs)))
+
+
+def lsh_dense_keys(sig, b: int, r: int, n_buckets: int) -> np.ndarray:
+    """Dense bucket ids: sum of the band's values modulo the number of buckets (Section 3.2)."""
+    sig = np.ascontiguousarray(sig, dtype=np.uint32)
+    n_docs, K = sig.shape
+    keys = np.zeros((n_docs, max(b, 0)), dtype=np.uint64)
+    rc = _load().sedd_ref_lsh_dense_keys(_ptr(sig), n_docs, K, b, r, int(n_buckets), _ptr(keys))
+    if rc:
+        raise OracleError(rc)
+    return keys
 
 
 def min_match_for(theta: float, K: int) -> int:

@@ -313,3 +313,25 @@ int sedd_ref_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_
   free(parent); free(col); free(lowest);
   return SEDD_REF_OK;
 }
+
+/*
+ * Dense bucket ids (Section 3.2, last paragraph): the r values of a band are summed and the
+ * bucket is the remainder of the sum modulo the number of buckets,
+ *   key[d*b + j] = (sum_{i<r} sig[d*K + j*r + i]) mod n_buckets.
+ * The sum is the exact integer (it stays below r * 2^32).  The paper sets the number of buckets
+ * to 4 sqrt(N); the caller passes it.  Buckets are deliberately coarse: they only propose
+ * candidate pairs, which sedd_ref_cluster_verified then tests on the full signatures.
+ */
+int sedd_ref_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, int32_t r,
+                            uint64_t n_buckets, uint64_t *keys) {
+  if (K < 1 || b < 1 || r < 1 || (int64_t)b * r > K || n_buckets < 1) return SEDD_REF_EINVAL;
+  if (n_docs == 0) return SEDD_REF_OK;
+  if (!sig || !keys) return SEDD_REF_EINVAL;
+  for (uint64_t d = 0; d < n_docs; d++)
+    for (int32_t j = 0; j < b; j++) {
+      u128 sum = 0;
+      for (int32_t i = 0; i < r; i++) sum += sig[d * (uint64_t)K + (uint64_t)j * r + i];
+      keys[d * (uint64_t)b + j] = (uint64_t)(sum % n_buckets);
+    }
+  return SEDD_REF_OK;
+}

@@ -139,3 +139,75 @@ def test_argument_validation():
     with pytest.raises(oracle.OracleError):
         oracle.cluster_verified(keys, sig, -1)
     assert oracle.cluster_verified(keys[:0], sig[:0], 1).size == 0
+
+
+# ---- dense bucket ids (Section 3.2: sum of the band's values modulo the number of buckets) ----
+
+def test_dense_keys_closed_form_and_range():
+    rng = np.random.default_rng(21)
+    for (K, b, r, nb) in [(128, 16, 8, 4000), (64, 64, 1, 7), (40, 3, 7, 1), (256, 32, 8, 12649),
+                          (16, 1, 16, (1 << 40) + 5)]:
+        sig = rng.integers(0, 1 << 32, size=(9, K), dtype=np.uint64).astype(np.uint32)
+        sig[0] = 0xFFFFFFFF                       # the sum must not wrap at 32 or 64 bits
+        sig[1] = 0
+        keys = oracle.lsh_dense_keys(sig, b, r, nb)
+        assert keys.shape == (9, b) and (keys < np.uint64(nb)).all()
+        for d in range(9):
+            for j in range(b):
+                want = sum(int(v) for v in sig[d, j * r:(j + 1) * r]) % nb
+                assert int(keys[d, j]) == want
+    # hand values: band (1, 2, 3) -> 6 mod 4 = 2; all-ones band of 8 -> 8 (2^32 - 1) mod 1000
+    assert int(oracle.lsh_dense_keys(np.array([[1, 2, 3]], np.uint32), 1, 3, 4)[0, 0]) == 2
+    assert int(oracle.lsh_dense_keys(np.full((1, 8), 0xFFFFFFFF, np.uint32), 1, 8, 1000)[0, 0]) \
+        == (8 * 0xFFFFFFFF) % 1000 == 360
+
+
+def test_dense_keys_depend_on_the_band_as_a_multiset_and_only_on_leading_columns():
+    rng = np.random.default_rng(22)
+    sig = rng.integers(0, 1 << 32, size=(50, 32), dtype=np.uint64).astype(np.uint32)
+    keys = oracle.lsh_dense_keys(sig, 3, 8, 977)
+    perm = sig.copy()
+    perm[:, :8] = sig[:, 7::-1]                   # a sum does not see the order inside a band
+    assert np.array_equal(oracle.lsh_dense_keys(perm, 3, 8, 977), keys)
+    tail = sig.copy()
+    tail[:, 24:] ^= 0x1234
+    assert np.array_equal(oracle.lsh_dense_keys(tail, 3, 8, 977), keys)
+    # equal bands give equal buckets; r = 1 is the value modulo the count
+    assert np.array_equal(oracle.lsh_dense_keys(sig, 32, 1, 1013), sig.astype(np.uint64) % np.uint64(1013))
+
+
+def test_dense_buckets_are_balanced_and_coarse():
+    """Random signatures spread evenly over the buckets (the paper's bucket-balance analysis):
+    with N = 40000 and 4 sqrt(N) = 800 buckets the mean bucket holds 50 documents."""
+    rng = np.random.default_rng(23)
+    n = 40_000
+    nb = oracle.dense_bucket_count(n)
+    assert nb == 800 and oracle.dense_bucket_count(1_000_000) == 4000
+    assert oracle.dense_bucket_count(32_800_000, k=2) == 11454       # floor(2 sqrt(N))
+    sig = rng.integers(0, 1 << 32, size=(n, 8), dtype=np.uint64).astype(np.uint32)
+    keys = oracle.lsh_dense_keys(sig, 1, 8, nb)[:, 0]
+    counts = np.bincount(keys.astype(np.int64), minlength=nb)
+    assert counts.sum() == n and abs(counts.mean() - 50) < 1e-9
+    assert counts.std() < 2 * np.sqrt(50) and counts.max() < 50 + 6 * np.sqrt(50)
+
+
+def test_dense_buckets_with_verification_find_the_planted_duplicates():
+    """Coarse buckets propose many candidate pairs; the count-match test keeps the real ones."""
+    rng = np.random.default_rng(24)
+    n, K, b, r = 3000, 64, 8, 8
+    sig = rng.integers(0, 1 << 32, size=(n, K), dtype=np.uint64).astype(np.uint32)
+    src = rng.choice(n // 2, size=200, replace=False)
+    dup = n // 2 + np.arange(200)
+    sig[dup] = sig[src]
+    noisy = rng.random((200, K)) < 0.1            # about 90 % of the entries still agree
+    sig[dup] = np.where(noisy, rng.integers(0, 1 << 32, size=(200, K), dtype=np.uint64).astype(np.uint32), sig[dup])
+    keys = oracle.lsh_dense_keys(sig, b, r, oracle.dense_bucket_count(n))
+    cid = oracle.cluster_verified(keys, sig, oracle.min_match_for(0.8, K))
+    same_band = (sig[dup].reshape(200, b, r) == sig[src].reshape(200, b, r)).all(axis=2).any(axis=1)
+    enough = (sig[dup] == sig[src]).sum(axis=1) >= oracle.min_match_for(0.8, K)
+    found = cid[dup] == cid[src]
+    assert (found >= (same_band & enough)).all()  # an untouched band + enough agreement: found
+    assert found.sum() >= 150
+    others = np.setdiff1d(np.arange(n), np.concatenate([src, dup]))
+    assert (cid[others] == others).all()          # random documents never verify
+    assert np.array_equal(cid, _verified_bruteforce(keys, sig, oracle.min_match_for(0.8, K)))
