@@ -86,6 +86,18 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
                   uint64_t *keys, void *stream);
 
 /*
+ * Dense bucket ids (Section 3.2, last paragraph: the r values of a band are summed and the
+ * remainder modulo the number of buckets is the bucket).  key[d*b + j] =
+ * (sum_{i<r} sig[d*K + j*r + i]) mod n_buckets, the sum being the exact integer.  The paper sets
+ * n_buckets = 4 sqrt(n_docs).  These buckets are coarse on purpose: they only propose candidate
+ * pairs and are meant to be followed by sedd_cluster_verified, not by sedd_cluster.
+ *
+ * sig, keys as in sedd_lsh_keys; 1 <= n_buckets < 2^61.
+ */
+int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, int32_t r,
+                        uint64_t n_buckets, uint64_t *keys, void *stream);
+
+/*
  * Bucket grouping into duplicate clusters (Section 2.2 "Constructing a union graph" and
  * "Generating the final list of duplicates"; Appendix A.2: per-band graphs are merged).
  * Documents u, v are linked when keys[u*b + j] == keys[v*b + j] for some band j (same j on
@@ -107,9 +119,11 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
  * integers.  min_match = 0 gives the clusters of sedd_cluster.
  *
  * keys, cluster_id as in sedd_cluster; sig device, uint32[n_docs*K], all K columns are compared.
- * Cost: every document of a bucket is compared with the bucket's first document, and only those
- * that fail with the rest of the bucket, which yields the components of the exhaustive
- * comparison without its quadratic cost on buckets of alike documents.
+ * Cost: in a bucket of at most 64 documents every document is compared with the bucket's first
+ * document, and only those that fail with the rest of the bucket.  A larger bucket is compared
+ * all pairs, 64 x 64 documents at a time through LDS, first against its leading 64 documents;
+ * blocks of pairs whose documents are all joined to the bucket's first document by then are
+ * skipped.  Both yield the components of the exhaustive comparison.
  */
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
                           int32_t b, int32_t min_match, int64_t *cluster_id, void *stream);

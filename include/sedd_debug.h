@@ -52,9 +52,10 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
  * (waits for the device to go idle first).
  */
 #define SEDD_STAT_SLOW_TILES 0 /* shingle tiles the min-hash kernel recomputed on its exact path */
-#define SEDD_STAT_VERIFY_COUNTS 1 /* sedd_cluster_verified of the last call: low word = records
-                                     compared with their bucket's first record, high word = records
-                                     then compared with their whole bucket */
+#define SEDD_STAT_VERIFY_COUNTS 1 /* sedd_cluster_verified, last call: two 64-bit slots holding four
+                                     32-bit counts: records compared with their bucket's first
+                                     record, records then compared with their whole bucket, buckets
+                                     compared tile by tile, unused */
 #define SEDD_STAT_N 16
 int sedd_debug_stats(uint64_t *out);
 

@@ -17,7 +17,7 @@ import os
 
 __all__ = [
     "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
-    "sedd_cluster_verified", "min_match_for",
+    "sedd_cluster_verified", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
@@ -60,6 +60,8 @@ def lib():
         L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
         L.sedd_cluster.restype = C.c_int
         L.sedd_cluster.argtypes = [vp, u64, i32, vp, vp]
+        L.sedd_lsh_dense_keys.restype = C.c_int
+        L.sedd_lsh_dense_keys.argtypes = [vp, u64, i32, i32, i32, u64, vp, vp]
         L.sedd_cluster_verified.restype = C.c_int
         L.sedd_cluster_verified.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
         L.sedd_strerror.restype = C.c_char_p
@@ -175,6 +177,28 @@ def sedd_cluster(keys, out=None, stream=None):
         if out.numel() != n_docs:
             raise ValueError("out has the wrong size")
     _check(lib().sedd_cluster(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)), "sedd_cluster")
+    return out
+
+
+def dense_bucket_count(n_docs: int, k: int = 4) -> int:
+    """Number of dense buckets the paper uses, k * sqrt(N) with k = 4: floor(sqrt(k^2 N)), >= 1."""
+    import math
+    return max(1, math.isqrt(k * k * int(n_docs)))
+
+
+def sedd_lsh_dense_keys(sig, b: int, r: int, n_buckets: int, out=None, stream=None):
+    """uint64 [n_docs, b] dense bucket ids: band sum modulo n_buckets (Section 3.2)."""
+    torch = _torch()
+    sig = _dev(sig, torch.uint32, "sig")
+    n_docs, K = sig.shape
+    if out is None:
+        out = torch.empty((n_docs, max(b, 0)), dtype=torch.uint64, device=sig.device)
+    else:
+        out = _dev(out, torch.uint64, "out")
+        if out.numel() != n_docs * b:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_lsh_dense_keys(_ptr(sig), n_docs, K, b, r, int(n_buckets), _ptr(out),
+                                     _stream(stream)), "sedd_lsh_dense_keys")
     return out
 
 

@@ -21,6 +21,20 @@ k_lsh_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int 
   keys[idx] = acc;
 }
 
+// Dense bucket id (Section 3.2): sum of the band's r values modulo the number of buckets.
+__global__ void __launch_bounds__(256)
+k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int r,
+                 uint64_t n_buckets, uint64_t *__restrict__ keys) {
+  uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_docs * (uint64_t)b) return;
+  uint64_t d = idx / (uint32_t)b;
+  uint32_t j = (uint32_t)(idx - d * (uint32_t)b);
+  const uint32_t *src = sig + d * (uint64_t)K + (uint64_t)j * r;
+  uint64_t sum = 0;  // r <= SEDD_MAX_K values below 2^32: no overflow
+  for (int i = 0; i < r; i++) sum += src[i];
+  keys[idx] = sum % n_buckets;
+}
+
 // ---- radix sort of (key, doc) per band ---------------------------------------------------
 //
 // Records of band j live in [j*n, (j+1)*n) of band-major arrays.  Stable passes over 8-bit
@@ -223,6 +237,10 @@ k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, ui
 // The components, and so the cluster ids, are exactly those of the exhaustive comparison.
 
 constexpr int TEAM = 16;  // lanes that compare one pair of signatures
+struct BigGroup {  // a group of more than BIG_GROUP records (verified path)
+  uint32_t start, size;
+};
+constexpr uint32_t BIG_GROUP = 64;
 
 // slot for every lane with pred set, taken from *counter by one atomic per wavefront
 __device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
@@ -236,11 +254,14 @@ __device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
   return pred ? base + (uint32_t)__popcll(m & ((uint64_t(1) << lane) - 1)) : 0xFFFFFFFFu;
 }
 
-// records that are not the first of their group: one list entry each, one atomic per block of
-// SORT_TILE records
+// Records that are not the first of their group go to list1 (one atomic per block of SORT_TILE
+// records), except those that can see, BIG_GROUP records before or after them, a record of their
+// own group: their group is large and is compared tile by tile instead.  The first record of a
+// large group appends the group to `big`.
 __global__ void __launch_bounds__(SORT_THREADS)
 k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
-         uint32_t *__restrict__ list1, uint32_t *__restrict__ counts) {
+         uint32_t *__restrict__ list1, uint32_t *__restrict__ counts,
+         BigGroup *__restrict__ big) {
   __shared__ uint32_t s_base;
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const uint64_t *src = bk + (uint64_t)band * n;
@@ -248,7 +269,27 @@ k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; it++) {
     const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
-    if (e < n && e > 0 && ((src[e] ^ src[e - 1]) & mask) == 0) flags |= 1u << it;
+    if (e >= n) continue;
+    const uint64_t low = src[e] & mask;
+    const bool follower = e > 0 && (src[e - 1] & mask) == low;
+    const bool far_after = e + BIG_GROUP < n && (src[e + BIG_GROUP] & mask) == low;
+    if (follower) {
+      const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
+      if (!far_before && !far_after) flags |= 1u << it;
+    } else if (far_after) {
+      // head of a large group: its end by binary search over the rest of the band
+      uint32_t lo = e + BIG_GROUP + 1, hi = n;
+      while (lo < hi) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if ((src[mid] & mask) > low) hi = mid;
+        else lo = mid + 1;
+      }
+      const uint32_t slot = atomicAdd(counts + 2, 1u);
+      BigGroup g;
+      g.start = band * n + e;
+      g.size = lo - e;
+      big[slot] = g;
+    }
   }
   uint32_t tot;
   const uint32_t pre = block_exclusive_scan<SORT_THREADS>(__popc(flags), &tot);
@@ -346,8 +387,11 @@ k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
       const uint64_t key = bk[i];
       const uint32_t band0 = (i / n) * n;
       const uint32_t gs = group_lower_bound(bk, mask, band0, i, key & mask);
-      bool joined = false;
-      if (bk[gs] == key) joined = team_verify_pair(sig, K, min_match, parent, bd[gs], bd[i], tl);
+      // a group of more than BIG_GROUP records is compared tile by tile (k_v_tiles)
+      const bool large = gs + BIG_GROUP < band0 + n && ((bk[gs + BIG_GROUP] ^ key) & mask) == 0;
+      bool joined = large;
+      if (!large && bk[gs] == key)
+        joined = team_verify_pair(sig, K, min_match, parent, bd[gs], bd[i], tl);
       outsider = !joined && tl == 0;
     }
     const uint32_t slot = wave_append(outsider, counts + 1);
@@ -380,6 +424,184 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
   }
 }
 
+// ---- large groups: all pairs, tile by tile (the count-match kernel of Section 3.3) -------------
+//
+// A large group is cut into tiles of VT records.  Tile (ti, tj), ti <= tj, compares the records
+// of tile ti with those of tile tj: 256 threads, each accumulating the equal-entry counts of a
+// 4 x 4 block of pairs while the two tiles' signatures pass through LDS VKC columns at a time
+// (stored column-major so that a thread reads its 4 + 4 values with two 16-byte LDS loads).
+// Pairs at or above min_match (and with equal full keys) are united.
+// Phase 0 runs the tiles (0, tj) of every group, phase 1 the others; a phase-1 tile whose records
+// are all in the component of the group's first record already is skipped, which keeps a large
+// group of alike documents (exact copies, empty documents) linear instead of quadratic.
+
+constexpr int VT = 64;
+constexpr int VKC = 32;
+
+// exclusive prefix sums over the large groups of their phase-0 and phase-1 tile counts
+__global__ void __launch_bounds__(1024)
+k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts,
+               uint64_t big_cap, uint64_t *__restrict__ pre) {
+  __shared__ uint64_t s_part[1024 / 64];
+  __shared__ uint64_t s_carry[2];
+  const uint32_t nb = min((uint64_t)counts[2], big_cap);
+  uint64_t *pre0 = pre, *pre1 = pre + big_cap + 1;
+  if (threadIdx.x < 2) s_carry[threadIdx.x] = 0;
+  __syncthreads();
+  for (uint32_t base = 0; base < nb; base += 1024) {
+    const uint32_t g = base + threadIdx.x;
+    uint64_t v[2] = {0, 0};
+    if (g < nb) {
+      const uint64_t T = (big[g].size + VT - 1) / VT;
+      v[0] = T;
+      v[1] = T * (T - 1) / 2;
+    }
+    for (int which = 0; which < 2; which++) {
+      // block-wide exclusive scan of v[which]
+      uint64_t inc = v[which];
+      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+      }
+      __syncthreads();
+      if (lane == 63) s_part[wave] = inc;
+      __syncthreads();
+      uint64_t before = s_carry[which];
+      for (int w = 0; w < wave; w++) before += s_part[w];
+      if (g < nb) (which ? pre1 : pre0)[g] = before + inc - v[which];
+      __syncthreads();
+      if (threadIdx.x == 1023) s_carry[which] = before + inc;
+      __syncthreads();
+    }
+  }
+  if (threadIdx.x == 0) {
+    pre0[nb] = s_carry[0];
+    pre1[nb] = s_carry[1];
+  }
+}
+
+__global__ void __launch_bounds__(256)
+k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
+          const uint32_t *__restrict__ sig, int K, int min_match, uint32_t *parent,
+          const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts, uint64_t big_cap,
+          const uint64_t *__restrict__ pre_all) {
+  __shared__ uint32_t sm[VKC][2 * VT];  // [column][record]: records 0..63 of tile ti, 64..127 of tile tj
+  __shared__ uint32_t sm_doc[2 * VT];
+  __shared__ uint64_t sm_key[2 * VT];
+  const uint32_t nb = min((uint64_t)counts[2], big_cap);
+  const uint64_t *pre = pre_all + (phase ? big_cap + 1 : 0);
+  const uint64_t total = pre[nb];
+  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
+  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
+    // group of tile t: last g with pre[g] <= t
+    uint32_t lo = 0, hi = nb;
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (pre[mid] <= t) lo = mid;
+      else hi = mid;
+    }
+    const BigGroup g = big[lo];
+    const uint64_t local = t - pre[lo];
+    const uint64_t T = (g.size + VT - 1) / VT;
+    uint64_t ti, tj;
+    if (phase == 0) {
+      ti = 0;
+      tj = local;
+    } else {
+      // tiles (ti, tj) with 1 <= ti <= tj < T in row-major order; row ti starts at
+      // off(ti) = (ti - 1) T - (ti - 1) ti / 2
+      uint64_t r = (uint64_t)((2.0 * (double)T - 1.0 -
+                               sqrt((2.0 * (double)T - 1.0) * (2.0 * (double)T - 1.0) -
+                                    8.0 * (double)local)) * 0.5) + 1;
+      if (r < 1) r = 1;
+      if (r > T - 1) r = T - 1;
+      while (r > 1 && (r - 1) * T - (r - 1) * r / 2 > local) r--;
+      while (r + 1 <= T - 1 && r * T - r * (r + 1) / 2 <= local) r++;
+      ti = r;
+      tj = ti + (local - ((ti - 1) * T - (ti - 1) * ti / 2));
+    }
+    __syncthreads();  // the previous tile's LDS reads are done
+    bool alike = true;
+    if (tid < 2 * VT) {
+      const uint64_t rec = (tid < VT ? ti * VT + tid : tj * VT + (tid - VT));
+      uint32_t doc = 0xFFFFFFFFu;
+      uint64_t key = 0;
+      if (rec < g.size) {
+        doc = bd[g.start + rec];
+        key = bk[g.start + rec];
+        if (phase) alike = uf_find(parent, doc) == uf_find(parent, bd[g.start]);
+      }
+      sm_doc[tid] = doc;
+      sm_key[tid] = key;
+    }
+    if (phase && __syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
+
+    uint32_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) acc[i][j] = 0;
+    for (int kc = 0; kc < K; kc += VKC) {
+      __syncthreads();  // sm_doc visible; previous chunk consumed
+      {
+        // thread -> (record, half of the chunk): 16 columns of one record, written column-major
+        const int rec = tid >> 1, c0 = (tid & 1) * (VKC / 2);
+        const uint32_t doc = sm_doc[rec];
+        uint32_t v[VKC / 2];
+#pragma unroll
+        for (int c = 0; c < VKC / 2; c++) v[c] = 0;
+        if (doc != 0xFFFFFFFFu) {
+          const uint32_t *row = sig + (uint64_t)doc * K + kc + c0;
+          if (vec_ok && kc + c0 + VKC / 2 <= K) {
+#pragma unroll
+            for (int c = 0; c < VKC / 2; c += 4) {
+              const uint4 q = *reinterpret_cast<const uint4 *>(row + c);
+              v[c] = q.x; v[c + 1] = q.y; v[c + 2] = q.z; v[c + 3] = q.w;
+            }
+          } else {
+#pragma unroll
+            for (int c = 0; c < VKC / 2; c++)
+              if (kc + c0 + c < K) v[c] = row[c];
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < VKC / 2; c++) sm[c0 + c][rec] = v[c];
+      }
+      __syncthreads();
+      const int kmax = min(VKC, K - kc);
+      auto step = [&](int k) {
+        const uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[k][ty * 4]);
+        const uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[k][VT + tx * 4]);
+        const uint32_t rv[4] = {r4.x, r4.y, r4.z, r4.w};
+        const uint32_t cv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) acc[i][j] += rv[i] == cv[j];
+      };
+      if (kmax == VKC) {
+#pragma unroll 8
+        for (int k = 0; k < VKC; k++) step(k);
+      } else {
+        for (int k = 0; k < kmax; k++) step(k);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const int ri = ty * 4 + i, cj = VT + tx * 4 + j;
+        const uint32_t u = sm_doc[ri], v = sm_doc[cj];
+        if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) continue;
+        if (ti == tj && ri >= cj - VT) continue;  // upper triangle of a diagonal tile
+        if ((int)acc[i][j] >= min_match && sm_key[ri] == sm_key[cj]) uf_unite(parent, u, v);
+      }
+  }
+}
+
 __global__ void k_write_roots(uint32_t *parent, uint32_t n, int64_t *__restrict__ cluster_id) {
   uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) cluster_id[i] = (int64_t)uf_find(parent, i);
@@ -398,6 +620,9 @@ __global__ void k_copy_sorted(const uint64_t *__restrict__ bk, const uint32_t *_
 struct SortBufs {
   uint64_t *ka, *kb;
   uint32_t *da, *db, *hist, *tmp, *parent;
+  BigGroup *big;       // capacity big_cap
+  uint64_t *tile_pre;  // 2 * (big_cap + 1) prefix sums of tile counts
+  uint64_t big_cap;
   uint32_t nblk;
 };
 
@@ -410,9 +635,14 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
   const uint64_t o_da = cv.take<uint32_t>(total), o_db = cv.take<uint32_t>(total);
   const uint64_t o_h = cv.take<uint32_t>(nh), o_t = cv.take<uint32_t>(scan_tmp_count(nh));
   const uint64_t o_p = cv.take<uint32_t>(n);
+  const uint64_t big_cap = total / BIG_GROUP + 1;
+  const uint64_t o_big = cv.take<BigGroup>(big_cap), o_pre = cv.take<uint64_t>(2 * (big_cap + 1));
   uint8_t *A = nullptr;
   int rc = scratch_ensure(cv.off, &A);
   if (rc) return rc;
+  sb->big = (BigGroup *)(A + o_big);
+  sb->tile_pre = (uint64_t *)(A + o_pre);
+  sb->big_cap = big_cap;
   sb->ka = (uint64_t *)(A + o_ka);
   sb->kb = (uint64_t *)(A + o_kb);
   sb->da = (uint32_t *)(A + o_da);
@@ -486,6 +716,22 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
   return SEDD_OK;
 }
 
+int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, int32_t r,
+                        uint64_t n_buckets, uint64_t *keys, void *stream) {
+  hipStream_t st = (hipStream_t)stream;
+  if (K < 1 || K > SEDD_MAX_K || b < 1 || r < 1 || (int64_t)b * r > K) return SEDD_EINVAL;
+  if (n_buckets < 1 || n_buckets >= (uint64_t(1) << 61)) return SEDD_EINVAL;
+  if (n_docs == 0) return SEDD_OK;
+  if (!sig || !keys || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  const uint64_t total = n_docs * (uint64_t)b;
+  if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  ProfScope prof(SEDD_PROF_LSH_KEYS, st);
+  hipLaunchKernelGGL(k_lsh_dense_keys, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sig,
+                     n_docs, (int)K, (int)b, (int)r, n_buckets, keys);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
 static int check_cluster_args(const void *keys, uint64_t n_docs, int32_t b, const void *out) {
   if (b < 1 || b > SEDD_MAX_BANDS) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
@@ -536,7 +782,8 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   unsigned long long *stats = nullptr;
   rc = stats_ensure(&stats);
   if (rc) return rc;
-  // two list lengths, kept beside the device counters (cleared by every call)
+  // list lengths (followers, outsiders, large groups), kept beside the device counters and
+  // cleared by every call
   uint32_t *counts = (uint32_t *)(stats + SEDD_STAT_VERIFY_COUNTS);
   const int bits = grouping_bits(n_docs, 4096);
   {
@@ -552,11 +799,20 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   uint32_t *list1 = (uint32_t *)sb.kb, *list2 = sb.db;
   hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 2u, 0u);
+  hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 4u, 0u);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
-                     list1, counts);
+                     list1, counts, sb.big);
   SEDD_LAUNCH_CHECK();
+  // large groups: tile plan, then the tiles against each group's first tile, then the rest
+  hipLaunchKernelGGL(k_v_plan_tiles, dim3(1), dim3(1024), 0, st, sb.big, counts, sb.big_cap,
+                     sb.tile_pre);
+  SEDD_LAUNCH_CHECK();
+  for (int phase = 0; phase < 2; phase++) {
+    hipLaunchKernelGGL(k_v_tiles, dim3(256 * 8), dim3(256), 0, st, phase, sb.ka, sb.da, sig, (int)K,
+                       (int)min_match, sb.parent, sb.big, counts, sb.big_cap, sb.tile_pre);
+    SEDD_LAUNCH_CHECK();
+  }
   // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
   const uint32_t grid = 256 * 16;
   hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,

@@ -502,3 +502,71 @@ def test_cluster_verified_rejects_bad_arguments(sedd):
         sedd.sedd_cluster_verified(keys, sig, -1)
     with pytest.raises(ValueError):
         sedd.sedd_cluster_verified(keys, sig[:3], 1)
+
+
+# ---- dense buckets (Section 3.2) and the tiled count-match path -------------------------------
+
+@pytest.mark.parametrize("K,b,r,nb", [(128, 16, 8, 4000), (64, 64, 1, 7), (40, 3, 7, 1),
+                                      (256, 32, 8, 12649), (16, 1, 16, (1 << 40) + 5)])
+def test_lsh_dense_keys_parity(sedd, K, b, r, nb):
+    say("dense keys", K, b, r, nb)
+    rng = np.random.default_rng(K + b)
+    sig = rng.integers(0, 1 << 32, size=(3001, K), dtype=np.uint64).astype(np.uint32)
+    sig[0] = 0xFFFFFFFF
+    sig[1] = 0
+    got = host(sedd.sedd_lsh_dense_keys(dev(sig), b, r, nb))
+    assert np.array_equal(got, oracle.lsh_dense_keys(sig, b, r, nb))
+
+
+def _planted_signatures(seed, n, K, n_dup, keep=0.9):
+    rng = np.random.default_rng(seed)
+    sig = rng.integers(0, 1 << 32, size=(n, K), dtype=np.uint64).astype(np.uint32)
+    src = rng.choice(n // 2, size=n_dup, replace=False)
+    dup = n // 2 + np.arange(n_dup)
+    noisy = rng.random((n_dup, K)) >= keep
+    sig[dup] = np.where(noisy, rng.integers(0, 1 << 32, size=(n_dup, K), dtype=np.uint64).astype(np.uint32),
+                        sig[src])
+    return sig
+
+
+@pytest.mark.parametrize("n,K,b,r,k_buckets", [(6000, 64, 8, 8, 4), (40_000, 32, 4, 8, 1),
+                                               (100_000, 64, 8, 8, 4), (30_000, 100, 5, 20, 2)])
+def test_dense_buckets_then_verified_clusters(sedd, n, K, b, r, k_buckets):
+    """The paper's own flow: coarse buckets of tens to hundreds of documents, all pairs inside
+    a bucket compared on the full signatures."""
+    say("dense + verified", n, K, b, r, k_buckets)
+    sig = _planted_signatures(n, n, K, n // 20)
+    nb = oracle.dense_bucket_count(n, k_buckets)
+    wkeys = oracle.lsh_dense_keys(sig, b, r, nb)
+    d_sig = dev(sig)
+    keys = sedd.sedd_lsh_dense_keys(d_sig, b, r, nb)
+    assert np.array_equal(host(keys), wkeys)
+    for theta in (0.8, 0.5):
+        mm = oracle.min_match_for(theta, K)
+        got = host(sedd.sedd_cluster_verified(keys, d_sig, mm))
+        want = oracle.cluster_verified(wkeys, sig, mm)
+        assert np.array_equal(got, want), theta
+    say("  buckets", nb, "mean size", n / nb, "duplicates", int((want != np.arange(n)).sum()))
+
+
+def test_verified_clusters_mixed_small_and_large_groups(sedd):
+    """Buckets of 1 to 400 documents in one call; signatures from a few prototypes so that many
+    pairs verify, some chains form and some large groups are entirely alike."""
+    say("verified mixed group sizes")
+    rng = np.random.default_rng(5)
+    sizes = np.concatenate([rng.integers(1, 8, size=300), rng.integers(60, 70, size=10),
+                            rng.integers(100, 400, size=6), [65, 64, 63, 128, 129, 1]])
+    n = int(sizes.sum())
+    keys = np.zeros((n, 2), dtype=np.uint64)
+    keys[:, 0] = np.repeat(np.arange(sizes.size), sizes) * 7919
+    keys[:, 1] = rng.integers(0, n // 3, size=n)
+    perm = rng.permutation(n)
+    keys = keys[perm]
+    K = 48
+    proto = rng.integers(0, 1 << 32, size=(12, K), dtype=np.uint64).astype(np.uint32)
+    sig = proto[rng.integers(0, 12, size=n)].copy()
+    flip = rng.random((n, K)) < rng.random((n, 1)) * 0.5
+    sig[flip] = rng.integers(0, 1 << 32, size=int(flip.sum()), dtype=np.uint64).astype(np.uint32)
+    for mm in (0, 24, 39, 48):
+        got = host(sedd.sedd_cluster_verified(dev(keys), dev(sig), mm))
+        assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
