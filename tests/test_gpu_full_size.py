@@ -290,3 +290,40 @@ def test_config5_full_size_sweep(sedd):
             if K != 512:
                 del sig
         del sig512
+
+
+def test_dense_buckets_on_documents(sedd):
+    """The paper's candidate generation on real signatures: 300k documents of the medium
+    workload, 4 sqrt(N) = 2190 buckets of about 137 documents per band, every pair of a bucket
+    compared (the tiled count-match path).  Keys against the oracle on sampled documents,
+    cluster ids of all documents against the all-pairs recomputation."""
+    r = corpus.config(2).scaled(300_000)
+    gen = corpus.Corpus(r)
+    say("dense buckets on", r.n_docs, "documents of config 2")
+    data, off = gen.generate()
+    sig = sedd.sedd_minhash(torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(),
+                            r.shingle_n, r.K)
+    nb = sedd.dense_bucket_count(r.n_docs)
+    assert nb == oracle.dense_bucket_count(r.n_docs) == 2190
+    keys = sedd.sedd_lsh_dense_keys(sig, r.b, r.r, nb)
+    ids, _ = _sample_docs(gen, r, [(0, r.n_docs)], np.diff(off), n_random=1000, n_longest=2,
+                          n_copies=0, seed=6)
+    want_sig = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 0)
+    _check_sampled_signatures(sig, ids, want_sig, r.K, "dense")
+    got_keys = keys.view(torch.int64)[torch.from_numpy(ids).cuda()].cpu().numpy().view(np.uint64)
+    assert np.array_equal(got_keys, oracle.lsh_dense_keys(want_sig, r.b, r.r, nb))
+    mm = sedd.min_match_for(0.8, r.K)
+    cid = sedd.sedd_cluster_verified(keys, sig, mm)
+    torch.cuda.synchronize()
+    want, n_pairs, n_edges = _verified_components_min_label(keys, sig, r.n_docs, r.b, mm,
+                                                            max_bucket=1024)
+    got = cid.cpu().numpy()
+    bad = np.nonzero(got != want)[0]
+    assert bad.size == 0, f"{bad.size} cluster ids differ, first {bad[:5]}"
+    # the sparse 61-bit keys find the same verified pairs wherever a whole band agrees; dense
+    # buckets can only add pairs to those
+    sparse = sedd.sedd_cluster_verified(sedd.sedd_lsh_keys(sig, r.b, r.r), sig, mm).cpu().numpy()
+    assert (got[sparse] == got).all()
+    say(f"  {n_pairs} candidate pairs, {n_edges} verified, "
+        f"{int((got != np.arange(r.n_docs)).sum())} duplicates "
+        f"({int((sparse != np.arange(r.n_docs)).sum())} with sparse keys)")
