@@ -65,14 +65,13 @@ int sedd_debug_stats(uint64_t *out);
  * the elapsed milliseconds and the number of timed spans per stage into the HOST arrays
  * ms[SEDD_PROF_N], spans[SEDD_PROF_N], and forgets them.
  */
-#define SEDD_PROF_MINHASH 0      /* K hash functions + minimum (the dominant kernel) */
-#define SEDD_PROF_SHINGLE_HASH 1 /* Eq. 1 base hash per shingle */
-#define SEDD_PROF_TOKENIZE 2     /* token marking, counting and token records */
-#define SEDD_PROF_WORKLIST 3     /* tile lists and scans */
-#define SEDD_PROF_LSH_KEYS 4
-#define SEDD_PROF_SORT 5
-#define SEDD_PROF_UNION 6
-#define SEDD_PROF_VERIFY 7       /* pairwise signature comparison inside buckets + union-find */
+#define SEDD_PROF_MINHASH 0  /* Eq. 1 per shingle + K hash functions + minimum (the dominant kernel) */
+#define SEDD_PROF_TOKENIZE 1 /* token marking, counting and token records */
+#define SEDD_PROF_WORKLIST 2 /* tile lists and scans */
+#define SEDD_PROF_LSH_KEYS 3
+#define SEDD_PROF_SORT 4
+#define SEDD_PROF_UNION 5
+#define SEDD_PROF_VERIFY 6   /* pairwise signature comparison inside buckets + union-find */
 #define SEDD_PROF_N 8
 int sedd_profile_enable(int on);
 int sedd_profile_read(double *ms, uint64_t *spans);

@@ -1,18 +1,19 @@
 // sedd_minhash: shingling, Eq. 1 base hash, K hash functions and per-document minimum.
 //
 // Pipeline per chunk of consecutive documents (all on the caller's stream, no host waits):
-//   1. byte tiles     each non-empty document is cut into 4 KiB tiles aligned to 16-byte
+//   1. byte tiles     each non-empty document is cut into 1 KiB tiles aligned to 16-byte
 //                     addresses; a scan over per-document tile counts builds the work list.
-//   2. words          (word mode) one block per byte tile marks token starts from a 16-byte
-//                     vector load per thread, counts them, and after a scan writes one record
-//                     per token: its Eq. 1 hash W and q^len.
+//   2. words          (word mode) one wavefront per byte tile marks token starts from a 16-byte
+//                     vector load per lane and counts them; after a scan a second pass writes
+//                     one record per token: the Eq. 1 hash of "token 0x20" and the length.
 //   3. shingle tiles  per-document shingle counts, scanned into shingle offsets and a second
 //                     work list of tiles of TS shingles.
-//   4. base hash      one thread per shingle: Horner over n token records (word mode) or over
-//                     n bytes (byte mode) gives x(s) of Eq. 1.
-//   5. min-hash       one wavefront per shingle tile, lane = hash function: the 61-bit
-//                     multiply-add mod 2^61-1, truncation to 32 bits and running minimum.
-//                     This is where the time goes: K modular multiplies per shingle.
+//   4. min-hash       one wavefront per shingle tile.  Phase A (lane = shingle): x(s) of Eq. 1
+//                     by Horner over n token records (word mode) or from the tile's bytes with
+//                     the reuse form of Eq. 2 (byte mode), into LDS.  Phase B (lane = hash
+//                     function): the 61-bit multiply-add mod 2^61-1, truncation to 32 bits and
+//                     running minimum.  This is where the time goes: K modular multiplies per
+//                     shingle.
 #include <algorithm>
 #include <vector>
 

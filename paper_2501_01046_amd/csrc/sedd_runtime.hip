@@ -255,7 +255,6 @@ int sedd_profile_read(double *ms, uint64_t *spans) {
 const char *sedd_profile_label(int label) {
   switch (label) {
     case SEDD_PROF_MINHASH: return "minhash";
-    case SEDD_PROF_SHINGLE_HASH: return "shingle_hash";
     case SEDD_PROF_TOKENIZE: return "tokenize";
     case SEDD_PROF_WORKLIST: return "worklist";
     case SEDD_PROF_LSH_KEYS: return "lsh_keys";
