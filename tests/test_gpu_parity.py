@@ -570,3 +570,45 @@ def test_verified_clusters_mixed_small_and_large_groups(sedd):
     for mm in (0, 24, 39, 48):
         got = host(sedd.sedd_cluster_verified(dev(keys), dev(sig), mm))
         assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
+
+
+# ---- seeded fuzz of tokenisation and shingling ------------------------------------------------
+
+def _fuzz_docs(seed, n_docs):
+    """Documents over a small alphabet rich in every whitespace byte, with lengths that put
+    token and document boundaries at all offsets relative to the 16-byte segments and 1 KiB
+    tiles the kernels work in; some long tokens, some empty and whitespace-only documents."""
+    rng = np.random.default_rng(seed)
+    alphabet = np.frombuffer(b"ab\xc3\xa9z0\x00\x7f\xff \t\n\r\x0b\x0c  ", dtype=np.uint8)
+    docs = []
+    for _ in range(n_docs):
+        kind = rng.integers(0, 10)
+        if kind == 0:
+            docs.append(b"")
+        elif kind == 1:
+            docs.append(bytes(rng.choice(alphabet[-8:], size=int(rng.integers(1, 40)))))
+        elif kind == 2:                                  # long tokens, up to 3 KiB
+            parts = [bytes(rng.integers(97, 123, size=int(l), dtype=np.uint8))
+                     for l in rng.integers(1, 3000, size=int(rng.integers(1, 4)))]
+            docs.append(b" ".join(parts))
+        else:
+            ln = int(rng.integers(1, 2500))
+            docs.append(bytes(rng.choice(alphabet, size=ln)))
+    return docs
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_fuzz_shingle_hashes_and_signatures(sedd, seed):
+    say("fuzz", seed)
+    docs = _fuzz_docs(seed, 400)
+    data, off = _pack(docs, lead=seed % 16)
+    d_data, d_off = dev(data), dev(off)
+    for byte_mode, n in ((False, 1), (False, 3), (False, 5), (True, 1), (True, 4), (True, 13)):
+        wx, woff = _oracle_x(docs, n, byte_mode)
+        x, soff = sedd.debug_shingle_hashes(d_data, d_off, n, int(byte_mode))
+        assert np.array_equal(host(soff), woff), (byte_mode, n)
+        assert np.array_equal(host(x), wx), (byte_mode, n)
+        want = oracle.minhash(data, off, n, 24, seed, int(byte_mode))
+        got = host(sedd.sedd_minhash(d_data, d_off, n, 24, seed, int(byte_mode)))
+        bad = np.nonzero((got != want).any(axis=1))[0]
+        assert bad.size == 0, (byte_mode, n, bad[:5])
