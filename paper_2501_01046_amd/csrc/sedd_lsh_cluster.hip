@@ -438,6 +438,16 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 constexpr int VT = 64;
 constexpr int VKC = 32;
 
+// acc[4 i + j] += (r[i] == c[j]) for the 16 pairs of a 4 x 4 block
+__device__ __forceinline__ void count_match_4x4(uint32_t (&acc)[16], const uint4 r, const uint4 c) {
+  const uint32_t rv[4] = {r.x, r.y, r.z, r.w};
+  const uint32_t cv[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) acc[4 * i + j] += rv[i] == cv[j];
+}
+
 // exclusive prefix sums over the large groups of their phase-0 and phase-1 tile counts
 __global__ void __launch_bounds__(1024)
 k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts,
@@ -495,14 +505,22 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
   const uint64_t total = pre[nb];
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
   const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
-  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
-    // group of tile t: last g with pre[g] <= t
-    uint32_t lo = 0, hi = nb;
+  // every block takes a contiguous range of tiles: one search for the group of its first tile,
+  // after that the group index only moves forward
+  const uint64_t per_block = (total + gridDim.x - 1) / gridDim.x;
+  const uint64_t t_begin = blockIdx.x * per_block;
+  const uint64_t t_end = t_begin + per_block < total ? t_begin + per_block : total;
+  uint32_t lo = 0;
+  {
+    uint32_t hi = nb;  // last g with pre[g] <= t_begin
     while (hi - lo > 1) {
       const uint32_t mid = (lo + hi) >> 1;
-      if (pre[mid] <= t) lo = mid;
+      if (pre[mid] <= t_begin) lo = mid;
       else hi = mid;
     }
+  }
+  for (uint64_t t = t_begin; t < t_end; t++) {
+    while (lo + 1 < nb && pre[lo + 1] <= t) lo++;
     const BigGroup g = big[lo];
     const uint64_t local = t - pre[lo];
     const uint64_t T = (g.size + VT - 1) / VT;
@@ -539,54 +557,63 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
     }
     if (phase && __syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
 
-    uint32_t acc[4][4];
+    uint32_t acc[16];  // acc[4 i + j]: row 4 ty + i against column 4 tx + j
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < 16; i++) acc[i] = 0;
+    // thread -> (record, half of a chunk): 16 columns of one record, stored column-major.  The
+    // values of the next chunk are fetched into registers while the current one is compared.
+    const int l_rec = tid >> 1, l_c0 = (tid & 1) * (VKC / 2);
+    uint32_t v[VKC / 2];
+    auto fetch = [&](int kc) {
+      const uint32_t doc = sm_doc[l_rec];
 #pragma unroll
-      for (int j = 0; j < 4; j++) acc[i][j] = 0;
-    for (int kc = 0; kc < K; kc += VKC) {
-      __syncthreads();  // sm_doc visible; previous chunk consumed
-      {
-        // thread -> (record, half of the chunk): 16 columns of one record, written column-major
-        const int rec = tid >> 1, c0 = (tid & 1) * (VKC / 2);
-        const uint32_t doc = sm_doc[rec];
-        uint32_t v[VKC / 2];
+      for (int c = 0; c < VKC / 2; c++) v[c] = 0;
+      if (doc != 0xFFFFFFFFu) {
+        const uint32_t *row = sig + (uint64_t)doc * K + kc + l_c0;
+        if (vec_ok && kc + l_c0 + VKC / 2 <= K) {
 #pragma unroll
-        for (int c = 0; c < VKC / 2; c++) v[c] = 0;
-        if (doc != 0xFFFFFFFFu) {
-          const uint32_t *row = sig + (uint64_t)doc * K + kc + c0;
-          if (vec_ok && kc + c0 + VKC / 2 <= K) {
-#pragma unroll
-            for (int c = 0; c < VKC / 2; c += 4) {
-              const uint4 q = *reinterpret_cast<const uint4 *>(row + c);
-              v[c] = q.x; v[c + 1] = q.y; v[c + 2] = q.z; v[c + 3] = q.w;
-            }
-          } else {
-#pragma unroll
-            for (int c = 0; c < VKC / 2; c++)
-              if (kc + c0 + c < K) v[c] = row[c];
+          for (int c = 0; c < VKC / 2; c += 4) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(row + c);
+            v[c] = q.x; v[c + 1] = q.y; v[c + 2] = q.z; v[c + 3] = q.w;
           }
+        } else {
+#pragma unroll
+          for (int c = 0; c < VKC / 2; c++)
+            if (kc + l_c0 + c < K) v[c] = row[c];
         }
-#pragma unroll
-        for (int c = 0; c < VKC / 2; c++) sm[c0 + c][rec] = v[c];
       }
+    };
+    __syncthreads();  // sm_doc visible
+    fetch(0);
+    for (int kc = 0; kc < K; kc += VKC) {
+      if (kc) __syncthreads();  // the previous chunk has been compared
+#pragma unroll
+      for (int c = 0; c < VKC / 2; c++) sm[l_c0 + c][l_rec] = v[c];
       __syncthreads();
+      if (kc + VKC < K) fetch(kc + VKC);
       const int kmax = min(VKC, K - kc);
-      auto step = [&](int k) {
-        const uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[k][ty * 4]);
-        const uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[k][VT + tx * 4]);
-        const uint32_t rv[4] = {r4.x, r4.y, r4.z, r4.w};
-        const uint32_t cv[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-          for (int j = 0; j < 4; j++) acc[i][j] += rv[i] == cv[j];
-      };
+      // the LDS reads of column k + 1 are issued before the compares of column k
+      uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[0][ty * 4]);
+      uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[0][VT + tx * 4]);
       if (kmax == VKC) {
 #pragma unroll 8
-        for (int k = 0; k < VKC; k++) step(k);
+        for (int k = 0; k < VKC; k++) {
+          const int kn = k + 1 < VKC ? k + 1 : k;
+          const uint4 rn = *reinterpret_cast<const uint4 *>(&sm[kn][ty * 4]);
+          const uint4 cn = *reinterpret_cast<const uint4 *>(&sm[kn][VT + tx * 4]);
+          count_match_4x4(acc, r4, c4);
+          r4 = rn;
+          c4 = cn;
+        }
       } else {
-        for (int k = 0; k < kmax; k++) step(k);
+        for (int k = 0; k < kmax; k++) {
+          const int kn = k + 1 < kmax ? k + 1 : k;
+          const uint4 rn = *reinterpret_cast<const uint4 *>(&sm[kn][ty * 4]);
+          const uint4 cn = *reinterpret_cast<const uint4 *>(&sm[kn][VT + tx * 4]);
+          count_match_4x4(acc, r4, c4);
+          r4 = rn;
+          c4 = cn;
+        }
       }
     }
 #pragma unroll
@@ -597,7 +624,7 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
         const uint32_t u = sm_doc[ri], v = sm_doc[cj];
         if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) continue;
         if (ti == tj && ri >= cj - VT) continue;  // upper triangle of a diagonal tile
-        if ((int)acc[i][j] >= min_match && sm_key[ri] == sm_key[cj]) uf_unite(parent, u, v);
+        if ((int)acc[4 * i + j] >= min_match && sm_key[ri] == sm_key[cj]) uf_unite(parent, u, v);
       }
   }
 }
