@@ -121,12 +121,15 @@ ProfScope::~ProfScope() {
 
 // ---- exclusive scan ----------------------------------------------------------------------
 //
-// Blocks of 256 threads x 4 values.  Level 0 reduces each block to one partial, the partials
-// are scanned recursively, then each block rescans its values on top of its partial.
+// Blocks of 256 threads x 4 values.  Level 0 reduces each block to one partial; then each block
+// rescans its values on top of the sum of the partials before it.  Up to SCAN_DIRECT partials
+// every block adds those up itself (a few coalesced loads), which saves the launch that would
+// scan them; beyond that the partials are scanned recursively first.
 
 constexpr int SCAN_THREADS = 256;
 constexpr int SCAN_PER_THREAD = 4;
 constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
+constexpr uint64_t SCAN_DIRECT = 2048;
 
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, uint64_t n) {
@@ -140,8 +143,11 @@ k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, u
   if (threadIdx.x == 0) partial[blockIdx.x] = tot;
 }
 
+// partial_is_sum: partial[b] is the sum of block b (the block adds up partial[0 .. b) itself);
+// otherwise partial[b] already is the exclusive prefix of block b.
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_scan_down(const uint32_t *in, uint32_t *out, uint64_t n, const uint32_t *__restrict__ partial) {
+k_scan_down(const uint32_t *in, uint32_t *out, uint64_t n, const uint32_t *__restrict__ partial,
+            int partial_is_sum) {
   uint64_t i0 = (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
   uint32_t v[SCAN_PER_THREAD];
   uint32_t s = 0;
@@ -150,8 +156,20 @@ k_scan_down(const uint32_t *in, uint32_t *out, uint64_t n, const uint32_t *__res
     v[j] = (i0 + j < n) ? in[i0 + j] : 0u;
     s += v[j];
   }
+  uint32_t before = 0;
+  if (partial) {
+    if (partial_is_sum) {
+      uint32_t mine = 0;
+      for (uint32_t b = threadIdx.x; b < blockIdx.x; b += SCAN_THREADS) mine += partial[b];
+      uint32_t tot_before;
+      block_exclusive_scan<SCAN_THREADS>(mine, &tot_before);
+      before = tot_before;
+    } else {
+      before = partial[blockIdx.x];
+    }
+  }
   uint32_t tot;
-  uint32_t ex = block_exclusive_scan<SCAN_THREADS>(s, &tot) + (partial ? partial[blockIdx.x] : 0u);
+  uint32_t ex = block_exclusive_scan<SCAN_THREADS>(s, &tot) + before;
 #pragma unroll
   for (int j = 0; j < SCAN_PER_THREAD; j++) {
     if (i0 + j < n) out[i0 + j] = ex;
@@ -174,17 +192,20 @@ int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *
   uint64_t nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
   if (nb == 1) {
     hipLaunchKernelGGL(k_scan_down, dim3(1), dim3(SCAN_THREADS), 0, s, in, out, n,
-                       (const uint32_t *)nullptr);
+                       (const uint32_t *)nullptr, 0);
     SEDD_LAUNCH_CHECK();
     return SEDD_OK;
   }
   hipLaunchKernelGGL(k_scan_reduce, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, tmp, n);
   SEDD_LAUNCH_CHECK();
-  uint32_t *next_tmp = tmp + ((nb + 63) & ~uint64_t(63));
-  int rc = scan_exclusive_u32(tmp, tmp, nb, next_tmp, s);
-  if (rc) return rc;
+  const int direct = nb <= SCAN_DIRECT ? 1 : 0;
+  if (!direct) {
+    uint32_t *next_tmp = tmp + ((nb + 63) & ~uint64_t(63));
+    int rc = scan_exclusive_u32(tmp, tmp, nb, next_tmp, s);
+    if (rc) return rc;
+  }
   hipLaunchKernelGGL(k_scan_down, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, out, n,
-                     (const uint32_t *)tmp);
+                     (const uint32_t *)tmp, direct);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
