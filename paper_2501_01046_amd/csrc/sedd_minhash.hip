@@ -271,7 +271,8 @@ __device__ __forceinline__ uint32_t load_prev_byte(const uint8_t *__restrict__ p
 // the segment: the lane below's last bit (by shuffle), or for lane 0 the byte before the tile.
 // Must be called by all 64 lanes of the tile's wavefront.
 __device__ __forceinline__ uint32_t token_starts(uint32_t lane, uint32_t prev_byte, uint32_t wm) {
-  uint32_t prev = __shfl_up(wm >> 15, 1, 64);
+  // wave_shr:1 (lane l reads lane l - 1; lane 0 keeps the first operand)
+  uint32_t prev = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(wm >> 15), 0x138, 0xF, 0xF, false);
   if (lane == 0) prev = is_ws(prev_byte) ? 0u : 1u;
   return wm & ~((wm << 1) | prev) & 0xFFFFu;
 }
@@ -396,7 +397,8 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
     const uint32_t starts0 = token_starts(lane, prev_byte, sg.wm);
 
     *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = q_own;
-    const uint32_t wm_up = __shfl_down(sg.wm, 1, 64);
+    // wave_shl:1 (lane l reads lane l + 1; the last lane gets 0)
+    const uint32_t wm_up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sg.wm, 0x130, 0xF, 0xF, false);
     if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
     if (lane == 0) {
       *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = q_la;
