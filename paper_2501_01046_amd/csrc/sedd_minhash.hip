@@ -307,9 +307,7 @@ k_count_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles
     if (t >= n_slots) break;
     const Segment sg = make_segment(q[i], bt[i].tile0 + lane * 16, bt[i].vs, bt[i].ve);
     const uint32_t starts = token_starts(lane, pv[i], sg.wm);
-    uint32_t cnt = __popc(starts);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+    const uint32_t cnt = (uint32_t)__builtin_amdgcn_readlane((int)wave_inclusive_scan(__popc(starts)), 63);
     if (lane == 0) wcnt[t] = cnt;  // 0 for the slots past the tile count (they pad the scan)
   }
 }
@@ -408,7 +406,7 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
     }
     const uint32_t cnt = __popc(starts0);
     const uint32_t inc = wave_inclusive_scan(cnt);
-    const uint32_t tot = __shfl(inc, 63, 64);
+    const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
     {
       uint32_t st = starts0, j = inc - cnt;
       while (st) {
