@@ -9,21 +9,33 @@ namespace sedd {
 
 // key = sum_i sig[i] * Q^i mod p, by Horner from the last row.  One thread per (doc, band).
 __global__ void __launch_bounds__(256)
-k_lsh_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int r,
+k_lsh_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int r, int vec4,
            uint64_t *__restrict__ keys) {
   uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_docs * (uint64_t)b) return;
   uint64_t d = idx / (uint32_t)b;
   uint32_t j = (uint32_t)(idx - d * (uint32_t)b);
   const uint32_t *src = sig + d * (uint64_t)K + (uint64_t)j * r;
-  uint64_t acc = src[r - 1];
-  for (int i = r - 2; i >= 0; i--) acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)src[i]);
+  uint64_t acc = 0;
+  if (vec4) {
+    // r and K are multiples of 4 and sig is 16-byte aligned: the band is read as 16-byte vectors
+    for (int i = r - 4; i >= 0; i -= 4) {
+      const uint4 q = *reinterpret_cast<const uint4 *>(src + i);
+      acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)q.w);
+      acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)q.z);
+      acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)q.y);
+      acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)q.x);
+    }
+  } else {
+    acc = src[r - 1];
+    for (int i = r - 2; i >= 0; i--) acc = addmod(mulmod31(acc, Q_BAND), (uint64_t)src[i]);
+  }
   keys[idx] = acc;
 }
 
 // Dense bucket id (Section 3.2): sum of the band's r values modulo the number of buckets.
 __global__ void __launch_bounds__(256)
-k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int r,
+k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b, int r, int vec4,
                  uint64_t n_buckets, uint64_t *__restrict__ keys) {
   uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= n_docs * (uint64_t)b) return;
@@ -31,7 +43,14 @@ k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b
   uint32_t j = (uint32_t)(idx - d * (uint32_t)b);
   const uint32_t *src = sig + d * (uint64_t)K + (uint64_t)j * r;
   uint64_t sum = 0;  // r <= SEDD_MAX_K values below 2^32: no overflow
-  for (int i = 0; i < r; i++) sum += src[i];
+  if (vec4) {
+    for (int i = 0; i < r; i += 4) {
+      const uint4 q = *reinterpret_cast<const uint4 *>(src + i);
+      sum += (uint64_t)q.x + q.y + q.z + q.w;
+    }
+  } else {
+    for (int i = 0; i < r; i++) sum += src[i];
+  }
   keys[idx] = sum % n_buckets;
 }
 
@@ -738,7 +757,8 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
   if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   ProfScope prof(SEDD_PROF_LSH_KEYS, (hipStream_t)stream);
   hipLaunchKernelGGL(k_lsh_keys, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0,
-                     (hipStream_t)stream, sig, n_docs, (int)K, (int)b, (int)r, keys);
+                     (hipStream_t)stream, sig, n_docs, (int)K, (int)b, (int)r,
+                     (r % 4 == 0 && K % 4 == 0 && ((uintptr_t)sig & 15) == 0) ? 1 : 0, keys);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
@@ -754,7 +774,8 @@ int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t
   if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   ProfScope prof(SEDD_PROF_LSH_KEYS, st);
   hipLaunchKernelGGL(k_lsh_dense_keys, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sig,
-                     n_docs, (int)K, (int)b, (int)r, n_buckets, keys);
+                     n_docs, (int)K, (int)b, (int)r,
+                     (r % 4 == 0 && K % 4 == 0 && ((uintptr_t)sig & 15) == 0) ? 1 : 0, n_buckets, keys);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
