@@ -106,14 +106,20 @@ k_radix_hist(const uint64_t *__restrict__ bk, uint32_t n, uint32_t nblk, int shi
 // Stable scatter of one tile.  Wavefront w owns the tile's records [w*1024, (w+1)*1024), 16 per
 // lane, all loaded before the first is used.  Ranking needs no block barrier: the lanes of a
 // wavefront that hold the same digit find each other with ballots, the first of them advances the
-// wavefront's own counter of that digit in LDS.  Two barriers follow: one before the per-digit
-// prefix over the four wavefronts, one before the stores.
+// wavefront's own counter of that digit in LDS.  The records are then put in digit order in LDS
+// and written out from there, so that consecutive threads write consecutive addresses of a
+// digit's run (writing straight from the ranking order leaves cache lines half written for long
+// enough that they go to memory more than once).
 __global__ void __launch_bounds__(SORT_THREADS)
 k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
                 uint32_t nblk, int shift, const uint32_t *__restrict__ pos,
                 uint64_t *__restrict__ ok, uint32_t *__restrict__ od) {
   constexpr int WAVES = SORT_THREADS / 64;
-  __shared__ uint32_t wc[WAVES][RADIX];  // per wavefront: digit count, later the global offset
+  __shared__ uint32_t wc[WAVES][RADIX];  // per wavefront: digit count, later its offset in the tile
+  __shared__ uint32_t s_lstart[RADIX];   // first position of the digit in the sorted tile
+  __shared__ uint32_t s_gbase[RADIX];    // where the tile's run of the digit starts in the output
+  __shared__ uint64_t s_key[SORT_TILE];
+  __shared__ uint32_t s_doc[SORT_TILE];
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t *sk = bk + (uint64_t)band * n;
@@ -156,13 +162,21 @@ k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd
   }
   __syncthreads();
   {
-    // this thread's digit: global start of the block's run, then one sub-run per wavefront
-    uint32_t base = pos[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk];
+    // this thread's digit: its records of the four wavefronts follow each other in the tile
+    uint32_t c[WAVES], tot = 0;
 #pragma unroll
     for (int w = 0; w < WAVES; w++) {
-      const uint32_t c = wc[w][threadIdx.x];
-      wc[w][threadIdx.x] = base;
-      base += c;
+      c[w] = wc[w][threadIdx.x];
+      tot += c[w];
+    }
+    uint32_t all;
+    uint32_t at = block_exclusive_scan<SORT_THREADS>(tot, &all);
+    s_lstart[threadIdx.x] = at;
+    s_gbase[threadIdx.x] = pos[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk];
+#pragma unroll
+    for (int w = 0; w < WAVES; w++) {
+      wc[w][threadIdx.x] = at;
+      at += c[w];
     }
   }
   __syncthreads();
@@ -170,9 +184,22 @@ k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd
   for (int it = 0; it < SORT_ITEMS; it++) {
     if (e0 + it * 64 < n) {
       const uint32_t digit = (uint32_t)(key[it] >> shift) & (RADIX - 1);
-      const uint32_t o = wc[wave][digit] + rank[it];
-      ok[o] = key[it];
-      od[o] = doc[it];
+      const uint32_t lp = wc[wave][digit] + rank[it];
+      s_key[lp] = key[it];
+      s_doc[lp] = doc[it];
+    }
+  }
+  __syncthreads();
+  const uint32_t n_valid = min(SORT_TILE, n - blk * SORT_TILE);
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const uint32_t i = it * SORT_THREADS + threadIdx.x;
+    if (i < n_valid) {
+      const uint64_t k = s_key[i];
+      const uint32_t digit = (uint32_t)(k >> shift) & (RADIX - 1);
+      const uint32_t o = s_gbase[digit] + (i - s_lstart[digit]);
+      ok[o] = k;
+      od[o] = s_doc[i];
     }
   }
 }
