@@ -93,3 +93,28 @@ def test_product_package_does_not_import_the_oracle():
             text = open(path, errors="replace").read()
             assert "import oracle" not in text and "from oracle" not in text, path
             assert "sedd_oracle" not in text and "sedd_ref_" not in text, path
+
+
+def test_verified_and_dense_calls_reject_bad_arguments_before_the_device():
+    L = sedd.lib()
+    L.sedd_cluster_verified.argtypes = [C.c_void_p, C.c_void_p, u64, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.c_void_p]
+    L.sedd_lsh_dense_keys.argtypes = [C.c_void_p, u64, C.c_int32, C.c_int32, C.c_int32, u64,
+                                      C.c_void_p, C.c_void_p]
+    assert L.sedd_cluster_verified(FAKE, FAKE, u64(4), 0, 16, 1, FAKE, None) == -1        # K < 1
+    assert L.sedd_cluster_verified(FAKE, FAKE, u64(4), 128, 16, -1, FAKE, None) == -1     # min_match < 0
+    assert L.sedd_cluster_verified(FAKE, None, u64(4), 128, 16, 103, FAKE, None) == -1    # no signatures
+    assert L.sedd_cluster_verified(None, FAKE, u64(4), 128, 16, 103, FAKE, None) == -1
+    assert L.sedd_cluster_verified(FAKE, FAKE, u64(4), 128, 0, 103, FAKE, None) == -1
+    assert L.sedd_cluster_verified(None, None, u64(0), 128, 16, 103, None, None) == 0
+    assert L.sedd_lsh_dense_keys(FAKE, u64(4), 128, 16, 8, u64(0), FAKE, None) == -1       # no buckets
+    assert L.sedd_lsh_dense_keys(FAKE, u64(4), 128, 17, 8, u64(10), FAKE, None) == -1      # b*r > K
+    assert L.sedd_lsh_dense_keys(FAKE, u64(4), 128, 16, 8, u64(1 << 61), FAKE, None) == -1
+    assert L.sedd_lsh_dense_keys(None, u64(0), 128, 16, 8, u64(10), None, None) == 0
+
+
+def test_threshold_and_bucket_count_helpers():
+    assert sedd.min_match_for(0.8, 128) == 103 and sedd.min_match_for(0.8, 125) == 100
+    assert sedd.min_match_for(0.7, 10) == 7 and sedd.min_match_for(0.0, 5) == 0
+    assert sedd.dense_bucket_count(1_000_000) == 4000 and sedd.dense_bucket_count(0) == 1
+    assert sedd.dense_bucket_count(40_000) == 800 and sedd.dense_bucket_count(10, k=1) == 3
