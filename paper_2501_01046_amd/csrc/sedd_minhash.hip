@@ -732,13 +732,12 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   constexpr int LW = 64 / P;
   const uint32_t grp = threadIdx.x / LW;
   const int kbase = blockIdx.y * (LW * F) + (threadIdx.x % LW);
-  uint64_t a[F], b[F];
+  uint64_t b[F];
   uint32_t a0[F], a12[F], m[F];
 #pragma unroll
   for (int j = 0; j < F; j++) {
     int k = kbase + LW * j;
     const int kk = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
-    a[j] = coef_a[kk];
     b[j] = coef_b[kk];
     const CoefSplit c = coef_split[kk];
     a0[j] = c.a0;
@@ -772,6 +771,9 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
     if (threadIdx.x == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
 #pragma unroll
     for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+    uint64_t a[F];
+#pragma unroll
+    for (int j = 0; j < F; j++) a[j] = coef_a[kbase + LW * j < K ? kbase + LW * j : 0];
     for (uint32_t s = grp; s < cnt; s += P) {
       const XLimbs xv = sx[s];
       const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
