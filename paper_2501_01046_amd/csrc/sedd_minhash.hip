@@ -40,10 +40,12 @@ __device__ __forceinline__ XLimbs x_limbs(uint64_t x) {
   return r;
 }
 
-// coefficients of one hash function in the same limb form: a = a1 * 2^31 + a0
+// what the hot loop needs of one hash function, in one 16-byte record: a in the same limb form
+// (a = a1 * 2^31 + a0) and b
 struct CoefSplit {
   uint32_t a0;   // a mod 2^31
   uint32_t a12;  // 2 * (a >> 31)
+  uint64_t b;
 };
 
 // Token records, structure of arrays: tok_v[i] = Eq. 1 hash of "token 0x20" = W + 32 * 257^len,
@@ -113,6 +115,7 @@ __global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, CoefSpl
       CoefSplit c;
       c.a0 = (uint32_t)ak & 0x7FFFFFFFu;
       c.a12 = (uint32_t)(ak >> 31) << 1;
+      c.b = b[k];
       split[k] = c;
     }
   }
@@ -638,8 +641,7 @@ __device__ __forceinline__ uint64_t words_x_unrolled(const TokenRecs &rec,
 template <int F, int P, int MODE>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
-          const uint64_t *__restrict__ coef_a, const uint64_t *__restrict__ coef_b,
-          const CoefSplit *__restrict__ coef_split, int K,
+          const uint64_t *__restrict__ coef_a, const CoefSplit *__restrict__ coef_split, int K,
           uint32_t *__restrict__ sig /* first document of the chunk */, HotConsts hc,
           unsigned long long *__restrict__ slow_tiles) {
   __shared__ XLimbs sx[TS];
@@ -738,10 +740,10 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   for (int j = 0; j < F; j++) {
     int k = kbase + LW * j;
     const int kk = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
-    b[j] = coef_b[kk];
     const CoefSplit c = coef_split[kk];
     a0[j] = c.a0;
     a12[j] = c.a12;
+    b[j] = c.b;
     m[j] = 0xFFFFFFFFu;
   }
   __syncthreads();
@@ -831,8 +833,7 @@ __global__ void k_debug_add_total(uint64_t *total, const uint32_t *sbase_last) {
 // launches the hot kernel over nht candidate tiles (tiles beyond the device-side count exit)
 static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
                           const uint32_t *n_tiles, uint64_t nht, const uint64_t *coef_a,
-                          const uint64_t *coef_b, const CoefSplit *coef_s, int K, uint32_t *csig,
-                          hipStream_t st) {
+                          const CoefSplit *coef_s, int K, uint32_t *csig, hipStream_t st) {
   unsigned long long *stats = nullptr;
   int rc = stats_ensure(&stats);
   if (rc) return rc;
@@ -847,7 +848,7 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   ProfScope prof(SEDD_PROF_MINHASH, st);
 #define SEDD_LAUNCH_MH(FF, PP, MM)                                                          \
   hipLaunchKernelGGL((k_minhash<FF, PP, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
-                     coef_a, coef_b, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
+                     coef_a, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
 #define SEDD_LAUNCH_MH_F(MM)                       \
   do {                                             \
     if (P == 1) SEDD_LAUNCH_MH(4, 1, MM);          \
@@ -1143,7 +1144,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
     } else {
-      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K,
+      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_s, (int)K,
                           sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
     }
@@ -1234,7 +1235,7 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   SEDD_LAUNCH_CHECK();
   XSource xsrc = {};
   xsrc.given = x;  // tiles index it by shingle offset
-  return launch_minhash(X_GIVEN, xsrc, htd, htb + nd, nht, coef_a, coef_b, coef_s, (int)K, sig, st);
+  return launch_minhash(X_GIVEN, xsrc, htd, htb + nd, nht, coef_a, coef_s, (int)K, sig, st);
 }
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {
