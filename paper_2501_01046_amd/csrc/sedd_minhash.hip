@@ -23,7 +23,7 @@ namespace sedd {
 
 constexpr int TB_LANES = 64;
 constexpr uint32_t TB = TB_LANES * 16;    // bytes per byte tile: one wavefront, 16 bytes per lane
-constexpr uint32_t TS = 256;              // shingles per hash tile
+constexpr uint32_t TS = 320;              // shingles per hash tile
 constexpr int QPOW_N = 256;
 
 // x(s) of Eq. 1 as the hot kernel multiplies by it: x = x1 * 2^31 + x0 with x0 < 2^31,
@@ -684,11 +684,11 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
       sx[i] = x_limbs(acc);
     }
   } else if (MODE == X_BYTES) {
-    // Byte windows.  The tile's bytes are staged in LDS; lane l owns the windows 4l .. 4l+3: it
-    // evaluates the last of them by Horner over its bytes and derives the others with the reuse
+    // Byte windows.  The tile's bytes are staged in LDS; lane l owns the WPL = TS / 64 windows
+    // from WPL l on: it evaluates the last of them by Horner over its bytes and derives the others with the reuse
     // form of Eq. 1 (Eq. 2 read backwards, so that the step multiplies by q instead of dividing):
     //   x(i-1) = q (x(i) - c[i+per-1] q^(per-1)) + c[i-1]      (mod p).
-    // The windows of row j = i mod 4 are stored from slot off_j on, consecutive lanes in
+    // The windows of row j = i mod WPL are stored from slot off_j on, consecutive lanes in
     // consecutive slots; the slots [0, cnt) then hold every window once, in an order that does
     // not matter to a minimum.
     __shared__ uint32_t sm_b[MODE == X_BYTES ? (TS + SEDD_MAX_SHINGLE_N + 8) / 4 + 1 : 1];
@@ -702,19 +702,21 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
     __syncthreads();
     const uint8_t *tb = reinterpret_cast<const uint8_t *>(sm_b) + o;  // tb[i] = byte i of the tile
     const uint32_t l = threadIdx.x;
-    if (4 * l < cnt) {
-      const uint32_t m = min(4u, cnt - 4 * l);
-      const uint32_t top = 4 * l + m - 1;
+    constexpr uint32_t WPL = TS / 64;
+    static_assert(TS % 64 == 0, "whole windows per lane");
+    if (WPL * l < cnt) {
+      const uint32_t m = min(WPL, cnt - WPL * l);
+      const uint32_t top = WPL * l + m - 1;
       uint64_t acc = 0;
       for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, tb[top + j]);
       const uint64_t Q = xsrc.qpow[per - 1];  // per <= SEDD_MAX_SHINGLE_N < QPOW_N
       const uint32_t q_lo = (uint32_t)Q, q_hi = (uint32_t)(Q >> 32);
       for (uint32_t i = top;; i--) {
-        const uint32_t j = i & 3u;
-        uint32_t slot = l;  // off_j + l, off_j = sum over rows before j of ceil((cnt - row) / 4)
-        for (uint32_t row = 0; row < j; row++) slot += (cnt - row + 3) >> 2;
+        const uint32_t j = i - WPL * l;
+        uint32_t slot = l;  // off_j + l, off_j = sum over rows before j of ceil((cnt - row) / WPL)
+        for (uint32_t row = 0; row < j; row++) slot += (cnt - row + WPL - 1) / WPL;
         sx[slot] = x_limbs(fold61(acc));
-        if (i == 4 * l) break;
+        if (i == WPL * l) break;
         // x(i-1) from x(i)
         const uint32_t c_hi = tb[i + per - 1], c_lo = tb[i - 1];
         const uint64_t lo = (uint64_t)q_lo * c_hi;
