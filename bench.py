@@ -42,7 +42,7 @@ STREAM_CHUNK_BYTES = 2 << 30
 # rocprofv3 --pmc runs summarised in profiles/hbm_traffic_cfg2_medium_1M.txt (FETCH_SIZE x 2 KiB
 # + WRITE_SIZE x 1 KiB, both scaled by a 1 GiB copy).  It is a recorded measurement, not
 # collected by this script; it only applies to the default workload.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH_CFG2 = 641.2e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH_CFG2 = 592.7e6
 
 
 def ops_per_shingle(recipe, K):
