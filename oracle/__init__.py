@@ -17,6 +17,9 @@ _SRC = os.path.join(_HERE, "sedd_oracle.c")
 _LIB = os.path.join(_HERE, "libsedd_oracle.so")
 
 P61 = (1 << 61) - 1
+P_PAPER = 4294967           # the modulus Section 3.2 quotes for the paper's experiments
+FLAG_BYTE_SHINGLES = 1
+FLAG_PAPER_PRIME = 2
 
 
 def build(force: bool = False) -> str:
@@ -43,6 +46,12 @@ def _load():
         lib.sedd_ref_powmod.argtypes = [u64, u64]
         lib.sedd_ref_base_hash.restype = u64
         lib.sedd_ref_base_hash.argtypes = [vp, u64]
+        lib.sedd_ref_base_hash_pp.restype = u64
+        lib.sedd_ref_base_hash_pp.argtypes = [vp, u64]
+        lib.sedd_ref_coeffs_pp.restype = C.c_int
+        lib.sedd_ref_coeffs_pp.argtypes = [u64, i32, vp, vp]
+        lib.sedd_ref_minhash_shingles_pp.restype = C.c_int
+        lib.sedd_ref_minhash_shingles_pp.argtypes = [vp, u64, i32, u64, vp]
         lib.sedd_ref_coeffs.restype = C.c_int
         lib.sedd_ref_coeffs.argtypes = [u64, i32, vp, vp]
         lib.sedd_ref_doc_shingles.restype = u64
@@ -96,20 +105,27 @@ def base_hash(s) -> int:
     return _load().sedd_ref_base_hash(_ptr(s), s.size)
 
 
-def coeffs(seed: int, K: int):
+def base_hash_pp(s) -> int:
+    """Eq. 1 modulo the paper's own prime."""
+    s = _as_bytes(s)
+    return _load().sedd_ref_base_hash_pp(_ptr(s), s.size)
+
+
+def coeffs(seed: int, K: int, paper_prime: bool = False):
     a = np.zeros(K, dtype=np.uint64)
     b = np.zeros(K, dtype=np.uint64)
-    rc = _load().sedd_ref_coeffs(seed, K, a.ctypes.data, b.ctypes.data)
+    fn = _load().sedd_ref_coeffs_pp if paper_prime else _load().sedd_ref_coeffs
+    rc = fn(seed, K, a.ctypes.data, b.ctypes.data)
     if rc:
         raise OracleError(rc)
     return a, b
 
 
-def doc_shingles(text, n: int, byte_mode: bool = False) -> np.ndarray:
+def doc_shingles(text, n: int, byte_mode: bool = False, paper_prime: bool = False) -> np.ndarray:
     """Base hashes (Eq. 1) of the shingles of one document, in order."""
     t = _as_bytes(text)
     lib = _load()
-    flags = 1 if byte_mode else 0
+    flags = (FLAG_BYTE_SHINGLES if byte_mode else 0) | (FLAG_PAPER_PRIME if paper_prime else 0)
     cnt = lib.sedd_ref_doc_shingles(_ptr(t), t.size, n, flags, None, 0)
     out = np.zeros(cnt, dtype=np.uint64)
     if cnt:
@@ -117,10 +133,11 @@ def doc_shingles(text, n: int, byte_mode: bool = False) -> np.ndarray:
     return out
 
 
-def minhash_shingles(x, K: int, seed: int = 0) -> np.ndarray:
+def minhash_shingles(x, K: int, seed: int = 0, paper_prime: bool = False) -> np.ndarray:
     x = np.ascontiguousarray(x, dtype=np.uint64)
     sig = np.zeros(K, dtype=np.uint32)
-    rc = _load().sedd_ref_minhash_shingles(_ptr(x), x.size, K, seed, sig.ctypes.data)
+    fn = _load().sedd_ref_minhash_shingles_pp if paper_prime else _load().sedd_ref_minhash_shingles
+    rc = fn(_ptr(x), x.size, K, seed, sig.ctypes.data)
     if rc:
         raise OracleError(rc)
     return sig

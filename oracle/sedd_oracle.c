@@ -31,6 +31,11 @@
  *   Byte shingles: every window of n bytes; a document of 1..n-1 bytes has
  *   one shingle (the whole document).
  *   Band key: Eq. 1's polynomial over the band's r values with base Q, mod p.
+ *   Paper-prime mode (flags bit 1): Section 3.2 names p' = 4,294,967 as the
+ *   modulus of its experiments.  With that bit set, Eq. 1 is taken mod p'
+ *   and the H functions are h'_k(s) = (a'_k * x'(s) + b'_k) mod p' with
+ *   a'_k = (a_k mod (p'-1)) + 1 and b'_k = b_k mod p' (a_k, b_k as above);
+ *   the value is below 2^23 and is stored as it is.
  *
  * Parity with the paper authors' released code is unpinned: the paper prints
  * no hash value, signature or bucket id for any input.  The functions here
@@ -85,6 +90,20 @@ uint64_t sedd_ref_base_hash(const uint8_t *s, uint64_t len) {
   return x;
 }
 
+/* ---- paper-prime mode: the modulus Section 3.2 quotes for the paper's experiments ---- */
+
+static const uint64_t P_PAPER = 4294967ULL;
+
+/* Eq. 1 with p' in place of p */
+uint64_t sedd_ref_base_hash_pp(const uint8_t *s, uint64_t len) {
+  uint64_t x = 0, pw = 1;
+  for (uint64_t i = 0; i < len; i++) {
+    x = (x + (uint64_t)s[i] * pw) % P_PAPER;    /* < 2^8 * 2^23 + 2^23: no overflow */
+    pw = (pw * Q_CHAR) % P_PAPER;
+  }
+  return x;
+}
+
 /* coefficients of the K hash functions */
 int sedd_ref_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
   if (K < 1 || !a || !b) return SEDD_REF_EINVAL;
@@ -97,6 +116,21 @@ int sedd_ref_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
     b[k] = mulmod(s0, gb);
   }
   return SEDD_REF_OK;
+}
+
+/* paper-prime coefficients: a'_k in [1, p'-1], b'_k in [0, p'-1] */
+int sedd_ref_coeffs_pp(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
+  int rc = sedd_ref_coeffs(seed, K, a, b);
+  if (rc) return rc;
+  for (int32_t k = 0; k < K; k++) {
+    a[k] = a[k] % (P_PAPER - 1) + 1;
+    b[k] = b[k] % P_PAPER;
+  }
+  return SEDD_REF_OK;
+}
+
+static uint64_t shingle_hash(const uint8_t *s, uint64_t len, uint32_t flags) {
+  return (flags & 2u) ? sedd_ref_base_hash_pp(s, len) : sedd_ref_base_hash(s, len);
 }
 
 static int is_space(uint8_t c) { return c == 0x20 || (c >= 0x09 && c <= 0x0D); }
@@ -112,9 +146,9 @@ uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32
   if (n < 1) return 0;
   if (flags & 1u) {                                   /* byte n-grams */
     if (len == 0) return 0;
-    if (len < (uint64_t)n) { if (out && cap) out[0] = sedd_ref_base_hash(t, len); return 1; }
+    if (len < (uint64_t)n) { if (out && cap) out[0] = shingle_hash(t, len, flags); return 1; }
     for (uint64_t i = 0; i + n <= len; i++) {
-      if (out && count < cap) out[count] = sedd_ref_base_hash(t + i, (uint64_t)n);
+      if (out && count < cap) out[count] = shingle_hash(t + i, (uint64_t)n, flags);
       count++;
     }
     return count;
@@ -149,7 +183,7 @@ uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32
       if (j) buf[w++] = 0x20;
       memcpy(buf + w, t + ts[s + j], tl[s + j]); w += tl[s + j];
     }
-    if (out && count < cap) out[count] = sedd_ref_base_hash(buf, w);
+    if (out && count < cap) out[count] = shingle_hash(buf, w, flags);
     count++;
   }
   free(buf); free(ts); free(tl);
@@ -179,11 +213,30 @@ int sedd_ref_minhash_shingles(const uint64_t *x, uint64_t n_sh, int32_t K, uint6
   return SEDD_REF_OK;
 }
 
+/* the same with the paper-prime functions h'_k */
+int sedd_ref_minhash_shingles_pp(const uint64_t *x, uint64_t n_sh, int32_t K, uint64_t seed,
+                                 uint32_t *sig) {
+  if (K < 1 || !sig || (n_sh && !x)) return SEDD_REF_EINVAL;
+  uint64_t *a = (uint64_t *)malloc((size_t)K * 8), *b = (uint64_t *)malloc((size_t)K * 8);
+  if (!a || !b) { free(a); free(b); return SEDD_REF_ENOMEM; }
+  sedd_ref_coeffs_pp(seed, K, a, b);
+  for (int32_t k = 0; k < K; k++) {
+    uint32_t m = 0xFFFFFFFFu;
+    for (uint64_t s = 0; s < n_sh; s++) {
+      uint64_t h = (a[k] * (x[s] % P_PAPER) + b[k]) % P_PAPER;   /* < 2^46: no overflow */
+      if ((uint32_t)h < m) m = (uint32_t)h;
+    }
+    sig[k] = m;
+  }
+  free(a); free(b);
+  return SEDD_REF_OK;
+}
+
 /* sig[d*K + k] = min over the shingles s of document d of h_k(s) */
 int sedd_ref_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
                      int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags,
                      uint32_t *sig) {
-  if (shingle_n < 1 || K < 1 || (flags & ~1u)) return SEDD_REF_EINVAL;
+  if (shingle_n < 1 || K < 1 || (flags & ~3u)) return SEDD_REF_EINVAL;
   if (n_docs == 0) return SEDD_REF_OK;
   if (!doc_offsets || !sig) return SEDD_REF_EINVAL;
   for (uint64_t d = 0; d < n_docs; d++)
@@ -196,7 +249,8 @@ int sedd_ref_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t
     uint64_t n_sh = sedd_ref_doc_shingles(t, len, shingle_n, flags, NULL, 0);
     if (n_sh > xcap) { xcap = n_sh * 2; free(x); x = (uint64_t *)malloc(xcap * 8); if (!x) return SEDD_REF_ENOMEM; }
     sedd_ref_doc_shingles(t, len, shingle_n, flags, x, n_sh);
-    int rc = sedd_ref_minhash_shingles(x, n_sh, K, seed, sig + d * (uint64_t)K);
+    int rc = (flags & 2u) ? sedd_ref_minhash_shingles_pp(x, n_sh, K, seed, sig + d * (uint64_t)K)
+                          : sedd_ref_minhash_shingles(x, n_sh, K, seed, sig + d * (uint64_t)K);
     if (rc) { free(x); return rc; }
   }
   free(x);

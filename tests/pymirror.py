@@ -12,8 +12,11 @@ GA = 1425089352415399810
 GB = 955111447119501601
 
 
-def eq1(s: bytes, q: int = Q) -> int:
-    return sum(c * q ** i for i, c in enumerate(s)) % P
+P_PAPER = 4294967            # Section 3.2: the modulus of the paper's experiments
+
+
+def eq1(s: bytes, q: int = Q, p: int = P) -> int:
+    return sum(c * q ** i for i, c in enumerate(s)) % p
 
 
 def shingle_strings(text: bytes, n: int, byte_mode: bool):
@@ -72,3 +75,16 @@ def jaccard(text_a: bytes, text_b: bytes, n: int, byte_mode: bool = False) -> fl
     if not A and not B:
         return 1.0
     return len(A & B) / len(A | B)
+
+
+# ---- paper-prime mode: Eq. 1 and the H functions modulo the paper's own p ----
+
+def coeffs_pp(seed: int, K: int):
+    a, b = coeffs(seed, K)
+    return [x % (P_PAPER - 1) + 1 for x in a], [x % P_PAPER for x in b]
+
+
+def signature_pp(text: bytes, n: int, K: int, seed: int = 0, byte_mode: bool = False):
+    a, b = coeffs_pp(seed, K)
+    xs = [eq1(s, Q, P_PAPER) for s in shingle_strings(text, n, byte_mode)]
+    return [min((a[k] * x + b[k]) % P_PAPER for x in xs) if xs else 0xFFFFFFFF for k in range(K)]
