@@ -40,6 +40,7 @@ extern "C" {
 
 /* flags of sedd_minhash */
 #define SEDD_FLAG_BYTE_SHINGLES 1u /* shingles are byte n-grams instead of word n-grams */
+#define SEDD_FLAG_PAPER_PRIME 2u   /* Eq. 1 and the K functions modulo 4,294,967 (see below) */
 
 /* largest K / shingle_n / b the kernels accept */
 #define SEDD_MAX_K 4096
@@ -62,6 +63,13 @@ extern "C" {
  *      a_k = s0 * Ga^(k+1) mod p, b_k = s0 * Gb^(k+1) mod p, s0 = (seed mod (p-1)) + 1,
  *      Ga = 1425089352415399810, Gb = 955111447119501601.
  *   4. sig[d*K + k] = min over the document's shingles of h_k(s); 0xFFFFFFFF if none.
+ *
+ * SEDD_FLAG_PAPER_PRIME: Section 3.2 quotes p' = 4,294,967 as the modulus of the paper's
+ * experiments (small enough that h * q stays a 32-bit integer).  With this flag steps 2 and 3
+ * use it: x'(s) = (sum_i s_i * 257^(i-1)) mod p' and h'_k(s) = (a'_k * x'(s) + b'_k) mod p' with
+ * a'_k = (a_k mod (p'-1)) + 1, b'_k = b_k mod p'; the values are below 2^23 and are stored as
+ * they are.  A 22-bit range is exhausted by documents with millions of shingles (every
+ * minimum tends to 0): the mode is meant for comparison with the paper's setting.
  *
  * bytes        device, uint8; read in [doc_offsets[0], doc_offsets[n_docs]).
  * doc_offsets  device, uint64[n_docs+1], non-decreasing byte offsets into `bytes`.

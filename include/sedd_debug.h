@@ -13,7 +13,8 @@ extern "C" {
 #endif
 
 /*
- * Base hashes x(s) of every shingle (Section 3.2, Eq. 1), in document order.
+ * Base hashes x(s) of every shingle (Section 3.2, Eq. 1), in document order (modulo 2^61-1, or
+ * modulo 4,294,967 with SEDD_FLAG_PAPER_PRIME).
  *   shingle_offsets  device, uint64[n_docs+1]: document d owns x[shingle_offsets[d] ..
  *                    shingle_offsets[d+1]).
  *   x                device, uint64[x_cap]; entries beyond x_cap are not written (the
@@ -25,6 +26,9 @@ int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
 
 /* Coefficients a_k, b_k of the K hash functions: device uint64[K] each. */
 int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream);
+
+/* The same for SEDD_FLAG_PAPER_PRIME: a'_k and b'_k (both below 4,294,967) as uint64. */
+int sedd_debug_coeffs_pp(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream);
 
 /* Exclusive prefix sum of n uint32 values (device), out may alias in. */
 int sedd_debug_scan_u32(const uint32_t *in, uint32_t *out, uint64_t n, void *stream);
@@ -46,6 +50,11 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
 int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
                               uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,
                               void *stream);
+
+/* The same with the functions of SEDD_FLAG_PAPER_PRIME; x is taken modulo 4,294,967. */
+int sedd_debug_minhash_from_x_pp(const uint64_t *x, const uint64_t *shingle_offsets,
+                                 uint64_t n_docs, uint64_t n_shingles, int32_t K, uint64_t seed,
+                                 uint32_t *sig, void *stream);
 
 /*
  * Device-side counters since the library was loaded, copied to the HOST array out[SEDD_STAT_N]

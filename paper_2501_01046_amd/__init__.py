@@ -22,10 +22,11 @@ __all__ = [
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
     "debug_shingle_hashes_offsets",
-    "FLAG_BYTE_SHINGLES",
+    "FLAG_BYTE_SHINGLES", "FLAG_PAPER_PRIME",
 ]
 
 FLAG_BYTE_SHINGLES = 1
+FLAG_PAPER_PRIME = 2      # Eq. 1 and the K functions modulo 4,294,967 (Section 3.2)
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsedd.so")
 _lib = None
@@ -80,6 +81,10 @@ def lib():
         L.sedd_debug_sort_bands.argtypes = [vp, u64, i32, vp, vp, vp]
         L.sedd_debug_minhash_from_x.restype = C.c_int
         L.sedd_debug_minhash_from_x.argtypes = [vp, vp, u64, u64, i32, u64, vp, vp]
+        L.sedd_debug_minhash_from_x_pp.restype = C.c_int
+        L.sedd_debug_minhash_from_x_pp.argtypes = [vp, vp, u64, u64, i32, u64, vp, vp]
+        L.sedd_debug_coeffs_pp.restype = C.c_int
+        L.sedd_debug_coeffs_pp.argtypes = [u64, i32, vp, vp, vp]
         L.sedd_debug_stats.restype = C.c_int
         L.sedd_debug_stats.argtypes = [vp]
         L.sedd_profile_enable.restype = C.c_int
@@ -277,11 +282,12 @@ def debug_shingle_hashes_offsets(text, doc_offsets, shingle_n: int, flags: int =
     return None, soff.cpu().numpy()
 
 
-def debug_coeffs(seed: int, K: int, stream=None):
+def debug_coeffs(seed: int, K: int, stream=None, paper_prime: bool = False):
     torch = _torch()
     a = torch.zeros(max(K, 0), dtype=torch.uint64, device="cuda")
     b = torch.zeros(max(K, 0), dtype=torch.uint64, device="cuda")
-    _check(lib().sedd_debug_coeffs(seed, K, _ptr(a), _ptr(b), _stream(stream)), "sedd_debug_coeffs")
+    fn = lib().sedd_debug_coeffs_pp if paper_prime else lib().sedd_debug_coeffs
+    _check(fn(seed, K, _ptr(a), _ptr(b), _stream(stream)), "sedd_debug_coeffs")
     return a, b
 
 
@@ -309,7 +315,8 @@ def debug_set_chunk_bytes(n: int):
     _check(lib().sedd_debug_set_chunk_bytes(n), "sedd_debug_set_chunk_bytes")
 
 
-def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None, out=None):
+def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None, out=None,
+                         paper_prime: bool = False):
     """Signatures from caller-supplied shingle hashes (the K-hash / minimum kernel alone)."""
     torch = _torch()
     x = _dev(x, torch.uint64, "x")
@@ -321,9 +328,9 @@ def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None,
         sig = _dev(out, torch.uint32, "out")
         if sig.numel() != n_docs * K:
             raise ValueError("out has the wrong size")
-    _check(lib().sedd_debug_minhash_from_x(_ptr(x), _ptr(shingle_offsets), n_docs, x.numel(), K,
-                                           seed, _ptr(sig), _stream(stream)),
-           "sedd_debug_minhash_from_x")
+    fn = lib().sedd_debug_minhash_from_x_pp if paper_prime else lib().sedd_debug_minhash_from_x
+    _check(fn(_ptr(x), _ptr(shingle_offsets), n_docs, x.numel(), K, seed, _ptr(sig),
+              _stream(stream)), "sedd_debug_minhash_from_x")
     return sig
 
 

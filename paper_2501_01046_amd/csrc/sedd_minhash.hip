@@ -90,6 +90,55 @@ __device__ __forceinline__ void store_token(const TokenRecs &tr, uint32_t idx, u
   if (len >= LONG_TOKEN) tr.long_len[idx] = len;
 }
 
+// ---- paper-prime mode (SEDD_FLAG_PAPER_PRIME) ------------------------------------------------
+//
+// Section 3.2 quotes p' = 4,294,967 as the modulus of Eq. 1 in the paper's experiments.  p' is
+// not a Mersenne prime, so a product is reduced through an estimate of its quotient.
+constexpr uint32_t PP = 4294967u;
+
+// t mod p' for t < 2^46.  With T = t >> 14 (< 2^32) and M = floor(2^46 / p'), floor(T M / 2^32)
+// is the quotient or up to 2 below it; the remainder estimate then lies in [0, 3 p') (< 2^24).
+__device__ __forceinline__ uint32_t red_pp(uint64_t t) {
+  constexpr uint32_t M = (uint32_t)((uint64_t(1) << 46) / PP);
+  const uint32_t q = __umulhi((uint32_t)(t >> 14), M);
+  uint32_t r = (uint32_t)t - q * PP;
+  r = min(r, r - PP);  // r - p' wraps to a huge value when r < p'
+  r = min(r, r - PP);
+  return r;
+}
+__device__ __forceinline__ uint32_t mulmod_pp(uint32_t a, uint32_t b) {
+  return red_pp((uint64_t)a * b);
+}
+__device__ inline uint32_t powmod_pp(uint32_t g, uint64_t e) {
+  uint32_t r = 1, base = g;
+  while (e) {
+    if (e & 1) r = mulmod_pp(r, base);
+    base = mulmod_pp(base, base);
+    e >>= 1;
+  }
+  return r;
+}
+
+// One hash function h'(x) = (a x + b) mod p' as the hot loop uses it: a, b and the 32-bit
+// fixed-point reciprocals ap = ceil(a 2^32 / p'), bp = ceil(b 2^32 / p'), both rounded up.
+struct CoefPP {
+  uint32_t a, b, ap, bp;
+};
+// Per token length l < QPOW_N: pw1 = 257^(l+1) mod p', sp = 32 * 257^l mod p'.
+struct PowPP {
+  uint32_t pw1, sp;
+};
+
+__device__ __forceinline__ void store_token_pp(const TokenRecs &tr, uint32_t idx, uint32_t w,
+                                               uint32_t len, const PowPP *__restrict__ ptab) {
+  const uint32_t sp = len < (uint32_t)QPOW_N ? ptab[len].sp : mulmod_pp(32u, powmod_pp(257u, len));
+  uint32_t v = w + sp;
+  v = min(v, v - PP);
+  reinterpret_cast<uint32_t *>(tr.v)[idx] = v;  // this mode keeps 32-bit token values
+  tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
+  if (len >= LONG_TOKEN) tr.long_len[idx] = len;
+}
+
 static uint64_t g_chunk_bytes_override = 0;
 
 // ---- small kernels -------------------------------------------------------------------------
@@ -131,6 +180,36 @@ __global__ void k_coeffs(uint64_t seed, int K, uint64_t *a, uint64_t *b, CoefSpl
     e.pad = 0;
     e.nsp = P61 - sp;
     e.pad2 = 0;
+    ptab[k] = e;
+  }
+}
+
+// paper-prime coefficients a'_k = (a_k mod (p'-1)) + 1, b'_k = b_k mod p' and the token tables;
+// raw (optional) receives a'_k and b'_k as 64-bit values for the stage tests
+__global__ void k_coeffs_pp(uint64_t seed, int K, CoefPP *coef, PowPP *ptab, uint64_t *raw_a,
+                            uint64_t *raw_b) {
+  int k = blockIdx.x * blockDim.x + threadIdx.x;
+  uint64_t s0 = seed % (P61 - 1) + 1;
+  if (k < K) {
+    const uint64_t ak = mulmod(s0, powmod(G_A, (uint64_t)k + 1));
+    const uint64_t bk = mulmod(s0, powmod(G_B, (uint64_t)k + 1));
+    const uint32_t a = (uint32_t)(ak % (PP - 1)) + 1, b = (uint32_t)(bk % PP);
+    if (coef) {
+      CoefPP c;
+      c.a = a;
+      c.b = b;
+      c.ap = (uint32_t)((((uint64_t)a << 32) + PP - 1) / PP);  // a < p': below 2^32
+      c.bp = (uint32_t)((((uint64_t)b << 32) + PP - 1) / PP);
+      coef[k] = c;
+    }
+    if (raw_a) raw_a[k] = a;
+    if (raw_b) raw_b[k] = b;
+  }
+  if (ptab && k < QPOW_N) {
+    const uint32_t pw = powmod_pp(257u, (uint64_t)k);
+    PowPP e;
+    e.pw1 = mulmod_pp(pw, 257u);
+    e.sp = mulmod_pp(pw, 32u);
     ptab[k] = e;
   }
 }
@@ -356,6 +435,23 @@ __device__ __noinline__ WalkedToken walk_token(const uint8_t *__restrict__ pbase
   return r;
 }
 
+// the same modulo the paper's prime (w in the low word)
+__device__ __noinline__ WalkedToken walk_token_pp(const uint8_t *__restrict__ pbase, uint32_t p0,
+                                                  uint32_t ve) {
+  uint32_t w = 0, pw = 1, l = 0;
+  for (uint32_t p = p0; p < ve; p++) {
+    const uint32_t c = pbase[p];
+    if (is_ws(c)) break;
+    w = red_pp((uint64_t)pw * c + w);
+    pw = mulmod_pp(pw, 257u);
+    l++;
+  }
+  WalkedToken r;
+  r.w = w;
+  r.len = l;
+  return r;
+}
+
 // One wavefront per byte tile.
 // Pass 1 (lane = 16-byte segment): the tile's bytes, plus LOOK bytes of look-ahead, go to LDS
 // together with the bitmap of token bytes; every lane drops the positions of the tokens that
@@ -371,11 +467,13 @@ constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from L
 
 constexpr uint32_t SM_TEXT_WORDS = (TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2;
 
+// PAPER: the token hashes are taken modulo the paper's prime (32-bit records) instead.
+template <bool PAPER>
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
              const uint64_t *__restrict__ qpow, const PowSplit *__restrict__ ptab,
-             TokenRecs rec) {
+             const PowPP *__restrict__ ptab_pp, TokenRecs rec) {
   // text: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
   // than the wavefront's longest
   __shared__ uint32_t sm_text[SM_TEXT_WORDS];
@@ -438,6 +536,13 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
           active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
       const uint32_t flen = fast ? run : 0u;
       uint64_t acc = 0;
+      uint32_t acc_pp = 0;
+      constexpr uint32_t R3_PP = R3 % PP;
+      // acc <- acc * 257^3 + D in the mode's modulus
+      auto absorb = [&](uint32_t D) {
+        if (PAPER) acc_pp = red_pp((uint64_t)acc_pp * R3_PP + D);  // < 2^45 + 2^25
+        else acc = horner3_lazy(acc, D);
+      };
       if (!__any(flen > 8)) {
         // every token of this pass has at most 8 bytes: one 12-byte read, three digits
         const uint32_t wd = pos >> 2;
@@ -451,8 +556,13 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
         const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
         const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
         const uint32_t D2 = d2 + (d2 >> 8);
-        acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
-        acc = horner3_lazy(acc, D0);
+        if (PAPER) {
+          acc_pp = D2;  // < 2^17
+          absorb(D1);
+        } else {
+          acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
+        }
+        absorb(D0);
       } else {
         const uint32_t nd = (flen + 2) / 3;
         uint32_t maxnd = nd;
@@ -468,17 +578,21 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
           const uint32_t d = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & m;
           // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
           const uint32_t D = d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
-          acc = horner3_lazy(acc, D);
+          absorb(D);
         }
       }
-      uint64_t w = fold61(acc);
+      uint64_t w = PAPER ? (uint64_t)acc_pp : fold61(acc);
       uint32_t len = flen;
       if (active && !fast) {
-        const WalkedToken wt = walk_token(pbase, tile0 + pos, ve);
+        const WalkedToken wt = PAPER ? walk_token_pp(pbase, tile0 + pos, ve)
+                                     : walk_token(pbase, tile0 + pos, ve);
         w = wt.w;
         len = wt.len;
       }
-      if (active) store_token(rec, first_idx + j, w, len, qpow, ptab);
+      if (active) {
+        if (PAPER) store_token_pp(rec, first_idx + j, (uint32_t)w, len, ptab_pp);
+        else store_token(rec, first_idx + j, w, len, qpow, ptab);
+      }
     }
   }
 }
@@ -521,6 +635,7 @@ struct XSource {
   TokenRecs rec;          // token records (word mode)
   const uint64_t *qpow;   // 257^i, i < QPOW_N
   const PowSplit *ptab;   // Horner multipliers per token length, QPOW_N entries
+  const PowPP *ptab_pp;   // the same for the paper-prime mode
   const uint64_t *given;  // caller-supplied hashes (debug entry), indexed like the shingle stream
   uint32_t n;             // shingle length
 };
@@ -806,9 +921,232 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   }
 }
 
+// ---- the hot kernel of the paper-prime mode ----------------------------------------------------
+//
+// Same tiling as k_minhash: one wavefront per shingle tile, phase A fills LDS with the tile's
+// x'(s) = Eq. 1 mod p', phase B evaluates h'_k(s) = (a'_k x' + b'_k) mod p' for the lane's
+// functions over the tile.  Per (shingle, function):
+//   q = (x ap + bp) >> 32            one 32x32+64 multiply-add; ap, bp are rounded up, so q is
+//                                    the quotient of a x + b by p', or (rarely) one more
+//   s = (a x + b) - q p'             low 32 bits, two 24-bit multiply-adds (a, x, q, p' < 2^24)
+//   m = min(m, s)                    unsigned
+// x ap + bp exceeds 2^32 (a x + b) / p' by less than x + 2, i.e. the quotient estimate by less
+// than (p' + 1) / 2^32: q is one too large only if the remainder is within PP_EDGE of p'.  Then
+// s = h' - p' wraps to a huge unsigned value and the minimum ignores it.  So a tile minimum
+// below p' - PP_EDGE is exact (everything ignored was larger); a lane whose minimum is not
+// redoes its functions over the tile with the plain reduction.  That happens with probability
+// (PP_EDGE / p')^count per function: in practice only for tiles of one or two shingles, where
+// the second pass costs next to nothing.  4 instructions per evaluation.
+constexpr uint32_t PP_EDGE = 4400;  // > p' (p' + 2) / 2^32 = 4295.0
+
+__device__ __forceinline__ uint32_t token_value_pp(const TokenRecs &rec, uint32_t i) {
+  return reinterpret_cast<const uint32_t *>(rec.v)[i];
+}
+
+// x' of shingle i of tile ht (any token lengths; the general form)
+template <int MODE>
+__device__ __forceinline__ uint32_t shingle_x_pp(const XSource &xsrc, const HTile &ht, uint32_t i) {
+  if (MODE == X_GIVEN) return (uint32_t)(xsrc.given[ht.x_off + i] % PP);
+  if (MODE == X_BYTES) {
+    const uint32_t d = ht.doc;
+    const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
+    const uint32_t per = min(len, xsrc.n);
+    const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
+    uint32_t acc = 0;
+    for (uint32_t j = per; j-- > 0;) acc = red_pp((uint64_t)acc * 257u + p[j]);
+    return acc;
+  }
+  const TokenRecs &rec = xsrc.rec;
+  const uint32_t first = ht.tok0 + i, last = first + ht.per - 1;
+  const uint32_t l_last = token_len(rec, last);
+  const uint32_t sp = l_last < (uint32_t)QPOW_N ? xsrc.ptab_pp[l_last].sp
+                                                : mulmod_pp(32u, powmod_pp(257u, l_last));
+  uint32_t acc = token_value_pp(rec, last) + (PP - sp);  // the bare last token
+  acc = min(acc, acc - PP);
+  for (uint32_t m = last; m-- > first;) {
+    const uint32_t lm = token_len(rec, m);
+    const uint32_t pw1 = lm < (uint32_t)QPOW_N ? xsrc.ptab_pp[lm].pw1 : powmod_pp(257u, (uint64_t)lm + 1);
+    acc = red_pp((uint64_t)acc * pw1 + token_value_pp(rec, m));
+  }
+  return acc;
+}
+
+// the same for PER tokens shorter than LONG_TOKEN bytes, all loads issued up front
+template <int PER>
+__device__ __forceinline__ uint32_t words_x_pp_unrolled(const TokenRecs &rec,
+                                                        const PowPP *__restrict__ ptab,
+                                                        uint32_t first, bool *long_tok) {
+  uint32_t len[PER], V[PER];
+#pragma unroll
+  for (int m = 0; m < PER; m++) {
+    len[m] = rec.len[first + m];
+    V[m] = token_value_pp(rec, first + m);
+  }
+  PowPP e[PER];
+#pragma unroll
+  for (int m = 0; m < PER; m++) e[m] = ptab[len[m]];
+  bool lt = false;
+#pragma unroll
+  for (int m = 0; m < PER; m++) lt |= len[m] == LONG_TOKEN;
+  *long_tok = lt;
+  uint32_t acc = V[PER - 1] + (PP - e[PER - 1].sp);
+  acc = min(acc, acc - PP);
+#pragma unroll
+  for (int m = PER - 2; m >= 0; m--) acc = red_pp((uint64_t)acc * e[m].pw1 + V[m]);
+  return acc;
+}
+
+template <int F, int P, int MODE>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
+k_minhash_pp(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
+             const CoefPP *__restrict__ coef, int K,
+             uint32_t *__restrict__ sig /* first document of the chunk */) {
+  // half-wave g reads row g: shingle i sits at sx[i % P][i / P]; rows are padded with repeats of
+  // shingle 0 (a repeat cannot change a minimum) to a common multiple of 4 entries
+  constexpr uint32_t ROW = TS / P + 8;
+  __shared__ __attribute__((aligned(16))) uint32_t sx[P][ROW];
+  const uint32_t t = blockIdx.x;
+  const HTile ht = tiles[t];  // the list is allocated for the launch bound: safe past the count
+  if (t >= *n_tiles) return;
+  const uint32_t d = ht.doc, cnt = ht.cnt;
+
+  if (MODE == X_WORDS) {
+    const TokenRecs &rec = xsrc.rec;
+    const PowPP *__restrict__ ptab = xsrc.ptab_pp;
+    const uint32_t per = ht.per;
+    for (uint32_t i = threadIdx.x; i < cnt; i += 64) {
+      const uint32_t first = ht.tok0 + i;
+      bool long_tok = true;
+      uint32_t acc = 0;
+      if (per == 5) acc = words_x_pp_unrolled<5>(rec, ptab, first, &long_tok);
+      else if (per == 3) acc = words_x_pp_unrolled<3>(rec, ptab, first, &long_tok);
+      else if (per == 4) acc = words_x_pp_unrolled<4>(rec, ptab, first, &long_tok);
+      else if (per == 2) acc = words_x_pp_unrolled<2>(rec, ptab, first, &long_tok);
+      else if (per == 1) acc = words_x_pp_unrolled<1>(rec, ptab, first, &long_tok);
+      if (long_tok) acc = shingle_x_pp<MODE>(xsrc, ht, i);  // also every other shingle length
+      sx[i % P][i / P] = acc;
+    }
+  } else if (MODE == X_BYTES) {
+    // the tile's bytes are staged in LDS; lane l owns the WPL windows from WPL l on: the last
+    // of them by Horner over its bytes, the others by the reuse form of Eq. 1 (Eq. 2 read
+    // backwards):  x(i-1) = q (x(i) - c[i+per-1] q^(per-1)) + c[i-1]   (mod p')
+    __shared__ uint32_t sm_b[MODE == X_BYTES ? (TS + SEDD_MAX_SHINGLE_N + 8) / 4 + 1 : 1];
+    const uint32_t vs = xsrc.dv[d], dlen = xsrc.dv[d + 1] - vs;
+    const uint32_t per = min(dlen, xsrc.n);
+    const uint32_t b0 = vs + (ht.x_off - xsrc.sbase[d]);  // frame position of the first window
+    const uint32_t o = b0 & 3u;
+    const uint32_t ndw = (o + cnt + per - 1 + 3) >> 2;    // aligned words that hold >= 1 byte of it
+    for (uint32_t w = threadIdx.x; w < ndw; w += 64)
+      sm_b[w] = *reinterpret_cast<const uint32_t *>(xsrc.pbase + (b0 - o) + 4 * w);
+    __syncthreads();
+    const uint8_t *tb = reinterpret_cast<const uint8_t *>(sm_b) + o;  // tb[i] = byte i of the tile
+    const uint32_t l = threadIdx.x;
+    constexpr uint32_t WPL = TS / 64;
+    if (WPL * l < cnt) {
+      const uint32_t m = min(WPL, cnt - WPL * l);
+      const uint32_t top = WPL * l + m - 1;
+      uint32_t acc = 0;
+      for (uint32_t j = per; j-- > 0;) acc = red_pp((uint64_t)acc * 257u + tb[top + j]);
+      // 257^(per-1) = pw1 of length per - 2; per = 1 needs 257^0 = 1
+      const uint32_t qn = per >= 2 ? xsrc.ptab_pp[per - 2].pw1 : 1u;
+      const uint32_t neg_qn = PP - qn;  // in [1, p')
+      for (uint32_t i = top;; i--) {
+        sx[i % P][i / P] = acc;
+        if (i == WPL * l) break;
+        const uint32_t c_hi = tb[i + per - 1], c_lo = tb[i - 1];
+        const uint32_t dd = red_pp((uint64_t)c_hi * neg_qn + acc);  // x(i) - c_hi q^(per-1)
+        acc = red_pp((uint64_t)dd * 257u + c_lo);
+      }
+    }
+  } else {
+    for (uint32_t i = threadIdx.x; i < cnt; i += 64) sx[i % P][i / P] = shingle_x_pp<MODE>(xsrc, ht, i);
+  }
+  __syncthreads();
+  // pad every row to R entries, R = the longest row rounded up to a multiple of 4
+  const uint32_t cnt0 = (cnt + P - 1) / P, R = (cnt0 + 3) & ~3u;
+  if (threadIdx.x < 8 * P) {
+    const uint32_t row = threadIdx.x / 8, j = threadIdx.x % 8;
+    const uint32_t have = (cnt + P - 1 - row) / P;  // entries of this row
+    if (have + j < R) sx[row][have + j] = sx[0][0];
+  }
+
+  constexpr int LW = 64 / P;
+  const uint32_t grp = threadIdx.x / LW;
+  const int kbase = blockIdx.y * (LW * F) + (threadIdx.x % LW);
+  uint32_t a[F], b[F], ap[F], m[F];
+  uint64_t bp[F];
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    int k = kbase + LW * j;
+    const int kk = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
+    const uint4 c = *reinterpret_cast<const uint4 *>(coef + kk);
+    a[j] = c.x;
+    b[j] = c.y;
+    ap[j] = c.z;
+    bp[j] = c.w;
+    m[j] = 0xFFFFFFFFu;
+  }
+  __syncthreads();
+
+  const int neg_p = -(int)PP;
+  auto eval = [&](uint32_t x) {
+#pragma unroll
+    for (int j = 0; j < F; j++) {
+      const uint32_t q = (uint32_t)(((uint64_t)x * ap[j] + bp[j]) >> 32);
+      // the two 24-bit multiply-adds, spelled out: the compiler would otherwise emit two
+      // multiplies and a three-operand addition
+      uint32_t sv;
+      asm("v_mad_u32_u24 %0, %2, %3, %4\n\tv_mad_i32_i24 %0, %1, %5, %0"
+          : "=&v"(sv)
+          : "v"(q), "v"(a[j]), "v"(x), "v"(b[j]), "s"(neg_p));
+      m[j] = min(m[j], sv);
+    }
+  };
+  const uint4 *row = reinterpret_cast<const uint4 *>(&sx[grp][0]);
+  const uint32_t steps = R / 4;
+#pragma unroll 2
+  for (uint32_t s4 = 0; s4 < steps; s4++) {
+    const uint4 xv = row[s4];
+    eval(xv.x);
+    eval(xv.y);
+    eval(xv.z);
+    eval(xv.w);
+  }
+  bool redo = false;
+#pragma unroll
+  for (int j = 0; j < F; j++) redo |= m[j] >= PP - PP_EDGE;
+  if (__any(redo)) {
+    // rare (see above): the plain reduction over this half-wave's row
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+    for (uint32_t i = 0; i < R; i++) {
+      const uint32_t x = sx[grp][i];
+#pragma unroll
+      for (int j = 0; j < F; j++) m[j] = min(m[j], red_pp((uint64_t)a[j] * x + b[j]));
+    }
+  }
+  if (P == 2) {
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)__shfl_xor(m[j], 32, 64));
+  }
+  uint32_t *out = sig + (uint64_t)d * K;
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    int k = kbase + LW * j;
+    if (grp == 0 && k < K) {
+      if (ht.single) {
+        out[k] = m[j];
+      } else {
+        const uint32_t cur = __hip_atomic_load(out + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (m[j] < cur) atomicMin(out + k, m[j]);
+      }
+    }
+  }
+}
+
 // ---- stage-level output of the shingle hashes (debug entry) ----------------------------------
 
-template <int MODE>
+template <int MODE, bool PAPER>
 __global__ void __launch_bounds__(64)
 k_debug_write_x(XSource xsrc, const HTile *__restrict__ tiles,
                 const uint32_t *__restrict__ n_tiles, const uint64_t *__restrict__ total,
@@ -818,7 +1156,7 @@ k_debug_write_x(XSource xsrc, const HTile *__restrict__ tiles,
   const HTile ht = tiles[t];
   const uint64_t base = *total + ht.x_off;
   for (uint32_t i = threadIdx.x; i < ht.cnt; i += 64) {
-    const uint64_t x = shingle_x<MODE>(xsrc, ht, i);
+    const uint64_t x = PAPER ? (uint64_t)shingle_x_pp<MODE>(xsrc, ht, i) : shingle_x<MODE>(xsrc, ht, i);
     if (base + i < cap) out_x[base + i] = x;
   }
 }
@@ -835,7 +1173,8 @@ __global__ void k_debug_add_total(uint64_t *total, const uint32_t *sbase_last) {
 // launches the hot kernel over nht candidate tiles (tiles beyond the device-side count exit)
 static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
                           const uint32_t *n_tiles, uint64_t nht, const uint64_t *coef_a,
-                          const CoefSplit *coef_s, int K, uint32_t *csig, hipStream_t st) {
+                          const CoefSplit *coef_s, const CoefPP *coef_pp, int K, uint32_t *csig,
+                          hipStream_t st) {
   unsigned long long *stats = nullptr;
   int rc = stats_ensure(&stats);
   if (rc) return rc;
@@ -848,9 +1187,15 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   const HotConsts hc = {1u << 29, 8u, 1u};
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
-#define SEDD_LAUNCH_MH(FF, PP, MM)                                                          \
-  hipLaunchKernelGGL((k_minhash<FF, PP, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
-                     coef_a, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
+#define SEDD_LAUNCH_MH(FF, HW, MM)                                                              \
+  do {                                                                                         \
+    if (coef_pp)                                                                               \
+      hipLaunchKernelGGL((k_minhash_pp<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles,       \
+                         n_tiles, coef_pp, K, csig);                                           \
+    else                                                                                       \
+      hipLaunchKernelGGL((k_minhash<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
+                         coef_a, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);           \
+  } while (0)
 #define SEDD_LAUNCH_MH_F(MM)                       \
   do {                                             \
     if (P == 1) SEDD_LAUNCH_MH(4, 1, MM);          \
@@ -938,6 +1283,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
                        uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st) {
   const bool debug = dbg_off != nullptr;
   const int byte_mode = (flags & SEDD_FLAG_BYTE_SHINGLES) ? 1 : 0;
+  const bool paper = (flags & SEDD_FLAG_PAPER_PRIME) != 0;
 
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
@@ -1021,6 +1367,8 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_cs = cv.take<CoefSplit>(K);
   const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
   const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
+  const uint64_t o_cpp = cv.take<CoefPP>(K);
+  const uint64_t o_ptpp = cv.take<PowPP>(QPOW_N);
   const uint64_t o_total = cv.take<uint64_t>(1);
   const uint64_t o_dv = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_btb = cv.take<uint32_t>(max_nd + 1);
@@ -1041,6 +1389,8 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
   uint64_t *qpow = (uint64_t *)(A + o_qpow), *total = (uint64_t *)(A + o_total);
   PowSplit *ptab = (PowSplit *)(A + o_ptab);
+  CoefPP *coef_pp = (CoefPP *)(A + o_cpp);
+  PowPP *ptab_pp = (PowPP *)(A + o_ptpp);
   uint32_t *dv = (uint32_t *)(A + o_dv), *btb = (uint32_t *)(A + o_btb);
   BTile *btd = (BTile *)(A + o_btd);
   uint32_t *wbase = (uint32_t *)(A + o_wbase);
@@ -1058,14 +1408,19 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   xsrc.rec = rec;
   xsrc.qpow = qpow;
   xsrc.ptab = ptab;
+  xsrc.ptab_pp = ptab_pp;
   xsrc.given = nullptr;
   xsrc.n = (uint32_t)n;
   const int mode = byte_mode ? X_BYTES : X_WORDS;
 
   {
     int nthr = std::max(K, QPOW_N);
-    hipLaunchKernelGGL(k_coeffs, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
-                       coef_b, coef_s, qpow, ptab);
+    if (paper)
+      hipLaunchKernelGGL(k_coeffs_pp, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K,
+                         coef_pp, ptab_pp, (uint64_t *)nullptr, (uint64_t *)nullptr);
+    else
+      hipLaunchKernelGGL(k_coeffs, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
+                         coef_b, coef_s, qpow, ptab);
     SEDD_LAUNCH_CHECK();
   }
   if (debug) {
@@ -1113,8 +1468,12 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       SEDD_LAUNCH_CHECK();
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
-      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase, btd,
-                         btb + nd, wbase, qpow, ptab, rec);
+      if (paper)
+        hipLaunchKernelGGL(k_emit_words<true>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
+      else
+        hipLaunchKernelGGL(k_emit_words<false>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
       SEDD_LAUNCH_CHECK();
     }
     {
@@ -1133,12 +1492,14 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
     }
     xsrc.pbase = pbase;
     if (debug) {
-      if (byte_mode)
-        hipLaunchKernelGGL(k_debug_write_x<X_BYTES>, dim3((uint32_t)nht), dim3(64), 0, st, xsrc, htd,
-                           htb + nd, total, dbg_x, dbg_cap);
-      else
-        hipLaunchKernelGGL(k_debug_write_x<X_WORDS>, dim3((uint32_t)nht), dim3(64), 0, st, xsrc, htd,
-                           htb + nd, total, dbg_x, dbg_cap);
+#define SEDD_LAUNCH_DBG(MM, PAPER)                                                              \
+  hipLaunchKernelGGL((k_debug_write_x<MM, PAPER>), dim3((uint32_t)nht), dim3(64), 0, st, xsrc, \
+                     htd, htb + nd, total, dbg_x, dbg_cap)
+      if (byte_mode && paper) SEDD_LAUNCH_DBG(X_BYTES, true);
+      else if (byte_mode) SEDD_LAUNCH_DBG(X_BYTES, false);
+      else if (paper) SEDD_LAUNCH_DBG(X_WORDS, true);
+      else SEDD_LAUNCH_DBG(X_WORDS, false);
+#undef SEDD_LAUNCH_DBG
       SEDD_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_debug_write_offsets, dim3(gdoc), dim3(256), 0, st, sbase, nd, total,
                          dbg_off + c.d0);
@@ -1146,7 +1507,8 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
     } else {
-      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_s, (int)K,
+      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_s,
+                          paper ? coef_pp : (const CoefPP *)nullptr, (int)K,
                           sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
     }
@@ -1164,7 +1526,7 @@ int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_d
                  int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,
                  void *stream) {
   if (shingle_n < 1 || shingle_n > SEDD_MAX_SHINGLE_N || K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
-  if (flags & ~SEDD_FLAG_BYTE_SHINGLES) return SEDD_EINVAL;
+  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME)) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   return run_minhash(bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
@@ -1175,7 +1537,7 @@ int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
                               uint64_t n_docs, int32_t shingle_n, uint32_t flags, uint64_t *x,
                               uint64_t x_cap, uint64_t *shingle_offsets, void *stream) {
   if (shingle_n < 1 || shingle_n > SEDD_MAX_SHINGLE_N) return SEDD_EINVAL;
-  if (flags & ~SEDD_FLAG_BYTE_SHINGLES) return SEDD_EINVAL;
+  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME)) return SEDD_EINVAL;
   if (!shingle_offsets || (x_cap && !x)) return SEDD_EINVAL;
   if (n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   if (n_docs == 0) {
@@ -1196,9 +1558,17 @@ int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *
   return SEDD_OK;
 }
 
-int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
-                              uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,
-                              void *stream) {
+int sedd_debug_coeffs_pp(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream) {
+  if (K < 1 || K > SEDD_MAX_K || !a || !b) return SEDD_EINVAL;
+  hipLaunchKernelGGL(k_coeffs_pp, dim3((K + 255) / 256), dim3(256), 0, (hipStream_t)stream, seed,
+                     (int)K, (CoefPP *)nullptr, (PowPP *)nullptr, a, b);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+static int minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
+                          uint64_t n_shingles, int32_t K, uint64_t seed, bool paper, uint32_t *sig,
+                          void *stream) {
   if (K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!shingle_offsets || !sig || (n_shingles && !x)) return SEDD_EINVAL;
@@ -1209,6 +1579,7 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   Carver cv;
   const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
   const uint64_t o_cs = cv.take<CoefSplit>(K);
+  const uint64_t o_cpp = cv.take<CoefPP>(K);
   const uint64_t o_sbase = cv.take<uint32_t>(n_docs + 1), o_htb = cv.take<uint32_t>(n_docs + 1);
   const uint64_t o_htd = cv.take<HTile>(nht);
   const uint64_t o_tmp = cv.take<uint32_t>(scan_tmp_count(n_docs + 1));
@@ -1220,8 +1591,13 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   HTile *htd = (HTile *)(A + o_htd);
   uint32_t *tmp = (uint32_t *)(A + o_tmp);
   CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
-  hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
-                     coef_b, coef_s, (uint64_t *)nullptr, (PowSplit *)nullptr);
+  CoefPP *coef_pp = (CoefPP *)(A + o_cpp);
+  if (paper)
+    hipLaunchKernelGGL(k_coeffs_pp, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_pp,
+                       (PowPP *)nullptr, (uint64_t *)nullptr, (uint64_t *)nullptr);
+  else
+    hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
+                       coef_b, coef_s, (uint64_t *)nullptr, (PowSplit *)nullptr);
   SEDD_LAUNCH_CHECK();
   const uint64_t nsig = n_docs * (uint64_t)K;
   hipLaunchKernelGGL(k_fill_u32, dim3((uint32_t)std::min<uint64_t>((nsig + 255) / 256, 65536)),
@@ -1237,7 +1613,20 @@ int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets
   SEDD_LAUNCH_CHECK();
   XSource xsrc = {};
   xsrc.given = x;  // tiles index it by shingle offset
-  return launch_minhash(X_GIVEN, xsrc, htd, htb + nd, nht, coef_a, coef_s, (int)K, sig, st);
+  return launch_minhash(X_GIVEN, xsrc, htd, htb + nd, nht, coef_a, coef_s,
+                        paper ? coef_pp : (const CoefPP *)nullptr, (int)K, sig, st);
+}
+
+int sedd_debug_minhash_from_x(const uint64_t *x, const uint64_t *shingle_offsets, uint64_t n_docs,
+                              uint64_t n_shingles, int32_t K, uint64_t seed, uint32_t *sig,
+                              void *stream) {
+  return minhash_from_x(x, shingle_offsets, n_docs, n_shingles, K, seed, false, sig, stream);
+}
+
+int sedd_debug_minhash_from_x_pp(const uint64_t *x, const uint64_t *shingle_offsets,
+                                 uint64_t n_docs, uint64_t n_shingles, int32_t K, uint64_t seed,
+                                 uint32_t *sig, void *stream) {
+  return minhash_from_x(x, shingle_offsets, n_docs, n_shingles, K, seed, true, sig, stream);
 }
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {
