@@ -35,6 +35,11 @@ if ROOT not in sys.path:
 OPS_PER_PAIR = 8
 OPS_PER_BASE_STEP_WORD = 8
 OPS_PER_BASE_STEP_BYTE = 4
+# The paper-prime mode (modulus 4,294,967): per (shingle, function) one 32x32+64 multiply-add,
+# two 24-bit multiply-adds and half a three-input minimum; per Eq. 1 step one product reduced
+# through a quotient estimate (10 operations), two of them per byte window (reuse form).
+OPS_PER_PAIR_PP = 3.5
+OPS_PER_BASE_STEP_PP = 10
 # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one 32-bit integer lane-operation per lane per clock
 PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 STREAM_CHUNK_BYTES = 2 << 30
@@ -51,6 +56,11 @@ def ops_per_shingle(recipe, K):
     else:
         base = (recipe.shingle_n - 1) * OPS_PER_BASE_STEP_WORD
     return K * OPS_PER_PAIR + base
+
+
+def ops_per_shingle_pp(recipe, K):
+    base = (2 if recipe.byte_mode else recipe.shingle_n - 1) * OPS_PER_BASE_STEP_PP
+    return K * OPS_PER_PAIR_PP + base
 
 
 def load_corpus(torch, corpus, recipe, stream_chunk=None):
@@ -149,25 +159,25 @@ def main() -> int:
     t_gen = time.time() - t0
     n_docs = recipe.n_docs
 
-    def run_path(K, b, r, n, sig, keys, cid):
+    def run_path(K, b, r, n, sig, keys, cid, mode_flags):
         for text, off, d0, d1 in pieces:
-            sedd.sedd_minhash(text, off, n, K, 0, flags, out=sig[d0:d1])
+            sedd.sedd_minhash(text, off, n, K, 0, mode_flags, out=sig[d0:d1])
         sedd.sedd_lsh_keys(sig, b, r, out=keys)
         sedd.sedd_cluster(keys, out=cid)
 
-    def measure(K, b, r, n, steps, warmup):
+    def measure(K, b, r, n, steps, warmup, mode_flags=flags):
         sig = torch.empty((n_docs, K), dtype=torch.uint32, device="cuda")
         keys = torch.empty((n_docs, b), dtype=torch.uint64, device="cuda")
         cid = torch.empty((n_docs,), dtype=torch.int64, device="cuda")
         for _ in range(warmup):
-            run_path(K, b, r, n, sig, keys, cid)
+            run_path(K, b, r, n, sig, keys, cid, mode_flags)
         torch.cuda.synchronize()
         sedd.profile_enable(True)
         sedd.profile_read()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
-            run_path(K, b, r, n, sig, keys, cid)
+            run_path(K, b, r, n, sig, keys, cid, mode_flags)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         sedd.profile_enable(False)
@@ -262,6 +272,7 @@ def main() -> int:
         "stage_ms": {k: round(v[0] / 3, 4) for k, v in v_stages.items() if v[0]},
         "duplicates_found": int((vcid.cpu().numpy() != np.arange(n_docs)).sum()),
     }
+    h_vcid = vcid.cpu().numpy().copy()
 
     # The paper's own candidate generation (dense buckets, 4 sqrt(N) of them) followed by the
     # all-pairs count-match verification: also outside the timed steps.
@@ -297,6 +308,73 @@ def main() -> int:
             "duplicates_found": int((vcid.cpu().numpy() != np.arange(n_docs)).sum()),
         }
         del dkeys
+
+    # The same path with the paper's own modulus (p = 4,294,967) for Eq. 1 and the K functions:
+    # outside the timed steps.  Reported: its throughput, the instruction-count fraction of its
+    # hot kernel, and how far its clusters are from those of the 61-bit modulus.
+    paper = None
+    if n_docs <= 2_000_000 and not streamed:
+        p_steps = max(1, min(3, args.steps))
+        p_el, p_stages, p_sig, p_keys, p_cid = measure(K, b, r, n, p_steps, 1,
+                                                        flags | sedd.FLAG_PAPER_PRIME)
+        p_mh_ms = p_stages["minhash"][0]
+        p_ops = n_shingles * ops_per_shingle_pp(recipe, K) * p_steps
+        p_tops = p_ops / (p_mh_ms * 1e-3) / 1e12 if p_mh_ms else 0.0
+        h_pcid = p_cid.cpu().numpy()
+        p_vcid = sedd.sedd_cluster_verified(p_keys, p_sig, min_match).cpu().numpy()
+        # accuracy: the slot-match rate of planted near-duplicate pairs against their exact
+        # Jaccard similarity (brute-force shingle sets on the host), under both moduli
+        import oracle
+        gen = corpus.Corpus(recipe)
+        pairs = []
+        for dnum in range(min(n_docs, 200000)):
+            kind, src, _ = gen.meta(dnum)
+            if kind == 1 and max(h_off[dnum + 1] - h_off[dnum], h_off[src + 1] - h_off[src]) < 50000:
+                pairs.append((dnum, int(src)))
+            if len(pairs) >= 1500:
+                break
+        est = None
+        if pairs:
+            def doc(i):
+                return h_data[int(h_off[i]):int(h_off[i + 1])].tobytes()
+            J = np.array([jaccard_of_pair(oracle, doc(u), doc(v), n, recipe.byte_mode)
+                          for u, v in pairs])
+            ia = torch.tensor([u for u, _ in pairs], device="cuda")
+            ib = torch.tensor([v for _, v in pairs], device="cuda")
+
+            def rate(sg):
+                s32 = sg.view(torch.int32)
+                return (s32[ia] == s32[ib]).to(torch.float64).mean(dim=1).cpu().numpy()
+            e61, epp = rate(sig) - J, rate(p_sig) - J
+            est = {"planted_pairs": len(pairs), "mean_jaccard": round(float(J.mean()), 4),
+                   "mean_error_61_bit": round(float(e61.mean()), 5),
+                   "rms_error_61_bit": round(float(np.sqrt((e61 ** 2).mean())), 5),
+                   "mean_error_paper_prime": round(float(epp.mean()), 5),
+                   "rms_error_paper_prime": round(float(np.sqrt((epp ** 2).mean())), 5),
+                   "sampling_rms_expected": round(float(np.sqrt((J * (1 - J) / K).mean())), 5)}
+        s32 = p_sig.view(torch.int32)
+        n_long = int((np.diff(h_off.astype(np.int64)) >= 1_000_000).sum())
+        paper = {
+            "modulus": 4294967, "docs_per_s": round(n_docs * p_steps / p_el, 1),
+            "ms_per_step": round(1e3 * p_el / p_steps, 3),
+            "stage_ms_per_step": {k: round(v[0] / p_steps, 4) for k, v in p_stages.items() if v[0]},
+            "k_minhash_pp": {"ops_per_shingle": ops_per_shingle_pp(recipe, K),
+                             "achieved_TOPs": round(p_tops, 3),
+                             "frac_of_alu_peak": round(p_tops / PEAK_TOPS, 4),
+                             "hash_evals_per_s": round(n_shingles * K * p_steps / (p_mh_ms * 1e-3), 1)
+                             if p_mh_ms else 0},
+            "jaccard_estimate": est,
+            "duplicates_found": int((h_pcid != np.arange(n_docs)).sum()),
+            "verified_duplicates_found": int((p_vcid != np.arange(n_docs)).sum()),
+            "verified_duplicates_found_61_bit": int((h_vcid != np.arange(n_docs)).sum()),
+            # range exhaustion: documents of a million shingles or more leave minima near 0
+            "documents_of_1MB_or_more": n_long,
+            "largest_cluster": int(np.bincount(h_pcid).max()),
+            "largest_cluster_61_bit": int(np.bincount(cid.cpu().numpy()).max()),
+            "largest_verified_cluster": int(np.bincount(p_vcid).max()),
+            "largest_verified_cluster_61_bit": int(np.bincount(h_vcid).max()),
+        }
+        del p_sig, p_keys, p_cid
 
     cpu_baseline = None
     parity = None
@@ -343,6 +421,7 @@ def main() -> int:
         "exact_path_tiles": sedd.debug_stats()[sedd.STAT_SLOW_TILES],
         "verified_clusters": verified,
         "dense_buckets_verified": dense,
+        "paper_prime_mode": paper,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity_sample_ok": parity,

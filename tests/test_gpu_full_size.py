@@ -258,6 +258,46 @@ def test_config4_full_size_long_documents(sedd):
                              verified=True)
 
 
+def test_config2_full_size_paper_prime(sedd):
+    """The medium workload with the paper's own modulus (SEDD_FLAG_PAPER_PRIME)."""
+    r = corpus.config(2)
+    gen = corpus.Corpus(r)
+    say("config 2 at full size, paper-prime mode:", r.n_docs, "documents")
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 2, 1 << 62)
+    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=4000, n_longest=6, n_copies=0,
+                               seed=22)
+    # documents around the internal 256 MB chunk edges (about 99k documents per chunk)
+    edge = [d for c in range(1, 10) for d in range(c * 98_000, c * 98_000 + 2_500, 25)]
+    ids = np.array(sorted(set(ids.tolist()) | set(edge)), dtype=np.int64)
+    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 2)
+    _check_sampled_signatures(sig, ids, want, r.K, "config 2 paper prime")
+    vals = sig.view(torch.int32)
+    assert int(vals.max().item()) < 4294967 and int(vals.min().item()) >= -1
+    say(f"  signatures ok on {ids.size} sampled docs")
+    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 2 paper prime",
+                             verified=True)
+
+
+def test_config4_full_size_paper_prime(sedd):
+    """Long documents with the paper's own modulus: the 22-bit range is exhausted, which the
+    results must reproduce exactly (minima of a few units, large chance buckets)."""
+    r = corpus.config(4)
+    gen = corpus.Corpus(r)
+    say("config 4 at full size, paper-prime mode:", r.n_docs, "documents")
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 3, 1 << 62)
+    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1200, n_longest=1, n_copies=0,
+                               seed=44)
+    long_ids = np.nonzero(lengths > 1_000_000)[0]
+    extra = long_ids[np.argsort(lengths[long_ids])[:3]]
+    ids = np.array(sorted(set(ids.tolist()) | set(int(x) for x in extra)), dtype=np.int64)
+    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 3)
+    _check_sampled_signatures(sig, ids, want, r.K, "config 4 paper prime")
+    say(f"  signatures ok on {ids.size} sampled docs")
+    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 4 paper prime")
+    t_long = torch.from_numpy(long_ids).cuda()
+    assert int(sig.view(torch.int32)[t_long].max().item()) < 256    # every minimum collapsed
+
+
 def test_config5_full_size_sweep(sedd):
     """2M documents; K in {64,128,256,512} x (b,r) in {(8,16),(16,8),(32,8),(64,4)} x n in {3,5}."""
     r = corpus.config(5)
