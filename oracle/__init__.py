@@ -20,6 +20,7 @@ P61 = (1 << 61) - 1
 P_PAPER = 4294967           # the modulus Section 3.2 quotes for the paper's experiments
 FLAG_BYTE_SHINGLES = 1
 FLAG_PAPER_PRIME = 2
+FLAG_ROLLING_FAMILY = 4
 
 
 def build(force: bool = False) -> str:
@@ -52,6 +53,12 @@ def _load():
         lib.sedd_ref_coeffs_pp.argtypes = [u64, i32, vp, vp]
         lib.sedd_ref_minhash_shingles_pp.restype = C.c_int
         lib.sedd_ref_minhash_shingles_pp.argtypes = [vp, u64, i32, u64, vp]
+        lib.sedd_ref_base_hash_q.restype = u64
+        lib.sedd_ref_base_hash_q.argtypes = [vp, u64, u64]
+        lib.sedd_ref_bases.restype = C.c_int
+        lib.sedd_ref_bases.argtypes = [u64, i32, vp]
+        lib.sedd_ref_doc_shingles_q.restype = u64
+        lib.sedd_ref_doc_shingles_q.argtypes = [vp, u64, i32, u32, u64, vp, u64]
         lib.sedd_ref_coeffs.restype = C.c_int
         lib.sedd_ref_coeffs.argtypes = [u64, i32, vp, vp]
         lib.sedd_ref_doc_shingles.restype = u64
@@ -109,6 +116,33 @@ def base_hash_pp(s) -> int:
     """Eq. 1 modulo the paper's own prime."""
     s = _as_bytes(s)
     return _load().sedd_ref_base_hash_pp(_ptr(s), s.size)
+
+
+def base_hash_q(s, q: int) -> int:
+    """Eq. 1 to the base q, modulo 2^61 - 1."""
+    s = _as_bytes(s)
+    return _load().sedd_ref_base_hash_q(_ptr(s), s.size, q)
+
+
+def bases(seed: int, K: int) -> np.ndarray:
+    """Bases q_k of the rolling-family mode."""
+    q = np.zeros(K, dtype=np.uint64)
+    rc = _load().sedd_ref_bases(seed, K, q.ctypes.data)
+    if rc:
+        raise OracleError(rc)
+    return q
+
+
+def doc_shingles_q(text, n: int, q: int, byte_mode: bool = False) -> np.ndarray:
+    """Eq. 1 to the base q of the shingles of one document, in order."""
+    t = _as_bytes(text)
+    lib = _load()
+    flags = FLAG_BYTE_SHINGLES if byte_mode else 0
+    cnt = lib.sedd_ref_doc_shingles_q(_ptr(t), t.size, n, flags, q, None, 0)
+    out = np.zeros(cnt, dtype=np.uint64)
+    if cnt:
+        lib.sedd_ref_doc_shingles_q(_ptr(t), t.size, n, flags, q, out.ctypes.data, cnt)
+    return out
 
 
 def coeffs(seed: int, K: int, paper_prime: bool = False):

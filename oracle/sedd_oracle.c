@@ -36,6 +36,12 @@
  *   and the H functions are h'_k(s) = (a'_k * x'(s) + b'_k) mod p' with
  *   a'_k = (a_k mod (p'-1)) + 1 and b'_k = b_k mod p' (a_k, b_k as above);
  *   the value is below 2^23 and is stored as it is.
+ *   Rolling-family mode (flags bit 2): the other way to read "H hash
+ *   functions" next to Eq. 1: every function is Eq. 1 itself with a base of
+ *   its own, h_k(s) = (sum_i s_i * q_k^(i-1) mod p) mod 2^32 with
+ *   q_k = 257 + (a_k mod (p - 257)), a base above the alphabet size as
+ *   Section 3.2 asks; p = 2^61 - 1.  b_k is not used.  Not combinable with
+ *   the paper-prime bit.
  *
  * Parity with the paper authors' released code is unpinned: the paper prints
  * no hash value, signature or bucket id for any input.  The functions here
@@ -104,6 +110,16 @@ uint64_t sedd_ref_base_hash_pp(const uint8_t *s, uint64_t len) {
   return x;
 }
 
+/* Eq. 1 with an arbitrary base q < p */
+uint64_t sedd_ref_base_hash_q(const uint8_t *s, uint64_t len, uint64_t q) {
+  uint64_t x = 0, pw = 1;
+  for (uint64_t i = 0; i < len; i++) {
+    x = addmod(x, mulmod((uint64_t)s[i], pw));
+    pw = mulmod(pw, q);
+  }
+  return x;
+}
+
 /* coefficients of the K hash functions */
 int sedd_ref_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
   if (K < 1 || !a || !b) return SEDD_REF_EINVAL;
@@ -129,7 +145,20 @@ int sedd_ref_coeffs_pp(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b) {
   return SEDD_REF_OK;
 }
 
-static uint64_t shingle_hash(const uint8_t *s, uint64_t len, uint32_t flags) {
+/* bases of the rolling-family mode: q_k in [257, p-1] */
+int sedd_ref_bases(uint64_t seed, int32_t K, uint64_t *q) {
+  if (K < 1 || !q) return SEDD_REF_EINVAL;
+  uint64_t *b = (uint64_t *)malloc((size_t)K * 8);
+  if (!b) return SEDD_REF_ENOMEM;
+  sedd_ref_coeffs(seed, K, q, b);
+  for (int32_t k = 0; k < K; k++) q[k] = 257 + q[k] % (P61 - 257);
+  free(b);
+  return SEDD_REF_OK;
+}
+
+/* the shingle hash of the mode: q is the base where flags bit 2 is set, else ignored */
+static uint64_t shingle_hash(const uint8_t *s, uint64_t len, uint32_t flags, uint64_t q) {
+  if (flags & 4u) return sedd_ref_base_hash_q(s, len, q);
   return (flags & 2u) ? sedd_ref_base_hash_pp(s, len) : sedd_ref_base_hash(s, len);
 }
 
@@ -140,15 +169,15 @@ static int is_space(uint8_t c) { return c == 0x20 || (c >= 0x09 && c <= 0x0D); }
  * Returns the number of shingles; writes at most cap of them to out
  * (out may be NULL to count only).
  */
-uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32_t flags,
-                               uint64_t *out, uint64_t cap) {
+static uint64_t doc_shingles_q(const uint8_t *t, uint64_t len, int32_t n, uint32_t flags,
+                               uint64_t q, uint64_t *out, uint64_t cap) {
   uint64_t count = 0;
   if (n < 1) return 0;
   if (flags & 1u) {                                   /* byte n-grams */
     if (len == 0) return 0;
-    if (len < (uint64_t)n) { if (out && cap) out[0] = shingle_hash(t, len, flags); return 1; }
+    if (len < (uint64_t)n) { if (out && cap) out[0] = shingle_hash(t, len, flags, q); return 1; }
     for (uint64_t i = 0; i + n <= len; i++) {
-      if (out && count < cap) out[count] = shingle_hash(t + i, (uint64_t)n, flags);
+      if (out && count < cap) out[count] = shingle_hash(t + i, (uint64_t)n, flags, q);
       count++;
     }
     return count;
@@ -183,11 +212,22 @@ uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32
       if (j) buf[w++] = 0x20;
       memcpy(buf + w, t + ts[s + j], tl[s + j]); w += tl[s + j];
     }
-    if (out && count < cap) out[count] = shingle_hash(buf, w, flags);
+    if (out && count < cap) out[count] = shingle_hash(buf, w, flags, q);
     count++;
   }
   free(buf); free(ts); free(tl);
   return count;
+}
+
+uint64_t sedd_ref_doc_shingles(const uint8_t *t, uint64_t len, int32_t n, uint32_t flags,
+                               uint64_t *out, uint64_t cap) {
+  return doc_shingles_q(t, len, n, flags & 3u, 0, out, cap);
+}
+
+/* the same with Eq. 1 taken to the base q (rolling-family mode) */
+uint64_t sedd_ref_doc_shingles_q(const uint8_t *t, uint64_t len, int32_t n, uint32_t flags,
+                                 uint64_t q, uint64_t *out, uint64_t cap) {
+  return doc_shingles_q(t, len, n, (flags & 1u) | 4u, q, out, cap);
 }
 
 /*
@@ -236,24 +276,44 @@ int sedd_ref_minhash_shingles_pp(const uint64_t *x, uint64_t n_sh, int32_t K, ui
 int sedd_ref_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
                      int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags,
                      uint32_t *sig) {
-  if (shingle_n < 1 || K < 1 || (flags & ~3u)) return SEDD_REF_EINVAL;
+  if (shingle_n < 1 || K < 1 || (flags & ~7u) || (flags & 6u) == 6u) return SEDD_REF_EINVAL;
   if (n_docs == 0) return SEDD_REF_OK;
   if (!doc_offsets || !sig) return SEDD_REF_EINVAL;
   for (uint64_t d = 0; d < n_docs; d++)
     if (doc_offsets[d + 1] < doc_offsets[d]) return SEDD_REF_EINVAL;
   if (doc_offsets[n_docs] > doc_offsets[0] && !bytes) return SEDD_REF_EINVAL;
   uint64_t *x = NULL, xcap = 0;
+  uint64_t *qk = NULL;
+  if (flags & 4u) {
+    qk = (uint64_t *)malloc((size_t)K * 8);
+    if (!qk) return SEDD_REF_ENOMEM;
+    sedd_ref_bases(seed, K, qk);
+  }
   for (uint64_t d = 0; d < n_docs; d++) {
     const uint8_t *t = bytes + doc_offsets[d];
     uint64_t len = doc_offsets[d + 1] - doc_offsets[d];
-    uint64_t n_sh = sedd_ref_doc_shingles(t, len, shingle_n, flags, NULL, 0);
-    if (n_sh > xcap) { xcap = n_sh * 2; free(x); x = (uint64_t *)malloc(xcap * 8); if (!x) return SEDD_REF_ENOMEM; }
+    uint64_t n_sh = doc_shingles_q(t, len, shingle_n, flags, 257, NULL, 0);
+    if (n_sh > xcap) { xcap = n_sh * 2; free(x); x = (uint64_t *)malloc(xcap * 8); if (!x) { free(qk); return SEDD_REF_ENOMEM; } }
+    if (flags & 4u) {
+      /* every function hashes the shingles itself, with its own base */
+      for (int32_t k = 0; k < K; k++) {
+        doc_shingles_q(t, len, shingle_n, flags, qk[k], x, n_sh);
+        uint32_t m = 0xFFFFFFFFu;
+        for (uint64_t s = 0; s < n_sh; s++) {
+          uint32_t h32 = (uint32_t)(x[s] & 0xFFFFFFFFu);
+          if (h32 < m) m = h32;
+        }
+        sig[d * (uint64_t)K + k] = m;
+      }
+      continue;
+    }
     sedd_ref_doc_shingles(t, len, shingle_n, flags, x, n_sh);
     int rc = (flags & 2u) ? sedd_ref_minhash_shingles_pp(x, n_sh, K, seed, sig + d * (uint64_t)K)
                           : sedd_ref_minhash_shingles(x, n_sh, K, seed, sig + d * (uint64_t)K);
     if (rc) { free(x); return rc; }
   }
   free(x);
+  free(qk);
   return SEDD_REF_OK;
 }
 

@@ -88,3 +88,15 @@ def signature_pp(text: bytes, n: int, K: int, seed: int = 0, byte_mode: bool = F
     a, b = coeffs_pp(seed, K)
     xs = [eq1(s, Q, P_PAPER) for s in shingle_strings(text, n, byte_mode)]
     return [min((a[k] * x + b[k]) % P_PAPER for x in xs) if xs else 0xFFFFFFFF for k in range(K)]
+
+
+# ---- rolling-family mode: every function is Eq. 1 with its own base ----
+
+def bases(seed: int, K: int):
+    a, _ = coeffs(seed, K)
+    return [257 + x % (P - 257) for x in a]
+
+
+def signature_rf(text: bytes, n: int, K: int, seed: int = 0, byte_mode: bool = False):
+    sh = shingle_strings(text, n, byte_mode)
+    return [min(eq1(s, q) % (1 << 32) for s in sh) if sh else 0xFFFFFFFF for q in bases(seed, K)]

@@ -141,7 +141,7 @@ def test_truncation_happens_before_the_minimum():
 
 def test_argument_validation():
     off = np.array([0, 3], dtype=np.uint64)
-    for kw in (dict(shingle_n=0, K=8), dict(shingle_n=5, K=0), dict(shingle_n=5, K=8, flags=4)):
+    for kw in (dict(shingle_n=0, K=8), dict(shingle_n=5, K=0), dict(shingle_n=5, K=8, flags=8), dict(shingle_n=5, K=8, flags=6)):
         with pytest.raises(oracle.OracleError):
             oracle.minhash(b"abc", off, **kw)
     with pytest.raises(oracle.OracleError):

@@ -115,7 +115,7 @@ def test_set_semantics_and_prefix_property():
 
 def test_flag_bits_are_checked():
     with pytest.raises(oracle.OracleError):
-        oracle.minhash(b"a b", [0, 3], 5, 4, 0, 4)
+        oracle.minhash(b"a b", [0, 3], 5, 4, 0, 8)
     # the two modes are different functions of the same text
     t = b"one two three four five six seven"
     assert (oracle.minhash(t, [0, len(t)], 5, 16, 0, 0) != oracle.minhash(t, [0, len(t)], 5, 16, 0, PAPER)).any()
