@@ -41,6 +41,7 @@ extern "C" {
 /* flags of sedd_minhash */
 #define SEDD_FLAG_BYTE_SHINGLES 1u /* shingles are byte n-grams instead of word n-grams */
 #define SEDD_FLAG_PAPER_PRIME 2u   /* Eq. 1 and the K functions modulo 4,294,967 (see below) */
+#define SEDD_FLAG_ROLLING_FAMILY 4u /* function k is Eq. 1 itself to a base q_k (see below) */
 
 /* largest K / shingle_n / b the kernels accept */
 #define SEDD_MAX_K 4096
@@ -70,6 +71,13 @@ extern "C" {
  * a'_k = (a_k mod (p'-1)) + 1, b'_k = b_k mod p'; the values are below 2^23 and are stored as
  * they are.  A 22-bit range is exhausted by documents with millions of shingles (every
  * minimum tends to 0): the mode is meant for comparison with the paper's setting.
+ *
+ * SEDD_FLAG_ROLLING_FAMILY: the other way to obtain K functions from Section 3.2: function k is
+ * Eq. 1 with a base of its own, h_k(s) = ((sum_i s_i * q_k^(i-1)) mod p) mod 2^32 with
+ * q_k = 257 + (a_k mod (p - 257)) and p = 2^61-1; b_k is not used.  Every function then has to
+ * hash every shingle from its characters (about 10 times the work of step 3 on 5-word
+ * shingles), and shingles that differ only in their first character keep their order under
+ * every function.  Provided for comparison; not combinable with SEDD_FLAG_PAPER_PRIME.
  *
  * bytes        device, uint8; read in [doc_offsets[0], doc_offsets[n_docs]).
  * doc_offsets  device, uint64[n_docs+1], non-decreasing byte offsets into `bytes`.

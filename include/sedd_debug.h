@@ -14,7 +14,8 @@ extern "C" {
 
 /*
  * Base hashes x(s) of every shingle (Section 3.2, Eq. 1), in document order (modulo 2^61-1, or
- * modulo 4,294,967 with SEDD_FLAG_PAPER_PRIME).
+ * modulo 4,294,967 with SEDD_FLAG_PAPER_PRIME; SEDD_FLAG_ROLLING_FAMILY has no function-independent
+ * shingle hash and is rejected).
  *   shingle_offsets  device, uint64[n_docs+1]: document d owns x[shingle_offsets[d] ..
  *                    shingle_offsets[d+1]).
  *   x                device, uint64[x_cap]; entries beyond x_cap are not written (the
@@ -29,6 +30,9 @@ int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *
 
 /* The same for SEDD_FLAG_PAPER_PRIME: a'_k and b'_k (both below 4,294,967) as uint64. */
 int sedd_debug_coeffs_pp(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream);
+
+/* Bases q_k of SEDD_FLAG_ROLLING_FAMILY: device uint64[K]. */
+int sedd_debug_bases(uint64_t seed, int32_t K, uint64_t *q, void *stream);
 
 /* Exclusive prefix sum of n uint32 values (device), out may alias in. */
 int sedd_debug_scan_u32(const uint32_t *in, uint32_t *out, uint64_t n, void *stream);

@@ -22,11 +22,12 @@ __all__ = [
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
     "debug_shingle_hashes_offsets",
-    "FLAG_BYTE_SHINGLES", "FLAG_PAPER_PRIME",
+    "FLAG_BYTE_SHINGLES", "FLAG_PAPER_PRIME", "FLAG_ROLLING_FAMILY", "debug_bases",
 ]
 
 FLAG_BYTE_SHINGLES = 1
 FLAG_PAPER_PRIME = 2      # Eq. 1 and the K functions modulo 4,294,967 (Section 3.2)
+FLAG_ROLLING_FAMILY = 4   # function k is Eq. 1 itself to a base q_k of its own
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsedd.so")
 _lib = None
@@ -83,6 +84,8 @@ def lib():
         L.sedd_debug_minhash_from_x.argtypes = [vp, vp, u64, u64, i32, u64, vp, vp]
         L.sedd_debug_minhash_from_x_pp.restype = C.c_int
         L.sedd_debug_minhash_from_x_pp.argtypes = [vp, vp, u64, u64, i32, u64, vp, vp]
+        L.sedd_debug_bases.restype = C.c_int
+        L.sedd_debug_bases.argtypes = [u64, i32, vp, vp]
         L.sedd_debug_coeffs_pp.restype = C.c_int
         L.sedd_debug_coeffs_pp.argtypes = [u64, i32, vp, vp, vp]
         L.sedd_debug_stats.restype = C.c_int
@@ -289,6 +292,13 @@ def debug_coeffs(seed: int, K: int, stream=None, paper_prime: bool = False):
     fn = lib().sedd_debug_coeffs_pp if paper_prime else lib().sedd_debug_coeffs
     _check(fn(seed, K, _ptr(a), _ptr(b), _stream(stream)), "sedd_debug_coeffs")
     return a, b
+
+
+def debug_bases(seed: int, K: int, stream=None):
+    torch = _torch()
+    q = torch.zeros(max(K, 0), dtype=torch.uint64, device="cuda")
+    _check(lib().sedd_debug_bases(seed, K, _ptr(q), _stream(stream)), "sedd_debug_bases")
+    return q
 
 
 def debug_scan_u32(values, stream=None):

@@ -139,6 +139,14 @@ __device__ __forceinline__ void store_token_pp(const TokenRecs &tr, uint32_t idx
   if (len >= LONG_TOKEN) tr.long_len[idx] = len;
 }
 
+// position record of the rolling-family mode (32-bit values, like the paper-prime records)
+__device__ __forceinline__ void store_token_pos(const TokenRecs &tr, uint32_t idx, uint32_t pos,
+                                                uint32_t len) {
+  reinterpret_cast<uint32_t *>(tr.v)[idx] = pos;
+  tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
+  if (len >= LONG_TOKEN) tr.long_len[idx] = len;
+}
+
 static uint64_t g_chunk_bytes_override = 0;
 
 // ---- small kernels -------------------------------------------------------------------------
@@ -467,8 +475,11 @@ constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from L
 
 constexpr uint32_t SM_TEXT_WORDS = (TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2;
 
-// PAPER: the token hashes are taken modulo the paper's prime (32-bit records) instead.
-template <bool PAPER>
+// EM selects what a record holds beside the length: the token's Eq. 1 hash mod 2^61-1 (EM_P61),
+// the same modulo the paper's prime as a 32-bit value (EM_PP), or the token's position in the
+// chunk frame as a 32-bit value (EM_POS, for the mode whose functions hash the bytes themselves).
+enum { EM_P61 = 0, EM_PP = 1, EM_POS = 2 };
+template <int EM>
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
@@ -540,7 +551,7 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
       constexpr uint32_t R3_PP = R3 % PP;
       // acc <- acc * 257^3 + D in the mode's modulus
       auto absorb = [&](uint32_t D) {
-        if (PAPER) acc_pp = red_pp((uint64_t)acc_pp * R3_PP + D);  // < 2^45 + 2^25
+        if (EM == EM_PP) acc_pp = red_pp((uint64_t)acc_pp * R3_PP + D);  // < 2^45 + 2^25
         else acc = horner3_lazy(acc, D);
       };
       if (!__any(flen > 8)) {
@@ -556,7 +567,7 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
         const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
         const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
         const uint32_t D2 = d2 + (d2 >> 8);
-        if (PAPER) {
+        if (EM == EM_PP) {
           acc_pp = D2;  // < 2^17
           absorb(D1);
         } else {
@@ -581,16 +592,17 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
           absorb(D);
         }
       }
-      uint64_t w = PAPER ? (uint64_t)acc_pp : fold61(acc);
+      uint64_t w = EM == EM_PP ? (uint64_t)acc_pp : fold61(acc);
       uint32_t len = flen;
       if (active && !fast) {
-        const WalkedToken wt = PAPER ? walk_token_pp(pbase, tile0 + pos, ve)
-                                     : walk_token(pbase, tile0 + pos, ve);
+        const WalkedToken wt = EM == EM_PP ? walk_token_pp(pbase, tile0 + pos, ve)
+                                           : walk_token(pbase, tile0 + pos, ve);
         w = wt.w;
         len = wt.len;
       }
       if (active) {
-        if (PAPER) store_token_pp(rec, first_idx + j, (uint32_t)w, len, ptab_pp);
+        if (EM == EM_PP) store_token_pp(rec, first_idx + j, (uint32_t)w, len, ptab_pp);
+        else if (EM == EM_POS) store_token_pos(rec, first_idx + j, tile0 + pos, len);
         else store_token(rec, first_idx + j, w, len, qpow, ptab);
       }
     }
@@ -1144,6 +1156,310 @@ k_minhash_pp(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__re
   }
 }
 
+// ---- rolling-family mode (SEDD_FLAG_ROLLING_FAMILY) --------------------------------------------
+//
+// The other reading of "H hash functions" next to Eq. 1: function k is Eq. 1 itself to a base q_k
+// of its own, h_k(s) = (sum_i s_i q_k^(i-1) mod p) mod 2^32, q_k = 257 + (a_k mod (p - 257)).
+// Nothing is shared between the functions any more: every (shingle, function) pair has to see
+// the shingle's characters.  Lane = function (F per lane); the characters are wave-uniform.
+//
+// Word shingles: a shingle of tokens t_0 .. t_{n-1} joined by single spaces is
+//   x = S_0 + P_0 (S_1 + P_1 (... + P_{n-2} T_{n-1})),  T_j = Eq. 1 of token j to the base q_k,
+//   S_j = T_j + 32 q_k^len_j (the token and its space),  P_j = q_k^(len_j + 1).
+// A lane walks the tile's tokens once: it hashes the new last token from its bytes (len
+// multiply-adds), combines it with the n - 1 pairs (S, P) it keeps of the tokens before it
+// (n - 1 multiply-adds), and shifts that window by one token.  The powers q_k^e, e <= RF_POW_MAX,
+// come from a table laid out [e][k]; longer tokens take a per-lane power.  About len + n
+// modular multiply-adds per (shingle, function) against one in the affine family.
+// Shingles of more than RF_RING + 1 tokens are hashed from their bytes, token by token.
+//
+// Byte shingles: Eq. 2, the reuse form, read backwards per function:
+//   x(i-1) = q_k (x(i) - c[i+n-1] q_k^(n-1)) + c[i-1]    (two multiply-adds per window).
+
+constexpr int RF_POW_MAX = 64;  // table rows: q_k^0 .. q_k^RF_POW_MAX
+constexpr int RF_RING = 4;      // tokens kept per lane: shingles of up to 5 tokens
+
+// q_k and the table of its powers
+__global__ void k_coeffs_rf(uint64_t seed, int K, uint64_t *__restrict__ qk,
+                            uint64_t *__restrict__ pwtab) {
+  int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= K) return;
+  const uint64_t s0 = seed % (P61 - 1) + 1;
+  const uint64_t ak = mulmod(s0, powmod(G_A, (uint64_t)k + 1));
+  const uint64_t q = 257 + ak % (P61 - 257);
+  qk[k] = q;
+  if (pwtab) {
+    uint64_t pw = 1;
+    for (int e = 0; e <= RF_POW_MAX; e++) {
+      pwtab[(size_t)e * K + k] = pw;
+      pw = mulmod(pw, q);
+    }
+  }
+}
+
+struct MulSplit {
+  uint32_t a0, a0_2, a12;
+};
+__device__ __forceinline__ MulSplit mul_split(uint64_t P) {
+  MulSplit r;
+  r.a0 = (uint32_t)P & 0x7FFFFFFFu;
+  r.a0_2 = r.a0 << 1;
+  r.a12 = (uint32_t)(P >> 31) << 1;
+  return r;
+}
+// 32 v for v < p: a shift by 5 is a rotation of the 61-bit residue
+__device__ __forceinline__ uint64_t mul32_mod(uint64_t v) {
+  return ((v << 5) & P61) | (v >> 56);
+}
+
+struct RfArgs {
+  const uint8_t *pbase;     // chunk text frame
+  const uint32_t *tok_pos;  // token positions in the frame (word mode)
+  const uint8_t *tok_len;   // min(len, LONG_TOKEN)
+  const uint32_t *tok_long; // lengths of the tokens of LONG_TOKEN bytes or more
+  const uint32_t *dv;       // document frame positions (byte mode)
+  const uint32_t *sbase;    // shingle offsets per document (byte mode)
+  const uint64_t *qk;       // bases
+  const uint64_t *pwtab;    // [RF_POW_MAX + 1][K] powers
+  uint32_t n;               // shingle length
+};
+
+template <int F>
+struct RfLane {
+  uint64_t q[F];
+  MulSplit qs[F];
+  int k[F];
+};
+
+// q_k^e for the lane's functions (e is wave-uniform)
+template <int F>
+__device__ __forceinline__ void rf_powers(const RfArgs &ra, const RfLane<F> &ln, int K, uint32_t e,
+                                          uint64_t (&out)[F]) {
+#pragma unroll
+  for (int j = 0; j < F; j++)
+    out[j] = e <= (uint32_t)RF_POW_MAX ? ra.pwtab[(size_t)e * K + ln.k[j]] : powmod(ln.q[j], e);
+}
+
+// T = Eq. 1 of the bytes [pos, pos + len) to the lane's bases (Horner from the last byte), added
+// on top of acc * q^len: acc <- acc q^len + T.  acc may be lazily reduced (< 2^61 + 8).
+template <int F>
+__device__ __forceinline__ void rf_absorb_bytes(const RfArgs &ra, const RfLane<F> &ln, uint32_t pos,
+                                                uint32_t len, const HotConsts &hc,
+                                                uint64_t (&acc)[F]) {
+  const uint8_t *__restrict__ p = ra.pbase + pos;
+  for (uint32_t i = len; i-- > 0;) {
+    const uint32_t c = p[i];
+#pragma unroll
+    for (int j = 0; j < F; j++)
+      acc[j] = horner_step_lazy(acc[j], ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, c, hc);
+  }
+}
+
+template <int F>
+__device__ __forceinline__ void rf_store(const HTile &ht, const RfLane<F> &ln, int K,
+                                         uint32_t *__restrict__ sig, const uint32_t (&m)[F]) {
+  uint32_t *out = sig + (uint64_t)ht.doc * K;
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    const int k = ln.k[j];
+    if (k < K) {
+      if (ht.single) {
+        out[k] = m[j];
+      } else {
+        const uint32_t cur = __hip_atomic_load(out + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (m[j] < cur) atomicMin(out + k, m[j]);
+      }
+    }
+  }
+}
+
+template <int F>
+__device__ __forceinline__ void rf_lane_init(const RfArgs &ra, int K, RfLane<F> &ln) {
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    const int k = blockIdx.y * (64 * F) + 64 * j + threadIdx.x;
+    ln.k[j] = k;
+    ln.q[j] = ra.qk[k < K ? k : 0];  // lanes past K compute function 0 and store nothing
+    if (k >= K) ln.k[j] = K;         // table reads of such a lane use column 0 (see rf_powers)
+    ln.qs[j] = mul_split(ln.q[j]);
+  }
+}
+
+template <int F>
+__global__ void __launch_bounds__(64)
+k_minhash_rf_words(RfArgs ra, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
+                   int K, uint32_t *__restrict__ sig, HotConsts hc) {
+  const uint32_t t = blockIdx.x;
+  const HTile ht = tiles[t];  // the list is allocated for the launch bound: safe past the count
+  if (t >= *n_tiles) return;
+  RfLane<F> ln;
+  rf_lane_init<F>(ra, K, ln);
+  // table column of a lane past K: any valid one
+  RfLane<F> tl = ln;
+#pragma unroll
+  for (int j = 0; j < F; j++) tl.k[j] = ln.k[j] < K ? ln.k[j] : 0;
+
+  const uint32_t per = ht.per, cnt = ht.cnt;
+  uint32_t m[F];
+#pragma unroll
+  for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+
+  auto tok_len = [&](uint32_t i) {
+    uint32_t l = ra.tok_len[i];
+    if (l == LONG_TOKEN) l = ra.tok_long[i];
+    return l;
+  };
+
+  if (per > (uint32_t)RF_RING + 1) {
+    // long shingles: every shingle from its bytes, last token first
+    for (uint32_t i = 0; i < cnt; i++) {
+      uint64_t x[F];
+#pragma unroll
+      for (int j = 0; j < F; j++) x[j] = 0;
+      for (uint32_t tkn = ht.tok0 + i + per; tkn-- > ht.tok0 + i;) {
+        if (tkn != ht.tok0 + i + per - 1) {
+#pragma unroll
+          for (int j = 0; j < F; j++)  // the space after this token
+            x[j] = horner_step_lazy(x[j], ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, 32u, hc);
+        }
+        rf_absorb_bytes<F>(ra, ln, ra.tok_pos[tkn], tok_len(tkn), hc, x);
+      }
+#pragma unroll
+      for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)fold61(x[j]));
+    }
+    rf_store<F>(ht, ln, K, sig, m);
+    return;
+  }
+
+  // the window of the per - 1 tokens before the newest one: S (token and its space) and P
+  uint64_t S[RF_RING][F], Pw[RF_RING][F];
+#pragma unroll
+  for (int r = 0; r < RF_RING; r++)
+#pragma unroll
+    for (int j = 0; j < F; j++) S[r][j] = Pw[r][j] = 0;
+
+  // token -> T (bare), and its (S, P) pair
+  auto hash_token = [&](uint32_t tkn, uint64_t (&T)[F], uint64_t (&Sn)[F], uint64_t (&Pn)[F]) {
+    const uint32_t len = tok_len(tkn);
+#pragma unroll
+    for (int j = 0; j < F; j++) T[j] = 0;
+    rf_absorb_bytes<F>(ra, ln, ra.tok_pos[tkn], len, hc, T);
+    uint64_t ql[F];
+    rf_powers<F>(ra, tl, K, len, ql);
+    rf_powers<F>(ra, tl, K, len + 1, Pn);
+#pragma unroll
+    for (int j = 0; j < F; j++) {
+      const uint64_t sp = mul32_mod(ql[j]);       // < 2^61
+      const uint64_t v = T[j] + sp;                // < 2^62 + 8
+      Sn[j] = (v & P61) + (v >> 61);               // < 2^61 + 2
+    }
+  };
+
+  // warm-up: the first per - 1 tokens fill the window
+  for (uint32_t w = 0; w + 1 < per; w++) {
+    uint64_t T[F], Sn[F], Pn[F];
+    hash_token(ht.tok0 + w, T, Sn, Pn);
+#pragma unroll
+    for (int r = 0; r < RF_RING; r++) {
+      if ((uint32_t)r == w) {
+#pragma unroll
+        for (int j = 0; j < F; j++) {
+          S[r][j] = Sn[j];
+          Pw[r][j] = Pn[j];
+        }
+      }
+    }
+  }
+  for (uint32_t i = 0; i < cnt; i++) {
+    uint64_t T[F], Sn[F], Pn[F];
+    hash_token(ht.tok0 + i + per - 1, T, Sn, Pn);
+    uint64_t x[F];
+#pragma unroll
+    for (int j = 0; j < F; j++) x[j] = T[j];
+#pragma unroll
+    for (int r = RF_RING - 1; r >= 0; r--) {
+      if ((uint32_t)r + 1 < per) {  // wave-uniform
+#pragma unroll
+        for (int j = 0; j < F; j++) {
+          const MulSplit ps = mul_split(Pw[r][j]);
+          x[j] = horner_step_lazy(x[j], ps.a0, ps.a0_2, ps.a12, S[r][j], hc);
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)fold61(x[j]));
+    // shift the window: slot r <- slot r + 1, the newest token enters slot per - 2
+#pragma unroll
+    for (int r = 0; r < RF_RING; r++) {
+#pragma unroll
+      for (int j = 0; j < F; j++) {
+        if ((uint32_t)r + 2 == per) {
+          S[r][j] = Sn[j];
+          Pw[r][j] = Pn[j];
+        } else if (r + 1 < RF_RING) {
+          S[r][j] = S[r + 1][j];
+          Pw[r][j] = Pw[r + 1][j];
+        }
+      }
+    }
+  }
+  rf_store<F>(ht, ln, K, sig, m);
+}
+
+template <int F>
+__global__ void __launch_bounds__(64)
+k_minhash_rf_bytes(RfArgs ra, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
+                   int K, uint32_t *__restrict__ sig, HotConsts hc) {
+  __shared__ uint32_t sm_b[(TS + SEDD_MAX_SHINGLE_N + 8) / 4 + 1];
+  const uint32_t t = blockIdx.x;
+  const HTile ht = tiles[t];
+  if (t >= *n_tiles) return;
+  RfLane<F> ln;
+  rf_lane_init<F>(ra, K, ln);
+  const uint32_t d = ht.doc, cnt = ht.cnt;
+  const uint32_t vs = ra.dv[d], dlen = ra.dv[d + 1] - vs;
+  const uint32_t per = min(dlen, ra.n);
+  const uint32_t b0 = vs + (ht.x_off - ra.sbase[d]);  // frame position of the first window
+  const uint32_t o = b0 & 3u;
+  const uint32_t ndw = (o + cnt + per - 1 + 3) >> 2;
+  for (uint32_t w = threadIdx.x; w < ndw; w += 64)
+    sm_b[w] = *reinterpret_cast<const uint32_t *>(ra.pbase + (b0 - o) + 4 * w);
+  __syncthreads();
+  const uint8_t *tb = reinterpret_cast<const uint8_t *>(sm_b) + o;  // tb[i] = byte i of the tile
+
+  uint64_t x[F], nqn[F];
+  uint32_t m[F];
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    x[j] = 0;
+    nqn[j] = P61 - powmod(ln.q[j], per - 1);  // -q^(per-1), in [1, p - 1]
+  }
+  // the last window by Horner, then backwards
+  for (uint32_t jb = per; jb-- > 0;) {
+    const uint32_t c = tb[cnt - 1 + jb];
+#pragma unroll
+    for (int j = 0; j < F; j++)
+      x[j] = horner_step_lazy(x[j], ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, c, hc);
+  }
+#pragma unroll
+  for (int j = 0; j < F; j++) m[j] = (uint32_t)fold61(x[j]);
+  for (uint32_t i = cnt - 1; i > 0; i--) {
+    const uint32_t c_hi = tb[i + per - 1], c_lo = tb[i - 1];
+#pragma unroll
+    for (int j = 0; j < F; j++) {
+      // x(i) - c_hi q^(per-1): c_hi (p - q^(per-1)) < 2^69 is folded in two halves
+      const uint64_t lo = (uint64_t)(uint32_t)nqn[j] * c_hi;
+      const uint64_t hi = (uint64_t)(uint32_t)(nqn[j] >> 32) * c_hi + (lo >> 32);  // < 2^37
+      const uint64_t tq = (((hi & 0x1FFFFFFFull) << 32) | (uint32_t)lo) + (hi >> 29);
+      uint64_t dd = x[j] + tq;  // < 2^62 + 2^9
+      dd = (dd & P61) + (dd >> 61);
+      x[j] = horner_step_lazy(dd, ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, c_lo, hc);
+      m[j] = min(m[j], (uint32_t)fold61(x[j]));
+    }
+  }
+  rf_store<F>(ht, ln, K, sig, m);
+}
+
 // ---- stage-level output of the shingle hashes (debug entry) ----------------------------------
 
 template <int MODE, bool PAPER>
@@ -1208,6 +1524,28 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   else SEDD_LAUNCH_MH_F(X_GIVEN);
 #undef SEDD_LAUNCH_MH_F
 #undef SEDD_LAUNCH_MH
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+// the same for the rolling-family kernels: lane = function, F = 2 functions per lane above K = 64
+static int launch_minhash_rf(int byte_mode, const RfArgs &ra, const HTile *tiles,
+                             const uint32_t *n_tiles, uint64_t nht, int K, uint32_t *csig,
+                             hipStream_t st) {
+  const int F = K > 64 ? 2 : 1;
+  const HotConsts hc = {1u << 29, 8u, 1u};
+  dim3 grid((uint32_t)nht, (uint32_t)((K + 64 * F - 1) / (64 * F)));
+  ProfScope prof(SEDD_PROF_MINHASH, st);
+#define SEDD_LAUNCH_RF(KERNEL, FF) \
+  hipLaunchKernelGGL((KERNEL<FF>), grid, dim3(64), 0, st, ra, tiles, n_tiles, K, csig, hc)
+  if (byte_mode) {
+    if (F == 2) SEDD_LAUNCH_RF(k_minhash_rf_bytes, 2);
+    else SEDD_LAUNCH_RF(k_minhash_rf_bytes, 1);
+  } else {
+    if (F == 2) SEDD_LAUNCH_RF(k_minhash_rf_words, 2);
+    else SEDD_LAUNCH_RF(k_minhash_rf_words, 1);
+  }
+#undef SEDD_LAUNCH_RF
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
@@ -1284,6 +1622,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const bool debug = dbg_off != nullptr;
   const int byte_mode = (flags & SEDD_FLAG_BYTE_SHINGLES) ? 1 : 0;
   const bool paper = (flags & SEDD_FLAG_PAPER_PRIME) != 0;
+  const bool rolling = (flags & SEDD_FLAG_ROLLING_FAMILY) != 0;
 
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
@@ -1369,6 +1708,8 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
   const uint64_t o_cpp = cv.take<CoefPP>(K);
   const uint64_t o_ptpp = cv.take<PowPP>(QPOW_N);
+  const uint64_t o_rfq = cv.take<uint64_t>(rolling ? K : 1);
+  const uint64_t o_rfp = cv.take<uint64_t>(rolling ? (uint64_t)(RF_POW_MAX + 1) * K : 1);
   const uint64_t o_total = cv.take<uint64_t>(1);
   const uint64_t o_dv = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_btb = cv.take<uint32_t>(max_nd + 1);
@@ -1391,6 +1732,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
   PowSplit *ptab = (PowSplit *)(A + o_ptab);
   CoefPP *coef_pp = (CoefPP *)(A + o_cpp);
   PowPP *ptab_pp = (PowPP *)(A + o_ptpp);
+  uint64_t *rf_q = (uint64_t *)(A + o_rfq), *rf_pw = (uint64_t *)(A + o_rfp);
   uint32_t *dv = (uint32_t *)(A + o_dv), *btb = (uint32_t *)(A + o_btb);
   BTile *btd = (BTile *)(A + o_btd);
   uint32_t *wbase = (uint32_t *)(A + o_wbase);
@@ -1418,6 +1760,9 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
     if (paper)
       hipLaunchKernelGGL(k_coeffs_pp, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K,
                          coef_pp, ptab_pp, (uint64_t *)nullptr, (uint64_t *)nullptr);
+    else if (rolling)
+      hipLaunchKernelGGL(k_coeffs_rf, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, rf_q,
+                         rf_pw);
     else
       hipLaunchKernelGGL(k_coeffs, dim3((nthr + 255) / 256), dim3(256), 0, st, seed, (int)K, coef_a,
                          coef_b, coef_s, qpow, ptab);
@@ -1469,10 +1814,13 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
       if (paper)
-        hipLaunchKernelGGL(k_emit_words<true>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+        hipLaunchKernelGGL(k_emit_words<EM_PP>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
+      else if (rolling)
+        hipLaunchKernelGGL(k_emit_words<EM_POS>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
                            btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
       else
-        hipLaunchKernelGGL(k_emit_words<false>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+        hipLaunchKernelGGL(k_emit_words<EM_P61>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
                            btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
       SEDD_LAUNCH_CHECK();
     }
@@ -1506,6 +1854,19 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
       SEDD_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_debug_add_total, dim3(1), dim3(1), 0, st, total, sbase + nd);
       SEDD_LAUNCH_CHECK();
+    } else if (rolling) {
+      RfArgs ra;
+      ra.pbase = pbase;
+      ra.tok_pos = reinterpret_cast<const uint32_t *>(rec.v);
+      ra.tok_len = rec.len;
+      ra.tok_long = rec.long_len;
+      ra.dv = dv;
+      ra.sbase = sbase;
+      ra.qk = rf_q;
+      ra.pwtab = rf_pw;
+      ra.n = (uint32_t)n;
+      rc = launch_minhash_rf(byte_mode, ra, htd, htb + nd, nht, (int)K, sig + c.d0 * (uint64_t)K, st);
+      if (rc) return rc;
     } else {
       rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_s,
                           paper ? coef_pp : (const CoefPP *)nullptr, (int)K,
@@ -1526,7 +1887,9 @@ int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_d
                  int32_t shingle_n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,
                  void *stream) {
   if (shingle_n < 1 || shingle_n > SEDD_MAX_SHINGLE_N || K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
-  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME)) return SEDD_EINVAL;
+  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME | SEDD_FLAG_ROLLING_FAMILY))
+    return SEDD_EINVAL;
+  if ((flags & SEDD_FLAG_PAPER_PRIME) && (flags & SEDD_FLAG_ROLLING_FAMILY)) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   return run_minhash(bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
@@ -1554,6 +1917,14 @@ int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *
   if (K < 1 || K > SEDD_MAX_K || !a || !b) return SEDD_EINVAL;
   hipLaunchKernelGGL(k_coeffs, dim3((K + 255) / 256), dim3(256), 0, (hipStream_t)stream, seed,
                      (int)K, a, b, (CoefSplit *)nullptr, (uint64_t *)nullptr, (PowSplit *)nullptr);
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+int sedd_debug_bases(uint64_t seed, int32_t K, uint64_t *q, void *stream) {
+  if (K < 1 || K > SEDD_MAX_K || !q) return SEDD_EINVAL;
+  hipLaunchKernelGGL(k_coeffs_rf, dim3((K + 255) / 256), dim3(256), 0, (hipStream_t)stream, seed,
+                     (int)K, q, (uint64_t *)nullptr);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }

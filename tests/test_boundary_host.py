@@ -45,7 +45,7 @@ u64 = C.c_uint64
 FAKE = C.c_void_p(0x1000)     # never dereferenced: these calls must fail validation first
 
 
-@pytest.mark.parametrize("n,K,flags", [(0, 8, 0), (65, 8, 0), (5, 0, 0), (5, 4097, 0), (5, 8, 4), (5, 8, 0x80000000), (-1, 8, 0)])
+@pytest.mark.parametrize("n,K,flags", [(0, 8, 0), (65, 8, 0), (5, 0, 0), (5, 4097, 0), (5, 8, 8), (5, 8, 6), (5, 8, 0x80000000), (-1, 8, 0)])
 def test_minhash_rejects_bad_scalars(n, K, flags):
     L = sedd.lib()
     assert L.sedd_minhash(FAKE, FAKE, u64(4), n, K, u64(0), flags, FAKE, None) == -1
