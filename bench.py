@@ -309,21 +309,13 @@ def main() -> int:
         }
         del dkeys
 
-    # The same path with the paper's own modulus (p = 4,294,967) for Eq. 1 and the K functions:
-    # outside the timed steps.  Reported: its throughput, the instruction-count fraction of its
-    # hot kernel, and how far its clusters are from those of the 61-bit modulus.
+    # The same path under the two other readings of "H hash functions": the paper's own modulus
+    # (p = 4,294,967) for Eq. 1 and the K functions, and Eq. 1 itself to K different bases.
+    # Outside the timed steps.  Reported per mode: throughput, the instruction-count fraction of
+    # its hot kernel, and how well its signatures estimate the Jaccard similarity of planted pairs.
     paper = None
+    rolling = None
     if n_docs <= 2_000_000 and not streamed:
-        p_steps = max(1, min(3, args.steps))
-        p_el, p_stages, p_sig, p_keys, p_cid = measure(K, b, r, n, p_steps, 1,
-                                                        flags | sedd.FLAG_PAPER_PRIME)
-        p_mh_ms = p_stages["minhash"][0]
-        p_ops = n_shingles * ops_per_shingle_pp(recipe, K) * p_steps
-        p_tops = p_ops / (p_mh_ms * 1e-3) / 1e12 if p_mh_ms else 0.0
-        h_pcid = p_cid.cpu().numpy()
-        p_vcid = sedd.sedd_cluster_verified(p_keys, p_sig, min_match).cpu().numpy()
-        # accuracy: the slot-match rate of planted near-duplicate pairs against their exact
-        # Jaccard similarity (brute-force shingle sets on the host), under both moduli
         import oracle
         gen = corpus.Corpus(recipe)
         pairs = []
@@ -333,48 +325,68 @@ def main() -> int:
                 pairs.append((dnum, int(src)))
             if len(pairs) >= 1500:
                 break
-        est = None
-        if pairs:
-            def doc(i):
-                return h_data[int(h_off[i]):int(h_off[i + 1])].tobytes()
-            J = np.array([jaccard_of_pair(oracle, doc(u), doc(v), n, recipe.byte_mode)
-                          for u, v in pairs])
-            ia = torch.tensor([u for u, _ in pairs], device="cuda")
-            ib = torch.tensor([v for _, v in pairs], device="cuda")
 
-            def rate(sg):
-                s32 = sg.view(torch.int32)
-                return (s32[ia] == s32[ib]).to(torch.float64).mean(dim=1).cpu().numpy()
-            e61, epp = rate(sig) - J, rate(p_sig) - J
-            est = {"planted_pairs": len(pairs), "mean_jaccard": round(float(J.mean()), 4),
-                   "mean_error_61_bit": round(float(e61.mean()), 5),
-                   "rms_error_61_bit": round(float(np.sqrt((e61 ** 2).mean())), 5),
-                   "mean_error_paper_prime": round(float(epp.mean()), 5),
-                   "rms_error_paper_prime": round(float(np.sqrt((epp ** 2).mean())), 5),
-                   "sampling_rms_expected": round(float(np.sqrt((J * (1 - J) / K).mean())), 5)}
-        s32 = p_sig.view(torch.int32)
+        def doc(i):
+            return h_data[int(h_off[i]):int(h_off[i + 1])].tobytes()
+        J = np.array([jaccard_of_pair(oracle, doc(u), doc(v), n, recipe.byte_mode)
+                      for u, v in pairs]) if pairs else None
+        ia = torch.tensor([u for u, _ in pairs], device="cuda", dtype=torch.int64)
+        ib = torch.tensor([v for _, v in pairs], device="cuda", dtype=torch.int64)
+
+        def estimate_error(sg):
+            if not pairs:
+                return None
+            s32 = sg.view(torch.int32)
+            e = (s32[ia] == s32[ib]).to(torch.float64).mean(dim=1).cpu().numpy() - J
+            return {"mean": round(float(e.mean()), 5), "rms": round(float(np.sqrt((e ** 2).mean())), 5)}
+        err61 = estimate_error(sig)
         n_long = int((np.diff(h_off.astype(np.int64)) >= 1_000_000).sum())
-        paper = {
-            "modulus": 4294967, "docs_per_s": round(n_docs * p_steps / p_el, 1),
-            "ms_per_step": round(1e3 * p_el / p_steps, 3),
-            "stage_ms_per_step": {k: round(v[0] / p_steps, 4) for k, v in p_stages.items() if v[0]},
-            "k_minhash_pp": {"ops_per_shingle": ops_per_shingle_pp(recipe, K),
-                             "achieved_TOPs": round(p_tops, 3),
-                             "frac_of_alu_peak": round(p_tops / PEAK_TOPS, 4),
-                             "hash_evals_per_s": round(n_shingles * K * p_steps / (p_mh_ms * 1e-3), 1)
-                             if p_mh_ms else 0},
-            "jaccard_estimate": est,
-            "duplicates_found": int((h_pcid != np.arange(n_docs)).sum()),
-            "verified_duplicates_found": int((p_vcid != np.arange(n_docs)).sum()),
-            "verified_duplicates_found_61_bit": int((h_vcid != np.arange(n_docs)).sum()),
-            # range exhaustion: documents of a million shingles or more leave minima near 0
-            "documents_of_1MB_or_more": n_long,
-            "largest_cluster": int(np.bincount(h_pcid).max()),
-            "largest_cluster_61_bit": int(np.bincount(cid.cpu().numpy()).max()),
-            "largest_verified_cluster": int(np.bincount(p_vcid).max()),
-            "largest_verified_cluster_61_bit": int(np.bincount(h_vcid).max()),
-        }
-        del p_sig, p_keys, p_cid
+        h_cid61 = cid.cpu().numpy()
+
+        def mode_leg(mode_flag, ops_ps, steps_m):
+            el, st, m_sig, m_keys, m_cid = measure(K, b, r, n, steps_m, 1, flags | mode_flag)
+            mh = st["minhash"][0]
+            tops = n_shingles * ops_ps * steps_m / (mh * 1e-3) / 1e12 if mh else 0.0
+            h_mcid = m_cid.cpu().numpy()
+            m_vcid = sedd.sedd_cluster_verified(m_keys, m_sig, min_match).cpu().numpy()
+            leg = {
+                "docs_per_s": round(n_docs * steps_m / el, 1),
+                "ms_per_step": round(1e3 * el / steps_m, 3),
+                "stage_ms_per_step": {k: round(v[0] / steps_m, 4) for k, v in st.items() if v[0]},
+                "hot_kernel": {"ops_per_shingle": round(ops_ps, 1), "achieved_TOPs": round(tops, 3),
+                               "frac_of_alu_peak": round(tops / PEAK_TOPS, 4),
+                               "hash_evals_per_s": round(n_shingles * K * steps_m / (mh * 1e-3), 1)
+                               if mh else 0},
+                "jaccard_estimate": {"planted_pairs": len(pairs),
+                                     "mean_jaccard": round(float(J.mean()), 4) if pairs else None,
+                                     "error": estimate_error(m_sig), "error_61_bit_affine": err61,
+                                     "sampling_rms_expected":
+                                         round(float(np.sqrt((J * (1 - J) / K).mean())), 5) if pairs else None},
+                "duplicates_found": int((h_mcid != np.arange(n_docs)).sum()),
+                "verified_duplicates_found": int((m_vcid != np.arange(n_docs)).sum()),
+                "verified_duplicates_found_61_bit_affine": int((h_vcid != np.arange(n_docs)).sum()),
+                # range exhaustion: documents of a million shingles or more leave minima near 0
+                "documents_of_1MB_or_more": n_long,
+                "largest_cluster": int(np.bincount(h_mcid).max()),
+                "largest_cluster_61_bit_affine": int(np.bincount(h_cid61).max()),
+                "largest_verified_cluster": int(np.bincount(m_vcid).max()),
+                "largest_verified_cluster_61_bit_affine": int(np.bincount(h_vcid).max()),
+            }
+            del m_sig, m_keys, m_cid
+            return leg
+
+        paper = mode_leg(sedd.FLAG_PAPER_PRIME, ops_per_shingle_pp(recipe, K),
+                         max(1, min(3, args.steps)))
+        paper["modulus"] = 4294967
+        # rolling family: per (shingle, function) about (mean token length + n - 1) modular
+        # multiply-adds of 8 operations on word shingles, 2 on byte shingles
+        if recipe.byte_mode:
+            rf_mads = 2.0
+        else:
+            tokens = n_shingles + (n - 1) * n_docs
+            rf_mads = (n_bytes - tokens) / max(1, tokens) + (n - 1)
+        rolling = mode_leg(sedd.FLAG_ROLLING_FAMILY, K * rf_mads * OPS_PER_PAIR, 1)
+        rolling["multiply_adds_per_evaluation"] = round(rf_mads, 2)
 
     cpu_baseline = None
     parity = None
@@ -422,6 +434,7 @@ def main() -> int:
         "verified_clusters": verified,
         "dense_buckets_verified": dense,
         "paper_prime_mode": paper,
+        "rolling_family_mode": rolling,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity_sample_ok": parity,

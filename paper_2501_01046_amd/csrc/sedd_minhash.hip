@@ -1246,12 +1246,20 @@ template <int F>
 __device__ __forceinline__ void rf_absorb_bytes(const RfArgs &ra, const RfLane<F> &ln, uint32_t pos,
                                                 uint32_t len, const HotConsts &hc,
                                                 uint64_t (&acc)[F]) {
-  const uint8_t *__restrict__ p = ra.pbase + pos;
-  for (uint32_t i = len; i-- > 0;) {
-    const uint32_t c = p[i];
+  // the bytes come in as aligned words (the frame starts on a 16-byte boundary and a word that
+  // holds one byte of the text lies inside the text's allocation), last word first
+  uint32_t i = pos + len;
+  while (i > pos) {
+    const uint32_t wb = (i - 1) & ~3u;
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(ra.pbase + wb);
+    const uint32_t lo = max(wb, pos);
+    for (uint32_t b = i; b-- > lo;) {
+      const uint32_t c = (w >> (8u * (b - wb))) & 0xFFu;
 #pragma unroll
-    for (int j = 0; j < F; j++)
-      acc[j] = horner_step_lazy(acc[j], ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, c, hc);
+      for (int j = 0; j < F; j++)
+        acc[j] = horner_step_lazy(acc[j], ln.qs[j].a0, ln.qs[j].a0_2, ln.qs[j].a12, c, hc);
+    }
+    i = lo;
   }
 }
 
