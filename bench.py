@@ -7,10 +7,13 @@ one the headline metric is quoted on: 1M web-text-shaped documents, 5-word shing
 16 bands of 8 rows.  Prints one JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--docs N]
-                    [--sweep] [--no-cpu-baseline]
+                    [--sweep] [--no-cpu-baseline] [--no-host-leg]
 
 --config 3 keeps the whole text resident and feeds sedd_minhash 2 GB at a time; --config 5
 --sweep runs the K x (b, r) x n grid and adds the planted-pair S-curve fit per setting.
+After the timed steps the same buffers serve a few untimed measurements reported beside the
+headline: verified clusters, the dense-bucket flow, the two alternative hash-function modes, and
+the path fed from pinned host memory (the PCIe-inclusive rate).
 The CPU oracle is timed on a bounded sample of the same corpus and reported beside the GPU
 figure as `cpu_baseline`; it is a reported baseline, not the target.
 """
@@ -117,6 +120,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--theta", type=float, default=0.8,
                     help="similarity threshold of the verified-cluster measurement")
+    ap.add_argument("--no-host-leg", action="store_true",
+                    help="skip the measurement with the text resident in pinned host memory")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference point for HBM "
                          "byte counters collected with rocprofv3 --pmc)")
@@ -388,6 +393,97 @@ def main() -> int:
         rolling = mode_leg(sedd.FLAG_ROLLING_FAMILY, K * rf_mads * OPS_PER_PAIR, 1)
         rolling["multiply_adds_per_evaluation"] = round(rf_mads, 2)
 
+    # The same path with the text resident in pinned HOST memory: pieces of at most 2 GB go
+    # through two device staging buffers, the upload of piece i+1 on a copy stream overlapping
+    # sedd_minhash of piece i.  Outside the timed steps; never the headline value.
+    host_leg = None
+    if not args.no_host_leg:
+        HOST_LEG_BYTES = 8 << 30
+        chunk = min(STREAM_CHUNK_BYTES, max(64 << 20, n_bytes // 6))
+        subs, tot = [], 0
+        for text, off, d0, d1 in pieces:
+            if tot >= HOST_LEG_BYTES:
+                break
+            h_t, h_o = text.cpu().numpy(), off.cpu().numpy()
+            a, nd = 0, d1 - d0
+            while a < nd and tot < HOST_LEG_BYTES:
+                e = int(np.searchsorted(h_o, h_o[a] + np.uint64(chunk), side="right")) - 1
+                e = min(nd, max(a + 1, e))
+                lo, hi = int(h_o[a]), int(h_o[e])
+                p_t = torch.empty(hi - lo, dtype=torch.uint8, pin_memory=True)
+                p_t.numpy()[:] = h_t[lo:hi]
+                p_o = torch.empty(e - a + 1, dtype=torch.int64, pin_memory=True)
+                p_o.numpy()[:] = (h_o[a:e + 1] - h_o[a]).view(np.int64)
+                subs.append((p_t, p_o, d0 + a, d0 + e))
+                tot += hi - lo
+                a = e
+            del h_t, h_o
+        leg_docs = subs[-1][3]                       # documents [0, leg_docs) take part
+        stage = [(torch.empty(max(x[0].numel() for x in subs), dtype=torch.uint8, device="cuda"),
+                  torch.empty(max(x[1].numel() for x in subs), dtype=torch.int64, device="cuda"))
+                 for _ in range(2)]
+        copy_s, comp_s = torch.cuda.Stream(), torch.cuda.current_stream()
+        ref = sig[:leg_docs].clone()
+        h_sig = torch.empty_like(ref)
+
+        def one_pass(compute):
+            done, copied = [None, None], {}
+
+            def upload(i):
+                t, o, _, _ = subs[i]
+                st = stage[i % 2]
+                with torch.cuda.stream(copy_s):
+                    if done[i % 2] is not None:
+                        copy_s.wait_event(done[i % 2])
+                    st[0][:t.numel()].copy_(t, non_blocking=True)
+                    st[1][:o.numel()].copy_(o, non_blocking=True)
+                    ev = torch.cuda.Event()
+                    ev.record(copy_s)
+                    copied[i] = ev
+            upload(0)
+            for i in range(len(subs)):
+                if i + 1 < len(subs):
+                    upload(i + 1)
+                comp_s.wait_event(copied[i])
+                t, o, d0, d1 = subs[i]
+                st = stage[i % 2]
+                if compute:
+                    sedd.sedd_minhash(st[0][:t.numel()], st[1][:o.numel()].view(torch.uint64), n, K,
+                                      0, flags, out=h_sig[d0:d1])
+                ev = torch.cuda.Event()
+                ev.record(comp_s)
+                done[i % 2] = ev
+            if compute:
+                sedd.sedd_lsh_keys(h_sig, b, r, out=keys[:leg_docs])
+                sedd.sedd_cluster(keys[:leg_docs], out=cid[:leg_docs])
+
+        def timed(compute, reps):
+            one_pass(compute)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                one_pass(compute)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps
+        reps = max(1, min(3, args.steps))
+        t_path = timed(True, reps)
+        same = bool(torch.equal(h_sig.view(torch.int32), ref.view(torch.int32)))
+        t_copy = timed(False, reps)
+        host_leg = {
+            "what": "text in pinned host memory, double-buffered upload overlapped with sedd_minhash; "
+                    "then band keys and clusters of the same documents",
+            "documents": leg_docs, "text_bytes": tot, "pieces": len(subs), "piece_bytes": chunk,
+            "ms_per_pass": round(1e3 * t_path, 3), "docs_per_s": round(leg_docs / t_path, 1),
+            "text_GB_per_s": round(tot / t_path / 1e9, 3),
+            "upload_only_ms_per_pass": round(1e3 * t_copy, 3),
+            "upload_only_GB_per_s": round(tot / t_copy / 1e9, 3),
+            "signatures_equal_device_resident_run": same,
+        }
+        # keys and cid held the whole corpus before this leg: restore them
+        sedd.sedd_lsh_keys(sig, b, r, out=keys)
+        sedd.sedd_cluster(keys, out=cid)
+        del stage, subs, ref, h_sig
+
     cpu_baseline = None
     parity = None
     if not args.no_cpu_baseline:
@@ -435,6 +531,7 @@ def main() -> int:
         "dense_buckets_verified": dense,
         "paper_prime_mode": paper,
         "rolling_family_mode": rolling,
+        "host_resident_input": host_leg,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "parity_sample_ok": parity,
