@@ -116,7 +116,7 @@ def main() -> int:
     ap.add_argument("--r", type=int, default=0)
     ap.add_argument("--shingle-n", type=int, default=0)
     ap.add_argument("--sweep", action="store_true", help="config 5 parameter grid")
-    ap.add_argument("--cpu-sample-docs", type=int, default=20000)
+    ap.add_argument("--cpu-sample-docs", type=int, default=60000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--theta", type=float, default=0.8,
                     help="similarity threshold of the verified-cluster measurement")

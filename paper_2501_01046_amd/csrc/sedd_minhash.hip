@@ -1226,9 +1226,10 @@ struct RfArgs {
 
 template <int F>
 struct RfLane {
-  uint64_t q[F];
+  uint64_t q[F];   // the lane's bases
   MulSplit qs[F];
-  int k[F];
+  int k[F];        // function index; >= K for a lane with nothing to store
+  int col[F];      // its column of the power table (a lane past K reads column 0)
 };
 
 // q_k^e for the lane's functions (e is wave-uniform)
@@ -1237,7 +1238,7 @@ __device__ __forceinline__ void rf_powers(const RfArgs &ra, const RfLane<F> &ln,
                                           uint64_t (&out)[F]) {
 #pragma unroll
   for (int j = 0; j < F; j++)
-    out[j] = e <= (uint32_t)RF_POW_MAX ? ra.pwtab[(size_t)e * K + ln.k[j]] : powmod(ln.q[j], e);
+    out[j] = e <= (uint32_t)RF_POW_MAX ? ra.pwtab[(size_t)e * K + ln.col[j]] : powmod(ln.q[j], e);
 }
 
 // T = Eq. 1 of the bytes [pos, pos + len) to the lane's bases (Horner from the last byte), added
@@ -1287,8 +1288,8 @@ __device__ __forceinline__ void rf_lane_init(const RfArgs &ra, int K, RfLane<F> 
   for (int j = 0; j < F; j++) {
     const int k = blockIdx.y * (64 * F) + 64 * j + threadIdx.x;
     ln.k[j] = k;
-    ln.q[j] = ra.qk[k < K ? k : 0];  // lanes past K compute function 0 and store nothing
-    if (k >= K) ln.k[j] = K;         // table reads of such a lane use column 0 (see rf_powers)
+    ln.col[j] = k < K ? k : 0;  // lanes past K compute function 0 and store nothing
+    ln.q[j] = ra.qk[ln.col[j]];
     ln.qs[j] = mul_split(ln.q[j]);
   }
 }
@@ -1302,10 +1303,6 @@ k_minhash_rf_words(RfArgs ra, const HTile *__restrict__ tiles, const uint32_t *_
   if (t >= *n_tiles) return;
   RfLane<F> ln;
   rf_lane_init<F>(ra, K, ln);
-  // table column of a lane past K: any valid one
-  RfLane<F> tl = ln;
-#pragma unroll
-  for (int j = 0; j < F; j++) tl.k[j] = ln.k[j] < K ? ln.k[j] : 0;
 
   const uint32_t per = ht.per, cnt = ht.cnt;
   uint32_t m[F];
@@ -1353,8 +1350,8 @@ k_minhash_rf_words(RfArgs ra, const HTile *__restrict__ tiles, const uint32_t *_
     for (int j = 0; j < F; j++) T[j] = 0;
     rf_absorb_bytes<F>(ra, ln, ra.tok_pos[tkn], len, hc, T);
     uint64_t ql[F];
-    rf_powers<F>(ra, tl, K, len, ql);
-    rf_powers<F>(ra, tl, K, len + 1, Pn);
+    rf_powers<F>(ra, ln, K, len, ql);
+    rf_powers<F>(ra, ln, K, len + 1, Pn);
 #pragma unroll
     for (int j = 0; j < F; j++) {
       const uint64_t sp = mul32_mod(ql[j]);       // < 2^61
