@@ -612,3 +612,19 @@ def test_fuzz_shingle_hashes_and_signatures(sedd, seed):
         got = host(sedd.sedd_minhash(d_data, d_off, n, 24, seed, int(byte_mode)))
         bad = np.nonzero((got != want).any(axis=1))[0]
         assert bad.size == 0, (byte_mode, n, bad[:5])
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_fuzz_signatures_in_the_other_hash_modes(sedd, seed):
+    """The same adversarial tokenisation inputs through the paper-prime and rolling-family modes."""
+    say("fuzz modes", seed)
+    docs = _fuzz_docs(seed, 250)
+    data, off = _pack(docs, lead=seed % 16)
+    d_data, d_off = dev(data), dev(off)
+    for mode in (sedd.FLAG_PAPER_PRIME, sedd.FLAG_ROLLING_FAMILY):
+        for byte_mode, n in ((False, 1), (False, 5), (False, 7), (True, 1), (True, 13)):
+            flags = mode | int(byte_mode)
+            want = oracle.minhash_sharded(data, off, n, 16, seed, flags, procs=NPROC)
+            got = host(sedd.sedd_minhash(d_data, d_off, n, 16, seed, flags))
+            bad = np.nonzero((got != want).any(axis=1))[0]
+            assert bad.size == 0, (mode, byte_mode, n, bad[:5])
