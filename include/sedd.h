@@ -8,7 +8,9 @@
  * Conventions shared by every call
  *   - Every pointer is a DEVICE pointer to memory the caller owns.  The
  *     library never frees or keeps a caller pointer.  Outputs are written only
- *     by the work the call enqueues.
+ *     by the work the call enqueues.  Arrays must be aligned to their element
+ *     size (uint32: 4, uint64 / int64: 8; `bytes` may start anywhere); a
+ *     misaligned pointer is SEDD_EINVAL.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue their kernels on it and return; results are ready when the
  *     stream has drained.  sedd_minhash first validates `doc_offsets` and plans

@@ -57,6 +57,9 @@ __device__ __forceinline__ uint64_t powmod(uint64_t g, uint64_t e) {
   }
   return r;
 }
+// true if p is a multiple of `align` bytes (the kernels use naturally aligned accesses and atomics)
+inline bool aligned_to(const void *p, uintptr_t align) { return ((uintptr_t)p & (align - 1)) == 0; }
+
 __device__ __forceinline__ bool is_ws(uint32_t c) { return c == 0x20u || (c - 0x09u) <= 4u; }
 
 // ---- block-level scan (device) ------------------------------------------------------------

@@ -780,6 +780,7 @@ int sedd_lsh_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t b, in
   if (K < 1 || K > SEDD_MAX_K || b < 1 || r < 1 || (int64_t)b * r > K) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!sig || !keys || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  if (!aligned_to(sig, 4) || !aligned_to(keys, 8)) return SEDD_EINVAL;
   const uint64_t total = n_docs * (uint64_t)b;
   if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   ProfScope prof(SEDD_PROF_LSH_KEYS, (hipStream_t)stream);
@@ -797,6 +798,7 @@ int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t
   if (n_buckets < 1 || n_buckets >= (uint64_t(1) << 61)) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!sig || !keys || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  if (!aligned_to(sig, 4) || !aligned_to(keys, 8)) return SEDD_EINVAL;
   const uint64_t total = n_docs * (uint64_t)b;
   if ((total + 255) / 256 >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   ProfScope prof(SEDD_PROF_LSH_KEYS, st);
@@ -811,6 +813,7 @@ static int check_cluster_args(const void *keys, uint64_t n_docs, int32_t b, cons
   if (b < 1 || b > SEDD_MAX_BANDS) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!keys || !out) return SEDD_EINVAL;
+  if (!aligned_to(keys, 8) || !aligned_to(out, 8)) return SEDD_EINVAL;
   if (n_docs >= (uint64_t(1) << 31) || n_docs * (uint64_t)b >= (uint64_t(1) << 32))
     return SEDD_EINVAL;
   return SEDD_OK;
@@ -849,7 +852,7 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   if (K < 1 || K > SEDD_MAX_K || min_match < 0) return SEDD_EINVAL;
   int rc = check_cluster_args(keys, n_docs, b, cluster_id);
   if (rc || n_docs == 0) return rc;
-  if (!sig) return SEDD_EINVAL;
+  if (!sig || !aligned_to(sig, 4)) return SEDD_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);

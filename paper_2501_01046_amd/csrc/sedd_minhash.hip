@@ -1897,6 +1897,7 @@ int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_d
   if ((flags & SEDD_FLAG_PAPER_PRIME) && (flags & SEDD_FLAG_ROLLING_FAMILY)) return SEDD_EINVAL;
   if (n_docs == 0) return SEDD_OK;
   if (!doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  if (!aligned_to(doc_offsets, 8) || !aligned_to(sig, 4)) return SEDD_EINVAL;
   return run_minhash(bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
                      nullptr, (hipStream_t)stream);
 }

@@ -113,6 +113,24 @@ def test_verified_and_dense_calls_reject_bad_arguments_before_the_device():
     assert L.sedd_lsh_dense_keys(None, u64(0), 128, 16, 8, u64(10), None, None) == 0
 
 
+def test_misaligned_arrays_are_rejected_before_the_device():
+    L = sedd.lib()
+    L.sedd_cluster_verified.argtypes = [C.c_void_p, C.c_void_p, u64, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.c_void_p]
+    L.sedd_lsh_dense_keys.argtypes = [C.c_void_p, u64, C.c_int32, C.c_int32, C.c_int32, u64,
+                                      C.c_void_p, C.c_void_p]
+    odd4, odd8 = C.c_void_p(0x1002), C.c_void_p(0x1004)       # not multiples of 4 / of 8
+    assert L.sedd_minhash(FAKE, odd8, u64(4), 5, 8, u64(0), 0, FAKE, None) == -1      # doc_offsets
+    assert L.sedd_minhash(FAKE, FAKE, u64(4), 5, 8, u64(0), 0, odd4, None) == -1      # sig
+    assert L.sedd_lsh_keys(odd4, u64(4), 128, 16, 8, FAKE, None) == -1
+    assert L.sedd_lsh_keys(FAKE, u64(4), 128, 16, 8, odd8, None) == -1
+    assert L.sedd_lsh_dense_keys(FAKE, u64(4), 128, 16, 8, u64(10), odd8, None) == -1
+    assert L.sedd_cluster(odd8, u64(4), 16, FAKE, None) == -1
+    assert L.sedd_cluster(FAKE, u64(4), 16, odd8, None) == -1
+    assert L.sedd_cluster_verified(FAKE, odd4, u64(4), 128, 16, 103, FAKE, None) == -1
+    assert L.sedd_cluster_verified(odd8, FAKE, u64(4), 128, 16, 103, FAKE, None) == -1
+
+
 def test_threshold_and_bucket_count_helpers():
     assert sedd.min_match_for(0.8, 128) == 103 and sedd.min_match_for(0.8, 125) == 100
     assert sedd.min_match_for(0.7, 10) == 7 and sedd.min_match_for(0.0, 5) == 0
