@@ -473,25 +473,66 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 // ---- large groups: all pairs, tile by tile (the count-match kernel of Section 3.3) -------------
 //
 // A large group is cut into tiles of VT records.  Tile (ti, tj), ti <= tj, compares the records
-// of tile ti with those of tile tj: 256 threads, each accumulating the equal-entry counts of a
-// 4 x 4 block of pairs while the two tiles' signatures pass through LDS VKC columns at a time
-// (stored column-major so that a thread reads its 4 + 4 values with two 16-byte LDS loads).
-// Pairs at or above min_match (and with equal full keys) are united.
+// of tile ti with those of tile tj: 256 threads, each holding a 4 x 4 block of pairs.
+//
+// The number of equal signature entries of a pair is bounded before it is counted.  Every
+// document has a one-bit sketch of its signature (bit k = the lowest bit of entry k, K bits).
+// Entries whose sketch bits differ are unequal, so  equal entries <= K - popcount(sketch_u xor
+// sketch_v).  The tile kernel passes the sketches of its 2 x VT records through LDS (column-major,
+// so that a thread reads its 4 + 4 words with two 16-byte loads), accumulates the popcounts of
+// the 16 xors, and only a pair whose bound reaches min_match (and whose full keys are equal, and
+// whose documents are not joined yet) has its full signatures compared, entry by entry, by its
+// thread.  Unrelated documents agree on about half of the sketch bits (K/2 +- sqrt(K)/2), far
+// below any useful threshold, so nearly all pairs of a coarse bucket cost two instructions per 32
+// entries instead of two per entry; the pairs that are united are exactly those of the full
+// comparison.
 // Phase 0 runs the tiles (0, tj) of every group, phase 1 the others; a phase-1 tile whose records
 // are all in the component of the group's first record already is skipped, which keeps a large
 // group of alike documents (exact copies, empty documents) linear instead of quadratic.
 
 constexpr int VT = 64;
-constexpr int VKC = 32;
+constexpr int VWC = 32;  // sketch words per record staged at a time (1024 signature entries)
 
-// acc[4 i + j] += (r[i] == c[j]) for the 16 pairs of a 4 x 4 block
-__device__ __forceinline__ void count_match_4x4(uint32_t (&acc)[16], const uint4 r, const uint4 c) {
-  const uint32_t rv[4] = {r.x, r.y, r.z, r.w};
-  const uint32_t cv[4] = {c.x, c.y, c.z, c.w};
-#pragma unroll
-  for (int i = 0; i < 4; i++)
-#pragma unroll
-    for (int j = 0; j < 4; j++) acc[4 * i + j] += rv[i] == cv[j];
+// sketch words per document
+__host__ __device__ static inline uint32_t sketch_words(int K) { return (uint32_t)((K + 31) / 32); }
+
+// bits[d * KW + w]: bit i = lowest bit of sig[d * K + 32 w + i] (0 past K).  A wavefront takes 64
+// consecutive entries of one document at a time (one coalesced load, one ballot, two words).
+// Does nothing when the call has no large group (counts[2] == 0).
+__global__ void __launch_bounds__(256)
+k_sig_sketch(const uint32_t *__restrict__ sig, uint32_t n, int K, uint32_t KW,
+             const uint32_t *__restrict__ counts, uint32_t *__restrict__ bits) {
+  if (counts[2] == 0) return;
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t per_doc = (uint32_t)((K + 63) / 64);  // 64-entry pieces per document
+  const uint64_t pieces = (uint64_t)n * per_doc;
+  const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const uint64_t n_waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+  for (uint64_t pc = wave; pc < pieces; pc += n_waves) {
+    const uint32_t d = (uint32_t)(pc / per_doc), part = (uint32_t)(pc % per_doc);
+    const uint32_t k = 64 * part + lane;
+    const uint32_t v = k < (uint32_t)K ? sig[(uint64_t)d * K + k] : 0u;
+    const uint64_t m = __ballot(v & 1u);
+    if (lane < 2 && 2 * part + lane < KW)
+      bits[(uint64_t)d * KW + 2 * part + lane] = (uint32_t)(m >> (32 * lane));
+  }
+}
+
+// equal entries of two signatures (one thread)
+__device__ __forceinline__ int exact_matches(const uint32_t *__restrict__ sig, uint32_t u, uint32_t v,
+                                             int K, bool vec_ok) {
+  const uint32_t *a = sig + (uint64_t)u * K, *b = sig + (uint64_t)v * K;
+  int m = 0;
+  if (vec_ok) {
+    for (int k = 0; k < K; k += 4) {
+      const uint4 x = *reinterpret_cast<const uint4 *>(a + k);
+      const uint4 y = *reinterpret_cast<const uint4 *>(b + k);
+      m += (x.x == y.x) + (x.y == y.y) + (x.z == y.z) + (x.w == y.w);
+    }
+  } else {
+    for (int k = 0; k < K; k++) m += a[k] == b[k];
+  }
+  return m;
 }
 
 // exclusive prefix sums over the large groups of their phase-0 and phase-1 tile counts
@@ -540,10 +581,10 @@ k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ co
 
 __global__ void __launch_bounds__(256)
 k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
-          const uint32_t *__restrict__ sig, int K, int min_match, uint32_t *parent,
-          const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts, uint64_t big_cap,
-          const uint64_t *__restrict__ pre_all) {
-  __shared__ uint32_t sm[VKC][2 * VT];  // [column][record]: records 0..63 of tile ti, 64..127 of tile tj
+          const uint32_t *__restrict__ sig, const uint32_t *__restrict__ bits, int K, int min_match,
+          uint32_t *parent, const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts,
+          uint64_t big_cap, const uint64_t *__restrict__ pre_all) {
+  __shared__ uint32_t sm[VWC][2 * VT];  // [sketch word][record]: records 0..63 of tile ti, 64..127 of tile tj
   __shared__ uint32_t sm_doc[2 * VT];
   __shared__ uint64_t sm_key[2 * VT];
   const uint32_t nb = min((uint64_t)counts[2], big_cap);
@@ -551,6 +592,8 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
   const uint64_t total = pre[nb];
   const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
   const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
+  const int KW = (int)sketch_words(K);
+  const int max_diff = K - min_match;  // a pair whose sketches differ in more bits cannot reach min_match
   // every block takes a contiguous range of tiles: one search for the group of its first tile,
   // after that the group index only moves forward
   const uint64_t per_block = (total + gridDim.x - 1) / gridDim.x;
@@ -602,64 +645,29 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
       sm_key[tid] = key;
     }
     if (phase && __syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
-
-    uint32_t acc[16];  // acc[4 i + j]: row 4 ty + i against column 4 tx + j
-#pragma unroll
-    for (int i = 0; i < 16; i++) acc[i] = 0;
-    // thread -> (record, half of a chunk): 16 columns of one record, stored column-major.  The
-    // values of the next chunk are fetched into registers while the current one is compared.
-    const int l_rec = tid >> 1, l_c0 = (tid & 1) * (VKC / 2);
-    uint32_t v[VKC / 2];
-    auto fetch = [&](int kc) {
-      const uint32_t doc = sm_doc[l_rec];
-#pragma unroll
-      for (int c = 0; c < VKC / 2; c++) v[c] = 0;
-      if (doc != 0xFFFFFFFFu) {
-        const uint32_t *row = sig + (uint64_t)doc * K + kc + l_c0;
-        if (vec_ok && kc + l_c0 + VKC / 2 <= K) {
-#pragma unroll
-          for (int c = 0; c < VKC / 2; c += 4) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(row + c);
-            v[c] = q.x; v[c + 1] = q.y; v[c + 2] = q.z; v[c + 3] = q.w;
-          }
-        } else {
-#pragma unroll
-          for (int c = 0; c < VKC / 2; c++)
-            if (kc + l_c0 + c < K) v[c] = row[c];
-        }
-      }
-    };
     __syncthreads();  // sm_doc visible
-    fetch(0);
-    for (int kc = 0; kc < K; kc += VKC) {
-      if (kc) __syncthreads();  // the previous chunk has been compared
+
+    uint32_t diff[16];  // diff[4 i + j]: sketch bits that differ, row 4 ty + i against column 4 tx + j
 #pragma unroll
-      for (int c = 0; c < VKC / 2; c++) sm[l_c0 + c][l_rec] = v[c];
+    for (int i = 0; i < 16; i++) diff[i] = 0;
+    // thread -> (record, every other sketch word of the pass)
+    const int l_rec = tid >> 1, l_w0 = tid & 1;
+    const uint32_t l_doc = sm_doc[l_rec];
+    for (int wc = 0; wc < KW; wc += VWC) {
+      if (wc) __syncthreads();  // the previous pass has been compared
+      const int wmax = min(VWC, KW - wc);
+      for (int w = l_w0; w < wmax; w += 2)
+        sm[w][l_rec] = l_doc != 0xFFFFFFFFu ? bits[(uint64_t)l_doc * KW + wc + w] : 0u;
       __syncthreads();
-      if (kc + VKC < K) fetch(kc + VKC);
-      const int kmax = min(VKC, K - kc);
-      // the LDS reads of column k + 1 are issued before the compares of column k
-      uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[0][ty * 4]);
-      uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[0][VT + tx * 4]);
-      if (kmax == VKC) {
-#pragma unroll 8
-        for (int k = 0; k < VKC; k++) {
-          const int kn = k + 1 < VKC ? k + 1 : k;
-          const uint4 rn = *reinterpret_cast<const uint4 *>(&sm[kn][ty * 4]);
-          const uint4 cn = *reinterpret_cast<const uint4 *>(&sm[kn][VT + tx * 4]);
-          count_match_4x4(acc, r4, c4);
-          r4 = rn;
-          c4 = cn;
-        }
-      } else {
-        for (int k = 0; k < kmax; k++) {
-          const int kn = k + 1 < kmax ? k + 1 : k;
-          const uint4 rn = *reinterpret_cast<const uint4 *>(&sm[kn][ty * 4]);
-          const uint4 cn = *reinterpret_cast<const uint4 *>(&sm[kn][VT + tx * 4]);
-          count_match_4x4(acc, r4, c4);
-          r4 = rn;
-          c4 = cn;
-        }
+      for (int w = 0; w < wmax; w++) {
+        const uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[w][ty * 4]);
+        const uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[w][VT + tx * 4]);
+        const uint32_t rv[4] = {r4.x, r4.y, r4.z, r4.w};
+        const uint32_t cv[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) diff[4 * i + j] += __popc(rv[i] ^ cv[j]);
       }
     }
 #pragma unroll
@@ -670,7 +678,10 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
         const uint32_t u = sm_doc[ri], v = sm_doc[cj];
         if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) continue;
         if (ti == tj && ri >= cj - VT) continue;  // upper triangle of a diagonal tile
-        if ((int)acc[4 * i + j] >= min_match && sm_key[ri] == sm_key[cj]) uf_unite(parent, u, v);
+        if ((int)diff[4 * i + j] > max_diff || sm_key[ri] != sm_key[cj]) continue;
+        // a candidate: the full comparison decides (skipped for documents joined already)
+        if (uf_find(parent, u) == uf_find(parent, v)) continue;
+        if (min_match <= 0 || exact_matches(sig, u, v, K, vec_ok) >= min_match) uf_unite(parent, u, v);
       }
   }
 }
@@ -693,13 +704,14 @@ __global__ void k_copy_sorted(const uint64_t *__restrict__ bk, const uint32_t *_
 struct SortBufs {
   uint64_t *ka, *kb;
   uint32_t *da, *db, *hist, *tmp, *parent;
+  uint32_t *sketch;    // one-bit signature sketches (verified path): n * sketch_words(K) words
   BigGroup *big;       // capacity big_cap
   uint64_t *tile_pre;  // 2 * (big_cap + 1) prefix sums of tile counts
   uint64_t big_cap;
   uint32_t nblk;
 };
 
-static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
+static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb, int K_sketch = 0) {
   const uint64_t total = n * b;
   const uint32_t nblk = (uint32_t)((n + SORT_TILE - 1) / SORT_TILE);
   const uint64_t nh = (uint64_t)b * RADIX * nblk;
@@ -710,9 +722,11 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb) {
   const uint64_t o_p = cv.take<uint32_t>(n);
   const uint64_t big_cap = total / BIG_GROUP + 1;
   const uint64_t o_big = cv.take<BigGroup>(big_cap), o_pre = cv.take<uint64_t>(2 * (big_cap + 1));
+  const uint64_t o_sk = cv.take<uint32_t>(K_sketch ? n * sketch_words(K_sketch) : 1);
   uint8_t *A = nullptr;
   int rc = scratch_ensure(cv.off, &A);
   if (rc) return rc;
+  sb->sketch = (uint32_t *)(A + o_sk);
   sb->big = (BigGroup *)(A + o_big);
   sb->tile_pre = (uint64_t *)(A + o_pre);
   sb->big_cap = big_cap;
@@ -855,7 +869,7 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   if (!sig || !aligned_to(sig, 4)) return SEDD_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   SortBufs sb;
-  rc = sort_layout(n_docs, (uint32_t)b, &sb);
+  rc = sort_layout(n_docs, (uint32_t)b, &sb, (int)K);
   if (rc) return rc;
   unsigned long long *stats = nullptr;
   rc = stats_ensure(&stats);
@@ -886,9 +900,12 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   hipLaunchKernelGGL(k_v_plan_tiles, dim3(1), dim3(1024), 0, st, sb.big, counts, sb.big_cap,
                      sb.tile_pre);
   SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, sketch_words(K),
+                     counts, sb.sketch);
+  SEDD_LAUNCH_CHECK();
   for (int phase = 0; phase < 2; phase++) {
-    hipLaunchKernelGGL(k_v_tiles, dim3(256 * 8), dim3(256), 0, st, phase, sb.ka, sb.da, sig, (int)K,
-                       (int)min_match, sb.parent, sb.big, counts, sb.big_cap, sb.tile_pre);
+    hipLaunchKernelGGL(k_v_tiles, dim3(256 * 8), dim3(256), 0, st, phase, sb.ka, sb.da, sig, sb.sketch,
+                       (int)K, (int)min_match, sb.parent, sb.big, counts, sb.big_cap, sb.tile_pre);
     SEDD_LAUNCH_CHECK();
   }
   // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
