@@ -308,10 +308,10 @@ __global__ void __launch_bounds__(SORT_THREADS)
 k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
          uint32_t *__restrict__ list1, uint32_t *__restrict__ counts,
          BigGroup *__restrict__ big) {
-  __shared__ uint32_t s_base;
+  __shared__ uint32_t s_base[2];
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const uint64_t *src = bk + (uint64_t)band * n;
-  uint32_t flags = 0;
+  uint32_t flags = 0, heads = 0;  // bit it: item it goes to list1 / is the head of a large group
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; it++) {
     const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
@@ -323,29 +323,39 @@ k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
       const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
       if (!far_before && !far_after) flags |= 1u << it;
     } else if (far_after) {
+      heads |= 1u << it;
+    }
+  }
+  // both counts through one scan (at most SORT_TILE = 2^12 of either per block) and one atomic
+  // each per block
+  static_assert(SORT_TILE <= (1u << 15), "two counts share one 32-bit scan");
+  uint32_t tot;
+  const uint32_t pre = block_exclusive_scan<SORT_THREADS>(__popc(flags) | (__popc(heads) << 16), &tot);
+  if (threadIdx.x == 0) {
+    s_base[0] = (tot & 0xFFFFu) ? atomicAdd(counts, tot & 0xFFFFu) : 0u;
+    s_base[1] = (tot >> 16) ? atomicAdd(counts + 2, tot >> 16) : 0u;
+  }
+  __syncthreads();
+  uint32_t o = s_base[0] + (pre & 0xFFFFu), oh = s_base[1] + (pre >> 16);
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
+    if (flags & (1u << it)) list1[o++] = band * n + e;
+    if (heads & (1u << it)) {
       // head of a large group: its end by binary search over the rest of the band
+      const uint64_t low = src[e] & mask;
       uint32_t lo = e + BIG_GROUP + 1, hi = n;
       while (lo < hi) {
         const uint32_t mid = lo + ((hi - lo) >> 1);
         if ((src[mid] & mask) > low) hi = mid;
         else lo = mid + 1;
       }
-      const uint32_t slot = atomicAdd(counts + 2, 1u);
       BigGroup g;
       g.start = band * n + e;
       g.size = lo - e;
-      big[slot] = g;
+      big[oh++] = g;
     }
   }
-  uint32_t tot;
-  const uint32_t pre = block_exclusive_scan<SORT_THREADS>(__popc(flags), &tot);
-  if (threadIdx.x == 0) s_base = tot ? atomicAdd(counts, tot) : 0u;
-  __syncthreads();
-  uint32_t o = s_base + pre;
-#pragma unroll
-  for (int it = 0; it < SORT_ITEMS; it++)
-    if (flags & (1u << it))
-      list1[o++] = band * n + blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
 }
 
 // number of equal entries of two signatures, computed by the TEAM lanes of one team; every
@@ -473,14 +483,16 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 // ---- large groups: all pairs, tile by tile (the count-match kernel of Section 3.3) -------------
 //
 // A large group is cut into tiles of VT records.  Tile (ti, tj), ti <= tj, compares the records
-// of tile ti with those of tile tj: 256 threads, each holding a 4 x 4 block of pairs.
+// of tile ti with those of tile tj: one wavefront, each lane holding an 8 x 8 block of pairs (a
+// tile costs a few dependent memory round trips and little arithmetic, so many small blocks in
+// flight matter more than threads per tile).
 //
 // The number of equal signature entries of a pair is bounded before it is counted.  Every
 // document has a one-bit sketch of its signature (bit k = the lowest bit of entry k, K bits).
 // Entries whose sketch bits differ are unequal, so  equal entries <= K - popcount(sketch_u xor
 // sketch_v).  The tile kernel passes the sketches of its 2 x VT records through LDS (column-major,
-// so that a thread reads its 4 + 4 words with two 16-byte loads), accumulates the popcounts of
-// the 16 xors, and only a pair whose bound reaches min_match (and whose full keys are equal, and
+// so that a lane reads its 8 + 8 words with four 16-byte loads), accumulates the popcounts of
+// the 64 xors, and only a pair whose bound reaches min_match (and whose full keys are equal, and
 // whose documents are not joined yet) has its full signatures compared, entry by entry, by its
 // thread.  Unrelated documents agree on about half of the sketch bits (K/2 +- sqrt(K)/2), far
 // below any useful threshold, so nearly all pairs of a coarse bucket cost two instructions per 32
@@ -491,7 +503,8 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 // group of alike documents (exact copies, empty documents) linear instead of quadratic.
 
 constexpr int VT = 64;
-constexpr int VWC = 32;  // sketch words per record staged at a time (1024 signature entries)
+constexpr int VWC = 8;   // sketch words per record staged at a time (256 signature entries)
+constexpr int VTHREADS = 64;
 
 // sketch words per document
 __host__ __device__ static inline uint32_t sketch_words(int K) { return (uint32_t)((K + 31) / 32); }
@@ -579,7 +592,7 @@ k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ co
   }
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(VTHREADS)
 k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
           const uint32_t *__restrict__ sig, const uint32_t *__restrict__ bits, int K, int min_match,
           uint32_t *parent, const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts,
@@ -590,7 +603,7 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
   const uint32_t nb = min((uint64_t)counts[2], big_cap);
   const uint64_t *pre = pre_all + (phase ? big_cap + 1 : 0);
   const uint64_t total = pre[nb];
-  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;  // rows 8 ty .., columns 8 tx ..
   const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
   const int KW = (int)sketch_words(K);
   const int max_diff = K - min_match;  // a pair whose sketches differ in more bits cannot reach min_match
@@ -632,53 +645,74 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
     }
     __syncthreads();  // the previous tile's LDS reads are done
     bool alike = true;
-    if (tid < 2 * VT) {
-      const uint64_t rec = (tid < VT ? ti * VT + tid : tj * VT + (tid - VT));
+    uint32_t my_doc[2];
+    uint32_t first_words[2][VWC];  // the records' first VWC sketch words, fetched before anything waits
+#pragma unroll
+    for (int h = 0; h < 2; h++) {  // lane l loads record l of tile ti and record l of tile tj
+      const uint64_t rec = (h == 0 ? ti : tj) * VT + tid;
       uint32_t doc = 0xFFFFFFFFu;
       uint64_t key = 0;
       if (rec < g.size) {
         doc = bd[g.start + rec];
         key = bk[g.start + rec];
-        if (phase) alike = uf_find(parent, doc) == uf_find(parent, bd[g.start]);
       }
-      sm_doc[tid] = doc;
-      sm_key[tid] = key;
-    }
-    if (phase && __syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
-    __syncthreads();  // sm_doc visible
-
-    uint32_t diff[16];  // diff[4 i + j]: sketch bits that differ, row 4 ty + i against column 4 tx + j
+      my_doc[h] = doc;
+      sm_doc[h * VT + tid] = doc;
+      sm_key[h * VT + tid] = key;
 #pragma unroll
-    for (int i = 0; i < 16; i++) diff[i] = 0;
-    // thread -> (record, every other sketch word of the pass)
-    const int l_rec = tid >> 1, l_w0 = tid & 1;
-    const uint32_t l_doc = sm_doc[l_rec];
+      for (int w = 0; w < VWC; w++)
+        first_words[h][w] = (doc != 0xFFFFFFFFu && w < KW) ? bits[(uint64_t)doc * KW + w] : 0u;
+    }
+    if (phase) {
+      const uint32_t head_root = uf_find(parent, bd[g.start]);
+#pragma unroll
+      for (int h = 0; h < 2; h++)
+        if (my_doc[h] != 0xFFFFFFFFu) alike = alike && uf_find(parent, my_doc[h]) == head_root;
+      if (__syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
+    }
+
+    uint32_t diff[64];  // diff[8 i + j]: sketch bits that differ, row 8 ty + i against column 8 tx + j
+#pragma unroll
+    for (int i = 0; i < 64; i++) diff[i] = 0;
     for (int wc = 0; wc < KW; wc += VWC) {
       if (wc) __syncthreads();  // the previous pass has been compared
       const int wmax = min(VWC, KW - wc);
-      for (int w = l_w0; w < wmax; w += 2)
-        sm[w][l_rec] = l_doc != 0xFFFFFFFFu ? bits[(uint64_t)l_doc * KW + wc + w] : 0u;
+      if (wc == 0) {
+#pragma unroll
+        for (int w = 0; w < VWC; w++) {
+          sm[w][tid] = first_words[0][w];
+          sm[w][VT + tid] = first_words[1][w];
+        }
+      } else {
+        for (int w = 0; w < wmax; w++) {
+          sm[w][tid] = my_doc[0] != 0xFFFFFFFFu ? bits[(uint64_t)my_doc[0] * KW + wc + w] : 0u;
+          sm[w][VT + tid] = my_doc[1] != 0xFFFFFFFFu ? bits[(uint64_t)my_doc[1] * KW + wc + w] : 0u;
+        }
+      }
       __syncthreads();
       for (int w = 0; w < wmax; w++) {
-        const uint4 r4 = *reinterpret_cast<const uint4 *>(&sm[w][ty * 4]);
-        const uint4 c4 = *reinterpret_cast<const uint4 *>(&sm[w][VT + tx * 4]);
-        const uint32_t rv[4] = {r4.x, r4.y, r4.z, r4.w};
-        const uint32_t cv[4] = {c4.x, c4.y, c4.z, c4.w};
+        const uint4 r0 = *reinterpret_cast<const uint4 *>(&sm[w][ty * 8]);
+        const uint4 r1 = *reinterpret_cast<const uint4 *>(&sm[w][ty * 8 + 4]);
+        const uint4 c0 = *reinterpret_cast<const uint4 *>(&sm[w][VT + tx * 8]);
+        const uint4 c1 = *reinterpret_cast<const uint4 *>(&sm[w][VT + tx * 8 + 4]);
+        const uint32_t rv[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+        const uint32_t cv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < 8; i++)
 #pragma unroll
-          for (int j = 0; j < 4; j++) diff[4 * i + j] += __popc(rv[i] ^ cv[j]);
+          for (int j = 0; j < 8; j++) diff[8 * i + j] += __popc(rv[i] ^ cv[j]);
       }
     }
 #pragma unroll
-    for (int i = 0; i < 4; i++)
+    for (int i = 0; i < 8; i++)
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const int ri = ty * 4 + i, cj = VT + tx * 4 + j;
+      for (int j = 0; j < 8; j++) {
+        if ((int)diff[8 * i + j] > max_diff) continue;  // the bound rules the pair out
+        const int ri = ty * 8 + i, cj = VT + tx * 8 + j;
         const uint32_t u = sm_doc[ri], v = sm_doc[cj];
         if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) continue;
         if (ti == tj && ri >= cj - VT) continue;  // upper triangle of a diagonal tile
-        if ((int)diff[4 * i + j] > max_diff || sm_key[ri] != sm_key[cj]) continue;
+        if (sm_key[ri] != sm_key[cj]) continue;
         // a candidate: the full comparison decides (skipped for documents joined already)
         if (uf_find(parent, u) == uf_find(parent, v)) continue;
         if (min_match <= 0 || exact_matches(sig, u, v, K, vec_ok) >= min_match) uf_unite(parent, u, v);
@@ -904,7 +938,7 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
                      counts, sb.sketch);
   SEDD_LAUNCH_CHECK();
   for (int phase = 0; phase < 2; phase++) {
-    hipLaunchKernelGGL(k_v_tiles, dim3(256 * 8), dim3(256), 0, st, phase, sb.ka, sb.da, sig, sb.sketch,
+    hipLaunchKernelGGL(k_v_tiles, dim3(256 * 24), dim3(VTHREADS), 0, st, phase, sb.ka, sb.da, sig, sb.sketch,
                        (int)K, (int)min_match, sb.parent, sb.big, counts, sb.big_cap, sb.tile_pre);
     SEDD_LAUNCH_CHECK();
   }
