@@ -139,9 +139,12 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
  * keys, cluster_id as in sedd_cluster; sig device, uint32[n_docs*K], all K columns are compared.
  * Cost: in a bucket of at most 64 documents every document is compared with the bucket's first
  * document, and only those that fail with the rest of the bucket.  A larger bucket is compared
- * all pairs, 64 x 64 documents at a time through LDS, first against its leading 64 documents;
- * blocks of pairs whose documents are all joined to the bucket's first document by then are
- * skipped.  Both yield the components of the exhaustive comparison.
+ * all pairs, 64 x 64 documents at a time, first against its leading 64 documents; blocks of pairs
+ * whose documents are all joined to the bucket's first document by then are skipped.  There the
+ * match count of a pair is first bounded from one-bit sketches of the two signatures (entries
+ * whose lowest bits differ are unequal) and the signatures are compared entry by entry only if
+ * the bound reaches min_match.  All of this yields the components of the exhaustive comparison.
+ * Scratch: beside the sort buffers, n_docs * ceil(K / 32) * 4 bytes for the sketches.
  */
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
                           int32_t b, int32_t min_match, int64_t *cluster_id, void *stream);
