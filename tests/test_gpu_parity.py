@@ -463,6 +463,28 @@ def test_cluster_verified_large_buckets(sedd):
     assert oracle.cluster_verified(keys, two, K).tolist()[:4] == [0, 1, 0, 1]
 
 
+@pytest.mark.parametrize("K", [1, 31, 33, 100, 130, 300, 1000])
+def test_cluster_verified_large_buckets_sketch_bound(sedd, K):
+    """Buckets of hundreds of documents go through the sketch-bounded tile kernel: signature
+    lengths around the 32-entry sketch words and beyond one staging pass, prototypes with noise
+    (match counts spread over 0..K), and signatures whose lowest bits all agree, where the bound
+    rules nothing out and every pair has to be counted."""
+    say("verified sketch bound", K)
+    rng = np.random.default_rng(K)
+    n, b = 700, 3
+    keys = rng.integers(0, 3, size=(n, b), dtype=np.uint64)             # buckets of ~230
+    _, sig = _proto_case(K, n, K, b, 3, 6, noise=0.5)
+    even = (sig & np.uint32(0xFFFFFFFE)).astype(np.uint32)               # all sketch bits zero
+    odd_rows = sig.copy()
+    odd_rows[::2] |= np.uint32(1)                                        # half the documents all-ones sketches
+    odd_rows[1::2] &= np.uint32(0xFFFFFFFE)
+    for name, sg in (("noise", sig), ("even", even), ("halves", odd_rows)):
+        d_keys, d_sig = dev(keys), dev(sg)
+        for mm in sorted({0, 1, max(1, K // 2), oracle.min_match_for(0.8, K), K, K + 1}):
+            got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+            assert np.array_equal(got, oracle.cluster_verified(keys, sg, mm)), (name, mm)
+
+
 def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
     """Buckets whose keys differ only above the sorted bits share one sorted group."""
     say("verified low-bit collisions")
