@@ -621,6 +621,10 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
       else hi = mid;
     }
   }
+  const bool can_cache = KW <= VWC;  // one staging pass: the row's sketch words are not overwritten
+  uint32_t cached_lo = 0xFFFFFFFFu;
+  uint64_t cached_ti = 0;
+  uint32_t my_doc[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};  // my_doc[0] outlives a tile while its row is cached
   for (uint64_t t = t_begin; t < t_end; t++) {
     while (lo + 1 < nb && pre[lo + 1] <= t) lo++;
     const BigGroup g = big[lo];
@@ -644,11 +648,14 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
       tj = ti + (local - ((ti - 1) * T - (ti - 1) * ti / 2));
     }
     __syncthreads();  // the previous tile's LDS reads are done
+    // consecutive tiles of a block mostly share their row tile (phase 0: always tile 0 of the
+    // group; phase 1: row-major order): its records, keys and sketches then stay in LDS
+    const bool row_cached = can_cache && lo == cached_lo && ti == cached_ti;
     bool alike = true;
-    uint32_t my_doc[2];
     uint32_t first_words[2][VWC];  // the records' first VWC sketch words, fetched before anything waits
 #pragma unroll
     for (int h = 0; h < 2; h++) {  // lane l loads record l of tile ti and record l of tile tj
+      if (h == 0 && row_cached) continue;
       const uint64_t rec = (h == 0 ? ti : tj) * VT + tid;
       uint32_t doc = 0xFFFFFFFFu;
       uint64_t key = 0;
@@ -668,8 +675,13 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
 #pragma unroll
       for (int h = 0; h < 2; h++)
         if (my_doc[h] != 0xFFFFFFFFu) alike = alike && uf_find(parent, my_doc[h]) == head_root;
-      if (__syncthreads_count(alike ? 0 : 1) == 0) continue;  // nothing left to learn here
+      if (__syncthreads_count(alike ? 0 : 1) == 0) {  // nothing left to learn here
+        if (!row_cached) cached_lo = 0xFFFFFFFFu;     // the row's sketches never reached LDS
+        continue;
+      }
     }
+    cached_lo = lo;
+    cached_ti = ti;
 
     uint32_t diff[64];  // diff[8 i + j]: sketch bits that differ, row 8 ty + i against column 8 tx + j
 #pragma unroll
@@ -680,7 +692,7 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
       if (wc == 0) {
 #pragma unroll
         for (int w = 0; w < VWC; w++) {
-          sm[w][tid] = first_words[0][w];
+          if (!row_cached) sm[w][tid] = first_words[0][w];
           sm[w][VT + tid] = first_words[1][w];
         }
       } else {
