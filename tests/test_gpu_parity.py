@@ -650,3 +650,32 @@ def test_fuzz_signatures_in_the_other_hash_modes(sedd, seed):
             got = host(sedd.sedd_minhash(d_data, d_off, n, 16, seed, flags))
             bad = np.nonzero((got != want).any(axis=1))[0]
             assert bad.size == 0, (mode, byte_mode, n, bad[:5])
+
+
+# ---- the largest parameters the calls accept ---------------------------------------------------
+
+def test_largest_K_bands_and_shingle_length(sedd):
+    """K = 4096 hash functions, 4096 bands of one row (and 1 band of 4096 rows), 64-token and
+    64-byte shingles: the limits stated in the header."""
+    say("maximum parameters")
+    data, off = corpus.generate(corpus.config(1).scaled(60))
+    K = 4096
+    for flags, n in ((0, 5), (0, 64), (1, 64), (2, 5), (3, 64)):
+        want = oracle.minhash_sharded(data, off, n, K, 3, flags, procs=NPROC)
+        sig = sedd.sedd_minhash(dev(data), dev(off), n, K, 3, flags)
+        assert np.array_equal(host(sig), want), (flags, n)
+        if flags == 0 and n == 5:
+            for b, r in ((4096, 1), (1, 4096), (512, 8)):
+                wkeys = oracle.lsh_keys(want, b, r)
+                keys = sedd.sedd_lsh_keys(sig, b, r)
+                assert np.array_equal(host(keys), wkeys), (b, r)
+                assert np.array_equal(host(sedd.sedd_cluster(keys)), oracle.cluster(wkeys)), (b, r)
+                for mm in (1, 3000, 4096):
+                    assert np.array_equal(host(sedd.sedd_cluster_verified(keys, sig, mm)),
+                                          oracle.cluster_verified(wkeys, want, mm)), (b, r, mm)
+            nb = 3
+            wd = oracle.lsh_dense_keys(want, 16, 256, nb)
+            dk = sedd.sedd_lsh_dense_keys(sig, 16, 256, nb)
+            assert np.array_equal(host(dk), wd)
+            assert np.array_equal(host(sedd.sedd_cluster_verified(dk, sig, 2000)),
+                                  oracle.cluster_verified(wd, want, 2000))
