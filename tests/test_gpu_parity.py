@@ -660,7 +660,7 @@ def test_largest_K_bands_and_shingle_length(sedd):
     say("maximum parameters")
     data, off = corpus.generate(corpus.config(1).scaled(60))
     K = 4096
-    for flags, n in ((0, 5), (0, 64), (1, 64), (2, 5), (3, 64)):
+    for flags, n in ((0, 5), (0, 64), (1, 64), (2, 5), (3, 64), (4, 5), (5, 64)):
         want = oracle.minhash_sharded(data, off, n, K, 3, flags, procs=NPROC)
         sig = sedd.sedd_minhash(dev(data), dev(off), n, K, 3, flags)
         assert np.array_equal(host(sig), want), (flags, n)
