@@ -149,6 +149,21 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
                           int32_t b, int32_t min_match, int64_t *cluster_id, void *stream);
 
+/*
+ * The count that the threshold test of Section 3.3, Eq. 3 ("similarity >= theta * H") needs, for
+ * theta = theta_num / theta_den: the smallest integer m with m * theta_den >= theta_num * K.
+ * Integer arithmetic only (0.8 * 125 is exactly 100, 0.8 * 128 gives 103).  Host-side, touches no
+ * device.  Returns SEDD_EINVAL for theta_den == 0, K < 0 or a result above 2^31 - 1.
+ */
+int32_t sedd_min_match(uint64_t theta_num, uint64_t theta_den, int32_t K);
+
+/*
+ * The number of dense buckets the paper pairs with sedd_lsh_dense_keys: k * sqrt(n_docs), k = 4 in
+ * Section 3.2 (the appendix on the effect of k varies it), taken as floor(sqrt(k^2 * n_docs)) and
+ * at least 1.  Integer arithmetic only, host-side.
+ */
+uint64_t sedd_dense_bucket_count(uint64_t n_docs, uint32_t k);
+
 /* Text for an error code (static storage). */
 const char *sedd_strerror(int code);
 /* Text of the HIP error behind the last SEDD_EDEVICE of this thread (static storage). */

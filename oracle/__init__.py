@@ -250,37 +250,35 @@ def cluster_verified(keys, sig, min_match: int) -> np.ndarray:
     return cid
 
 
-_shard_ctx = None   # inherited by forked workers; avoids pickling the corpus per job
-
-
-def _shard_worker(rng):
-    data, off, shingle_n, K, seed, flags = _shard_ctx
-    d0, d1 = rng
-    base = int(off[d0])
-    sub = data[base:int(off[d1])]
-    return d0, minhash(sub, off[d0:d1 + 1] - np.uint64(base), shingle_n, K, seed, flags)
-
-
 def minhash_sharded(data, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags: int = 0,
                     procs: int = 1) -> np.ndarray:
-    """The single-threaded oracle run as `procs` processes over disjoint document ranges."""
-    global _shard_ctx
+    """The single-threaded oracle run by `procs` worker threads over disjoint document ranges.
+
+    Each worker calls the same C routine (``sedd_ref_minhash``, which holds no shared state and
+    runs without the interpreter lock) on a contiguous range of documents: its text slice and its
+    offsets rebased to that slice.  A document's signature depends on nothing but its own bytes,
+    so the result equals ``minhash`` on the whole corpus (pinned in tests/test_oracle_minhash.py).
+    Threads rather than forked processes: the callers may hold a GPU context, which must not be
+    forked.
+    """
     data = _as_bytes(data)
     off = np.ascontiguousarray(doc_offsets, dtype=np.uint64)
     n_docs = max(0, off.size - 1)
     if procs <= 1 or n_docs < 2 * procs:
         return minhash(data, off, shingle_n, K, seed, flags)
-    import multiprocessing as mp
+    from concurrent.futures import ThreadPoolExecutor
     _load()
     n_sh = procs * 8
     cuts = [n_docs * i // n_sh for i in range(n_sh + 1)]
     jobs = [(cuts[i], cuts[i + 1]) for i in range(n_sh) if cuts[i + 1] > cuts[i]]
     sig = np.zeros((n_docs, K), dtype=np.uint32)
-    _shard_ctx = (data, off, shingle_n, K, seed, flags)
-    try:
-        with mp.get_context("fork").Pool(procs) as pool:
-            for d0, part in pool.imap_unordered(_shard_worker, jobs):
-                sig[d0:d0 + part.shape[0]] = part
-    finally:
-        _shard_ctx = None
+
+    def work(rng):
+        d0, d1 = rng
+        base = int(off[d0])
+        sub = data[base:int(off[d1])]
+        sig[d0:d1] = minhash(sub, off[d0:d1 + 1] - np.uint64(base), shingle_n, K, seed, flags)
+
+    with ThreadPoolExecutor(max_workers=procs) as pool:
+        list(pool.map(work, jobs))
     return sig

@@ -66,6 +66,10 @@ def lib():
         L.sedd_lsh_dense_keys.argtypes = [vp, u64, i32, i32, i32, u64, vp, vp]
         L.sedd_cluster_verified.restype = C.c_int
         L.sedd_cluster_verified.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp]
+        L.sedd_min_match.restype = i32
+        L.sedd_min_match.argtypes = [u64, u64, i32]
+        L.sedd_dense_bucket_count.restype = u64
+        L.sedd_dense_bucket_count.argtypes = [u64, u32]
         L.sedd_strerror.restype = C.c_char_p
         L.sedd_strerror.argtypes = [C.c_int]
         L.sedd_last_device_error.restype = C.c_char_p
@@ -190,8 +194,7 @@ def sedd_cluster(keys, out=None, stream=None):
 
 def dense_bucket_count(n_docs: int, k: int = 4) -> int:
     """Number of dense buckets the paper uses, k * sqrt(N) with k = 4: floor(sqrt(k^2 N)), >= 1."""
-    import math
-    return max(1, math.isqrt(k * k * int(n_docs)))
+    return int(lib().sedd_dense_bucket_count(int(n_docs), int(k)))
 
 
 def sedd_lsh_dense_keys(sig, b: int, r: int, n_buckets: int, out=None, stream=None):
@@ -213,9 +216,12 @@ def sedd_lsh_dense_keys(sig, b: int, r: int, n_buckets: int, out=None, stream=No
 def min_match_for(theta: float, K: int) -> int:
     """Smallest integer m with m >= theta * K: the count the threshold test of Section 3.3 needs.
     theta is read as the decimal fraction it prints as (0.8 * 125 is exactly 100)."""
-    from fractions import Fraction
-    t = Fraction(str(theta)) * K
-    return int(-((-t.numerator) // t.denominator))
+    from decimal import Decimal
+    num, den = Decimal(str(theta)).as_integer_ratio()
+    m = lib().sedd_min_match(num, den, int(K))
+    if m < 0:
+        raise SeddError(m, "sedd_min_match", "theta must be a non-negative fraction, K >= 0")
+    return int(m)
 
 
 def sedd_cluster_verified(keys, sig, min_match: int, out=None, stream=None):

@@ -228,6 +228,25 @@ const char *sedd_strerror(int code) {
 
 const char *sedd_last_device_error(void) { return g_dev_err; }
 
+int32_t sedd_min_match(uint64_t theta_num, uint64_t theta_den, int32_t K) {
+  if (theta_den == 0 || K < 0) return SEDD_EINVAL;
+  const unsigned __int128 t = (unsigned __int128)theta_num * (uint64_t)K;
+  const unsigned __int128 m = (t + theta_den - 1) / theta_den;  // ceiling of theta * K
+  if (m > (unsigned __int128)INT32_MAX) return SEDD_EINVAL;
+  return (int32_t)m;
+}
+
+uint64_t sedd_dense_bucket_count(uint64_t n_docs, uint32_t k) {
+  const unsigned __int128 v = (unsigned __int128)n_docs * k * k;  // below 2^128
+  // largest s with s * s <= v, bit by bit (s < 2^64)
+  uint64_t s = 0;
+  for (int bit = 63; bit >= 0; bit--) {
+    const uint64_t c = s | (uint64_t(1) << bit);
+    if ((unsigned __int128)c * c <= v) s = c;
+  }
+  return s ? s : 1;
+}
+
 int sedd_version(void) { return 100; }
 
 int sedd_release_scratch(void) {

@@ -136,3 +136,29 @@ def test_threshold_and_bucket_count_helpers():
     assert sedd.min_match_for(0.7, 10) == 7 and sedd.min_match_for(0.0, 5) == 0
     assert sedd.dense_bucket_count(1_000_000) == 4000 and sedd.dense_bucket_count(0) == 1
     assert sedd.dense_bucket_count(40_000) == 800 and sedd.dense_bucket_count(10, k=1) == 3
+
+
+def test_threshold_and_bucket_count_through_the_c_abi():
+    """sedd_min_match (Section 3.3, Eq. 3) and sedd_dense_bucket_count (Section 3.2) called
+    directly: integer arithmetic, hand values, big-integer cross-check, error returns."""
+    import math
+    import random
+    L = sedd.lib()
+    mm, nb = L.sedd_min_match, L.sedd_dense_bucket_count
+    assert mm(u64(8), u64(10), 128) == 103          # 102.4 -> 103
+    assert mm(u64(8), u64(10), 125) == 100          # exactly 100 stays 100
+    assert mm(u64(4), u64(5), 125) == 100           # the same theta, other fraction
+    assert mm(u64(1), u64(2), 3) == 2 and mm(u64(1), u64(1), 64) == 64 and mm(u64(0), u64(7), 64) == 0
+    assert mm(u64(3), u64(2), 10) == 15             # theta > 1: above K, links nothing
+    assert mm(u64(8), u64(0), 128) == -1 and mm(u64(8), u64(10), -1) == -1
+    assert mm(u64((1 << 64) - 1), u64(1), 4096) == -1            # result beyond int32
+    rng = random.Random(5)
+    for _ in range(300):
+        num, den, K = rng.randrange(0, 1 << 40), rng.randrange(1, 1 << 40), rng.randrange(0, 4097)
+        want = -((-num * K) // den)
+        assert mm(u64(num), u64(den), K) == (want if want < (1 << 31) else -1)
+    assert nb(u64(1_000_000), 4) == 4000 and nb(u64(40_000), 4) == 800 and nb(u64(0), 4) == 1
+    assert nb(u64(10), 1) == 3 and nb(u64(32_800_000), 2) == 11454 and nb(u64(5), 0) == 1
+    for _ in range(300):
+        n, k = rng.randrange(0, 1 << 63), rng.randrange(0, 1 << 32)
+        assert nb(u64(n), k) == max(1, math.isqrt(k * k * n))

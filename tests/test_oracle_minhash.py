@@ -205,3 +205,32 @@ def test_unrelated_documents_share_almost_no_slots():
     sig = oracle.minhash(data, off, 5, 128)
     same = (sig[:100] == sig[100:]).mean()
     assert same < 0.01
+
+
+@pytest.mark.parametrize("flags", [0, oracle.FLAG_BYTE_SHINGLES, oracle.FLAG_PAPER_PRIME,
+                                   oracle.FLAG_ROLLING_FAMILY])
+def test_sharded_wrapper_equals_the_single_call(flags):
+    """minhash_sharded (the reference of most GPU comparisons) is the plain oracle cut into
+    document ranges: same signatures for any worker count, with empty documents, offsets that
+    do not start at 0, and fewer documents than two per worker."""
+    data, off = _tiny_corpus(31, 700)
+    # empty documents: repeat some offsets; a leading gap: the first document starts at byte 37
+    off = np.concatenate([off[:200], off[199:200], off[199:400], off[399:400], off[399:]])
+    lead = np.frombuffer(b"unused lead-in bytes, not a document ", dtype=np.uint8)
+    data = np.concatenate([lead, data])
+    off = (off + np.uint64(lead.size)).astype(np.uint64)
+    n = 13 if flags & oracle.FLAG_BYTE_SHINGLES else 3
+    want = oracle.minhash(data, off, n, 24, 5, flags)
+    assert (want[200] == 0xFFFFFFFF).all()                   # the planted empty document
+    for procs in (1, 2, 3, 8):
+        got = oracle.minhash_sharded(data, off, n, 24, 5, flags, procs=procs)
+        assert np.array_equal(got, want), procs
+    # fewer documents than 2 * procs: the wrapper must fall back to one call
+    few = off[:6]
+    assert np.array_equal(oracle.minhash_sharded(data, few, n, 24, 5, flags, procs=8),
+                          oracle.minhash(data, few, n, 24, 5, flags))
+    # exactly 2 * procs documents, and a worker count that does not divide the document count
+    assert np.array_equal(oracle.minhash_sharded(data, off[:17], n, 24, 5, flags, procs=8),
+                          oracle.minhash(data, off[:17], n, 24, 5, flags))
+    assert np.array_equal(oracle.minhash_sharded(data, off[:101], n, 24, 5, flags, procs=7),
+                          oracle.minhash(data, off[:101], n, 24, 5, flags))
