@@ -91,6 +91,13 @@ int sedd_profile_read(double *ms, uint64_t *spans);
 const char *sedd_profile_label(int label);
 
 /*
+ * Whether the most recent sedd_cluster / sedd_cluster_verified call had to sort its records by
+ * the whole key (1) or grouped them by the low key bits alone (0), copied to the HOST word *out
+ * (waits for the device to go idle first).  Band keys from sedd_lsh_keys never need the whole key.
+ */
+int sedd_debug_last_regroup(uint32_t *out);
+
+/*
  * Upper bound on the text bytes processed per internal chunk of sedd_minhash (0 restores
  * the default).  Results never depend on it; tests use small values to cross chunk edges.
  */

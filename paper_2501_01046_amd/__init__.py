@@ -100,6 +100,8 @@ def lib():
         L.sedd_profile_read.argtypes = [vp, vp]
         L.sedd_profile_label.restype = C.c_char_p
         L.sedd_profile_label.argtypes = [C.c_int]
+        L.sedd_debug_last_regroup.restype = C.c_int
+        L.sedd_debug_last_regroup.argtypes = [vp]
         L.sedd_debug_set_chunk_bytes.restype = C.c_int
         L.sedd_debug_set_chunk_bytes.argtypes = [u64]
         _lib = L
@@ -360,6 +362,13 @@ def debug_stats():
     buf = (C.c_uint64 * _STAT_N)()
     _check(lib().sedd_debug_stats(buf), "sedd_debug_stats")
     return list(buf)
+
+
+def debug_last_regroup() -> int:
+    """1 if the last clustering call fell back to sorting by the whole key (waits for the device)."""
+    out = C.c_uint32(0)
+    _check(lib().sedd_debug_last_regroup(C.byref(out)), "sedd_debug_last_regroup")
+    return int(out.value)
 
 
 def profile_enable(on: bool):

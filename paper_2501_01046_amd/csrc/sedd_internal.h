@@ -114,6 +114,10 @@ int scratch_ensure(uint64_t bytes, uint8_t **base);
 // Grow-only pinned host buffer.
 int pinned_ensure(uint64_t bytes, void **ptr);
 
+// The fallback flag of the most recent clustering call (inside its workspace; debug read-out).
+// Forgotten when the arena it may point into is freed.
+extern uint32_t *g_last_gate;
+
 // Device counters that persist for the life of the process (SEDD_STAT_* indices).
 int stats_ensure(unsigned long long **p);
 
@@ -139,9 +143,10 @@ struct Carver {  // carves 256-byte aligned sub-buffers out of the arena
 };
 
 // Exclusive prefix sum of n uint32 (out may alias in).  tmp must hold scan_tmp_count(n) uint32.
+// With a gate (device pointer) the kernels are still launched but do nothing unless *gate != 0.
 uint64_t scan_tmp_count(uint64_t n);
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *tmp,
-                       hipStream_t s);
+                       hipStream_t s, const uint32_t *gate = nullptr);
 
 static inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 

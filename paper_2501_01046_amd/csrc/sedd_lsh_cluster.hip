@@ -89,8 +89,9 @@ k_to_band_major(const uint64_t *__restrict__ keys, uint32_t n, uint32_t b,
 
 __global__ void __launch_bounds__(SORT_THREADS)
 k_radix_hist(const uint64_t *__restrict__ bk, uint32_t n, uint32_t nblk, int shift,
-             uint32_t *__restrict__ hist) {
+             uint32_t *__restrict__ hist, const uint32_t *__restrict__ gate) {
   __shared__ uint32_t h[RADIX];
+  if (gate && *gate == 0) return;  // a pass of the full-key fallback that is not needed
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   h[threadIdx.x] = 0;
   __syncthreads();
@@ -113,8 +114,10 @@ k_radix_hist(const uint64_t *__restrict__ bk, uint32_t n, uint32_t nblk, int shi
 __global__ void __launch_bounds__(SORT_THREADS)
 k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
                 uint32_t nblk, int shift, const uint32_t *__restrict__ pos,
-                uint64_t *__restrict__ ok, uint32_t *__restrict__ od) {
+                uint64_t *__restrict__ ok, uint32_t *__restrict__ od,
+                const uint32_t *__restrict__ gate) {
   constexpr int WAVES = SORT_THREADS / 64;
+  if (gate && *gate == 0) return;
   __shared__ uint32_t wc[WAVES][RADIX];  // per wavefront: digit count, later its offset in the tile
   __shared__ uint32_t s_lstart[RADIX];   // first position of the digit in the sorted tile
   __shared__ uint32_t s_gbase[RADIX];    // where the tile's run of the digit starts in the output
@@ -238,7 +241,8 @@ __device__ __forceinline__ void uf_unite(uint32_t *parent, uint32_t a, uint32_t 
   }
 }
 
-__global__ void k_fill_small_u32(uint32_t *p, uint32_t n, uint32_t v) {
+__global__ void k_fill_small_u32(uint32_t *p, uint32_t n, uint32_t v, const uint32_t *gate) {
+  if (gate && *gate == 0) return;
   if (threadIdx.x < n) p[threadIdx.x] = v;
 }
 
@@ -250,21 +254,39 @@ __global__ void k_iota_u32(uint32_t *p, uint32_t n) {
 // Records sorted by the low bits selected by `mask`: every record is linked to the nearest
 // earlier record of its band with the same full key; the walk stops at the first record that
 // differs in the sorted bits.  (With a full sort the walk is one step.)
+//
+// The walk is capped: a record that has not met its key, nor the end of its group, after
+// WALK_CAP records raises *gate.  Keys whose sorted bits are uniform (the band keys of
+// sedd_lsh_keys are) never do; keys that agree in the sorted bits and differ above them
+// would otherwise make every record walk over all earlier ones.  When the gate is up the
+// remaining radix passes run (they are always enqueued, and return at once while it is down)
+// and a second launch of this kernel (retry = 1, mask = all ones) links the fully sorted records.
+// Links made by the first launch stay valid: it only ever unites records with equal keys.
+constexpr uint32_t WALK_CAP = 64;
 __global__ void __launch_bounds__(256)
 k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
-            uint32_t b, uint64_t mask, uint32_t *parent) {
+            uint32_t b, uint64_t mask, uint32_t *parent, uint32_t *gate, int retry) {
+  if (retry && *gate == 0) return;
   uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (uint64_t)n * b) return;
-  const uint32_t i = (uint32_t)(idx % n);
-  const uint64_t key = bk[idx];
-  for (uint32_t back = 1; back <= i; back++) {
-    const uint64_t other = bk[idx - back];
-    if ((other ^ key) & mask) break;
-    if (other == key) {
-      uf_unite(parent, bd[idx - back], bd[idx]);
-      break;
+  bool open = false;
+  if (idx < (uint64_t)n * b) {
+    const uint32_t i = (uint32_t)(idx % n);
+    const uint64_t key = bk[idx];
+    for (uint32_t back = 1; back <= i; back++) {
+      if (back > WALK_CAP) {
+        open = true;
+        break;
+      }
+      const uint64_t other = bk[idx - back];
+      if ((other ^ key) & mask) break;
+      if (other == key) {
+        uf_unite(parent, bd[idx - back], bd[idx]);
+        break;
+      }
     }
   }
+  // with mask = all ones the first step always ends the walk, so a retry never gets here
+  if (__any(open) && (threadIdx.x & 63) == 0) atomicOr(gate, 1u);
 }
 
 // ---- verified clusters (Section 3.3) --------------------------------------------------------
@@ -307,18 +329,25 @@ __device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
 __global__ void __launch_bounds__(SORT_THREADS)
 k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
          uint32_t *__restrict__ list1, uint32_t *__restrict__ counts,
-         BigGroup *__restrict__ big) {
+         BigGroup *__restrict__ big, uint32_t *gate, int retry) {
   __shared__ uint32_t s_base[2];
+  if (retry && *gate == 0) return;
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const uint64_t *src = bk + (uint64_t)band * n;
   uint32_t flags = 0, heads = 0;  // bit it: item it goes to list1 / is the head of a large group
+  bool mixed = false;  // a large group that holds more than one key: the sorted bits are too few
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; it++) {
     const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
     if (e >= n) continue;
-    const uint64_t low = src[e] & mask;
+    const uint64_t key = src[e], low = key & mask;
     const bool follower = e > 0 && (src[e - 1] & mask) == low;
-    const bool far_after = e + BIG_GROUP < n && (src[e + BIG_GROUP] & mask) == low;
+    bool far_after = false;
+    if (e + BIG_GROUP < n) {
+      const uint64_t other = src[e + BIG_GROUP];
+      far_after = (other & mask) == low;
+      mixed |= far_after && other != key;
+    }
     if (follower) {
       const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
       if (!far_before && !far_after) flags |= 1u << it;
@@ -326,6 +355,8 @@ k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
       heads |= 1u << it;
     }
   }
+  // (with mask = all ones a group holds one key, so a retry never raises the gate)
+  if (__any(mixed) && (threadIdx.x & 63) == 0) atomicOr(gate, 1u);
   // both counts through one scan (at most SORT_TILE = 2^12 of either per block) and one atomic
   // each per block
   static_assert(SORT_TILE <= (1u << 15), "two counts share one 32-bit scan");
@@ -426,9 +457,11 @@ __device__ __forceinline__ bool team_verify_pair(const uint32_t *__restrict__ si
 // step 1: one team per follower record, against the head of its group
 __global__ void __launch_bounds__(256)
 k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
-               uint64_t mask, const uint32_t *__restrict__ sig, int K, int min_match,
+               uint64_t mask_lo, const uint32_t *__restrict__ gate,
+               const uint32_t *__restrict__ sig, int K, int min_match,
                uint32_t *parent, const uint32_t *__restrict__ list1, uint32_t *counts,
                uint32_t *__restrict__ list2) {
+  const uint64_t mask = *gate ? ~uint64_t(0) : mask_lo;  // gate up: the records are fully sorted
   const uint32_t n1 = counts[0];
   const int tl = threadIdx.x & (TEAM - 1);
   const uint32_t teams = gridDim.x * (blockDim.x / TEAM);
@@ -458,9 +491,11 @@ k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
 // step 2: one wavefront per outsider, against every other record of its group
 __global__ void __launch_bounds__(256)
 k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
-                   uint64_t mask, const uint32_t *__restrict__ sig, int K, int min_match,
+                   uint64_t mask_lo, const uint32_t *__restrict__ gate,
+                   const uint32_t *__restrict__ sig, int K, int min_match,
                    uint32_t *parent, const uint32_t *__restrict__ list2,
                    const uint32_t *__restrict__ counts) {
+  const uint64_t mask = *gate ? ~uint64_t(0) : mask_lo;
   const uint32_t n2 = counts[1];
   const int tl = threadIdx.x & (TEAM - 1);
   const uint32_t team = (threadIdx.x & 63) / TEAM;
@@ -739,7 +774,8 @@ __global__ void k_write_roots(uint32_t *parent, uint32_t n, int64_t *__restrict_
 
 __global__ void k_copy_sorted(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
                               uint64_t total, uint64_t *__restrict__ ok,
-                              uint32_t *__restrict__ od) {
+                              uint32_t *__restrict__ od, const uint32_t *__restrict__ gate) {
+  if (gate && *gate == 0) return;
   uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < total) {
     ok[i] = bk[i];
@@ -750,6 +786,7 @@ __global__ void k_copy_sorted(const uint64_t *__restrict__ bk, const uint32_t *_
 struct SortBufs {
   uint64_t *ka, *kb;
   uint32_t *da, *db, *hist, *tmp, *parent;
+  uint32_t *gate;      // raised by the linking / marking kernel when the sorted bits are too few
   uint32_t *sketch;    // one-bit signature sketches (verified path): n * sketch_words(K) words
   BigGroup *big;       // capacity big_cap
   uint64_t *tile_pre;  // 2 * (big_cap + 1) prefix sums of tile counts
@@ -757,33 +794,59 @@ struct SortBufs {
   uint32_t nblk;
 };
 
-static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb, int K_sketch = 0) {
+// Where the buffers of one clustering call sit inside its workspace (256-byte aligned pieces).
+struct SortPlan {
+  uint64_t o_ka, o_kb, o_da, o_db, o_h, o_t, o_p, o_gate, o_big, o_pre, o_sk;
+  uint64_t big_cap, bytes;
+  uint32_t nblk;
+};
+
+// K_sketch = 0: the buffers of sedd_cluster; K_sketch = K: those of sedd_cluster_verified as well
+static SortPlan plan_sort(uint64_t n, uint32_t b, int K_sketch) {
+  SortPlan pl;
   const uint64_t total = n * b;
-  const uint32_t nblk = (uint32_t)((n + SORT_TILE - 1) / SORT_TILE);
-  const uint64_t nh = (uint64_t)b * RADIX * nblk;
+  pl.nblk = (uint32_t)((n + SORT_TILE - 1) / SORT_TILE);
+  const uint64_t nh = (uint64_t)b * RADIX * pl.nblk;
   Carver cv;
-  const uint64_t o_ka = cv.take<uint64_t>(total), o_kb = cv.take<uint64_t>(total);
-  const uint64_t o_da = cv.take<uint32_t>(total), o_db = cv.take<uint32_t>(total);
-  const uint64_t o_h = cv.take<uint32_t>(nh), o_t = cv.take<uint32_t>(scan_tmp_count(nh));
-  const uint64_t o_p = cv.take<uint32_t>(n);
-  const uint64_t big_cap = total / BIG_GROUP + 1;
-  const uint64_t o_big = cv.take<BigGroup>(big_cap), o_pre = cv.take<uint64_t>(2 * (big_cap + 1));
-  const uint64_t o_sk = cv.take<uint32_t>(K_sketch ? n * sketch_words(K_sketch) : 1);
+  pl.o_ka = cv.take<uint64_t>(total);
+  pl.o_kb = cv.take<uint64_t>(total);
+  pl.o_da = cv.take<uint32_t>(total);
+  pl.o_db = cv.take<uint32_t>(total);
+  pl.o_h = cv.take<uint32_t>(nh);
+  pl.o_t = cv.take<uint32_t>(scan_tmp_count(nh));
+  pl.o_p = cv.take<uint32_t>(n);
+  pl.o_gate = cv.take<uint32_t>(1);
+  pl.big_cap = K_sketch ? total / BIG_GROUP + 1 : 0;
+  pl.o_big = cv.take<BigGroup>(pl.big_cap + 1);
+  pl.o_pre = cv.take<uint64_t>(2 * (pl.big_cap + 1));
+  pl.o_sk = cv.take<uint32_t>(K_sketch ? n * sketch_words(K_sketch) : 1);
+  pl.bytes = cv.off;
+  return pl;
+}
+
+static void bind_sort(const SortPlan &pl, uint8_t *A, SortBufs *sb) {
+  sb->ka = (uint64_t *)(A + pl.o_ka);
+  sb->kb = (uint64_t *)(A + pl.o_kb);
+  sb->da = (uint32_t *)(A + pl.o_da);
+  sb->db = (uint32_t *)(A + pl.o_db);
+  sb->hist = (uint32_t *)(A + pl.o_h);
+  sb->tmp = (uint32_t *)(A + pl.o_t);
+  sb->parent = (uint32_t *)(A + pl.o_p);
+  sb->gate = (uint32_t *)(A + pl.o_gate);
+  sb->big = (BigGroup *)(A + pl.o_big);
+  sb->tile_pre = (uint64_t *)(A + pl.o_pre);
+  sb->sketch = (uint32_t *)(A + pl.o_sk);
+  sb->big_cap = pl.big_cap;
+  sb->nblk = pl.nblk;
+}
+
+// the buffers carved out of the library's own arena
+static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb, int K_sketch = 0) {
+  const SortPlan pl = plan_sort(n, b, K_sketch);
   uint8_t *A = nullptr;
-  int rc = scratch_ensure(cv.off, &A);
+  int rc = scratch_ensure(pl.bytes, &A);
   if (rc) return rc;
-  sb->sketch = (uint32_t *)(A + o_sk);
-  sb->big = (BigGroup *)(A + o_big);
-  sb->tile_pre = (uint64_t *)(A + o_pre);
-  sb->big_cap = big_cap;
-  sb->ka = (uint64_t *)(A + o_ka);
-  sb->kb = (uint64_t *)(A + o_kb);
-  sb->da = (uint32_t *)(A + o_da);
-  sb->db = (uint32_t *)(A + o_db);
-  sb->hist = (uint32_t *)(A + o_h);
-  sb->tmp = (uint32_t *)(A + o_t);
-  sb->parent = (uint32_t *)(A + o_p);
-  sb->nblk = nblk;
+  bind_sort(pl, A, sb);
   return SEDD_OK;
 }
 
@@ -797,6 +860,45 @@ static int grouping_bits(uint64_t n_docs, uint64_t slack) {
   return bits;
 }
 
+// Stable radix passes over the digits at shift0, shift0 + 8, ... below shift1 of the records in
+// sb->ka / sb->da; the result is again in sb->ka / sb->da and sb->kb / sb->db are free.
+// Without a gate an odd number of passes renames the two buffer pairs.  With a gate (device word;
+// every kernel returns at once while it is zero) the pairs keep their roles whatever the gate
+// says, so an odd number of passes ends with a copy back.
+static int sort_passes(uint32_t n, uint32_t b, int shift0, int shift1, SortBufs *sb,
+                       const uint32_t *gate, hipStream_t st) {
+  const uint64_t nh = (uint64_t)b * RADIX * sb->nblk;
+  uint64_t *src_k = sb->ka, *dst_k = sb->kb;
+  uint32_t *src_d = sb->da, *dst_d = sb->db;
+  for (int shift = shift0; shift < shift1; shift += RADIX_BITS) {
+    dim3 grid(sb->nblk, b);
+    hipLaunchKernelGGL(k_radix_hist, grid, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
+                       sb->hist, gate);
+    SEDD_LAUNCH_CHECK();
+    int rc = scan_exclusive_u32(sb->hist, sb->hist, nh, sb->tmp, st, gate);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_radix_scatter, grid, dim3(SORT_THREADS), 0, st, src_k, src_d, n,
+                       sb->nblk, shift, sb->hist, dst_k, dst_d, gate);
+    SEDD_LAUNCH_CHECK();
+    std::swap(src_k, dst_k);
+    std::swap(src_d, dst_d);
+  }
+  if (gate) {
+    if (src_k != sb->ka) {
+      const uint64_t total = (uint64_t)n * b;
+      hipLaunchKernelGGL(k_copy_sorted, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, src_k,
+                         src_d, total, sb->ka, sb->da, gate);
+      SEDD_LAUNCH_CHECK();
+    }
+    return SEDD_OK;
+  }
+  sb->kb = dst_k;
+  sb->db = dst_d;
+  sb->ka = src_k;
+  sb->da = src_d;
+  return SEDD_OK;
+}
+
 // leaves the records, sorted by the low key_bits bits (whole digits, or KEY_BITS for a full
 // sort), in sb->ka / sb->da; sb->kb / sb->db are free afterwards
 static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key_bits, SortBufs *sb,
@@ -805,27 +907,55 @@ static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key
   hipLaunchKernelGGL(k_to_band_major, dim3((n + 255) / 256), dim3(256), 0, st, keys, n, b, sb->ka,
                      sb->da);
   SEDD_LAUNCH_CHECK();
-  const uint64_t nh = (uint64_t)b * RADIX * sb->nblk;
-  uint64_t *src_k = sb->ka, *dst_k = sb->kb;
-  uint32_t *src_d = sb->da, *dst_d = sb->db;
-  for (int shift = 0; shift < key_bits; shift += RADIX_BITS) {
-    dim3 grid(sb->nblk, b);
-    hipLaunchKernelGGL(k_radix_hist, grid, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
-                       sb->hist);
-    SEDD_LAUNCH_CHECK();
-    int rc = scan_exclusive_u32(sb->hist, sb->hist, nh, sb->tmp, st);
+  return sort_passes(n, b, 0, key_bits, sb, nullptr, st);
+}
+
+// The fallback of the grouping sort: the passes over the key bits it left out, enqueued always,
+// executed only when *sb->gate is non-zero.
+static int sort_rest_if_gated(uint64_t n_docs, uint32_t b, int key_bits, SortBufs *sb,
+                              hipStream_t st) {
+  return sort_passes((uint32_t)n_docs, b, key_bits, KEY_BITS, sb, sb->gate, st);
+}
+
+
+// sedd_cluster on the buffers of `sb` (the caller has checked the arguments)
+static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_t *cluster_id,
+                       SortBufs &sb, bool timed, hipStream_t st) {
+  const int bits = grouping_bits(n_docs, 16);
+  const uint32_t n = (uint32_t)n_docs;
+  const uint64_t total = n_docs * (uint64_t)b;
+  const uint32_t link_grid = (uint32_t)((total + 255) / 256);
+  g_last_gate = sb.gate;
+  int rc;
+  {
+    ProfScope prof(timed ? SEDD_PROF_SORT : -1, st);
+    rc = sort_bands(keys, n_docs, b, bits, &sb, st);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_radix_scatter, grid, dim3(SORT_THREADS), 0, st, src_k, src_d, n,
-                       sb->nblk, shift, sb->hist, dst_k, dst_d);
-    SEDD_LAUNCH_CHECK();
-    std::swap(src_k, dst_k);
-    std::swap(src_d, dst_d);
   }
-  // after an odd number of passes the result sits in the second pair: rename the pairs
-  sb->kb = dst_k;
-  sb->db = dst_d;
-  sb->ka = src_k;
-  sb->da = src_d;
+  {
+    ProfScope prof(timed ? SEDD_PROF_UNION : -1, st);
+    hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, sb.gate, 1u, 0u,
+                       (const uint32_t *)nullptr);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_link_runs, dim3(link_grid), dim3(256), 0, st, sb.ka, sb.da, n, b,
+                       (uint64_t(1) << bits) - 1, sb.parent, sb.gate, 0);
+    SEDD_LAUNCH_CHECK();
+  }
+  {
+    // only if a walk hit its cap: sort by the rest of the key, link again
+    ProfScope prof(timed ? SEDD_PROF_SORT : -1, st);
+    rc = sort_rest_if_gated(n_docs, b, bits, &sb, st);
+    if (rc) return rc;
+  }
+  ProfScope prof(timed ? SEDD_PROF_UNION : -1, st);
+  hipLaunchKernelGGL(k_link_runs, dim3(link_grid), dim3(256), 0, st, sb.ka, sb.da, n, b,
+                     ~uint64_t(0), sb.parent, sb.gate, 1);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
+                     cluster_id);
+  SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
 
@@ -883,28 +1013,10 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
                  void *stream) {
   int rc = check_cluster_args(keys, n_docs, b, cluster_id);
   if (rc || n_docs == 0) return rc;
-  hipStream_t st = (hipStream_t)stream;
   SortBufs sb;
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
-  const int bits = grouping_bits(n_docs, 16);
-  {
-    ProfScope prof(SEDD_PROF_SORT, st);
-    rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
-    if (rc) return rc;
-  }
-  ProfScope prof(SEDD_PROF_UNION, st);
-  const uint32_t n = (uint32_t)n_docs;
-  hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
-  SEDD_LAUNCH_CHECK();
-  const uint64_t total = n_docs * (uint64_t)b;
-  hipLaunchKernelGGL(k_link_runs, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,
-                     sb.da, n, (uint32_t)b, (uint64_t(1) << bits) - 1, sb.parent);
-  SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
-                     cluster_id);
-  SEDD_LAUNCH_CHECK();
-  return SEDD_OK;
+  return run_cluster(keys, n_docs, (uint32_t)b, cluster_id, sb, true, (hipStream_t)stream);
 }
 
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
@@ -924,23 +1036,43 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   // cleared by every call
   uint32_t *counts = (uint32_t *)(stats + SEDD_STAT_VERIFY_COUNTS);
   const int bits = grouping_bits(n_docs, 4096);
+  g_last_gate = sb.gate;
   {
     ProfScope prof(SEDD_PROF_SORT, st);
     rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
     if (rc) return rc;
   }
-  ProfScope prof(SEDD_PROF_VERIFY, st);
   const uint32_t n = (uint32_t)n_docs;
-  const uint64_t total = n_docs * (uint64_t)b;
   const uint64_t mask = (uint64_t(1) << bits) - 1;
   // the sort leaves its result in the first buffer pair; the second pair holds the two lists
   uint32_t *list1 = (uint32_t *)sb.kb, *list2 = sb.db;
-  hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
+  {
+    ProfScope prof(SEDD_PROF_VERIFY, st);
+    hipLaunchKernelGGL(k_iota_u32, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 4u, 0u,
+                       (const uint32_t *)nullptr);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, sb.gate, 1u, 0u,
+                       (const uint32_t *)nullptr);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
+                       list1, counts, sb.big, sb.gate, 0);
+    SEDD_LAUNCH_CHECK();
+  }
+  {
+    // only if a large group held more than one key (the sorted bits were too few to separate
+    // the buckets): sort by the rest of the key and mark again, now on whole keys
+    ProfScope prof(SEDD_PROF_SORT, st);
+    rc = sort_rest_if_gated(n_docs, (uint32_t)b, bits, &sb, st);
+    if (rc) return rc;
+  }
+  ProfScope prof(SEDD_PROF_VERIFY, st);
+  hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 4u, 0u,
+                     (const uint32_t *)sb.gate);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 4u, 0u);
-  SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
-                     list1, counts, sb.big);
+  hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n,
+                     ~uint64_t(0), list1, counts, sb.big, sb.gate, 1);
   SEDD_LAUNCH_CHECK();
   // large groups: tile plan, then the tiles against each group's first tile, then the rest
   hipLaunchKernelGGL(k_v_plan_tiles, dim3(1), dim3(1024), 0, st, sb.big, counts, sb.big_cap,
@@ -956,15 +1088,25 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
   }
   // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
   const uint32_t grid = 256 * 16;
-  hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,
-                     (int)K, (int)min_match, sb.parent, list1, counts, list2);
+  hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask,
+                     (const uint32_t *)sb.gate, sig, (int)K, (int)min_match, sb.parent, list1, counts,
+                     list2);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_v_outsider_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask, sig,
-                     (int)K, (int)min_match, sb.parent, list2, counts);
+  hipLaunchKernelGGL(k_v_outsider_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask,
+                     (const uint32_t *)sb.gate, sig, (int)K, (int)min_match, sb.parent, list2, counts);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
                      cluster_id);
   SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
+int sedd_debug_last_regroup(uint32_t *out) {
+  if (!out) return SEDD_EINVAL;
+  *out = 0;
+  if (!g_last_gate) return SEDD_OK;
+  SEDD_HIP(hipDeviceSynchronize());
+  SEDD_HIP(hipMemcpy(out, g_last_gate, sizeof(uint32_t), hipMemcpyDeviceToHost));
   return SEDD_OK;
 }
 
@@ -981,7 +1123,7 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
   if (rc) return rc;
   const uint64_t total = n_docs * (uint64_t)b;
   hipLaunchKernelGGL(k_copy_sorted, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,
-                     sb.da, total, keys_sorted, docs_sorted);
+                     sb.da, total, keys_sorted, docs_sorted, (const uint32_t *)nullptr);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }

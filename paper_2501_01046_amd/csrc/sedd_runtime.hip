@@ -18,6 +18,7 @@ int set_device_error(hipError_t e, const char *what) {
   return e == hipErrorOutOfMemory ? SEDD_ENOMEM : SEDD_EDEVICE;
 }
 
+uint32_t *g_last_gate = nullptr;
 static uint8_t *g_arena = nullptr;
 static uint64_t g_arena_bytes = 0;
 static void *g_pinned = nullptr;
@@ -31,6 +32,7 @@ int scratch_ensure(uint64_t bytes, uint8_t **base) {
       SEDD_HIP(hipFree(g_arena));
       g_arena = nullptr;
       g_arena_bytes = 0;
+      g_last_gate = nullptr;
     }
     uint64_t want = (bytes + (uint64_t(1) << 21)) & ~((uint64_t(1) << 21) - 1);
     void *p = nullptr;
@@ -108,7 +110,7 @@ static hipEvent_t prof_event() {
 }
 
 ProfScope::ProfScope(int label, hipStream_t st) : st_(st), idx_(-1) {
-  if (!g_prof_on) return;
+  if (!g_prof_on || label < 0) return;  // a negative label: this scope is not timed
   ProfSpan sp{label, prof_event(), prof_event()};
   if (!sp.e0 || !sp.e1) return;
   (void)hipEventRecord(sp.e0, st);
@@ -131,8 +133,11 @@ constexpr int SCAN_PER_THREAD = 4;
 constexpr int SCAN_BLOCK = SCAN_THREADS * SCAN_PER_THREAD;
 constexpr uint64_t SCAN_DIRECT = 2048;
 
+// `gate` (optional, in every scan kernel): the launch does nothing unless *gate is non-zero.
 __global__ void __launch_bounds__(SCAN_THREADS)
-k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, uint64_t n) {
+k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, uint64_t n,
+              const uint32_t *__restrict__ gate) {
+  if (gate && *gate == 0) return;
   uint64_t i0 = (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
   uint32_t s = 0;
 #pragma unroll
@@ -147,7 +152,8 @@ k_scan_reduce(const uint32_t *__restrict__ in, uint32_t *__restrict__ partial, u
 // otherwise partial[b] already is the exclusive prefix of block b.
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_down(const uint32_t *in, uint32_t *out, uint64_t n, const uint32_t *__restrict__ partial,
-            int partial_is_sum) {
+            int partial_is_sum, const uint32_t *__restrict__ gate) {
+  if (gate && *gate == 0) return;
   uint64_t i0 = (uint64_t)blockIdx.x * SCAN_BLOCK + (uint64_t)threadIdx.x * SCAN_PER_THREAD;
   uint32_t v[SCAN_PER_THREAD];
   uint32_t s = 0;
@@ -187,25 +193,25 @@ uint64_t scan_tmp_count(uint64_t n) {
 }
 
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *tmp,
-                       hipStream_t s) {
+                       hipStream_t s, const uint32_t *gate) {
   if (n == 0) return SEDD_OK;
   uint64_t nb = (n + SCAN_BLOCK - 1) / SCAN_BLOCK;
   if (nb == 1) {
     hipLaunchKernelGGL(k_scan_down, dim3(1), dim3(SCAN_THREADS), 0, s, in, out, n,
-                       (const uint32_t *)nullptr, 0);
+                       (const uint32_t *)nullptr, 0, gate);
     SEDD_LAUNCH_CHECK();
     return SEDD_OK;
   }
-  hipLaunchKernelGGL(k_scan_reduce, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, tmp, n);
+  hipLaunchKernelGGL(k_scan_reduce, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, tmp, n, gate);
   SEDD_LAUNCH_CHECK();
   const int direct = nb <= SCAN_DIRECT ? 1 : 0;
   if (!direct) {
     uint32_t *next_tmp = tmp + ((nb + 63) & ~uint64_t(63));
-    int rc = scan_exclusive_u32(tmp, tmp, nb, next_tmp, s);
+    int rc = scan_exclusive_u32(tmp, tmp, nb, next_tmp, s, gate);
     if (rc) return rc;
   }
   hipLaunchKernelGGL(k_scan_down, dim3((uint32_t)nb), dim3(SCAN_THREADS), 0, s, in, out, n,
-                     (const uint32_t *)tmp, direct);
+                     (const uint32_t *)tmp, direct, gate);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
@@ -255,6 +261,7 @@ int sedd_release_scratch(void) {
     SEDD_HIP(hipFree(g_arena));
     g_arena = nullptr;
     g_arena_bytes = 0;
+    g_last_gate = nullptr;
   }
   if (g_pinned) {
     SEDD_HIP(hipHostFree(g_pinned));

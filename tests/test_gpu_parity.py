@@ -4,6 +4,7 @@ All of these go through the C-ABI (ctypes) via the thin binding.  Signatures, ba
 cluster ids are integers with a unique correct value, so the bar is exact equality.
 """
 import os
+import time
 
 import numpy as np
 import pytest
@@ -331,6 +332,56 @@ def test_cluster_long_chain_across_bands(sedd):
     assert np.array_equal(host(sedd.sedd_cluster(dev(keys))), want)
     perm = np.random.default_rng(0).permutation(n)
     assert np.array_equal(host(sedd.sedd_cluster(dev(keys[perm]))), oracle.cluster(keys[perm]))
+
+
+@pytest.mark.parametrize("kind", ["shifted", "seven_high_values", "uniform"])
+def test_cluster_keys_with_constant_low_bits_at_200k(sedd, kind):
+    """Keys whose low bits say nothing (d << 32: all distinct, all zero below bit 32; a few high
+    values over a small low part: large groups of interleaved buckets).  The grouping sort
+    cannot separate them; the calls must notice, sort by the whole key, and still finish in
+    milliseconds with the oracle's clusters.  Uniform keys must not take that detour."""
+    say("cluster constant low bits", kind)
+    n, b = 200_000, 4
+    rng = np.random.default_rng(7)
+    d = np.arange(n, dtype=np.uint64)
+    if kind == "shifted":
+        keys = np.stack([(d << np.uint64(32)), ((d // np.uint64(3)) << np.uint64(32)),
+                         ((d % np.uint64(50_000)) << np.uint64(29)), d << np.uint64(40)], axis=1)
+    elif kind == "seven_high_values":
+        c = rng.integers(0, 200, size=(n, b), dtype=np.uint64)
+        keys = ((d % np.uint64(7))[:, None] << np.uint64(40)) | c
+    else:
+        keys = rng.integers(0, (1 << 61) - 1, size=(n, b), dtype=np.uint64)
+        keys[n // 2:, 0] = keys[: n // 2, 0]                  # some real duplicates
+    keys = np.ascontiguousarray(keys)
+    want = oracle.cluster(keys)
+    d_keys = dev(keys)
+    sedd.sedd_cluster(d_keys)                                # first call pays the allocation
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    got = sedd.sedd_cluster(d_keys)
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0)
+    regroup = sedd.debug_last_regroup()
+    assert np.array_equal(host(got), want)
+    say(f"  {kind}: {ms:.2f} ms, whole-key sort: {regroup}")
+    if kind != "seven_high_values":                          # there the walks may all stay short
+        assert regroup == (0 if kind == "uniform" else 1)
+    assert ms < 200, f"sedd_cluster took {ms:.1f} ms on 200k x 4 records"
+    # the verified call on the same keys: threshold 0 is plain bucket grouping, K + 1 links nothing
+    sig = rng.integers(0, 1 << 32, size=(n, 8), dtype=np.uint64).astype(np.uint32)
+    sig[n // 2:] = sig[: n // 2]
+    d_sig = dev(sig)
+    for mm in (0, 8, 9):
+        t0 = time.perf_counter()
+        vgot = sedd.sedd_cluster_verified(d_keys, d_sig, mm)
+        torch.cuda.synchronize()
+        vms = 1e3 * (time.perf_counter() - t0)
+        vre = sedd.debug_last_regroup()
+        assert np.array_equal(host(vgot), oracle.cluster_verified(keys, sig, mm)), mm
+        assert vms < 2000, f"sedd_cluster_verified took {vms:.1f} ms"
+    say(f"  {kind}: verified {vms:.2f} ms, whole-key sort: {vre}")
+    assert vre == (0 if kind == "uniform" else 1)
 
 
 # ---- the whole path ------------------------------------------------------------------------
