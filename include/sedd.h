@@ -39,6 +39,7 @@ extern "C" {
 #define SEDD_EINVAL (-1)  /* bad argument (null pointer, K<1, b*r>K, offsets decreasing, ...) */
 #define SEDD_ENOMEM (-2)  /* device or pinned-host scratch allocation failed */
 #define SEDD_EDEVICE (-3) /* a HIP call failed; sedd_last_device_error() names it */
+#define SEDD_ELIMIT (-4)  /* the input exceeds a fixed limit of the entry point (sedd_cluster_static) */
 
 /* flags of sedd_minhash */
 #define SEDD_FLAG_BYTE_SHINGLES 1u /* shingles are byte n-grams instead of word n-grams */
@@ -133,6 +134,28 @@ int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t
  */
 int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
                  void *stream);
+
+/*
+ * sedd_cluster for callers that cannot allocate device memory while they call: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * result, same kernels as sedd_cluster; the sort buffers, the digit histograms and the
+ * union-find forest live in a fixed array of SEDD_STATIC_SCRATCH_MIB MiB that is part of the
+ * library's code object (each GPU the library runs on holds its copy until the process ends).
+ * The call makes no hipMalloc / hipFree, creates no event, and never touches the grow-only
+ * arena of the other calls.  Apart from one symbol look-up on its first call on a device it
+ * only launches kernels on `stream`; stage timing (sedd_profile_enable) skips it.
+ *
+ * Limit: the call needs 24 bytes per (document, band) record, 4 bytes per document, 1 KiB per
+ * band per 4096 documents and about 70 KiB besides; n_docs * b <= 1,048,576 with b <= 64 always
+ * fits (for example 65,536 documents x 16 bands).  A larger input returns SEDD_ELIMIT and
+ * enqueues nothing.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (on two
+ * streams, or from two threads) race; calls on one stream, or otherwise ordered, do not.
+ * Nothing in the array has to survive between calls; every call clears what it reads.
+ */
+#define SEDD_STATIC_SCRATCH_MIB 32
+int sedd_cluster_static(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
+                        void *stream);
 
 /*
  * Verified duplicate clusters (Section 2.3, last step; Section 3.3: inside every bucket all

@@ -17,7 +17,7 @@ import os
 
 __all__ = [
     "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
-    "sedd_cluster_verified", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
+    "sedd_cluster_verified", "sedd_cluster_static", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
@@ -62,6 +62,8 @@ def lib():
         L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
         L.sedd_cluster.restype = C.c_int
         L.sedd_cluster.argtypes = [vp, u64, i32, vp, vp]
+        L.sedd_cluster_static.restype = C.c_int
+        L.sedd_cluster_static.argtypes = [vp, u64, i32, vp, vp]
         L.sedd_lsh_dense_keys.restype = C.c_int
         L.sedd_lsh_dense_keys.argtypes = [vp, u64, i32, i32, i32, u64, vp, vp]
         L.sedd_cluster_verified.restype = C.c_int
@@ -191,6 +193,20 @@ def sedd_cluster(keys, out=None, stream=None):
         if out.numel() != n_docs:
             raise ValueError("out has the wrong size")
     _check(lib().sedd_cluster(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)), "sedd_cluster")
+    return out
+
+
+def sedd_cluster_static(keys, out, stream=None):
+    """sedd_cluster through the entry point that allocates nothing: `out` (int64 [n_docs]) is
+    required, scratch is the library's fixed array; raises SeddError(-4) beyond its limit."""
+    torch = _torch()
+    keys = _dev(keys, torch.uint64, "keys")
+    out = _dev(out, torch.int64, "out")
+    n_docs, b = keys.shape
+    if out.numel() != n_docs:
+        raise ValueError("out has the wrong size")
+    _check(lib().sedd_cluster_static(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)),
+           "sedd_cluster_static")
     return out
 
 

@@ -959,6 +959,31 @@ static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_
   return SEDD_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------------
+//
+// One fixed array in device memory, part of the code object: every GPU the library runs on holds
+// its own copy from the first use of the library on it until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address it yields for the current
+// device is what kernels and copies are given.
+constexpr uint64_t STATIC_SCRATCH_BYTES = uint64_t(SEDD_STATIC_SCRATCH_MIB) << 20;
+static __device__ __align__(256) uint8_t scratch[STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+static uint8_t *g_static_scratch[STATIC_MAX_DEVICES];  // per device, filled on first use
+
+static int static_scratch_for_current_device(uint8_t **out) {
+  int dev = -1;
+  SEDD_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return SEDD_ELIMIT;
+  if (!g_static_scratch[dev]) {
+    uint8_t *ptr = nullptr;
+    SEDD_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return SEDD_EDEVICE;
+    g_static_scratch[dev] = ptr;
+  }
+  *out = g_static_scratch[dev];
+  return SEDD_OK;
+}
+
 }  // namespace sedd
 
 using namespace sedd;
@@ -1017,6 +1042,21 @@ int sedd_cluster(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *clus
   rc = sort_layout(n_docs, (uint32_t)b, &sb);
   if (rc) return rc;
   return run_cluster(keys, n_docs, (uint32_t)b, cluster_id, sb, true, (hipStream_t)stream);
+}
+
+int sedd_cluster_static(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
+                        void *stream) {
+  int rc = check_cluster_args(keys, n_docs, b, cluster_id);
+  if (rc || n_docs == 0) return rc;
+  const SortPlan pl = plan_sort(n_docs, (uint32_t)b, 0);
+  if (pl.bytes > STATIC_SCRATCH_BYTES) return SEDD_ELIMIT;
+  uint8_t *A = nullptr;
+  rc = static_scratch_for_current_device(&A);
+  if (rc) return rc;
+  SortBufs sb;
+  bind_sort(pl, A, &sb);
+  // same kernels as sedd_cluster; no stage timing here (it would create events)
+  return run_cluster(keys, n_docs, (uint32_t)b, cluster_id, sb, false, (hipStream_t)stream);
 }
 
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,

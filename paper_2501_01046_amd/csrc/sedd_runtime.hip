@@ -228,6 +228,7 @@ const char *sedd_strerror(int code) {
     case SEDD_EINVAL: return "invalid argument";
     case SEDD_ENOMEM: return "scratch allocation failed";
     case SEDD_EDEVICE: return "HIP call failed (see sedd_last_device_error)";
+    case SEDD_ELIMIT: return "input exceeds a fixed limit of this entry point";
     default: return "unknown error code";
   }
 }
