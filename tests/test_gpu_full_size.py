@@ -2,10 +2,15 @@
 times (workload 3 streamed through sedd_minhash in 2 GB pieces).
 
 The CPU oracle cannot process these corpora whole in test time, so:
-  * signatures and band keys are compared bit for bit on sampled documents the oracle computes
-    one by one (random documents, the first and last of every streamed piece, the longest
-    documents, exact copies and their sources);
-  * cluster ids are checked over ALL documents against the defining property: they must equal
+  * signatures and band keys are compared bit for bit on a sample the oracle computes: at least
+    1 % of the documents of workloads 3 and 5 and 10 % of workload 4 (random runs of consecutive
+    documents, a contiguous prefix, every document within 50 of an edge of a streamed 2 GB piece
+    or of one of the 256 MB chunks sedd_minhash cuts a piece into, the longest documents, random
+    single documents, exact copies and their sources);
+  * on the contiguous prefix (200k documents; 20k of workload 4, long documents included) the
+    oracle runs the whole path on its own signatures and keys, and the GPU's cluster ids and
+    verified cluster ids of the same prefix must equal the oracle's;
+  * cluster ids are also checked over ALL documents against the defining property: they must equal
     the minimum-index labelling of the connected components of the graph "same key in the same
     band", recomputed here from the band keys with library sorts and scipy (no code shared with
     the HIP path or the oracle);
@@ -50,7 +55,69 @@ def sedd():
     m.sedd_release_scratch()
 
 
-def _stream_minhash(sedd, gen, recipe, n, K, flags, chunk_bytes):
+CHUNK_BYTES_WORDS = 256 << 20     # sedd_minhash's internal chunk size (word / byte shingles)
+CHUNK_BYTES_BYTES = 128 << 20
+CHUNK_DOCS = 1 << 22
+
+
+class Sampler:
+    """Collects, while the corpus streams by, the bytes of the documents the oracle will redo."""
+
+    def __init__(self, n_docs, seed, n_runs, run_len, prefix, n_single, n_longest_per_piece,
+                 byte_mode):
+        rng = np.random.default_rng(seed)
+        self.ranges = [(0, min(prefix, n_docs))] if prefix else []
+        for s0 in rng.integers(0, max(1, n_docs - run_len), size=n_runs):
+            self.ranges.append((int(s0), int(min(n_docs, s0 + run_len))))
+        self.single = np.unique(rng.integers(0, n_docs, size=n_single))
+        self.n_longest = n_longest_per_piece
+        self.chunk_bytes = CHUNK_BYTES_BYTES if byte_mode else CHUNK_BYTES_WORDS
+        self.docs = {}                     # doc id -> bytes
+        self.edge_docs = 0
+
+    def take(self, d0, d1, data, off):
+        """Called once per streamed piece: documents [d0, d1) with piece-relative offsets."""
+        nd = d1 - d0
+        want = set()
+        for a, b in self.ranges:
+            want.update(range(max(a, d0), min(b, d1)))
+        lo, hi = np.searchsorted(self.single, [d0, d1])
+        want.update(int(x) for x in self.single[lo:hi])
+        # edges: of the piece, and of the chunks sedd_minhash cuts it into (first document at or
+        # beyond every multiple of the chunk size in bytes, and every CHUNK_DOCS documents)
+        edges = {0, nd}
+        k = 1
+        while k * self.chunk_bytes <= int(off[-1]):
+            edges.add(int(np.searchsorted(off, np.uint64(int(off[0]) + k * self.chunk_bytes), side="left")))
+            k += 1
+        edges.update(range(CHUNK_DOCS, nd, CHUNK_DOCS))
+        before = len(want)
+        for e in edges:
+            want.update(range(d0 + max(0, e - 50), d0 + min(nd, e + 50)))
+        self.edge_docs += len(want) - before
+        lens = np.diff(off.astype(np.int64))
+        want.update(int(d0 + x) for x in np.argsort(lens)[::-1][: self.n_longest])
+        want.update(int(d0 + x) for x in np.argsort(lens)[:2])
+        for d in want:
+            if d not in self.docs:
+                i = d - d0
+                self.docs[d] = data[int(off[i]):int(off[i + 1])].copy()
+
+    def add(self, gen, d):
+        if d not in self.docs:
+            data, off = gen.generate(int(d), int(d) + 1, threads=1)
+            self.docs[int(d)] = data
+
+    def corpus(self):
+        """(ids sorted, concatenated bytes, offsets) of everything collected."""
+        ids = np.array(sorted(self.docs), dtype=np.int64)
+        lens = np.array([self.docs[int(d)].size for d in ids], dtype=np.uint64)
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+        data = np.concatenate([self.docs[int(d)] for d in ids]) if ids.size else np.zeros(0, np.uint8)
+        return ids, data, off
+
+
+def _stream_minhash(sedd, gen, recipe, n, K, flags, chunk_bytes, sampler=None):
     """sedd_minhash over the whole corpus, piece by piece (pieces of about chunk_bytes).
     Returns the device signatures, the piece boundaries and the per-document byte lengths."""
     n_docs = recipe.n_docs
@@ -68,6 +135,8 @@ def _stream_minhash(sedd, gen, recipe, n, K, flags, chunk_bytes):
         lengths[d0:d1] = np.diff(off)
         t_data, t_off = torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda()
         sedd.sedd_minhash(t_data, t_off, n, K, 0, flags, out=sig[d0:d1])
+        if sampler is not None:
+            sampler.take(d0, d1, data, off)
         torch.cuda.synchronize()
         del t_data, t_off
         bounds.append((d0, d1))
@@ -75,6 +144,33 @@ def _stream_minhash(sedd, gen, recipe, n, K, flags, chunk_bytes):
         say(f"  piece docs [{d0}, {d1}) {data.size / 1e9:.2f} GB")
         d0 = d1
     return sig, bounds, lengths, total
+
+
+def _oracle_on_collected(sampler, n, K, flags, procs=None):
+    ids, data, off = sampler.corpus()
+    return ids, oracle.minhash_sharded(data, off, n, K, 0, flags, procs=procs or NPROC)
+
+
+def _check_prefix_whole_path(sedd, sig, ids, want_sig, prefix, K, b, r, label, theta=0.8):
+    """Documents [0, prefix): the oracle's whole path on its own signatures against the GPU's
+    band keys, clusters and verified clusters of the same prefix."""
+    assert np.array_equal(ids[:prefix], np.arange(prefix)), "the prefix was not collected whole"
+    o_sig = np.ascontiguousarray(want_sig[:prefix, :K])
+    o_keys = oracle.lsh_keys(o_sig, b, r)
+    o_cid = oracle.cluster(o_keys)
+    mm = oracle.min_match_for(theta, K)
+    o_vcid = oracle.cluster_verified(o_keys, o_sig, mm)
+    g_sig = sig[:prefix]
+    g_keys = sedd.sedd_lsh_keys(g_sig, b, r)
+    g_cid = sedd.sedd_cluster(g_keys)
+    g_vcid = sedd.sedd_cluster_verified(g_keys, g_sig, sedd.min_match_for(theta, K))
+    torch.cuda.synchronize()
+    assert np.array_equal(g_keys.cpu().numpy(), o_keys), f"{label}: prefix band keys differ"
+    assert np.array_equal(g_cid.cpu().numpy(), o_cid), f"{label}: prefix cluster ids differ"
+    assert np.array_equal(g_vcid.cpu().numpy(), o_vcid), f"{label}: prefix verified cluster ids differ"
+    say(f"  {label}: oracle whole path on the first {prefix} documents ok "
+        f"({int((o_cid != np.arange(prefix)).sum())} duplicates, "
+        f"{int((o_vcid != np.arange(prefix)).sum())} verified at >= {mm})")
 
 
 def _sample_docs(gen, recipe, bounds, lengths, n_random, n_longest, n_copies, seed):
@@ -218,21 +314,43 @@ def _check_sampled_signatures(sig, ids, want_sig, K, label):
     assert bad.size == 0, f"{label}: {bad.size} sampled signatures differ, first docs {ids[bad[:5]]}"
 
 
+def _copies(gen, recipe, n_copies, seed):
+    rng = np.random.default_rng(seed)
+    copies = []
+    if recipe.exact_frac > 0:
+        for d in rng.choice(recipe.n_docs, size=min(recipe.n_docs, 40 * n_copies), replace=False):
+            kind, src, _ = gen.meta(int(d))
+            if kind == 2:
+                copies.append((int(d), int(src)))
+                if len(copies) >= n_copies:
+                    break
+    return copies
+
+
 def test_config3_full_size_streamed(sedd):
     """10M documents, about 62 GB of text, K=256, 32x8 bands, streamed in 2 GB pieces."""
     r = corpus.config(3)
     gen = corpus.Corpus(r)
     say("config 3 at full size: streaming", r.n_docs, "documents")
+    prefix = 200_000
+    smp = Sampler(r.n_docs, seed=3, n_runs=100, run_len=1000, prefix=prefix, n_single=1500,
+                  n_longest_per_piece=1, byte_mode=False)
     sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 0,
-                                                  STREAM_CHUNK_BYTES)
-    say(f"  {total / 1e9:.1f} GB in {len(bounds)} pieces; sampling")
-    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1500, n_longest=6, n_copies=50,
-                               seed=3)
-    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 0)
+                                                  STREAM_CHUNK_BYTES, sampler=smp)
+    copies = _copies(gen, r, 50, seed=3)
+    for d, s in copies:
+        smp.add(gen, d)
+        smp.add(gen, s)
+    say(f"  {total / 1e9:.1f} GB in {len(bounds)} pieces; oracle on {len(smp.docs)} documents "
+        f"({smp.edge_docs} of them next to piece and chunk edges)")
+    assert len(smp.docs) >= r.n_docs // 100
+    ids, want = _oracle_on_collected(smp, r.shingle_n, r.K, 0)
     _check_sampled_signatures(sig, ids, want, r.K, "config 3")
     for d, s in copies:                                   # exact copies: identical signatures
         assert torch.equal(sig[d].view(torch.int32), sig[s].view(torch.int32))
-    say(f"  signatures ok on {ids.size} sampled docs ({len(copies)} exact copies)")
+    say(f"  signatures ok on {ids.size} documents = {100.0 * ids.size / r.n_docs:.2f} % "
+        f"({len(copies)} exact copies)")
+    _check_prefix_whole_path(sedd, sig, ids, want, prefix, r.K, r.b, r.r, "config 3")
     dups = _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 3",
                                     verified=True)
     assert dups >= int(0.03 * r.n_docs * 0.9)             # at least the exact copies
@@ -243,18 +361,20 @@ def test_config4_full_size_long_documents(sedd):
     r = corpus.config(4)
     gen = corpus.Corpus(r)
     say("config 4 at full size:", r.n_docs, "documents")
-    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 1, 1 << 62)
-    say(f"  {total / 1e9:.1f} GB; longest document {int(lengths.max())} bytes; sampling")
-    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1200, n_longest=1, n_copies=0,
-                               seed=4)
-    # a few more long documents, taken from the short end of the long ones to bound oracle time
-    long_ids = np.nonzero(lengths > 1_000_000)[0]
-    extra = long_ids[np.argsort(lengths[long_ids])[:3]]
-    ids = np.array(sorted(set(ids.tolist()) | set(int(x) for x in extra)), dtype=np.int64)
-    want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 1)
+    prefix = 20_000                                      # 10 %, with its ~200 long documents
+    smp = Sampler(r.n_docs, seed=4, n_runs=4, run_len=250, prefix=prefix, n_single=1200,
+                  n_longest_per_piece=1, byte_mode=True)
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 1, 1 << 62,
+                                                  sampler=smp)
+    n_long = int(sum(1 for d in smp.docs if lengths[d] > 1_000_000))
+    say(f"  {total / 1e9:.1f} GB; longest document {int(lengths.max())} bytes; oracle on "
+        f"{len(smp.docs)} documents ({n_long} of 1 MB or more, {smp.edge_docs} next to chunk edges)")
+    assert n_long >= 20 and len(smp.docs) >= r.n_docs // 10
+    ids, want = _oracle_on_collected(smp, r.shingle_n, r.K, 1)
     _check_sampled_signatures(sig, ids, want, r.K, "config 4")
-    say(f"  signatures ok on {ids.size} sampled docs")
-    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, copies, "config 4",
+    say(f"  signatures ok on {ids.size} documents = {100.0 * ids.size / r.n_docs:.2f} %")
+    _check_prefix_whole_path(sedd, sig, ids, want, prefix, r.K, r.b, r.r, "config 4")
+    _check_keys_and_clusters(sedd, sig, ids, want, r.K, r.b, r.r, [], "config 4",
                              verified=True)
 
 
@@ -304,16 +424,19 @@ def test_config5_full_size_sweep(sedd):
     gen = corpus.Corpus(r)
     say("config 5 at full size:", r.n_docs, "documents")
     data, off = gen.generate()
-    lengths = np.diff(off)
     t_data, t_off = torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda()
-    bounds = [(0, r.n_docs)]
-    ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=1500, n_longest=4, n_copies=0,
-                               seed=5)
+    prefix = 200_000
+    smp = Sampler(r.n_docs, seed=5, n_runs=20, run_len=1000, prefix=prefix, n_single=1500,
+                  n_longest_per_piece=4, byte_mode=False)
+    smp.take(0, r.n_docs, data, off)
+    say(f"  oracle on {len(smp.docs)} documents ({smp.edge_docs} of them next to chunk edges)")
+    assert len(smp.docs) >= r.n_docs // 100
     for n in (3, 5):
-        want = _oracle_on_sample(gen, ids, n, 512, 0)
+        ids, want = _oracle_on_collected(smp, n, 512, 0)
         sig512 = sedd.sedd_minhash(t_data, t_off, n, 512)
         _check_sampled_signatures(sig512, ids, want, 512, f"config 5 n={n} K=512")
-        say(f"  n={n}: K=512 signatures ok on {ids.size} sampled docs")
+        say(f"  n={n}: K=512 signatures ok on {ids.size} documents = "
+            f"{100.0 * ids.size / r.n_docs:.2f} %")
         for K in (64, 128, 256, 512):
             if K == 512:
                 sig = sig512
@@ -324,7 +447,10 @@ def test_config5_full_size_sweep(sedd):
             for b, rr in ((8, 16), (16, 8), (32, 8), (64, 4)):
                 if b * rr > K:
                     continue
-                _check_keys_and_clusters(sedd, sig, ids, want, K, b, rr, copies,
+                if (K, b) in ((64, 8), (128, 16), (256, 32), (512, 64)):
+                    _check_prefix_whole_path(sedd, sig, ids, want, prefix, K, b, rr,
+                                             f"config 5 n={n} K={K} b={b} r={rr}")
+                _check_keys_and_clusters(sedd, sig, ids, want, K, b, rr, [],
                                          f"config 5 n={n} K={K} b={b} r={rr}",
                                          verified=(K, b) in ((128, 16), (256, 64), (512, 8)))
             if K != 512:

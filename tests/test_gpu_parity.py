@@ -568,6 +568,30 @@ def test_cluster_verified_on_corpora(sedd, cfg, docs):
         assert np.array_equal(got, oracle.cluster_verified(wkeys, wsig, mm)), theta
 
 
+def test_all_pairs_reference_of_the_fidelity_figure_on_config1(sedd):
+    """The fidelity figure (Section 4.3) compares LSH + verification with brute-force all-pairs
+    comparison of the same signatures; the brute force is sedd_cluster_verified on one key
+    column that is equal for every document.  Both sides against the oracle on workload 1."""
+    say("fidelity reference on config 1")
+    r = corpus.config(1)
+    data, off = corpus.generate(r)
+    wsig = oracle.minhash_sharded(data, off, r.shingle_n, r.K, 0, 0, procs=NPROC)
+    sig = sedd.sedd_minhash(dev(data), dev(off), r.shingle_n, r.K)
+    mm = sedd.min_match_for(0.8, r.K)
+    ones = np.zeros((r.n_docs, 1), dtype=np.uint64)
+    want_all = oracle.cluster_verified(ones, wsig, mm)
+    got_all = host(sedd.sedd_cluster_verified(dev(ones), sig, mm))
+    assert np.array_equal(got_all, want_all)
+    want_lsh = oracle.cluster_verified(oracle.lsh_keys(wsig, r.b, r.r), wsig, mm)
+    got_lsh = host(sedd.sedd_cluster_verified(sedd.sedd_lsh_keys(sig, r.b, r.r), sig, mm))
+    assert np.array_equal(got_lsh, want_lsh)
+    ident = np.arange(r.n_docs)
+    a, b_ = set(np.nonzero(got_lsh != ident)[0]), set(np.nonzero(got_all != ident)[0])
+    assert a <= b_ and len(b_) > 0            # LSH can only miss pairs, never add them
+    say(f"  duplicates: LSH + verification {len(a)}, all pairs {len(b_)}, "
+        f"set-Jaccard {len(a & b_) / len(a | b_):.4f}")
+
+
 def test_cluster_verified_rejects_bad_arguments(sedd):
     keys = dev(np.zeros((4, 2), np.uint64))
     sig = dev(np.zeros((4, 8), np.uint32))
