@@ -93,6 +93,15 @@ int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_d
                  void *stream);
 
 /*
+ * sedd_minhash with the size of the text stated: the same call, but doc_offsets[n_docs] > n_bytes
+ * (offsets that point past the caller's buffer) is SEDD_EINVAL, found before any kernel reads
+ * the text.  Bindings that know the buffer's size should call this one.
+ */
+int sedd_minhash_bounded(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
+                         uint64_t n_docs, int32_t shingle_n, int32_t K, uint64_t seed,
+                         uint32_t flags, uint32_t *sig, void *stream);
+
+/*
  * LSH band keys (Section 2.3: the signature is cut into b bands of r rows and each band
  * is hashed to a bucket).  key[d*b + j] = (sum_{i<r} sig[d*K + j*r + i] * Q^i) mod p with
  * Q = 1687994237021934823: Eq. 1's polynomial over the band's values.  Equal bands give

@@ -103,6 +103,13 @@ int sedd_debug_last_regroup(uint32_t *out);
  */
 int sedd_debug_set_chunk_bytes(uint64_t bytes);
 
+/*
+ * Bytes of text per wavefront of the streaming min-hash kernel (word shingles, 61-bit modulus):
+ * a multiple of 1024, at most 2^24; 0 restores the default.  Results never depend on it; tests
+ * use it to move the places where documents are split between wavefronts.
+ */
+int sedd_debug_set_piece_bytes(uint32_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,10 @@ def lib():
         u64, i32, u32, vp = C.c_uint64, C.c_int32, C.c_uint32, C.c_void_p
         L.sedd_minhash.restype = C.c_int
         L.sedd_minhash.argtypes = [vp, vp, u64, i32, i32, u64, u32, vp, vp]
+        L.sedd_minhash_bounded.restype = C.c_int
+        L.sedd_minhash_bounded.argtypes = [vp, u64, vp, u64, i32, i32, u64, u32, vp, vp]
+        L.sedd_debug_set_piece_bytes.restype = C.c_int
+        L.sedd_debug_set_piece_bytes.argtypes = [u32]
         L.sedd_lsh_keys.restype = C.c_int
         L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
         L.sedd_cluster.restype = C.c_int
@@ -160,8 +164,9 @@ def sedd_minhash(text, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags
         out = _dev(out, torch.uint32, "out")
         if out.numel() != n_docs * K:
             raise ValueError("out has the wrong size")
-    _check(lib().sedd_minhash(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, K, seed, flags,
-                              _ptr(out), _stream(stream)), "sedd_minhash")
+    # the bounded entry point: offsets that point past `text` are rejected, not followed
+    _check(lib().sedd_minhash_bounded(_ptr(text), text.numel(), _ptr(doc_offsets), n_docs, shingle_n,
+                                      K, seed, flags, _ptr(out), _stream(stream)), "sedd_minhash")
     return out
 
 
@@ -347,6 +352,10 @@ def debug_sort_bands(keys, stream=None):
 
 def debug_set_chunk_bytes(n: int):
     _check(lib().sedd_debug_set_chunk_bytes(n), "sedd_debug_set_chunk_bytes")
+
+
+def debug_set_piece_bytes(n: int):
+    _check(lib().sedd_debug_set_piece_bytes(n), "sedd_debug_set_piece_bytes")
 
 
 def debug_minhash_from_x(x, shingle_offsets, K: int, seed: int = 0, stream=None, out=None,

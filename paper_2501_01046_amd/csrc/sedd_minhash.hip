@@ -933,6 +933,444 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   }
 }
 
+// ---- the streaming kernel (word shingles, 61-bit modulus) ----------------------------------------
+//
+// The whole of sedd_minhash in one launch, for the default mode: the text is read from HBM once,
+// nothing but the signatures is written, and there is no work list.  The text (a frame that
+// starts on a 16-byte boundary at or below document 0) is cut into pieces of `piece` bytes; one
+// wavefront owns the tokens that START inside its piece, in document order, and with them the
+// shingles that start at those tokens.  Per document that reaches into the piece it walks
+// 1 KiB tiles of the document's bytes:
+//   pass 1 (lane = 16 bytes)   token-byte bitmap, token starts and their ranks, as in k_emit_words;
+//   rounds of 64 tokens        lane = token: Eq. 1 of the token from the LDS copy of the tile, the
+//                              record (hash of "token 0x20", length) goes into a ring in LDS;
+//                              lane = shingle: x(s) by Horner over its n ring records, into LDS;
+//                              lane = hash function: the K multiply-adds and the running minimum
+//                              over the round's shingles, exactly as in k_minhash.
+// The minima stay in registers until the document ends.  A document that lies inside the piece
+// is stored; one that crosses a piece boundary is merged with atomicMin by the pieces it touches
+// (the signatures start out as 0xFFFFFFFF).  A piece reads on past its end, inside the document
+// that crosses it, until the shingles of its own tokens are complete (n - 1 more tokens).
+// The one-shingle rule for documents of fewer than n tokens belongs to the piece that owns the
+// document's first token; a piece that meets the end of such a document and did not see its
+// beginning looks back for an earlier token byte before it decides.
+
+constexpr uint32_t RING = 128;  // ring of token records: the n - 1 before a round plus its 64
+static_assert(RING >= 64 + SEDD_MAX_SHINGLE_N - 1 && (RING & (RING - 1)) == 0, "ring too small");
+
+struct StreamArgs {
+  const uint8_t *frame;   // 16-byte aligned address at or below the first byte of document 0
+  const uint64_t *off;    // doc_offsets
+  uint64_t n_docs;
+  uint64_t shift;         // off[d] + shift = frame position of the first byte of document d
+  uint64_t frame_end;     // frame position of the end of the last document
+  uint32_t piece;         // bytes per wavefront, a multiple of TB
+  uint32_t n;             // shingle length
+  const uint64_t *qpow;   // 257^i, i < QPOW_N
+  const PowSplit *ptab;   // Horner multipliers per token length
+};
+
+// what the kernel does with a shingle hash: evaluate the K functions (production), count, or
+// write it out in order (the two passes of the stage-level debug entry)
+enum { SM_HASH = 0, SM_COUNT = 1, SM_WRITE = 2 };
+struct StreamDebug {
+  uint32_t *piece_count;  // SM_COUNT: shingles of each piece (out); SM_WRITE: their prefix sums (in)
+  uint32_t *doc_piece;    // SM_COUNT: the piece that holds the first byte of a non-empty document
+  uint32_t *doc_local;    // SM_COUNT: shingles that piece found before the document
+  uint64_t *x;            // SM_WRITE: shingle hashes in document order
+  uint64_t x_cap;         //           entries of x
+  uint64_t x_base;        //           index of this call's first shingle
+};
+
+// Eq. 1 of a token of flen <= FAST_TOKEN_MAX bytes at byte `pos` of the LDS copy of a tile
+// (flen = 0 for an idle lane), lazily reduced: Horner over 3-byte digits, last digit first.
+// Must be called by the whole wavefront.
+__device__ __forceinline__ uint64_t lds_token_hash(const uint32_t *sm_text, uint32_t pos,
+                                                   uint32_t flen) {
+  uint64_t acc;
+  if (!__any(flen > 8)) {
+    // every token of this round has at most 8 bytes: one 12-byte read, three digits
+    const uint32_t wd = pos >> 2;
+    const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2];
+    const uint64_t keep = ~0ull >> ((64u - 8u * flen) & 63u);  // flen >= 1 where it matters
+    const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, pos & 3u) & (uint32_t)keep;
+    const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, pos & 3u) & (uint32_t)(keep >> 32);
+    const uint32_t d0 = a0 & 0xFFFFFFu;
+    const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
+    const uint32_t d2 = a1 >> 16;
+    const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
+    const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
+    const uint32_t D2 = d2 + (d2 >> 8);
+    acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
+    acc = horner3_lazy(acc, D0);
+  } else {
+    acc = 0;
+    const uint32_t nd = (flen + 2) / 3;
+    uint32_t maxnd = nd;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
+    maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
+    for (uint32_t k = maxnd; k-- > 0;) {
+      const int rem = (int)flen - (int)(3 * k);  // bytes of the token from digit k on
+      const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
+      const uint32_t msk = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
+      const uint32_t o = pos + 3 * k;
+      const uint32_t lo = sm_text[o >> 2], hi = sm_text[(o >> 2) + 1];
+      const uint32_t dg = __builtin_amdgcn_alignbyte(hi, lo, o & 3u) & msk;
+      // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
+      acc = horner3_lazy(acc, dg + ((dg >> 8) & 0xFFu) + 513u * (dg >> 16));
+    }
+  }
+  return acc;
+}
+
+// Eq. 1 of the token that starts at p, byte by byte: up to max_len bytes or the first whitespace
+__device__ __noinline__ WalkedToken walk_token_far(const uint8_t *__restrict__ p, uint64_t max_len) {
+  uint64_t w = 0, pw = 1;
+  uint64_t l = 0;
+  for (; l < max_len; l++) {
+    const uint32_t c = p[l];
+    if (is_ws(c)) break;
+    w = addmod(w, mulmod(pw, (uint64_t)c));
+    pw = mul257(pw);
+  }
+  WalkedToken r;
+  r.w = w;
+  r.len = (uint32_t)l;
+  return r;
+}
+
+// x of the shingle made of the ring records first .. first + PER - 1 (ring indices are taken
+// modulo RING); valid if every token is shorter than LONG_TOKEN bytes, *long_tok says if not
+template <int PER>
+__device__ __forceinline__ uint64_t ring_x_unrolled(const uint64_t *ring_v, const uint32_t *ring_len,
+                                                    const PowSplit *__restrict__ ptab, uint32_t first,
+                                                    const HotConsts &hc, bool *long_tok) {
+  uint32_t len[PER];
+  uint64_t V[PER];
+#pragma unroll
+  for (int m = 0; m < PER; m++) {
+    len[m] = ring_len[(first + m) & (RING - 1)];
+    V[m] = ring_v[(first + m) & (RING - 1)];
+  }
+  bool lt = false;
+#pragma unroll
+  for (int m = 0; m < PER; m++) {
+    lt |= len[m] >= LONG_TOKEN;
+    len[m] = min(len[m], LONG_TOKEN);  // keeps the table index in range; the value is redone if long
+  }
+  *long_tok = lt;
+  uint4 e[PER];
+#pragma unroll
+  for (int m = 0; m < PER - 1; m++) e[m] = *reinterpret_cast<const uint4 *>(ptab + len[m]);
+  const uint64_t nsp = ptab[len[PER - 1]].nsp;
+  uint64_t acc = V[PER - 1] + nsp;  // bare last token, < 2^62
+  acc = (acc & P61) + (acc >> 61);
+#pragma unroll
+  for (int m = PER - 2; m >= 0; m--) acc = horner_step_lazy(acc, e[m].x, e[m].y, e[m].z, V[m], hc);
+  return fold61(acc);
+}
+
+// the same for any number of tokens and any token lengths
+__device__ __noinline__ uint64_t ring_x_general(const uint64_t *ring_v, const uint32_t *ring_len,
+                                                const uint64_t *__restrict__ qpow, uint32_t first,
+                                                uint32_t per) {
+  const uint32_t last = first + per - 1;
+  const uint64_t pw = qpow_global(qpow, ring_len[last & (RING - 1)]);
+  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
+  const uint64_t v_last = ring_v[last & (RING - 1)];
+  uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;
+  for (uint32_t m = last; m-- > first;) {
+    const uint64_t Pm = qpow_global(qpow, ring_len[m & (RING - 1)] + 1);
+    acc = addmod(mulmod(Pm, acc), ring_v[m & (RING - 1)]);
+  }
+  return acc;
+}
+
+template <int F, int P, int SM>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
+k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
+                 const CoefSplit *__restrict__ coef_split, int K, uint32_t *__restrict__ sig,
+                 HotConsts hc, unsigned long long *__restrict__ slow_tiles, StreamDebug dbg) {
+  __shared__ uint32_t sm_text[SM_TEXT_WORDS];
+  __shared__ uint32_t sm_bits[TB / 32 + 4];
+  __shared__ uint16_t sm_pos[MAX_TILE_TOKENS];
+  __shared__ uint64_t ring_v[RING];
+  __shared__ uint32_t ring_len[RING];
+  __shared__ XLimbs sx[64];
+  const uint32_t lane = threadIdx.x;
+  const uint64_t P0 = (uint64_t)blockIdx.x * sa.piece;  // frame position of the piece
+  const int64_t PE = (int64_t)sa.piece;                 // its end, relative to P0 like all below
+  const uint8_t *pbase = sa.frame + P0;
+  const uint32_t n = sa.n;
+  const PowSplit *__restrict__ ptab = sa.ptab;
+
+  // the lane's hash functions, as in k_minhash
+  constexpr int LW = 64 / P;
+  const uint32_t grp = lane / LW;
+  const int kbase = blockIdx.y * (LW * F) + (lane % LW);
+  uint64_t cb[F];
+  uint32_t a0[F], a12[F], m[F];
+#pragma unroll
+  for (int j = 0; j < F; j++) {
+    a0[j] = a12[j] = 0;
+    cb[j] = 0;
+    m[j] = 0xFFFFFFFFu;
+    if (SM == SM_HASH) {
+      const int k = kbase + LW * j;
+      const CoefSplit c = coef_split[k < K ? k : 0];  // lanes past K compute function 0, store nothing
+      a0[j] = c.a0;
+      a12[j] = c.a12;
+      cb[j] = c.b;
+    }
+  }
+
+  // First document that reaches into the piece: the smallest d with off[d+1] + shift > P0, found
+  // 64 probes at a time (the last piece ends at or before frame_end, so there is one).
+  uint64_t d;
+  {
+    uint64_t lo = 0, hi = sa.n_docs;  // the answer lies in [lo, hi)
+    while (hi - lo > 1) {
+      const uint64_t span = hi - lo, step = (span + 63) / 64;
+      const uint64_t last = lo + min((uint64_t)lane * step + step - 1, span - 1);
+      const bool reaches = sa.off[last + 1] + sa.shift > P0;
+      const uint64_t votes = __ballot(reaches);  // monotone in the lane; the last lane votes yes
+      const uint32_t f = (uint32_t)__ffsll((unsigned long long)votes) - 1u;
+      const uint64_t nlo = lo + (uint64_t)f * step;
+      hi = min(nlo + step, hi);
+      lo = nlo;
+    }
+    d = lo;
+  }
+  uint32_t emitted = 0;  // SM_COUNT / SM_WRITE: shingles this piece has produced so far
+  const uint32_t out_base = SM == SM_WRITE ? dbg.piece_count[blockIdx.x] : 0u;
+
+  for (; d < sa.n_docs; d++) {
+    const int64_t vs = (int64_t)(sa.off[d] + sa.shift - P0);
+    const int64_t ve = (int64_t)(sa.off[d + 1] + sa.shift - P0);
+    if (vs >= PE) break;  // starts beyond the piece: the next wavefront's
+    if (ve <= vs) continue;
+    if (SM == SM_COUNT && vs >= 0 && lane == 0) {
+      dbg.doc_piece[d] = blockIdx.x;
+      dbg.doc_local[d] = emitted;
+    }
+    uint32_t T = 0;        // tokens of the document seen from this piece
+    uint32_t n_owned = 0;  // those that start inside the piece (a prefix of the T)
+    uint32_t S_next = 0;   // shingles handled so far: those starting at tokens 0 .. S_next - 1
+    uint32_t nsh = 0;      // shingles evaluated for this document
+    int64_t cur = vs > 0 ? (vs & ~int64_t(15)) : 0;  // tile start, 16-byte aligned
+    bool done = false;
+
+    // evaluates the cnt shingle hashes in sx[0 .. cnt)
+    auto consume = [&](uint32_t cnt) {
+      if (SM == SM_COUNT) {
+        emitted += cnt;
+      } else if (SM == SM_WRITE) {
+        if (lane < cnt) {
+          const uint64_t at = dbg.x_base + out_base + emitted + lane;
+          const XLimbs xv = sx[lane];
+          if (at < dbg.x_cap) dbg.x[at] = ((uint64_t)xv.x1 << 31) | xv.x0;
+        }
+        emitted += cnt;
+      } else {
+        uint32_t mr[F], amb = 0;
+#pragma unroll
+        for (int j = 0; j < F; j++) mr[j] = 0xFFFFFFFFu;
+        auto eval = [&](const XLimbs &xv) {
+#pragma unroll
+          for (int j = 0; j < F; j++) {
+            uint64_t N = (uint64_t)a0[j] * xv.x1_4;
+            N += (uint64_t)a12[j] * xv.x0_2;
+            uint64_t U = (uint64_t)a12[j] * xv.x1 + cb[j];
+            U += (uint64_t)a0[j] * xv.x0;
+            const uint64_t Sv = (uint64_t)(uint32_t)N * hc.two29 + U;
+            const uint64_t W = (uint64_t)(uint32_t)(Sv >> 32) * hc.eight;  // hi: S >> 61, lo: bits 32..60
+            const uint32_t h = (uint32_t)Sv + (uint32_t)(N >> 32) + (uint32_t)(W >> 32);
+            amb = max(amb, (uint32_t)W);
+            mr[j] = min(mr[j], h);
+          }
+        };
+        const XLimbs *sxg = sx + grp;  // this half-wave's first shingle
+        const uint32_t steps = cnt / P;
+#pragma unroll(F >= 4 ? 2 : 4)
+        for (uint32_t s = 0; s < steps; s++) eval(sxg[s * P]);
+        if (P == 2 && (cnt & 1)) eval(sx[cnt - 1]);  // both halves: a repeat cannot change a minimum
+        if (__any(amb >= 0xFFFFFFF0u)) {
+          // rare: some evaluation sat within reach of a carry across bit 61; redo the round exactly
+          if (lane == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
+#pragma unroll
+          for (int j = 0; j < F; j++) {
+            mr[j] = 0xFFFFFFFFu;
+            const uint64_t a = coef_a[kbase + LW * j < K ? kbase + LW * j : 0];
+            for (uint32_t s = grp; s < cnt; s += P) {
+              const XLimbs xv = sx[s];
+              const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
+              mr[j] = min(mr[j], (uint32_t)addmod(mulmod(a, x), cb[j]));
+            }
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < F; j++) m[j] = min(m[j], mr[j]);
+      }
+      nsh += cnt;
+    };
+
+    while (cur < ve && !done) {
+      // ---- pass 1: the tile [cur, cur + TB) of the document, lane = 16 bytes ----
+      const uint8_t *tp = pbase + cur;
+      const uint32_t vs_t = vs > cur ? (uint32_t)(vs - cur) : 0u;  // the document inside the tile:
+      const uint32_t ve_t = ve - cur > int64_t(1) << 30 ? (1u << 30) : (uint32_t)(ve - cur);  // [vs_t, ve_t)
+      const uint4 q_own = load_raw16(tp, lane * 16, vs_t, ve_t);
+      const uint4 q_la = load_raw16(tp, TB, vs_t, ve_t);  // wave-uniform
+      const uint32_t prev_byte = cur > vs ? (uint32_t)tp[-1] : 0x20u;
+      const Segment sg = make_segment(q_own, lane * 16, vs_t, ve_t);
+      const Segment la = make_segment(q_la, TB, vs_t, ve_t);
+      const uint32_t starts0 = token_starts(lane, prev_byte, sg.wm);
+      __syncthreads();  // the previous tile's readers are done
+      *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = q_own;
+      const uint32_t wm_up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sg.wm, 0x130, 0xF, 0xF, false);
+      if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
+      if (lane == 0) {
+        *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = q_la;
+        sm_bits[TB / 32] = la.wm;
+        sm_bits[TB / 32 + 1] = 0;
+        sm_bits[TB / 32 + 2] = 0;
+      }
+      const uint32_t scnt = __popc(starts0);
+      const uint32_t inc = wave_inclusive_scan(scnt);
+      const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+      {
+        uint32_t stb = starts0, j = inc - scnt;
+        while (stb) {
+          const uint32_t bit = __ffs(stb) - 1;
+          sm_pos[j++] = (uint16_t)(lane * 16 + bit);
+          stb &= stb - 1;
+        }
+      }
+      __syncthreads();
+      const bool doc_ends_in_view = TB + LOOK >= ve_t;
+
+      // ---- rounds of 64 tokens ----
+      for (uint32_t base = 0; base < tot; base += TB_LANES) {
+        const uint32_t j = base + lane;
+        const bool active = j < tot;
+        const uint32_t pos = active ? sm_pos[j] : 0u;
+        // 64 bitmap bits from the token's first byte on: its length is the run of ones
+        const uint32_t dw = pos >> 5, sh = pos & 31;
+        const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
+        const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
+        const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
+        const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
+        const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
+        // the run ends at a real non-token byte (or at the document's end) inside the LDS copy
+        const bool fast =
+            active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
+        const uint32_t flen = fast ? run : 0u;
+        uint64_t w = fold61(lds_token_hash(sm_text, pos, flen));
+        uint32_t len = flen;
+        if (active && !fast) {
+          const WalkedToken wt = walk_token_far(tp + pos, (uint64_t)(ve - cur - (int64_t)pos));
+          w = wt.w;
+          len = wt.len;
+        }
+        if (active) {
+          // V = w + 32 * 257^len: the token followed by the joining space
+          uint64_t v;
+          if (len < (uint32_t)QPOW_N) {
+            const uint64_t nsp = ptab[len].nsp;
+            v = w >= nsp ? w - nsp : w + (P61 - nsp);
+          } else {
+            const uint64_t pw = powmod(257, len);
+            const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
+            v = addmod(w, sp == P61 ? 0 : sp);
+          }
+          const uint32_t ri = (T + lane) & (RING - 1);
+          ring_v[ri] = v;
+          ring_len[ri] = len;
+        }
+        const uint32_t in_round = min((uint32_t)TB_LANES, tot - base);
+        n_owned += (uint32_t)__popcll(__ballot(active && cur + (int64_t)pos < PE));
+        T += in_round;
+        __syncthreads();  // the ring is written
+        // shingles whose last token has arrived and whose first token is this piece's
+        const uint32_t S_hi = T >= n ? T - n + 1 : 0u;
+        const uint32_t S_lim = min(S_hi, n_owned);
+        if (S_lim > S_next) {
+          const uint32_t cnt = S_lim - S_next;  // at most 64
+          if (lane < cnt) {
+            const uint32_t first = S_next + lane;
+            bool long_tok = false;
+            uint64_t x;
+            if (n == 5) x = ring_x_unrolled<5>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            else if (n == 3) x = ring_x_unrolled<3>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            else if (n == 4) x = ring_x_unrolled<4>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            else if (n == 2) x = ring_x_unrolled<2>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            else if (n == 1) x = ring_x_unrolled<1>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            else {
+              long_tok = true;
+              x = 0;
+            }
+            if (long_tok) x = ring_x_general(ring_v, ring_len, sa.qpow, first, n);
+            sx[lane] = x_limbs(x);
+          }
+          __syncthreads();
+          consume(cnt);
+          S_next = S_lim;
+        }
+      }
+      cur += TB;
+      // past the end of the piece every owned token is known: stop once their shingles are done
+      if (cur >= PE && S_next >= n_owned) done = true;
+    }
+
+    // A document of 1 .. n-1 tokens is one shingle of all of them, owned with its first token.
+    // Here: the end of the document was reached without a full shingle, and a token of this piece
+    // came first in what the piece saw.  It is the document's first token unless the document
+    // began before the piece and holds a token byte there.
+    if (!done && S_next == 0 && T >= 1 && T < n && n_owned >= 1) {
+      bool earlier = false;
+      if (vs < 0) {
+        for (int64_t q = -1; q >= vs && !earlier; q -= 64) {
+          const int64_t pq = q - (int64_t)lane;
+          const bool tok_byte = pq >= vs && !is_ws(pbase[pq]);
+          earlier = __any(tok_byte);
+        }
+      }
+      if (!earlier) {
+        if (lane == 0) sx[0] = x_limbs(ring_x_general(ring_v, ring_len, sa.qpow, 0u, T));
+        __syncthreads();
+        consume(1u);
+      }
+    }
+
+    if (SM == SM_HASH && nsh) {
+      if (P == 2) {
+#pragma unroll
+        for (int j = 0; j < F; j++) m[j] = min(m[j], (uint32_t)__shfl_xor(m[j], 32, 64));
+      }
+      uint32_t *out = sig + d * (uint64_t)K;
+      const bool whole = vs >= 0 && ve <= PE;  // no other piece sees this document
+#pragma unroll
+      for (int j = 0; j < F; j++) {
+        const int k = kbase + LW * j;
+        if (grp == 0 && k < K) {
+          if (whole) {
+            out[k] = m[j];
+          } else {
+            // values only ever decrease: a (possibly stale) read that is not above m[j] settles it
+            const uint32_t c = __hip_atomic_load(out + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (m[j] < c) atomicMin(out + k, m[j]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+    if (ve >= PE) break;  // the document runs to the end of the piece or beyond: nothing after it is ours
+  }
+  if (SM == SM_COUNT && lane == 0) dbg.piece_count[blockIdx.x] = emitted;
+}
+
 // ---- the hot kernel of the paper-prime mode ----------------------------------------------------
 //
 // Same tiling as k_minhash: one wavefront per shingle tile, phase A fills LDS with the tile's
@@ -1614,6 +2052,170 @@ __global__ void k_validate_offsets(const uint64_t *__restrict__ off, uint64_t n,
 
 __global__ void k_zero_u32(uint32_t *p) { *p = 0; }
 
+// ---- host driver of the streaming kernel ---------------------------------------------------------
+
+static uint32_t g_piece_bytes_override = 0;
+
+// first and last offset and the validity flag in one 32-byte record
+__global__ void k_stream_probe(const uint64_t *__restrict__ off, uint64_t n, uint64_t *__restrict__ out) {
+  out[0] = off[0];
+  out[1] = off[n];
+}
+
+// debug entry: shingle offsets per document from the counting pass.  A non-empty document's
+// count was recorded by the piece that holds its first byte; an empty document takes the offset
+// of the next non-empty one (or the total).
+__global__ void k_stream_soff(const uint64_t *__restrict__ off, uint64_t n_docs,
+                              const uint32_t *__restrict__ piece_base,
+                              const uint32_t *__restrict__ doc_piece,
+                              const uint32_t *__restrict__ doc_local, uint32_t n_pieces,
+                              uint64_t *__restrict__ soff) {
+  const uint64_t d = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (d > n_docs) return;
+  uint64_t e = d;
+  while (e < n_docs && off[e + 1] == off[e]) e++;
+  soff[d] = e < n_docs ? (uint64_t)piece_base[doc_piece[e]] + doc_local[e]
+                       : (uint64_t)piece_base[n_pieces];
+}
+
+// The default mode of sedd_minhash (word shingles, 61-bit modulus, affine family): validation,
+// coefficients, the signature fill and one launch of k_minhash_stream.  One host wait, for the
+// first and last offset and the validity flag.  With dbg_off the two debug passes run instead.
+static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
+                              uint64_t n_docs, int32_t n, int32_t K, uint64_t seed, uint32_t *sig,
+                              uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st) {
+  const bool debug = dbg_off != nullptr;
+  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
+  Carver cv;
+  const uint64_t o_probe = cv.take<uint64_t>(4);
+  const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
+  const uint64_t o_cs = cv.take<CoefSplit>(K);
+  const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
+  const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
+  const uint64_t fixed_bytes = cv.off;
+  uint8_t *A = nullptr;
+  int rc = scratch_ensure(fixed_bytes, &A);
+  if (rc) return rc;
+  void *pin = nullptr;
+  rc = pinned_ensure(64, &pin);
+  if (rc) return rc;
+  uint64_t *d_probe = (uint64_t *)(A + o_probe);
+  uint32_t *d_bad = (uint32_t *)(d_probe + 2);
+  hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(1), 0, st, d_bad);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, d_probe);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
+                     doc_offsets, n_docs, max_doc, d_bad);
+  SEDD_LAUNCH_CHECK();
+  SEDD_HIP(hipMemcpyAsync(pin, d_probe, 24, hipMemcpyDeviceToHost, st));
+  SEDD_HIP(hipStreamSynchronize(st));
+  const uint64_t off0 = ((const uint64_t *)pin)[0], offn = ((const uint64_t *)pin)[1];
+  if (((const uint32_t *)pin)[4] || offn < off0 || offn > n_bytes) return SEDD_EINVAL;
+  if (offn > off0 && !bytes) return SEDD_EINVAL;
+
+  // the frame: 16-byte aligned, at or below the first byte of document 0
+  const uintptr_t first_byte = (uintptr_t)bytes + off0;
+  const uint64_t lead = first_byte & 15;
+  StreamArgs sa;
+  sa.frame = (const uint8_t *)(first_byte - lead);
+  sa.off = doc_offsets;
+  sa.n_docs = n_docs;
+  sa.shift = lead - off0;  // wraps; off[d] + shift is the frame position
+  sa.frame_end = lead + (offn - off0);
+  sa.n = (uint32_t)n;
+  // piece size: enough pieces to fill the chip several times over, few enough that the work per
+  // piece outweighs its start-up (document search, coefficient loads, the tokens read past its end)
+  uint32_t piece = g_piece_bytes_override;
+  if (!piece) {
+    piece = (uint32_t)std::min<uint64_t>(8192, (sa.frame_end / 32768) & ~uint64_t(TB - 1));
+    if (piece < TB) piece = TB;
+  }
+  sa.piece = piece;
+  const uint64_t n_pieces = offn > off0 ? (sa.frame_end + piece - 1) / piece : 0;
+  if (n_pieces >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+
+  uint64_t o_pc = 0, o_dp = 0, o_dl = 0, o_tmp = 0;
+  if (debug) {
+    o_pc = cv.take<uint32_t>(n_pieces + 1);
+    o_dp = cv.take<uint32_t>(n_docs);
+    o_dl = cv.take<uint32_t>(n_docs);
+    o_tmp = cv.take<uint32_t>(scan_tmp_count(n_pieces + 1));
+    rc = scratch_ensure(cv.off, &A);  // may move the arena: nothing in it is live yet
+    if (rc) return rc;
+  }
+  uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
+  CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
+  uint64_t *qpow = (uint64_t *)(A + o_qpow);
+  PowSplit *ptab = (PowSplit *)(A + o_ptab);
+  sa.qpow = qpow;
+  sa.ptab = ptab;
+  hipLaunchKernelGGL(k_coeffs, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, (int)K,
+                     coef_a, coef_b, coef_s, qpow, ptab);
+  SEDD_LAUNCH_CHECK();
+  const HotConsts hc = {1u << 29, 8u, 1u};
+  StreamDebug dbg = {};
+
+  if (debug) {
+    if (n_pieces >= (uint64_t(1) << 31) || sa.frame_end >= (uint64_t(1) << 32)) return SEDD_EINVAL;
+    uint32_t *pc = (uint32_t *)(A + o_pc);
+    dbg.piece_count = pc;
+    dbg.doc_piece = (uint32_t *)(A + o_dp);
+    dbg.doc_local = (uint32_t *)(A + o_dl);
+    dbg.x = dbg_x;
+    dbg.x_cap = dbg_cap;
+    dbg.x_base = 0;
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, pc + n_pieces, (uint64_t)1, 0u);
+    SEDD_LAUNCH_CHECK();
+    if (n_pieces) {
+      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM_COUNT>), dim3((uint32_t)n_pieces), dim3(64), 0, st,
+                         sa, (const uint64_t *)nullptr, (const CoefSplit *)nullptr, 1,
+                         (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg);
+      SEDD_LAUNCH_CHECK();
+    }
+    rc = scan_exclusive_u32(pc, pc, n_pieces + 1, (uint32_t *)(A + o_tmp), st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_stream_soff, dim3((uint32_t)((n_docs + 1 + 255) / 256)), dim3(256), 0, st,
+                       doc_offsets, n_docs, pc, dbg.doc_piece, dbg.doc_local, (uint32_t)n_pieces,
+                       dbg_off);
+    SEDD_LAUNCH_CHECK();
+    if (dbg_cap && n_pieces) {
+      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM_WRITE>), dim3((uint32_t)n_pieces), dim3(64), 0, st,
+                         sa, (const uint64_t *)nullptr, (const CoefSplit *)nullptr, 1,
+                         (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg);
+      SEDD_LAUNCH_CHECK();
+    }
+    return SEDD_OK;
+  }
+
+  unsigned long long *stats = nullptr;
+  rc = stats_ensure(&stats);
+  if (rc) return rc;
+  {
+    const uint64_t nsig = n_docs * (uint64_t)K;
+    const uint32_t grid = (uint32_t)std::min<uint64_t>((nsig + 255) / 256, 65536);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid), dim3(256), 0, st, sig, nsig, 0xFFFFFFFFu);
+    SEDD_LAUNCH_CHECK();
+  }
+  if (!n_pieces) return SEDD_OK;
+  // functions per lane F and half-wave split P as in launch_minhash
+  const int P = K <= 128 ? 2 : 1;
+  const int F = K <= 32 ? 1 : (K <= 64 ? 2 : 4);
+  const int per_block = (64 / P) * F;
+  dim3 grid((uint32_t)n_pieces, (uint32_t)((K + per_block - 1) / per_block));
+  ProfScope prof(SEDD_PROF_MINHASH, st);
+#define SEDD_LAUNCH_STREAM(FF, HW)                                                               \
+  hipLaunchKernelGGL((k_minhash_stream<FF, HW, SM_HASH>), grid, dim3(64), 0, st, sa, coef_a, coef_s, \
+                     (int)K, sig, hc, stats + SEDD_STAT_SLOW_TILES, dbg)
+  if (P == 1) SEDD_LAUNCH_STREAM(4, 1);
+  else if (F == 1) SEDD_LAUNCH_STREAM(1, 2);
+  else if (F == 2) SEDD_LAUNCH_STREAM(2, 2);
+  else SEDD_LAUNCH_STREAM(4, 2);
+#undef SEDD_LAUNCH_STREAM
+  SEDD_LAUNCH_CHECK();
+  return SEDD_OK;
+}
+
 // ---- host driver ---------------------------------------------------------------------------
 
 struct Chunk {
@@ -1621,13 +2223,17 @@ struct Chunk {
   uint64_t o0, o1;  // their byte range
 };
 
-static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_docs,
-                       int32_t n, int32_t K, uint64_t seed, uint32_t flags, uint32_t *sig,
-                       uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st) {
+static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
+                       uint64_t n_docs, int32_t n, int32_t K, uint64_t seed, uint32_t flags,
+                       uint32_t *sig, uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off,
+                       hipStream_t st) {
   const bool debug = dbg_off != nullptr;
   const int byte_mode = (flags & SEDD_FLAG_BYTE_SHINGLES) ? 1 : 0;
   const bool paper = (flags & SEDD_FLAG_PAPER_PRIME) != 0;
   const bool rolling = (flags & SEDD_FLAG_ROLLING_FAMILY) != 0;
+  if (!byte_mode && !paper && !rolling)
+    return run_minhash_stream(bytes, n_bytes, doc_offsets, n_docs, n, K, seed, sig, dbg_x, dbg_cap,
+                              dbg_off, st);
 
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
@@ -1656,7 +2262,7 @@ static int run_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64
     SEDD_HIP(hipStreamSynchronize(st));
     h_probe[0] = ((uint64_t *)pin)[0];
     h_probe[1] = ((uint64_t *)pin)[1];
-    if (h_probe[1] < h_probe[0]) return SEDD_EINVAL;
+    if (h_probe[1] < h_probe[0] || h_probe[1] > n_bytes) return SEDD_EINVAL;
     if (h_probe[1] > h_probe[0] && !bytes) return SEDD_EINVAL;
     const uint64_t total = h_probe[1] - h_probe[0];
     const uint64_t n_byte = total / chunk_bytes + 1, n_cnt = (n_docs - 1) / chunk_docs;
@@ -1898,7 +2504,21 @@ int sedd_minhash(const uint8_t *bytes, const uint64_t *doc_offsets, uint64_t n_d
   if (n_docs == 0) return SEDD_OK;
   if (!doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
   if (!aligned_to(doc_offsets, 8) || !aligned_to(sig, 4)) return SEDD_EINVAL;
-  return run_minhash(bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
+  return run_minhash(bytes, ~uint64_t(0), doc_offsets, n_docs, shingle_n, K, seed, flags, sig,
+                     nullptr, 0, nullptr, (hipStream_t)stream);
+}
+
+int sedd_minhash_bounded(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
+                         uint64_t n_docs, int32_t shingle_n, int32_t K, uint64_t seed,
+                         uint32_t flags, uint32_t *sig, void *stream) {
+  if (shingle_n < 1 || shingle_n > SEDD_MAX_SHINGLE_N || K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
+  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME | SEDD_FLAG_ROLLING_FAMILY))
+    return SEDD_EINVAL;
+  if ((flags & SEDD_FLAG_PAPER_PRIME) && (flags & SEDD_FLAG_ROLLING_FAMILY)) return SEDD_EINVAL;
+  if (n_docs == 0) return SEDD_OK;
+  if (!doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  if (!aligned_to(doc_offsets, 8) || !aligned_to(sig, 4)) return SEDD_EINVAL;
+  return run_minhash(bytes, n_bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
                      nullptr, (hipStream_t)stream);
 }
 
@@ -1915,8 +2535,8 @@ int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,
     return SEDD_OK;
   }
   if (!doc_offsets) return SEDD_EINVAL;
-  return run_minhash(bytes, doc_offsets, n_docs, shingle_n, 1, 0, flags, nullptr, x, x_cap,
-                     shingle_offsets, (hipStream_t)stream);
+  return run_minhash(bytes, ~uint64_t(0), doc_offsets, n_docs, shingle_n, 1, 0, flags, nullptr, x,
+                     x_cap, shingle_offsets, (hipStream_t)stream);
 }
 
 int sedd_debug_coeffs(uint64_t seed, int32_t K, uint64_t *a, uint64_t *b, void *stream) {
@@ -2008,6 +2628,12 @@ int sedd_debug_minhash_from_x_pp(const uint64_t *x, const uint64_t *shingle_offs
 
 int sedd_debug_set_chunk_bytes(uint64_t bytes) {
   g_chunk_bytes_override = bytes;
+  return SEDD_OK;
+}
+
+int sedd_debug_set_piece_bytes(uint32_t bytes) {
+  if (bytes % TB != 0 || bytes > (1u << 24)) return SEDD_EINVAL;
+  g_piece_bytes_override = bytes;
   return SEDD_OK;
 }
 
