@@ -711,6 +711,128 @@ def test_fuzz_shingle_hashes_and_signatures(sedd, seed):
         assert bad.size == 0, (byte_mode, n, bad[:5])
 
 
+def _piece_edge_docs():
+    """Documents built to put every special case of the streaming kernel on a boundary between
+    two wavefronts' pieces of the text (pieces are multiples of 1 KiB): documents of fewer than n
+    tokens that cross one or several pieces (a giant first token, giant whitespace runs before,
+    between and after the tokens), tokens that straddle a boundary, a document whose last few
+    tokens spill into the next piece, documents that end exactly on a boundary, empty documents
+    on a boundary, whitespace-only documents longer than a piece."""
+    rng = np.random.default_rng(17)
+
+    def word(l):
+        return bytes(rng.integers(97, 123, size=int(l), dtype=np.uint8))
+    docs = []
+    docs.append(word(3000) + b" " + word(5) + b" " + word(7))              # 3 tokens, first is giant
+    docs.append(b" " * 2500 + word(4) + b" " * 3000 + word(6) + b"\n" * 1500)   # 2 tokens, far apart
+    docs.append(word(2) + b" " * 5000)                                      # 1 token then whitespace
+    docs.append(b" " * 5000 + word(3))                                      # whitespace then 1 token
+    docs.append(b" " * 7000)                                                # nothing, several pieces
+    docs.append(b"")
+    docs.append(word(1024))                                                 # exactly one tile, one token
+    docs.append(b"")
+    docs.append(b"")
+    docs.append(b" ".join(word(l) for l in rng.integers(1, 9, size=900)))   # ordinary, crosses pieces
+    docs.append(word(700) + b" " + word(700) + b" " + word(700) + b" " + word(700))  # 4 tokens < n = 5
+    docs.append(word(700) + b" " + word(700) + b" " + word(700) + b" " + word(700) + b" " + word(2))
+    docs.append(word(10) + b" " * 1013 + word(1) + b" " + word(2) + b" " + word(3) + b" " + word(4))
+    for total in (1024, 2048, 1023, 1025):                                  # end on / next to a boundary
+        body = b" ".join(word(l) for l in rng.integers(1, 9, size=400))
+        docs.append(body[:total])
+    docs.append(word(70_000))                                               # one token, dozens of pieces
+    docs.append(word(5) + b" " + word(70_000) + b" " + word(5))
+    return docs
+
+
+@pytest.mark.parametrize("piece", [1024, 2048, 5120, 16384, 1 << 20])
+def test_stream_kernel_piece_size_invariance(sedd, piece):
+    """Results never depend on how the text is cut between wavefronts: shingle hashes in order
+    and signatures against the oracle for pieces from one tile to more than the whole text,
+    with different amounts of text in front of the first document."""
+    say("stream piece", piece)
+    sedd.debug_set_piece_bytes(piece)
+    try:
+        for lead in (0, 9, 1019):
+            docs = _piece_edge_docs() + (_edge_corpus() if lead == 9 else []) + _fuzz_docs(piece + lead, 60)
+            data, off = _pack(docs, lead)
+            d_data, d_off = dev(data), dev(off)
+            for n in (1, 2, 5, 7, 64):
+                wx, woff = _oracle_x(docs, n, False)
+                x, soff = sedd.debug_shingle_hashes(d_data, d_off, n, 0)
+                assert np.array_equal(host(soff), woff), (lead, n)
+                assert np.array_equal(host(x), wx), (lead, n)
+            for n, K in ((5, 128), (3, 256), (1, 40), (9, 64), (64, 32)):
+                want = oracle.minhash(data, off, n, K, 3, 0)
+                got = host(sedd.sedd_minhash(d_data, d_off, n, K, 3, 0))
+                bad = np.nonzero((got != want).any(axis=1))[0]
+                assert bad.size == 0, (lead, n, K, bad[:5])
+    finally:
+        sedd.debug_set_piece_bytes(0)
+
+
+def _token_with_hash(x, rng):
+    """A whitespace-free byte string whose Eq. 1 value is x: random high digits, then the base-257
+    expansion of what is left, retried until every digit is a usable byte."""
+    P = (1 << 61) - 1
+    ws = {0x09, 0x0A, 0x0B, 0x0C, 0x0D, 0x20}
+    while True:
+        high = [int(c) for c in rng.integers(0x21, 0x7F, size=4)]
+        rest = (x - sum(c * pow(257, 8 + i, P) for i, c in enumerate(high))) % P
+        low = []
+        for _ in range(8):                       # 257^8 > p: eight digits always suffice
+            low.append(rest % 257)
+            rest //= 257
+        if rest == 0 and all(c < 256 and c not in ws for c in low):
+            tok = bytes(low + high)
+            assert sum(c * pow(257, i, P) for i, c in enumerate(tok)) % P == x
+            return tok
+
+
+def test_stream_kernel_exact_path_for_values_next_to_the_modulus(sedd):
+    """Text whose shingle hashes are solved so that (a_k x + b_k) mod p lands within a few units
+    of 0 or p for some function: the streaming kernel's fast evaluation cannot decide those and
+    must redo the round exactly.  One-token documents (their single shingle is the token) and
+    the same tokens inside longer documents with n = 1."""
+    say("stream near-modulus values")
+    P = (1 << 61) - 1
+    K, seed = 128, 0
+    a, b = oracle.coeffs(seed, K)
+    rng = np.random.default_rng(4)
+    targets = [0, 1, 2, 5, P - 1, P - 2, P - 5, P - (1 << 32), P - (1 << 32) - 1, (1 << 32) - 1]
+    toks = []
+    for k in (0, 63, 64, 127):
+        inv = pow(int(a[k]), -1, P)
+        for t in targets:
+            xv = ((t - int(b[k])) * inv) % P
+            toks.append(_token_with_hash(xv, rng))
+    filler = [bytes(rng.integers(97, 123, size=int(l), dtype=np.uint8)) for l in rng.integers(1, 9, size=300)]
+    docs = [t for t in toks] + [b" ".join(filler[:150] + toks[:20] + filler[150:]),
+                                b" ".join(toks)]
+    data, off = _pack(docs, 3)
+    before = sedd.debug_stats()[sedd.STAT_SLOW_TILES]
+    for n in (1, 5):
+        want = oracle.minhash(data, off, n, K, seed, 0)
+        got = host(sedd.sedd_minhash(dev(data), dev(off), n, K, seed, 0))
+        bad = np.nonzero((got != want).any(axis=1))[0]
+        assert bad.size == 0, (n, bad[:5])
+    after = sedd.debug_stats()[sedd.STAT_SLOW_TILES]
+    assert after > before, "the exact path was never taken"
+
+
+def test_minhash_rejects_offsets_beyond_the_text(sedd):
+    """The binding passes the size of the text: offsets that point past it are refused before
+    any kernel follows them."""
+    say("minhash offsets past the text")
+    data = dev(np.full(64, 97, np.uint8))
+    out = torch.full((2, 8), 7, dtype=torch.int32, device="cuda").view(torch.uint32)
+    for flags in (0, 1, 2, 4):
+        with pytest.raises(sedd.SeddError) as e:
+            sedd.sedd_minhash(data, dev(np.array([0, 40, 65], dtype=np.uint64)), 5, 8, 0, flags, out=out)
+        assert e.value.code == -1
+    assert (out.view(torch.int32) == 7).all().item()
+    sedd.sedd_minhash(data, dev(np.array([0, 40, 64], dtype=np.uint64)), 5, 8, out=out)
+
+
 @pytest.mark.parametrize("seed", [21, 22])
 def test_fuzz_signatures_in_the_other_hash_modes(sedd, seed):
     """The same adversarial tokenisation inputs through the paper-prime and rolling-family modes."""
