@@ -1,19 +1,22 @@
 // sedd_minhash: shingling, Eq. 1 base hash, K hash functions and per-document minimum.
 //
-// Pipeline per chunk of consecutive documents (all on the caller's stream, no host waits):
+// Default mode (word shingles, 61-bit modulus, affine family): k_minhash_stream, one launch that
+// reads the text once; see the comment above that kernel.
+//
+// Byte shingles and the two alternative hash-function modes run per chunk of consecutive
+// documents (all on the caller's stream, no host waits inside the loop):
 //   1. byte tiles     each non-empty document is cut into 1 KiB tiles aligned to 16-byte
 //                     addresses; a scan over per-document tile counts builds the work list.
 //   2. words          (word mode) one wavefront per byte tile marks token starts from a 16-byte
 //                     vector load per lane and counts them; after a scan a second pass writes
-//                     one record per token: the Eq. 1 hash of "token 0x20" and the length.
+//                     one record per token (its Eq. 1 hash modulo the paper's prime, or its
+//                     position) and the length.
 //   3. shingle tiles  per-document shingle counts, scanned into shingle offsets and a second
 //                     work list of tiles of TS shingles.
 //   4. min-hash       one wavefront per shingle tile.  Phase A (lane = shingle): x(s) of Eq. 1
-//                     by Horner over n token records (word mode) or from the tile's bytes with
-//                     the reuse form of Eq. 2 (byte mode), into LDS.  Phase B (lane = hash
-//                     function): the 61-bit multiply-add mod 2^61-1, truncation to 32 bits and
-//                     running minimum.  This is where the time goes: K modular multiplies per
-//                     shingle.
+//                     from the token records or from the tile's bytes with the reuse form of
+//                     Eq. 2, into LDS.  Phase B (lane = hash function): the modular
+//                     multiply-add, truncation to 32 bits and running minimum.
 #include <algorithm>
 #include <vector>
 
@@ -71,25 +74,6 @@ struct PowSplit {
 __device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpow, uint32_t e) {
   return e < (uint32_t)QPOW_N ? qpow[e] : powmod(257, e);
 }
-__device__ __forceinline__ void store_token(const TokenRecs &tr, uint32_t idx, uint64_t w,
-                                            uint32_t len, const uint64_t *__restrict__ qpow,
-                                            const PowSplit *__restrict__ ptab) {
-  uint64_t v;
-  if (len < (uint32_t)QPOW_N) {
-    // w + 32 * 257^len = w - nsp (mod p)
-    const uint64_t nsp = ptab[len].nsp;
-    v = w >= nsp ? w - nsp : w + (P61 - nsp);
-  } else {
-    // 32 * 257^len: a shift by 5 is a rotation of the 61-bit residue
-    const uint64_t pw = powmod(257, len);
-    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
-    v = addmod(w, sp == P61 ? 0 : sp);
-  }
-  tr.v[idx] = v;
-  tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
-  if (len >= LONG_TOKEN) tr.long_len[idx] = len;
-}
-
 // ---- paper-prime mode (SEDD_FLAG_PAPER_PRIME) ------------------------------------------------
 //
 // Section 3.2 quotes p' = 4,294,967 as the modulus of Eq. 1 in the paper's experiments.  p' is
@@ -475,15 +459,15 @@ constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from L
 
 constexpr uint32_t SM_TEXT_WORDS = (TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2;
 
-// EM selects what a record holds beside the length: the token's Eq. 1 hash mod 2^61-1 (EM_P61),
-// the same modulo the paper's prime as a 32-bit value (EM_PP), or the token's position in the
-// chunk frame as a 32-bit value (EM_POS, for the mode whose functions hash the bytes themselves).
-enum { EM_P61 = 0, EM_PP = 1, EM_POS = 2 };
+// EM selects what a record holds beside the length: the token's Eq. 1 hash modulo the paper's
+// prime as a 32-bit value (EM_PP), or the token's position in the chunk frame as a 32-bit value
+// (EM_POS, for the mode whose functions hash the bytes themselves).  The default mode (61-bit
+// modulus) keeps no token records in memory: see k_minhash_stream.
+enum { EM_PP = 1, EM_POS = 2 };
 template <int EM>
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
-             const uint64_t *__restrict__ qpow, const PowSplit *__restrict__ ptab,
              const PowPP *__restrict__ ptab_pp, TokenRecs rec) {
   // text: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
   // than the wavefront's longest
@@ -602,8 +586,7 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
       }
       if (active) {
         if (EM == EM_PP) store_token_pp(rec, first_idx + j, (uint32_t)w, len, ptab_pp);
-        else if (EM == EM_POS) store_token_pos(rec, first_idx + j, tile0 + pos, len);
-        else store_token(rec, first_idx + j, w, len, qpow, ptab);
+        else store_token_pos(rec, first_idx + j, tile0 + pos, len);  // EM_POS: only the length is used
       }
     }
   }
@@ -646,8 +629,7 @@ struct XSource {
   const uint32_t *sbase;  // shingle offsets per document (byte mode)
   TokenRecs rec;          // token records (word mode)
   const uint64_t *qpow;   // 257^i, i < QPOW_N
-  const PowSplit *ptab;   // Horner multipliers per token length, QPOW_N entries
-  const PowPP *ptab_pp;   // the same for the paper-prime mode
+  const PowPP *ptab_pp;   // Horner multipliers per token length (paper-prime mode), QPOW_N entries
   const uint64_t *given;  // caller-supplied hashes (debug entry), indexed like the shingle stream
   uint32_t n;             // shingle length
 };
@@ -659,38 +641,20 @@ __device__ __forceinline__ uint32_t token_len(const TokenRecs &rec, uint32_t i) 
   return l;
 }
 
-// x of shingle i of tile ht.
-// Word mode: with V_m = hash of "token_m 0x20" and P_m = 257^(len_m + 1),
-//   x = V_0 + P_0 (V_1 + P_1 (... (V_{n-2} + P_{n-2} W_{n-1}))),   W_{n-1} = V_{n-1} - 32 * 257^len.
-// Byte mode: Horner over the window's bytes from the last to the first.
+// x of shingle i of tile ht, 61-bit modulus: a caller-supplied value, or Horner over the window's
+// bytes from the last to the first.  (Word shingles of this modulus are hashed by
+// k_minhash_stream from its token ring.)
 template <int MODE>
 __device__ __forceinline__ uint64_t shingle_x(const XSource &xsrc, const HTile &ht, uint32_t i) {
+  static_assert(MODE == X_GIVEN || MODE == X_BYTES, "word shingles take the streaming kernel");
   if (MODE == X_GIVEN) return xsrc.given[ht.x_off + i];
-  if (MODE == X_BYTES) {
-    const uint32_t d = ht.doc;
-    const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
-    const uint32_t per = min(len, xsrc.n);
-    const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
-    uint64_t acc = 0;
-    for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, p[j]);
-    return fold61(acc);
-  }
-  const TokenRecs &rec = xsrc.rec;
-  const uint32_t first = ht.tok0 + i, last = first + ht.per - 1;
-  const uint64_t pw = qpow_global(xsrc.qpow, token_len(rec, last));
-  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
-  const uint64_t v_last = rec.v[last];
-  uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;
-  for (uint32_t m = last; m-- > first;) {
-    const uint64_t P = qpow_global(xsrc.qpow, token_len(rec, m) + 1);
-    const uint32_t a0 = (uint32_t)P & 0x7FFFFFFFu, a12 = (uint32_t)(P >> 31) << 1;
-    const uint32_t x0 = (uint32_t)acc & 0x7FFFFFFFu, x1 = (uint32_t)(acc >> 31);
-    const uint64_t N = (uint64_t)a0 * (x1 << 2) + (uint64_t)a12 * (x0 << 1);
-    const uint64_t U = (uint64_t)a12 * x1 + (uint64_t)a0 * x0;
-    // P*acc = (N_lo << 29) + U + N_hi (mod p); V is added before the single reduction
-    acc = fold61(((uint64_t)(uint32_t)N << 29) + U + (N >> 32) + rec.v[m]);
-  }
-  return acc;
+  const uint32_t d = ht.doc;
+  const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
+  const uint32_t per = min(len, xsrc.n);
+  const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
+  uint64_t acc = 0;
+  for (uint32_t j = per; j-- > 0;) acc = horner257_lazy(acc, p[j]);
+  return fold61(acc);
 }
 
 // ---- the hot kernel ------------------------------------------------------------------------
@@ -736,35 +700,6 @@ __device__ __forceinline__ uint64_t horner_step_lazy(uint64_t acc, uint32_t a0, 
   return (uint64_t)(uint32_t)(Z >> 61) * hc.one + (Z & P61);
 }
 
-// x of the shingle made of the PER tokens first .. first+PER-1, all loads issued up front.
-// Valid only if every token is shorter than LONG_TOKEN bytes; *long_tok says whether one is not.
-template <int PER>
-__device__ __forceinline__ uint64_t words_x_unrolled(const TokenRecs &rec,
-                                                     const PowSplit *__restrict__ ptab,
-                                                     uint32_t first, const HotConsts &hc,
-                                                     bool *long_tok) {
-  uint32_t len[PER];
-  uint64_t V[PER];
-#pragma unroll
-  for (int m = 0; m < PER; m++) {
-    len[m] = rec.len[first + m];
-    V[m] = rec.v[first + m];
-  }
-  uint4 e[PER];
-#pragma unroll
-  for (int m = 0; m < PER - 1; m++) e[m] = *reinterpret_cast<const uint4 *>(ptab + len[m]);
-  const uint64_t nsp = ptab[len[PER - 1]].nsp;
-  bool lt = false;
-#pragma unroll
-  for (int m = 0; m < PER; m++) lt |= len[m] == LONG_TOKEN;
-  *long_tok = lt;
-  uint64_t acc = V[PER - 1] + nsp;  // bare last token, < 2^62
-  acc = (acc & P61) + (acc >> 61);
-#pragma unroll
-  for (int m = PER - 2; m >= 0; m--) acc = horner_step_lazy(acc, e[m].x, e[m].y, e[m].z, V[m], hc);
-  return fold61(acc);
-}
-
 template <int F, int P, int MODE>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
 k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restrict__ n_tiles,
@@ -777,40 +712,7 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   if (t >= *n_tiles) return;
   const uint32_t d = ht.doc, cnt = ht.cnt;
 
-  if (MODE == X_WORDS) {
-    // Straight-line evaluation for tokens shorter than LONG_TOKEN bytes (table multipliers,
-    // lazily reduced accumulator, unrolled for the usual shingle lengths); a lane that meets a
-    // longer token redoes its shingle the general way.
-    const TokenRecs &rec = xsrc.rec;
-    const PowSplit *__restrict__ ptab = xsrc.ptab;
-    const uint32_t per = ht.per;
-    for (uint32_t i = threadIdx.x; i < cnt; i += 64) {
-      const uint32_t first = ht.tok0 + i;
-      bool long_tok = false;
-      uint64_t acc;
-      if (per == 5) acc = words_x_unrolled<5>(rec, ptab, first, hc, &long_tok);
-      else if (per == 3) acc = words_x_unrolled<3>(rec, ptab, first, hc, &long_tok);
-      else if (per == 4) acc = words_x_unrolled<4>(rec, ptab, first, hc, &long_tok);
-      else if (per == 2) acc = words_x_unrolled<2>(rec, ptab, first, hc, &long_tok);
-      else if (per == 1) acc = words_x_unrolled<1>(rec, ptab, first, hc, &long_tok);
-      else {
-        const uint32_t last = first + per - 1;
-        const uint32_t l_last = rec.len[last];
-        long_tok = l_last == LONG_TOKEN;
-        acc = rec.v[last] + ptab[l_last].nsp;
-        acc = (acc & P61) + (acc >> 61);
-        for (uint32_t m = last; m-- > first;) {
-          const uint32_t lm = rec.len[m];
-          long_tok |= lm == LONG_TOKEN;
-          const uint4 e = *reinterpret_cast<const uint4 *>(ptab + lm);
-          acc = horner_step_lazy(acc, e.x, e.y, e.z, rec.v[m], hc);
-        }
-        acc = fold61(acc);
-      }
-      if (long_tok) acc = shingle_x<MODE>(xsrc, ht, i);
-      sx[i] = x_limbs(acc);
-    }
-  } else if (MODE == X_BYTES) {
+  if (MODE == X_BYTES) {
     // Byte windows.  The tile's bytes are staged in LDS; lane l owns the WPL = TS / 64 windows
     // from WPL l on: it evaluates the last of them by Horner over its bytes and derives the others with the reuse
     // form of Eq. 1 (Eq. 2 read backwards, so that the step multiplies by q instead of dividing):
@@ -1915,7 +1817,9 @@ k_debug_write_x(XSource xsrc, const HTile *__restrict__ tiles,
   const HTile ht = tiles[t];
   const uint64_t base = *total + ht.x_off;
   for (uint32_t i = threadIdx.x; i < ht.cnt; i += 64) {
-    const uint64_t x = PAPER ? (uint64_t)shingle_x_pp<MODE>(xsrc, ht, i) : shingle_x<MODE>(xsrc, ht, i);
+    uint64_t x;
+    if constexpr (PAPER) x = shingle_x_pp<MODE>(xsrc, ht, i);
+    else x = shingle_x<MODE>(xsrc, ht, i);
     if (base + i < cap) out_x[base + i] = x;
   }
 }
@@ -1946,27 +1850,32 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
   const HotConsts hc = {1u << 29, 8u, 1u};
   dim3 grid((uint32_t)nht, ky);
   ProfScope prof(SEDD_PROF_MINHASH, st);
-#define SEDD_LAUNCH_MH(FF, HW, MM)                                                              \
-  do {                                                                                         \
-    if (coef_pp)                                                                               \
-      hipLaunchKernelGGL((k_minhash_pp<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles,       \
-                         n_tiles, coef_pp, K, csig);                                           \
-    else                                                                                       \
-      hipLaunchKernelGGL((k_minhash<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
-                         coef_a, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES);           \
+#define SEDD_LAUNCH_PP(FF, HW, MM)                                                         \
+  hipLaunchKernelGGL((k_minhash_pp<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles, \
+                     coef_pp, K, csig)
+#define SEDD_LAUNCH_61(FF, HW, MM)                                                          \
+  hipLaunchKernelGGL((k_minhash<FF, HW, MM>), grid, dim3(64), 0, st, xsrc, tiles, n_tiles,  \
+                     coef_a, coef_s, K, csig, hc, stats + SEDD_STAT_SLOW_TILES)
+#define SEDD_LAUNCH_MH_F(LAUNCH, MM)           \
+  do {                                         \
+    if (P == 1) LAUNCH(4, 1, MM);              \
+    else if (F == 1) LAUNCH(1, 2, MM);         \
+    else if (F == 2) LAUNCH(2, 2, MM);         \
+    else LAUNCH(4, 2, MM);                     \
   } while (0)
-#define SEDD_LAUNCH_MH_F(MM)                       \
-  do {                                             \
-    if (P == 1) SEDD_LAUNCH_MH(4, 1, MM);          \
-    else if (F == 1) SEDD_LAUNCH_MH(1, 2, MM);     \
-    else if (F == 2) SEDD_LAUNCH_MH(2, 2, MM);     \
-    else SEDD_LAUNCH_MH(4, 2, MM);                 \
-  } while (0)
-  if (mode == X_WORDS) SEDD_LAUNCH_MH_F(X_WORDS);
-  else if (mode == X_BYTES) SEDD_LAUNCH_MH_F(X_BYTES);
-  else SEDD_LAUNCH_MH_F(X_GIVEN);
+  if (coef_pp) {
+    if (mode == X_WORDS) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_WORDS);
+    else if (mode == X_BYTES) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_BYTES);
+    else SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_GIVEN);
+  } else {
+    // word shingles with the 61-bit modulus never come here: k_minhash_stream hashes them
+    if (mode == X_WORDS) return SEDD_EINVAL;
+    if (mode == X_BYTES) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_61, X_BYTES);
+    else SEDD_LAUNCH_MH_F(SEDD_LAUNCH_61, X_GIVEN);
+  }
 #undef SEDD_LAUNCH_MH_F
-#undef SEDD_LAUNCH_MH
+#undef SEDD_LAUNCH_61
+#undef SEDD_LAUNCH_PP
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
 }
@@ -2360,7 +2269,6 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   xsrc.sbase = sbase;
   xsrc.rec = rec;
   xsrc.qpow = qpow;
-  xsrc.ptab = ptab;
   xsrc.ptab_pp = ptab_pp;
   xsrc.given = nullptr;
   xsrc.n = (uint32_t)n;
@@ -2426,13 +2334,10 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
       if (rc) return rc;
       if (paper)
         hipLaunchKernelGGL(k_emit_words<EM_PP>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
-                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
-      else if (rolling)
-        hipLaunchKernelGGL(k_emit_words<EM_POS>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
-                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
+                           btd, btb + nd, wbase, ptab_pp, rec);
       else
-        hipLaunchKernelGGL(k_emit_words<EM_P61>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
-                           btd, btb + nd, wbase, qpow, ptab, ptab_pp, rec);
+        hipLaunchKernelGGL(k_emit_words<EM_POS>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
+                           btd, btb + nd, wbase, ptab_pp, rec);
       SEDD_LAUNCH_CHECK();
     }
     {
@@ -2456,8 +2361,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
                      htd, htb + nd, total, dbg_x, dbg_cap)
       if (byte_mode && paper) SEDD_LAUNCH_DBG(X_BYTES, true);
       else if (byte_mode) SEDD_LAUNCH_DBG(X_BYTES, false);
-      else if (paper) SEDD_LAUNCH_DBG(X_WORDS, true);
-      else SEDD_LAUNCH_DBG(X_WORDS, false);
+      else SEDD_LAUNCH_DBG(X_WORDS, true);  // word shingles reach this driver with the paper's prime only
 #undef SEDD_LAUNCH_DBG
       SEDD_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_debug_write_offsets, dim3(gdoc), dim3(256), 0, st, sbase, nd, total,
