@@ -13,12 +13,16 @@
  *     misaligned pointer is SEDD_EINVAL.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue their kernels on it and return; results are ready when the
- *     stream has drained.  sedd_minhash first validates `doc_offsets` and plans
- *     bounded-size chunks with two small kernels and waits (twice) for a few
- *     numbers from them; everything after that is enqueued without host waits.
- *   - Return value: SEDD_OK (0) or a negative error code.  On SEDD_EINVAL
- *     nothing is written and no device work is enqueued.  `n_docs == 0` is a
- *     successful no-op that touches nothing.
+ *     stream has drained.  sedd_minhash first validates `doc_offsets` with two
+ *     small kernels and waits once for the first and last offset and the verdict
+ *     (twice with byte shingles or an alternative hash mode, which also plan
+ *     bounded-size chunks); everything after that is enqueued without host waits.
+ *   - Return value: SEDD_OK (0) or a negative error code.  On an error no output
+ *     is written.  Bad scalars, null or misaligned pointers are found before any
+ *     device work; offsets that decrease, exceed a document's size limit or (in
+ *     sedd_minhash_bounded) point past the text are found by two small validation
+ *     kernels, which read doc_offsets only, before anything reads the text.
+ *     `n_docs == 0` is a successful no-op that touches nothing.
  *   - Device scratch (chunk work lists, sort buffers, the union-find forest)
  *     lives in a grow-only allocation owned by the library, shared by all
  *     calls of the process: calls must not overlap in time on different
@@ -205,6 +209,23 @@ int32_t sedd_min_match(uint64_t theta_num, uint64_t theta_den, int32_t K);
  * at least 1.  Integer arithmetic only, host-side.
  */
 uint64_t sedd_dense_bucket_count(uint64_t n_docs, uint32_t k);
+
+/*
+ * Caller-provided workspace (Section 3.3's per-bucket buffers and the union graph of Section 2.2
+ * are scratch here: nothing in them outlives a call).  sedd_cluster_ws and
+ * sedd_cluster_verified_ws are sedd_cluster and sedd_cluster_verified with every scratch buffer
+ * carved out of `workspace` (device memory, any alignment) instead of the library's arena: they
+ * allocate nothing, and calls with different workspaces may overlap on different streams.
+ * sedd_cluster_workspace_bytes gives the size to pass: K = 0 for sedd_cluster_ws, the signature
+ * length for sedd_cluster_verified_ws; it returns 0 for arguments the calls would reject.
+ * A workspace that is too small is SEDD_ELIMIT, a null one SEDD_EINVAL; nothing is enqueued then.
+ */
+uint64_t sedd_cluster_workspace_bytes(uint64_t n_docs, int32_t b, int32_t K);
+int sedd_cluster_ws(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
+                    void *workspace, uint64_t workspace_bytes, void *stream);
+int sedd_cluster_verified_ws(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                             int32_t b, int32_t min_match, int64_t *cluster_id, void *workspace,
+                             uint64_t workspace_bytes, void *stream);
 
 /* Text for an error code (static storage). */
 const char *sedd_strerror(int code);

@@ -65,10 +65,6 @@ int sedd_debug_minhash_from_x_pp(const uint64_t *x, const uint64_t *shingle_offs
  * (waits for the device to go idle first).
  */
 #define SEDD_STAT_SLOW_TILES 0 /* shingle tiles the min-hash kernel recomputed on its exact path */
-#define SEDD_STAT_VERIFY_COUNTS 1 /* sedd_cluster_verified, last call: two 64-bit slots holding four
-                                     32-bit counts: records compared with their bucket's first
-                                     record, records then compared with their whole bucket, buckets
-                                     compared tile by tile, unused */
 #define SEDD_STAT_N 16
 int sedd_debug_stats(uint64_t *out);
 
@@ -102,6 +98,13 @@ int sedd_debug_last_regroup(uint32_t *out);
  * the default).  Results never depend on it; tests use small values to cross chunk edges.
  */
 int sedd_debug_set_chunk_bytes(uint64_t bytes);
+
+/*
+ * Makes every request for more than `bytes` of library-owned scratch fail with SEDD_ENOMEM, as a
+ * full device would (0 lifts the cap).  For tests of that return path: the failing call writes
+ * nothing and enqueues nothing, and the next call after the cap is lifted succeeds.
+ */
+int sedd_debug_set_scratch_cap(uint64_t bytes);
 
 /*
  * Bytes of text per wavefront of the streaming min-hash kernel (word shingles, 61-bit modulus):

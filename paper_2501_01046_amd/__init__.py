@@ -17,7 +17,8 @@ import os
 
 __all__ = [
     "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
-    "sedd_cluster_verified", "sedd_cluster_static", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
+    "sedd_cluster_verified", "sedd_cluster_static", "sedd_cluster_ws",
+    "sedd_cluster_workspace_bytes", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
     "debug_coeffs", "debug_scan_u32", "debug_sort_bands", "debug_set_chunk_bytes",
     "debug_minhash_from_x", "debug_stats", "profile_enable", "profile_read",
@@ -68,6 +69,14 @@ def lib():
         L.sedd_cluster.argtypes = [vp, u64, i32, vp, vp]
         L.sedd_cluster_static.restype = C.c_int
         L.sedd_cluster_static.argtypes = [vp, u64, i32, vp, vp]
+        L.sedd_cluster_workspace_bytes.restype = u64
+        L.sedd_cluster_workspace_bytes.argtypes = [u64, i32, i32]
+        L.sedd_cluster_ws.restype = C.c_int
+        L.sedd_cluster_ws.argtypes = [vp, u64, i32, vp, vp, u64, vp]
+        L.sedd_cluster_verified_ws.restype = C.c_int
+        L.sedd_cluster_verified_ws.argtypes = [vp, vp, u64, i32, i32, i32, vp, vp, u64, vp]
+        L.sedd_debug_set_scratch_cap.restype = C.c_int
+        L.sedd_debug_set_scratch_cap.argtypes = [u64]
         L.sedd_lsh_dense_keys.restype = C.c_int
         L.sedd_lsh_dense_keys.argtypes = [vp, u64, i32, i32, i32, u64, vp, vp]
         L.sedd_cluster_verified.restype = C.c_int
@@ -213,6 +222,43 @@ def sedd_cluster_static(keys, out, stream=None):
     _check(lib().sedd_cluster_static(_ptr(keys), n_docs, b, _ptr(out), _stream(stream)),
            "sedd_cluster_static")
     return out
+
+
+def sedd_cluster_workspace_bytes(n_docs: int, b: int, K: int = 0) -> int:
+    """Bytes of workspace sedd_cluster (K = 0) or sedd_cluster_verified (K = signature length)
+    needs when the caller provides it."""
+    return int(lib().sedd_cluster_workspace_bytes(int(n_docs), int(b), int(K)))
+
+
+def sedd_cluster_ws(keys, workspace, out=None, sig=None, min_match=None, stream=None):
+    """sedd_cluster (or, with sig and min_match, sedd_cluster_verified) on a caller-provided
+    workspace: a uint8 device tensor of at least sedd_cluster_workspace_bytes(...) bytes."""
+    torch = _torch()
+    keys = _dev(keys, torch.uint64, "keys")
+    workspace = _dev(workspace, torch.uint8, "workspace")
+    n_docs, b = keys.shape
+    if out is None:
+        out = torch.empty((n_docs,), dtype=torch.int64, device=keys.device)
+    else:
+        out = _dev(out, torch.int64, "out")
+        if out.numel() != n_docs:
+            raise ValueError("out has the wrong size")
+    if sig is None:
+        _check(lib().sedd_cluster_ws(_ptr(keys), n_docs, b, _ptr(out), _ptr(workspace),
+                                     workspace.numel(), _stream(stream)), "sedd_cluster_ws")
+    else:
+        sig = _dev(sig, torch.uint32, "sig")
+        if sig.shape[0] != n_docs:
+            raise ValueError("sig and keys describe different numbers of documents")
+        _check(lib().sedd_cluster_verified_ws(_ptr(keys), _ptr(sig), n_docs, sig.shape[1], b,
+                                              int(min_match), _ptr(out), _ptr(workspace),
+                                              workspace.numel(), _stream(stream)),
+               "sedd_cluster_verified_ws")
+    return out
+
+
+def debug_set_scratch_cap(n: int):
+    _check(lib().sedd_debug_set_scratch_cap(n), "sedd_debug_set_scratch_cap")
 
 
 def dense_bucket_count(n_docs: int, k: int = 4) -> int:

@@ -787,6 +787,7 @@ struct SortBufs {
   uint64_t *ka, *kb;
   uint32_t *da, *db, *hist, *tmp, *parent;
   uint32_t *gate;      // raised by the linking / marking kernel when the sorted bits are too few
+  uint32_t *counts;    // verified path: lengths of the follower, outsider and large-group lists
   uint32_t *sketch;    // one-bit signature sketches (verified path): n * sketch_words(K) words
   BigGroup *big;       // capacity big_cap
   uint64_t *tile_pre;  // 2 * (big_cap + 1) prefix sums of tile counts
@@ -796,7 +797,7 @@ struct SortBufs {
 
 // Where the buffers of one clustering call sit inside its workspace (256-byte aligned pieces).
 struct SortPlan {
-  uint64_t o_ka, o_kb, o_da, o_db, o_h, o_t, o_p, o_gate, o_big, o_pre, o_sk;
+  uint64_t o_ka, o_kb, o_da, o_db, o_h, o_t, o_p, o_gate, o_counts, o_big, o_pre, o_sk;
   uint64_t big_cap, bytes;
   uint32_t nblk;
 };
@@ -816,6 +817,7 @@ static SortPlan plan_sort(uint64_t n, uint32_t b, int K_sketch) {
   pl.o_t = cv.take<uint32_t>(scan_tmp_count(nh));
   pl.o_p = cv.take<uint32_t>(n);
   pl.o_gate = cv.take<uint32_t>(1);
+  pl.o_counts = cv.take<uint32_t>(4);
   pl.big_cap = K_sketch ? total / BIG_GROUP + 1 : 0;
   pl.o_big = cv.take<BigGroup>(pl.big_cap + 1);
   pl.o_pre = cv.take<uint64_t>(2 * (pl.big_cap + 1));
@@ -833,6 +835,7 @@ static void bind_sort(const SortPlan &pl, uint8_t *A, SortBufs *sb) {
   sb->tmp = (uint32_t *)(A + pl.o_t);
   sb->parent = (uint32_t *)(A + pl.o_p);
   sb->gate = (uint32_t *)(A + pl.o_gate);
+  sb->counts = (uint32_t *)(A + pl.o_counts);
   sb->big = (BigGroup *)(A + pl.o_big);
   sb->tile_pre = (uint64_t *)(A + pl.o_pre);
   sb->sketch = (uint32_t *)(A + pl.o_sk);
@@ -1059,27 +1062,26 @@ int sedd_cluster_static(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_
   return run_cluster(keys, n_docs, (uint32_t)b, cluster_id, sb, false, (hipStream_t)stream);
 }
 
-int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
-                          int32_t b, int32_t min_match, int64_t *cluster_id, void *stream) {
+static int check_verified_args(const void *keys, const void *sig, uint64_t n_docs, int32_t K, int32_t b,
+                               int32_t min_match, const void *out) {
   if (K < 1 || K > SEDD_MAX_K || min_match < 0) return SEDD_EINVAL;
-  int rc = check_cluster_args(keys, n_docs, b, cluster_id);
+  int rc = check_cluster_args(keys, n_docs, b, out);
   if (rc || n_docs == 0) return rc;
   if (!sig || !aligned_to(sig, 4)) return SEDD_EINVAL;
-  hipStream_t st = (hipStream_t)stream;
-  SortBufs sb;
-  rc = sort_layout(n_docs, (uint32_t)b, &sb, (int)K);
-  if (rc) return rc;
-  unsigned long long *stats = nullptr;
-  rc = stats_ensure(&stats);
-  if (rc) return rc;
-  // list lengths (followers, outsiders, large groups), kept beside the device counters and
-  // cleared by every call
-  uint32_t *counts = (uint32_t *)(stats + SEDD_STAT_VERIFY_COUNTS);
+  return SEDD_OK;
+}
+
+// sedd_cluster_verified on the buffers of `sb` (the caller has checked the arguments)
+static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                                uint32_t b, int32_t min_match, int64_t *cluster_id, SortBufs &sb,
+                                hipStream_t st) {
+  int rc;
+  uint32_t *counts = sb.counts;  // list lengths (followers, outsiders, large groups), cleared by every call
   const int bits = grouping_bits(n_docs, 4096);
   g_last_gate = sb.gate;
   {
     ProfScope prof(SEDD_PROF_SORT, st);
-    rc = sort_bands(keys, n_docs, (uint32_t)b, bits, &sb, st);
+    rc = sort_bands(keys, n_docs, b, bits, &sb, st);
     if (rc) return rc;
   }
   const uint32_t n = (uint32_t)n_docs;
@@ -1096,7 +1098,7 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
     hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, sb.gate, 1u, 0u,
                        (const uint32_t *)nullptr);
     SEDD_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
+    hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
                        list1, counts, sb.big, sb.gate, 0);
     SEDD_LAUNCH_CHECK();
   }
@@ -1104,14 +1106,14 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
     // only if a large group held more than one key (the sorted bits were too few to separate
     // the buckets): sort by the rest of the key and mark again, now on whole keys
     ProfScope prof(SEDD_PROF_SORT, st);
-    rc = sort_rest_if_gated(n_docs, (uint32_t)b, bits, &sb, st);
+    rc = sort_rest_if_gated(n_docs, b, bits, &sb, st);
     if (rc) return rc;
   }
   ProfScope prof(SEDD_PROF_VERIFY, st);
   hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, counts, 4u, 0u,
                      (const uint32_t *)sb.gate);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, (uint32_t)b), dim3(SORT_THREADS), 0, st, sb.ka, n,
+  hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, b), dim3(SORT_THREADS), 0, st, sb.ka, n,
                      ~uint64_t(0), list1, counts, sb.big, sb.gate, 1);
   SEDD_LAUNCH_CHECK();
   // large groups: tile plan, then the tiles against each group's first tile, then the rest
@@ -1139,6 +1141,56 @@ int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_
                      cluster_id);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
+}
+
+int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                          int32_t b, int32_t min_match, int64_t *cluster_id, void *stream) {
+  int rc = check_verified_args(keys, sig, n_docs, K, b, min_match, cluster_id);
+  if (rc || n_docs == 0) return rc;
+  SortBufs sb;
+  rc = sort_layout(n_docs, (uint32_t)b, &sb, (int)K);
+  if (rc) return rc;
+  return run_cluster_verified(keys, sig, n_docs, K, (uint32_t)b, min_match, cluster_id, sb,
+                              (hipStream_t)stream);
+}
+
+uint64_t sedd_cluster_workspace_bytes(uint64_t n_docs, int32_t b, int32_t K) {
+  if (b < 1 || b > SEDD_MAX_BANDS || K < 0 || K > SEDD_MAX_K) return 0;
+  if (n_docs >= (uint64_t(1) << 31) || n_docs * (uint64_t)b >= (uint64_t(1) << 32)) return 0;
+  if (n_docs == 0) return 256;
+  return plan_sort(n_docs, (uint32_t)b, (int)K).bytes + 256;  // room to align the caller's pointer
+}
+
+// the caller's workspace, aligned up to 256 bytes, if it is large enough for the plan
+static int bind_workspace(const SortPlan &pl, void *workspace, uint64_t workspace_bytes, SortBufs *sb) {
+  if (!workspace) return SEDD_EINVAL;
+  const uintptr_t base = ((uintptr_t)workspace + 255) & ~uintptr_t(255);
+  const uint64_t lost = base - (uintptr_t)workspace;
+  if (workspace_bytes < lost || workspace_bytes - lost < pl.bytes) return SEDD_ELIMIT;
+  bind_sort(pl, (uint8_t *)base, sb);
+  return SEDD_OK;
+}
+
+int sedd_cluster_ws(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_t *cluster_id,
+                    void *workspace, uint64_t workspace_bytes, void *stream) {
+  int rc = check_cluster_args(keys, n_docs, b, cluster_id);
+  if (rc || n_docs == 0) return rc;
+  SortBufs sb;
+  rc = bind_workspace(plan_sort(n_docs, (uint32_t)b, 0), workspace, workspace_bytes, &sb);
+  if (rc) return rc;
+  return run_cluster(keys, n_docs, (uint32_t)b, cluster_id, sb, true, (hipStream_t)stream);
+}
+
+int sedd_cluster_verified_ws(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
+                             int32_t b, int32_t min_match, int64_t *cluster_id, void *workspace,
+                             uint64_t workspace_bytes, void *stream) {
+  int rc = check_verified_args(keys, sig, n_docs, K, b, min_match, cluster_id);
+  if (rc || n_docs == 0) return rc;
+  SortBufs sb;
+  rc = bind_workspace(plan_sort(n_docs, (uint32_t)b, (int)K), workspace, workspace_bytes, &sb);
+  if (rc) return rc;
+  return run_cluster_verified(keys, sig, n_docs, K, (uint32_t)b, min_match, cluster_id, sb,
+                              (hipStream_t)stream);
 }
 
 int sedd_debug_last_regroup(uint32_t *out) {

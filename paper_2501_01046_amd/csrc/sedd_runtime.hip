@@ -24,7 +24,14 @@ static uint64_t g_arena_bytes = 0;
 static void *g_pinned = nullptr;
 static uint64_t g_pinned_bytes = 0;
 
+static uint64_t g_scratch_cap = 0;  // debug: arena sizes above this fail as if the device were full
+
 int scratch_ensure(uint64_t bytes, uint8_t **base) {
+  if (g_scratch_cap && bytes > g_scratch_cap) {
+    snprintf(g_dev_err, sizeof(g_dev_err), "scratch of %llu bytes exceeds the debug cap of %llu",
+             (unsigned long long)bytes, (unsigned long long)g_scratch_cap);
+    return SEDD_ENOMEM;
+  }
   if (bytes > g_arena_bytes) {
     // earlier calls may still be using the old arena
     SEDD_HIP(hipDeviceSynchronize());
@@ -320,6 +327,11 @@ int sedd_debug_stats(uint64_t *out) {
   if (rc) return rc;
   SEDD_HIP(hipDeviceSynchronize());
   SEDD_HIP(hipMemcpy(out, p, SEDD_STAT_N * sizeof(uint64_t), hipMemcpyDeviceToHost));
+  return SEDD_OK;
+}
+
+int sedd_debug_set_scratch_cap(uint64_t bytes) {
+  g_scratch_cap = bytes;
   return SEDD_OK;
 }
 

@@ -162,3 +162,39 @@ def test_threshold_and_bucket_count_through_the_c_abi():
     for _ in range(300):
         n, k = rng.randrange(0, 1 << 63), rng.randrange(0, 1 << 32)
         assert nb(u64(n), k) == max(1, math.isqrt(k * k * n))
+
+
+def test_scratch_cap_turns_into_enomem_before_the_device():
+    """SEDD_ENOMEM return path, forced from the host: with a cap on the library's scratch, a call
+    whose buffers exceed it fails before it touches the device; lifting the cap restores it."""
+    L = sedd.lib()
+    L.sedd_debug_set_scratch_cap.argtypes = [u64]
+    assert L.sedd_debug_set_scratch_cap(u64(1)) == 0
+    try:
+        assert L.sedd_cluster(FAKE, u64(4), 16, FAKE, None) == -2
+        assert b"allocation" in L.sedd_strerror(-2)
+        assert b"cap" in L.sedd_last_device_error()
+    finally:
+        assert L.sedd_debug_set_scratch_cap(u64(0)) == 0
+
+
+def test_workspace_size_and_argument_checks():
+    L = sedd.lib()
+    wb = L.sedd_cluster_workspace_bytes
+    wb.restype, wb.argtypes = u64, [u64, C.c_int32, C.c_int32]
+    plain, ver = wb(u64(100_000), 16, 0), wb(u64(100_000), 16, 128)
+    # 24 bytes per (document, band) record dominate; the verified call adds sketches and group lists
+    assert 24 * 1_600_000 < plain < 26 * 1_600_000
+    assert ver > plain + 100_000 * 4 * 4
+    assert wb(u64(0), 16, 0) > 0
+    assert wb(u64(100), 0, 0) == 0 and wb(u64(100), 16, -1) == 0 and wb(u64(1 << 31), 1, 0) == 0
+    assert wb(u64(65_536), 16, 0) <= (32 << 20) + 256       # what the static entry point promises
+    L.sedd_cluster_ws.argtypes = [C.c_void_p, u64, C.c_int32, C.c_void_p, C.c_void_p, u64, C.c_void_p]
+    L.sedd_cluster_verified_ws.argtypes = [C.c_void_p, C.c_void_p, u64, C.c_int32, C.c_int32, C.c_int32,
+                                           C.c_void_p, C.c_void_p, u64, C.c_void_p]
+    assert L.sedd_cluster_ws(FAKE, u64(4), 16, FAKE, None, u64(1 << 20), None) == -1       # no workspace
+    assert L.sedd_cluster_ws(FAKE, u64(4), 16, FAKE, FAKE, u64(100), None) == -4           # too small
+    assert L.sedd_cluster_ws(FAKE, u64(4), 0, FAKE, FAKE, u64(1 << 20), None) == -1
+    assert L.sedd_cluster_ws(None, u64(0), 16, None, None, u64(0), None) == 0
+    assert L.sedd_cluster_verified_ws(FAKE, FAKE, u64(4), 128, 16, 103, FAKE, FAKE, u64(100), None) == -4
+    assert L.sedd_cluster_verified_ws(FAKE, None, u64(4), 128, 16, 103, FAKE, FAKE, u64(1 << 20), None) == -1

@@ -384,6 +384,71 @@ def test_cluster_keys_with_constant_low_bits_at_200k(sedd, kind):
     assert vre == (0 if kind == "uniform" else 1)
 
 
+def test_cluster_on_caller_workspaces_and_two_streams(sedd):
+    """sedd_cluster_ws / sedd_cluster_verified_ws: same results as the arena calls, with a
+    misaligned workspace, and two calls in flight on two streams with a workspace each."""
+    say("cluster workspaces")
+    rng = np.random.default_rng(12)
+    cases = []
+    for n, b, K in ((30_000, 8, 32), (50_000, 4, 16)):
+        keys = rng.integers(0, n // 2, size=(n, b), dtype=np.uint64)
+        proto = rng.integers(0, 1 << 32, size=(50, K), dtype=np.uint64).astype(np.uint32)
+        sig = proto[rng.integers(0, 50, size=n)].copy()
+        noise = rng.random((n, K)) < 0.15
+        sig[noise] = rng.integers(0, 1 << 32, size=int(noise.sum()), dtype=np.uint64).astype(np.uint32)
+        cases.append((keys, sig, K))
+    arena_before = sedd.sedd_scratch_bytes()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for (keys, sig, K), st in zip(cases, streams):
+        n, b = keys.shape
+        need_c = sedd.sedd_cluster_workspace_bytes(n, b)
+        need_v = sedd.sedd_cluster_workspace_bytes(n, b, K)
+        ws_c = torch.empty(need_c + 3, dtype=torch.uint8, device="cuda")[3:]     # misaligned on purpose
+        ws_v = torch.empty(need_v, dtype=torch.uint8, device="cuda")
+        d_keys, d_sig = dev(keys), dev(sig)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            c = sedd.sedd_cluster_ws(d_keys, ws_c[: need_c], stream=st)
+            v = sedd.sedd_cluster_ws(d_keys, ws_v, sig=d_sig, min_match=K - 6, stream=st)
+        outs.append((c, v, ws_c, ws_v, d_keys, d_sig))
+    torch.cuda.synchronize()
+    assert sedd.sedd_scratch_bytes() == arena_before            # the arena was not used
+    for (keys, sig, K), (c, v, *_rest) in zip(cases, outs):
+        assert np.array_equal(host(c), oracle.cluster(keys))
+        assert np.array_equal(host(v), oracle.cluster_verified(keys, sig, K - 6))
+    keys, sig, K = cases[0]
+    small = torch.empty(1000, dtype=torch.uint8, device="cuda")
+    with pytest.raises(sedd.SeddError) as e:
+        sedd.sedd_cluster_ws(dev(keys), small)
+    assert e.value.code == -4
+
+
+def test_enomem_leaves_outputs_untouched_and_the_next_call_works(sedd):
+    say("scratch cap -> ENOMEM")
+    rng = np.random.default_rng(13)
+    keys = rng.integers(0, 5000, size=(20_000, 4), dtype=np.uint64)
+    d_keys = dev(keys)
+    out = torch.full((20_000,), -5, dtype=torch.int64, device="cuda")
+    sedd.debug_set_scratch_cap(4096)
+    try:
+        with pytest.raises(sedd.SeddError) as e:
+            sedd.sedd_cluster(d_keys, out=out)
+        assert e.value.code == -2
+        torch.cuda.synchronize()
+        assert bool((out == -5).all())
+        data, off = corpus.generate(corpus.config(1).scaled(200))
+        sig = torch.full((200, 16), 9, dtype=torch.int32, device="cuda").view(torch.uint32)
+        with pytest.raises(sedd.SeddError) as e:
+            sedd.sedd_minhash(dev(data), dev(off), 13, 16, 0, 1, out=sig)      # byte shingles: chunk scratch
+        assert e.value.code == -2
+        torch.cuda.synchronize()
+        assert bool((sig.view(torch.int32) == 9).all())
+    finally:
+        sedd.debug_set_scratch_cap(0)
+    assert np.array_equal(host(sedd.sedd_cluster(d_keys, out=out)), oracle.cluster(keys))
+
+
 # ---- the whole path ------------------------------------------------------------------------
 
 def _full_path(sedd, recipe, procs):
