@@ -655,8 +655,9 @@ def short_run(torch, sedd, corpus, np, c, ncore, theta, with_parity):
 
 
 def host_fed_leg(torch, sedd, np, wl, sig, keys, cid, K, b, r, n, steps):
-    """The whole corpus in pinned host memory, uploaded in pieces of at most 2 GB through two
-    device staging buffers on a copy stream while sedd_minhash works on the previous piece."""
+    """The whole corpus in pinned host memory, fed through sedd_minhash_host_chunked: the library
+    uploads pieces of at most 2 GB into two device staging buffers on its own stream while
+    sedd_minhash works on the previous piece."""
     n_bytes, flags = wl.n_bytes, wl.flags
     chunk = min(STREAM_CHUNK_BYTES, max(64 << 20, n_bytes // 6))
     try:
@@ -666,80 +667,52 @@ def host_fed_leg(torch, sedd, np, wl, sig, keys, cid, K, b, r, n, steps):
         avail = 64 << 30
     # pinned copy of the text: leave half of the free host memory alone
     budget = int(min(n_bytes, max(1 << 30, avail // 2)))
-    subs, tot = [], 0
+    take, tot = [], 0
     for text, off, d0, d1 in wl.pieces:
         if tot >= budget:
             break
-        h_o = off.cpu().numpy()
-        a, nd = 0, d1 - d0
-        while a < nd and tot < budget:
-            e = int(np.searchsorted(h_o, h_o[a] + np.uint64(chunk), side="right")) - 1
-            e = min(nd, max(a + 1, e))
-            lo, hi = int(h_o[a]), int(h_o[e])
-            p_t = torch.empty(hi - lo, dtype=torch.uint8, pin_memory=True)
-            p_t.copy_(text[lo:hi])                      # device -> pinned host
-            p_o = torch.empty(e - a + 1, dtype=torch.int64, pin_memory=True)
-            p_o.numpy()[:] = (h_o[a:e + 1] - h_o[a]).view(np.int64)
-            subs.append((p_t, p_o, d0 + a, d0 + e))
-            tot += hi - lo
-            a = e
-        del h_o
+        take.append((text, off, d0, d1))
+        tot += text.numel()
+    leg_docs = take[-1][3]
+    h_text = torch.empty(tot, dtype=torch.uint8, pin_memory=True)
+    h_off = torch.empty(leg_docs + 1, dtype=torch.int64, pin_memory=True)
+    at = 0
+    for text, off, d0, d1 in take:
+        h_text[at:at + text.numel()].copy_(text)                     # device -> pinned host
+        h_off[d0:d1 + 1].copy_((off.view(torch.int64) + at).cpu())
+        at += text.numel()
     torch.cuda.synchronize()
-    leg_docs = subs[-1][3]                       # documents [0, leg_docs) take part
-    stage = [(torch.empty(max(x[0].numel() for x in subs), dtype=torch.uint8, device="cuda"),
-              torch.empty(max(x[1].numel() for x in subs), dtype=torch.int64, device="cuda"))
-             for _ in range(2)]
-    copy_s, comp_s = torch.cuda.Stream(), torch.cuda.current_stream()
     h_sig = torch.empty((leg_docs, K), dtype=torch.uint32, device="cuda")
 
-    def one_pass(compute):
-        done, copied = [None, None], {}
+    def one_pass():
+        sedd.sedd_minhash_host_chunked(h_text, h_off, n, K, 0, flags, chunk_bytes=chunk, out=h_sig)
+        sedd.sedd_lsh_keys(h_sig, b, r, out=keys[:leg_docs])
+        sedd.sedd_cluster(keys[:leg_docs], out=cid[:leg_docs])
 
-        def upload(i):
-            t, o, _, _ = subs[i]
-            st = stage[i % 2]
-            with torch.cuda.stream(copy_s):
-                if done[i % 2] is not None:
-                    copy_s.wait_event(done[i % 2])
-                st[0][:t.numel()].copy_(t, non_blocking=True)
-                st[1][:o.numel()].copy_(o, non_blocking=True)
-                ev = torch.cuda.Event()
-                ev.record(copy_s)
-                copied[i] = ev
-        upload(0)
-        for i in range(len(subs)):
-            if i + 1 < len(subs):
-                upload(i + 1)
-            comp_s.wait_event(copied[i])
-            t, o, d0, d1 = subs[i]
-            st = stage[i % 2]
-            if compute:
-                sedd.sedd_minhash(st[0][:t.numel()], st[1][:o.numel()].view(torch.uint64), n, K,
-                                  0, flags, out=h_sig[d0:d1])
-            ev = torch.cuda.Event()
-            ev.record(comp_s)
-            done[i % 2] = ev
-        if compute:
-            sedd.sedd_lsh_keys(h_sig, b, r, out=keys[:leg_docs])
-            sedd.sedd_cluster(keys[:leg_docs], out=cid[:leg_docs])
-
-    def timed(compute, reps):
-        one_pass(compute)
+    def timed(fn, reps):
+        fn()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(reps):
-            one_pass(compute)
+            fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps
     reps = max(1, min(3, steps)) if tot < (8 << 30) else 1
-    t_path = timed(True, reps)
+    t_path = timed(one_pass, reps)
     same = bool(torch.equal(h_sig.view(torch.int32), sig[:leg_docs].view(torch.int32)))
-    t_copy = timed(False, reps)
+    # the upload by itself, same piece size, through one device buffer
+    stage = torch.empty(min(chunk, tot) + 16, dtype=torch.uint8, device="cuda")
+
+    def upload_only():
+        for a in range(0, tot, chunk):
+            e = min(tot, a + chunk)
+            stage[:e - a].copy_(h_text[a:e], non_blocking=True)
+    t_copy = timed(upload_only, reps)
     leg = {
-        "what": "text in pinned host memory, double-buffered upload overlapped with sedd_minhash; "
-                "then band keys and clusters of the same documents",
+        "what": "text in pinned host memory through sedd_minhash_host_chunked (double-buffered "
+                "upload overlapped with the hashing); then band keys and clusters of the same documents",
         "documents": leg_docs, "text_bytes": tot, "whole_corpus": bool(tot >= n_bytes),
-        "pieces": len(subs), "piece_bytes": chunk,
+        "piece_bytes": chunk,
         "ms_per_pass": round(1e3 * t_path, 3), "docs_per_s": round(leg_docs / t_path, 1),
         "text_GB_per_s": round(tot / t_path / 1e9, 3),
         "upload_only_ms_per_pass": round(1e3 * t_copy, 3),
@@ -752,6 +725,7 @@ def host_fed_leg(torch, sedd, np, wl, sig, keys, cid, K, b, r, n, steps):
     # keys and cid held the whole corpus before this leg: restore them
     sedd.sedd_lsh_keys(sig, b, r, out=keys)
     sedd.sedd_cluster(keys, out=cid)
+    sedd.sedd_release_scratch()              # the staging buffers are as large as two pieces
     return leg
 
 

@@ -106,6 +106,25 @@ int sedd_minhash_bounded(const uint8_t *bytes, uint64_t n_bytes, const uint64_t 
                          uint32_t flags, uint32_t *sig, void *stream);
 
 /*
+ * sedd_minhash for text that lives in HOST memory (Section 3.4: the paper hides the transfer of
+ * the text behind the hashing with double buffering).  host_bytes and host_doc_offsets are HOST
+ * pointers; sig is a DEVICE pointer as everywhere else.  The documents are cut into chunks of
+ * whole documents of at most chunk_bytes of text (0: 2 GiB; a longer document is a chunk of its
+ * own; at most 2^22 documents per chunk).  Chunk i+1 is uploaded on a stream of the library's own
+ * into one of two device staging buffers while chunk i is hashed on `stream`; the signatures are
+ * those of one sedd_minhash call on the whole text.
+ * Host memory should be pinned (hipHostMalloc): uploads from pageable memory are correct but do
+ * not overlap.  The offsets are validated on the host, so the default hash mode enqueues
+ * everything without waiting on the device; the call returns when the last upload has left the
+ * host buffers (they may then be changed or freed) and `sig` is complete when `stream` drains.
+ * The staging buffers (2 x the largest chunk) are kept for later calls; sedd_release_scratch
+ * frees them.  Like the scratch arena they are shared: calls must not overlap in time.
+ */
+int sedd_minhash_host_chunked(const uint8_t *host_bytes, const uint64_t *host_doc_offsets,
+                              uint64_t n_docs, int32_t shingle_n, int32_t K, uint64_t seed,
+                              uint32_t flags, uint64_t chunk_bytes, uint32_t *sig, void *stream);
+
+/*
  * LSH band keys (Section 2.3: the signature is cut into b bands of r rows and each band
  * is hashed to a bucket).  key[d*b + j] = (sum_{i<r} sig[d*K + j*r + i] * Q^i) mod p with
  * Q = 1687994237021934823: Eq. 1's polynomial over the band's values.  Equal bands give

@@ -16,7 +16,7 @@ import ctypes as C
 import os
 
 __all__ = [
-    "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_lsh_keys", "sedd_cluster",
+    "SeddError", "lib", "lib_path", "sedd_minhash", "sedd_minhash_host_chunked", "sedd_lsh_keys", "sedd_cluster",
     "sedd_cluster_verified", "sedd_cluster_static", "sedd_cluster_ws",
     "sedd_cluster_workspace_bytes", "min_match_for", "sedd_lsh_dense_keys", "dense_bucket_count",
     "sedd_release_scratch", "sedd_scratch_bytes", "sedd_version", "debug_shingle_hashes",
@@ -63,6 +63,8 @@ def lib():
         L.sedd_minhash_bounded.argtypes = [vp, u64, vp, u64, i32, i32, u64, u32, vp, vp]
         L.sedd_debug_set_piece_bytes.restype = C.c_int
         L.sedd_debug_set_piece_bytes.argtypes = [u32]
+        L.sedd_minhash_host_chunked.restype = C.c_int
+        L.sedd_minhash_host_chunked.argtypes = [vp, vp, u64, i32, i32, u64, u32, u64, vp, vp]
         L.sedd_lsh_keys.restype = C.c_int
         L.sedd_lsh_keys.argtypes = [vp, u64, i32, i32, i32, vp, vp]
         L.sedd_cluster.restype = C.c_int
@@ -176,6 +178,30 @@ def sedd_minhash(text, doc_offsets, shingle_n: int, K: int, seed: int = 0, flags
     # the bounded entry point: offsets that point past `text` are rejected, not followed
     _check(lib().sedd_minhash_bounded(_ptr(text), text.numel(), _ptr(doc_offsets), n_docs, shingle_n,
                                       K, seed, flags, _ptr(out), _stream(stream)), "sedd_minhash")
+    return out
+
+
+def sedd_minhash_host_chunked(text, doc_offsets, shingle_n: int, K: int, seed: int = 0,
+                              flags: int = 0, chunk_bytes: int = 0, out=None, stream=None):
+    """sedd_minhash for text in host memory: `text` (uint8) and `doc_offsets` (uint64 or int64,
+    n_docs + 1 entries) are CPU tensors, ideally pinned; the library uploads chunks of at most
+    chunk_bytes behind the hashing of the previous chunk.  Returns device signatures."""
+    torch = _torch()
+    for t, name in ((text, "text"), (doc_offsets, "doc_offsets")):
+        if not isinstance(t, torch.Tensor) or t.is_cuda or not t.is_contiguous():
+            raise TypeError(f"{name} must be a contiguous CPU tensor")
+    if text.dtype != torch.uint8 or doc_offsets.dtype not in (torch.uint64, torch.int64):
+        raise TypeError("text must be uint8 and doc_offsets uint64 (or int64)")
+    n_docs = max(0, doc_offsets.numel() - 1)
+    if out is None:
+        out = torch.empty((n_docs, max(int(K), 0)), dtype=torch.uint32, device="cuda")
+    else:
+        out = _dev(out, torch.uint32, "out")
+        if out.numel() != n_docs * K:
+            raise ValueError("out has the wrong size")
+    _check(lib().sedd_minhash_host_chunked(_ptr(text), _ptr(doc_offsets), n_docs, shingle_n, K, seed,
+                                           flags, int(chunk_bytes), _ptr(out), _stream(stream)),
+           "sedd_minhash_host_chunked")
     return out
 
 

@@ -113,6 +113,8 @@ int set_device_error(hipError_t e, const char *what);
 int scratch_ensure(uint64_t bytes, uint8_t **base);
 // Grow-only pinned host buffer.
 int pinned_ensure(uint64_t bytes, void **ptr);
+// Frees the device staging buffers of sedd_minhash_host_chunked (the device must be idle).
+int release_host_feed();
 
 // The fallback flag of the most recent clustering call (inside its workspace; debug read-out).
 // Forgotten when the arena it may point into is freed.

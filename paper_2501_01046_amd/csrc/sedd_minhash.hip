@@ -1990,9 +1990,12 @@ __global__ void k_stream_soff(const uint64_t *__restrict__ off, uint64_t n_docs,
 // The default mode of sedd_minhash (word shingles, 61-bit modulus, affine family): validation,
 // coefficients, the signature fill and one launch of k_minhash_stream.  One host wait, for the
 // first and last offset and the validity flag.  With dbg_off the two debug passes run instead.
+// host_ends: {doc_offsets[0], doc_offsets[n_docs]} when the caller has the offsets on the host and
+// has validated them there (then nothing waits on the device); nullptr otherwise.
 static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
                               uint64_t n_docs, int32_t n, int32_t K, uint64_t seed, uint32_t *sig,
-                              uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st) {
+                              uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st,
+                              const uint64_t *host_ends = nullptr) {
   const bool debug = dbg_off != nullptr;
   const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
   Carver cv;
@@ -2005,22 +2008,30 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
   uint8_t *A = nullptr;
   int rc = scratch_ensure(fixed_bytes, &A);
   if (rc) return rc;
-  void *pin = nullptr;
-  rc = pinned_ensure(64, &pin);
-  if (rc) return rc;
-  uint64_t *d_probe = (uint64_t *)(A + o_probe);
-  uint32_t *d_bad = (uint32_t *)(d_probe + 2);
-  hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(1), 0, st, d_bad);
-  SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, d_probe);
-  SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
-                     doc_offsets, n_docs, max_doc, d_bad);
-  SEDD_LAUNCH_CHECK();
-  SEDD_HIP(hipMemcpyAsync(pin, d_probe, 24, hipMemcpyDeviceToHost, st));
-  SEDD_HIP(hipStreamSynchronize(st));
-  const uint64_t off0 = ((const uint64_t *)pin)[0], offn = ((const uint64_t *)pin)[1];
-  if (((const uint32_t *)pin)[4] || offn < off0 || offn > n_bytes) return SEDD_EINVAL;
+  uint64_t off0, offn;
+  if (host_ends) {
+    off0 = host_ends[0];
+    offn = host_ends[1];
+  } else {
+    void *pin = nullptr;
+    rc = pinned_ensure(64, &pin);
+    if (rc) return rc;
+    uint64_t *d_probe = (uint64_t *)(A + o_probe);
+    uint32_t *d_bad = (uint32_t *)(d_probe + 2);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(1), 0, st, d_bad);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, d_probe);
+    SEDD_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
+                       doc_offsets, n_docs, max_doc, d_bad);
+    SEDD_LAUNCH_CHECK();
+    SEDD_HIP(hipMemcpyAsync(pin, d_probe, 24, hipMemcpyDeviceToHost, st));
+    SEDD_HIP(hipStreamSynchronize(st));
+    off0 = ((const uint64_t *)pin)[0];
+    offn = ((const uint64_t *)pin)[1];
+    if (((const uint32_t *)pin)[4]) return SEDD_EINVAL;
+  }
+  if (offn < off0 || offn > n_bytes) return SEDD_EINVAL;
   if (offn > off0 && !bytes) return SEDD_EINVAL;
 
   // the frame: 16-byte aligned, at or below the first byte of document 0
@@ -2392,6 +2403,65 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   return SEDD_OK;
 }
 
+// ---- text resident in host memory -------------------------------------------------------------
+//
+// Two device staging buffers for the text and two for the offsets, an upload stream and four
+// events, all owned by the library and kept between calls (sedd_release_scratch frees them).
+struct HostFeed {
+  uint8_t *text[2] = {nullptr, nullptr};
+  uint64_t *offs[2] = {nullptr, nullptr};
+  uint64_t text_bytes = 0, offs_count = 0;
+  hipStream_t copy = nullptr;
+  hipEvent_t copied[2] = {nullptr, nullptr}, done[2] = {nullptr, nullptr};
+};
+static HostFeed g_feed;
+
+static int feed_ensure(uint64_t text_bytes, uint64_t offs_count) {
+  HostFeed &f = g_feed;
+  if (!f.copy) {
+    SEDD_HIP(hipStreamCreateWithFlags(&f.copy, hipStreamNonBlocking));  // default priority
+    for (int i = 0; i < 2; i++) {
+      SEDD_HIP(hipEventCreateWithFlags(&f.copied[i], hipEventDisableTiming));
+      SEDD_HIP(hipEventCreateWithFlags(&f.done[i], hipEventDisableTiming));
+    }
+  }
+  if (text_bytes > f.text_bytes || offs_count > f.offs_count) {
+    SEDD_HIP(hipDeviceSynchronize());  // earlier calls may still read the old buffers
+    for (int i = 0; i < 2; i++) {
+      if (f.text[i]) SEDD_HIP(hipFree(f.text[i]));
+      if (f.offs[i]) SEDD_HIP(hipFree(f.offs[i]));
+      f.text[i] = nullptr;
+      f.offs[i] = nullptr;
+    }
+    f.text_bytes = f.offs_count = 0;
+    const uint64_t tb = std::max(text_bytes, f.text_bytes) + 64, oc = std::max(offs_count, f.offs_count);
+    for (int i = 0; i < 2; i++) {
+      void *p = nullptr, *q = nullptr;
+      if (hipMalloc(&p, tb) != hipSuccess || hipMalloc(&q, oc * sizeof(uint64_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        return SEDD_ENOMEM;
+      }
+      f.text[i] = (uint8_t *)p;
+      f.offs[i] = (uint64_t *)q;
+    }
+    f.text_bytes = tb;
+    f.offs_count = oc;
+  }
+  return SEDD_OK;
+}
+
+int release_host_feed() {
+  HostFeed &f = g_feed;
+  for (int i = 0; i < 2; i++) {
+    if (f.text[i]) SEDD_HIP(hipFree(f.text[i]));
+    if (f.offs[i]) SEDD_HIP(hipFree(f.offs[i]));
+    f.text[i] = nullptr;
+    f.offs[i] = nullptr;
+  }
+  f.text_bytes = f.offs_count = 0;
+  return SEDD_OK;
+}
+
 }  // namespace sedd
 
 using namespace sedd;
@@ -2424,6 +2494,87 @@ int sedd_minhash_bounded(const uint8_t *bytes, uint64_t n_bytes, const uint64_t 
   if (!aligned_to(doc_offsets, 8) || !aligned_to(sig, 4)) return SEDD_EINVAL;
   return run_minhash(bytes, n_bytes, doc_offsets, n_docs, shingle_n, K, seed, flags, sig, nullptr, 0,
                      nullptr, (hipStream_t)stream);
+}
+
+int sedd_minhash_host_chunked(const uint8_t *host_bytes, const uint64_t *host_doc_offsets,
+                              uint64_t n_docs, int32_t shingle_n, int32_t K, uint64_t seed,
+                              uint32_t flags, uint64_t chunk_bytes, uint32_t *sig, void *stream) {
+  if (shingle_n < 1 || shingle_n > SEDD_MAX_SHINGLE_N || K < 1 || K > SEDD_MAX_K) return SEDD_EINVAL;
+  if (flags & ~(SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME | SEDD_FLAG_ROLLING_FAMILY))
+    return SEDD_EINVAL;
+  if ((flags & SEDD_FLAG_PAPER_PRIME) && (flags & SEDD_FLAG_ROLLING_FAMILY)) return SEDD_EINVAL;
+  if (n_docs == 0) return SEDD_OK;
+  if (!host_doc_offsets || !sig || n_docs >= (uint64_t(1) << 31)) return SEDD_EINVAL;
+  if (!aligned_to(host_doc_offsets, 8) || !aligned_to(sig, 4)) return SEDD_EINVAL;
+  hipStream_t st = (hipStream_t)stream;
+  const uint64_t *off = host_doc_offsets;
+  // the offsets are on the host: validate them here
+  const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
+  for (uint64_t d = 0; d < n_docs; d++)
+    if (off[d + 1] < off[d] || off[d + 1] - off[d] >= max_doc) return SEDD_EINVAL;
+  if (off[n_docs] > off[0] && !host_bytes) return SEDD_EINVAL;
+  if (chunk_bytes == 0) chunk_bytes = uint64_t(2) << 30;
+  const uint64_t chunk_docs = uint64_t(1) << 22;
+  // chunks of whole documents: as many as fit chunk_bytes (at least one), at most chunk_docs
+  std::vector<uint64_t> cuts;
+  cuts.push_back(0);
+  uint64_t max_text = 0, max_docs = 0;
+  for (uint64_t d0 = 0; d0 < n_docs;) {
+    const uint64_t *hi = std::upper_bound(off + d0 + 1, off + n_docs + 1, off[d0] + chunk_bytes);
+    uint64_t d1 = (uint64_t)(hi - off) - 1;  // last index whose offset is within the budget
+    d1 = std::min(std::max(d1, d0 + 1), std::min(n_docs, d0 + chunk_docs));
+    max_text = std::max(max_text, off[d1] - off[d0]);
+    max_docs = std::max(max_docs, d1 - d0);
+    cuts.push_back(d1);
+    d0 = d1;
+  }
+  int rc = feed_ensure(max_text, max_docs + 1);
+  if (rc) return rc;
+  HostFeed &f = g_feed;
+  const bool plain = !(flags & (SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME | SEDD_FLAG_ROLLING_FAMILY));
+  const size_t n_chunks = cuts.size() - 1;
+  bool used[2] = {false, false};
+  auto upload = [&](size_t i) -> int {
+    const uint64_t d0 = cuts[i], d1 = cuts[i + 1];
+    const int s = (int)(i & 1);
+    if (used[s]) SEDD_HIP(hipStreamWaitEvent(f.copy, f.done[s], 0));  // its last reader has finished
+    const uint64_t nb = off[d1] - off[d0];
+    if (nb) SEDD_HIP(hipMemcpyAsync(f.text[s], host_bytes + off[d0], nb, hipMemcpyHostToDevice, f.copy));
+    SEDD_HIP(hipMemcpyAsync(f.offs[s], off + d0, (d1 - d0 + 1) * sizeof(uint64_t),
+                            hipMemcpyHostToDevice, f.copy));
+    SEDD_HIP(hipEventRecord(f.copied[s], f.copy));
+    return SEDD_OK;
+  };
+  // the first upload must not overtake work already queued on the caller's stream that may
+  // still read the staging buffers of an earlier call
+  SEDD_HIP(hipEventRecord(f.done[0], st));
+  SEDD_HIP(hipStreamWaitEvent(f.copy, f.done[0], 0));
+  rc = upload(0);
+  if (rc) return rc;
+  for (size_t i = 0; i < n_chunks; i++) {
+    const int s = (int)(i & 1);
+    if (i + 1 < n_chunks) {
+      rc = upload(i + 1);  // overlaps the hashing of chunk i
+      if (rc) return rc;
+    }
+    const uint64_t d0 = cuts[i], d1 = cuts[i + 1];
+    SEDD_HIP(hipStreamWaitEvent(st, f.copied[s], 0));
+    // the staged offsets are the caller's, unshifted: the text pointer is moved back instead
+    const uint8_t *base = f.text[s] - off[d0];
+    const uint64_t ends[2] = {off[d0], off[d1]};
+    if (plain)
+      rc = run_minhash_stream(base, off[d1], f.offs[s], d1 - d0, shingle_n, K, seed,
+                              sig + d0 * (uint64_t)K, nullptr, 0, nullptr, st, ends);
+    else
+      rc = run_minhash(base, off[d1], f.offs[s], d1 - d0, shingle_n, K, seed, flags,
+                       sig + d0 * (uint64_t)K, nullptr, 0, nullptr, st);
+    if (rc) return rc;
+    SEDD_HIP(hipEventRecord(f.done[s], st));
+    used[s] = true;
+  }
+  // the host buffers are free to change once the last upload has left them
+  SEDD_HIP(hipEventSynchronize(f.copied[(n_chunks - 1) & 1]));
+  return SEDD_OK;
 }
 
 int sedd_debug_shingle_hashes(const uint8_t *bytes, const uint64_t *doc_offsets,

@@ -276,7 +276,7 @@ int sedd_release_scratch(void) {
     g_pinned = nullptr;
     g_pinned_bytes = 0;
   }
-  return SEDD_OK;
+  return release_host_feed();
 }
 
 uint64_t sedd_scratch_bytes(void) { return g_arena_bytes; }

@@ -884,6 +884,38 @@ def test_stream_kernel_exact_path_for_values_next_to_the_modulus(sedd):
     assert after > before, "the exact path was never taken"
 
 
+@pytest.mark.parametrize("flags,n", [(0, 5), (1, 13), (2, 5), (4, 3)])
+def test_minhash_from_host_memory_in_chunks(sedd, flags, n):
+    """sedd_minhash_host_chunked: text and offsets in host memory (pinned and pageable), cut into
+    many chunks, a chunk size below the longest document, offsets that do not start at 0, empty
+    documents at chunk edges: signatures equal the oracle's and those of the resident call."""
+    say("host chunked", flags, n)
+    r = corpus.Recipe("h", seed=8, n_docs=900, vocab=2000, len_median=120, len_sigma=1.1, len_lo=0,
+                      len_hi=6000, near_frac=0.2, ws_variety=1)
+    data, off = corpus.generate(r)
+    lead = np.frombuffer(b"not part of any document ", dtype=np.uint8)
+    data = np.concatenate([lead, data])
+    off = np.concatenate([off[:300], off[299:300], off[299:]]) + np.uint64(lead.size)   # one empty doc
+    K = 48 if flags != 4 else 16
+    want = oracle.minhash_sharded(data, off, n, K, 2, flags, procs=NPROC)
+    resident = host(sedd.sedd_minhash(dev(data), dev(off), n, K, 2, flags))
+    assert np.array_equal(resident, want)
+    for pinned in (True, False):
+        h_text = torch.from_numpy(data.copy())
+        h_off = torch.from_numpy(off.astype(np.int64))
+        if pinned:
+            h_text, h_off = h_text.pin_memory(), h_off.pin_memory()
+        for chunk in (0, 1 << 20, 40_000, 3_000):
+            got = sedd.sedd_minhash_host_chunked(h_text, h_off, n, K, 2, flags, chunk_bytes=chunk)
+            torch.cuda.synchronize()
+            bad = np.nonzero((host(got) != want).any(axis=1))[0]
+            assert bad.size == 0, (pinned, chunk, bad[:5])
+    bad_off = torch.from_numpy(np.array([0, 50, 40, 60], dtype=np.int64))
+    with pytest.raises(sedd.SeddError) as e:
+        sedd.sedd_minhash_host_chunked(torch.from_numpy(data.copy()), bad_off, n, K)
+    assert e.value.code == -1
+
+
 def test_minhash_rejects_offsets_beyond_the_text(sedd):
     """The binding passes the size of the text: offsets that point past it are refused before
     any kernel follows them."""
