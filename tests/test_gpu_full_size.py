@@ -378,6 +378,39 @@ def test_config4_full_size_long_documents(sedd):
                              verified=True)
 
 
+def test_one_document_above_one_gigabyte(sedd):
+    """A single document of 1.2 GB between small ones, in one call: positions inside a document
+    beyond 2^30, about 150,000 wavefronts merging their minima into one signature row, and the
+    documents after it found by their offsets beyond 2^30."""
+    say("one document of 1.2 GB")
+    rng = np.random.default_rng(9)
+    words = [bytes(rng.integers(97, 123, size=int(l), dtype=np.uint8)) for l in rng.integers(1, 10, size=160_000)]
+    block = (b" ".join(words) + b"\n")
+    reps = (1_200_000_000 // len(block)) + 1
+    small = [b" ".join(words[i:i + 40]) for i in range(0, 4000, 40)]
+    docs = small[:50] + [block * reps] + small[50:]
+    data = np.frombuffer(b"".join(docs), dtype=np.uint8)
+    off = np.cumsum([0] + [len(d) for d in docs]).astype(np.uint64)
+    assert int(off[51] - off[50]) > (1 << 30)
+    K, n = 8, 5
+    t0 = time.time()
+    want = oracle.minhash_sharded(data, off, n, K, 1, 0, procs=NPROC)
+    say(f"  oracle {time.time() - t0:.1f} s")
+    d_data, d_off = torch.from_numpy(data.copy()).cuda(), torch.from_numpy(off).cuda()
+    got = sedd.sedd_minhash(d_data, d_off, n, K, 1, 0).cpu().numpy()
+    bad = np.nonzero((got != want).any(axis=1))[0]
+    assert bad.size == 0, f"documents {bad[:5]} differ"
+    del d_data, data
+    # byte shingles (the chunked path): one document of 160 MB, larger than a 128 MB chunk
+    docs = small[:50] + [block * (160_000_000 // len(block) + 1)] + small[50:]
+    data = np.frombuffer(b"".join(docs), dtype=np.uint8)
+    off = np.cumsum([0] + [len(d) for d in docs]).astype(np.uint64)
+    want_b = oracle.minhash_sharded(data, off, 13, K, 1, 1, procs=NPROC)
+    got_b = sedd.sedd_minhash(torch.from_numpy(data.copy()).cuda(), torch.from_numpy(off).cuda(),
+                              13, K, 1, 1).cpu().numpy()
+    assert np.array_equal(got_b, want_b)
+
+
 def test_config2_full_size_paper_prime(sedd):
     """The medium workload with the paper's own modulus (SEDD_FLAG_PAPER_PRIME)."""
     r = corpus.config(2)
