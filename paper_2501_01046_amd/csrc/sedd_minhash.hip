@@ -905,6 +905,31 @@ __device__ __forceinline__ uint64_t lds_token_hash(const uint32_t *sm_text, uint
     const uint32_t D2 = d2 + (d2 >> 8);
     acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
     acc = horner3_lazy(acc, D0);
+  } else if (!__any(flen > 16)) {
+    // at most 16 bytes (ordinary prose): one 20-byte read, five digits and a byte, no loop
+    const uint32_t wd = pos >> 2, sh = pos & 3u;
+    const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2], t3 = sm_text[wd + 3],
+                   t4 = sm_text[wd + 4];
+    // bytes 0..7 and 8..15 of the token, those past its end cleared
+    const uint32_t l_lo = min(flen, 8u), l_hi = flen - l_lo;
+    const uint64_t keep_lo = l_lo ? ~0ull >> (64u - 8u * l_lo) : 0ull;
+    const uint64_t keep_hi = l_hi ? ~0ull >> (64u - 8u * l_hi) : 0ull;
+    const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, sh) & (uint32_t)keep_lo;
+    const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, sh) & (uint32_t)(keep_lo >> 32);
+    const uint32_t a2 = __builtin_amdgcn_alignbyte(t3, t2, sh) & (uint32_t)keep_hi;
+    const uint32_t a3 = __builtin_amdgcn_alignbyte(t4, t3, sh) & (uint32_t)(keep_hi >> 32);
+    // three-byte digits: bytes 0-2, 3-5, 6-8, 9-11, 12-14, and byte 15
+    const uint32_t d0 = a0 & 0xFFFFFFu;
+    const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
+    const uint32_t d2 = __builtin_amdgcn_alignbyte(a2, a1, 2u) & 0xFFFFFFu;
+    const uint32_t d3 = __builtin_amdgcn_alignbyte(a3, a2, 1u) & 0xFFFFFFu;
+    const uint32_t d4 = a3 & 0xFFFFFFu;
+    auto digit = [](uint32_t d) { return d + ((d >> 8) & 0xFFu) + 513u * (d >> 16); };
+    acc = (uint64_t)(a3 >> 24) * R3 + digit(d4);  // exact, below 2^33
+    acc = horner3_lazy(acc, digit(d3));
+    acc = horner3_lazy(acc, digit(d2));
+    acc = horner3_lazy(acc, digit(d1));
+    acc = horner3_lazy(acc, digit(d0));
   } else {
     acc = 0;
     const uint32_t nd = (flen + 2) / 3;

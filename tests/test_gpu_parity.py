@@ -835,6 +835,26 @@ def test_stream_kernel_piece_size_invariance(sedd, piece):
         sedd.debug_set_piece_bytes(0)
 
 
+@pytest.mark.parametrize("max_len", [8, 9, 12, 15, 16, 17, 40])
+def test_stream_kernel_token_length_tiers(sedd, max_len):
+    """The token hash has a path for rounds of tokens of at most 8 bytes, one for at most 16 and
+    a general one: corpora whose longest word is exactly at and around those limits, with all
+    byte values (UTF-8 letters, control characters) inside the words."""
+    say("stream token lengths up to", max_len)
+    rng = np.random.default_rng(max_len)
+    pool = np.array([c for c in range(256) if c not in (9, 10, 11, 12, 13, 32)], dtype=np.uint8)
+    docs = []
+    for _ in range(120):
+        lens = rng.integers(1, max_len + 1, size=int(rng.integers(1, 400)))
+        lens[rng.integers(0, lens.size)] = max_len            # every document reaches the limit
+        docs.append(b" ".join(bytes(rng.choice(pool, size=int(l))) for l in lens))
+    data, off = _pack(docs, lead=max_len % 16)
+    wx, woff = _oracle_x(docs, 3, False)
+    x, soff = sedd.debug_shingle_hashes(dev(data), dev(off), 3, 0)
+    assert np.array_equal(host(soff), woff) and np.array_equal(host(x), wx)
+    _check_minhash(sedd, data, off, 5, 64, seed=max_len, flags=0, procs=NPROC)
+
+
 def _token_with_hash(x, rng):
     """A whitespace-free byte string whose Eq. 1 value is x: random high digits, then the base-257
     expansion of what is left, retried until every digit is a usable byte."""
