@@ -89,3 +89,38 @@ def test_static_entry_point_limit_and_arguments():
     with pytest.raises(sedd.SeddError) as e:
         sedd.sedd_cluster_static(keys, out)
     assert e.value.code == -4
+
+
+def test_static_entry_point_under_graph_capture():
+    """The callers the entry point is for: sedd_lsh_keys + sedd_cluster_static captured into one
+    HIP graph and replayed on new inputs written into the same buffers, with eager work and
+    synchronisation between the replays; every replay against sedd_cluster run eagerly."""
+    import paper_2501_01046_amd as sedd
+    sedd.lib()
+    n, K, b, r = 40_000, 64, 8, 8
+    rng = np.random.default_rng(21)
+
+    def signatures(seed):
+        g = np.random.default_rng(seed)
+        proto = g.integers(0, 1 << 32, size=(n // 3, K), dtype=np.uint64).astype(np.uint32)
+        return torch.from_numpy(proto[g.integers(0, n // 3, size=n)].copy()).cuda()
+    sig = signatures(0)
+    keys = torch.empty((n, b), dtype=torch.uint64, device="cuda")
+    cid = torch.empty((n,), dtype=torch.int64, device="cuda")
+    # first call outside the capture: the one symbol look-up per device happens here
+    sedd.sedd_lsh_keys(sig, b, r, out=keys)
+    sedd.sedd_cluster_static(keys, cid)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sedd.sedd_lsh_keys(sig, b, r, out=keys)
+        sedd.sedd_cluster_static(keys, cid)
+    for seed in (1, 2, 3, 4):
+        print("static: graph replay", seed, flush=True)
+        sig.copy_(signatures(seed))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = cid.cpu().numpy().copy()
+        want = sedd.sedd_cluster(sedd.sedd_lsh_keys(sig, b, r)).cpu().numpy()     # eager, arena scratch
+        assert np.array_equal(got, want), seed
+        assert (want != np.arange(n)).sum() > n // 2
