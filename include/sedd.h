@@ -24,9 +24,14 @@
  *     kernels, which read doc_offsets only, before anything reads the text.
  *     `n_docs == 0` is a successful no-op that touches nothing.
  *   - Device scratch (chunk work lists, sort buffers, the union-find forest)
- *     lives in a grow-only allocation owned by the library, shared by all
- *     calls of the process: calls must not overlap in time on different
- *     streams.  sedd_release_scratch() frees it.
+ *     lives in a grow-only allocation owned by the library, shared by the
+ *     calls that use it: those must not overlap in time, neither on different
+ *     streams nor from different threads.  sedd_release_scratch() frees it.
+ *     Calls that do NOT use it may run concurrently from several threads on
+ *     several streams: sedd_minhash / sedd_minhash_bounded in the default mode
+ *     (word shingles, no mode flag; its coefficient tables are cached per
+ *     (K, seed) and read-only), sedd_lsh_keys, sedd_lsh_dense_keys, and
+ *     sedd_cluster_ws / sedd_cluster_verified_ws with a workspace per call.
  *   - All arithmetic is exact unsigned integer arithmetic; results do not
  *     depend on launch shape, chunking or timing.
  */

@@ -115,6 +115,8 @@ int scratch_ensure(uint64_t bytes, uint8_t **base);
 int pinned_ensure(uint64_t bytes, void **ptr);
 // Frees the device staging buffers of sedd_minhash_host_chunked (the device must be idle).
 int release_host_feed();
+// Frees the coefficient sets and probe records of the streaming min-hash path (device idle).
+int release_stream_state();
 
 // The fallback flag of the most recent clustering call (inside its workspace; debug read-out).
 // Forgotten when the arena it may point into is freed.

@@ -18,6 +18,8 @@
 //                     Eq. 2, into LDS.  Phase B (lane = hash function): the modular
 //                     multiply-add, truncation to 32 bits and running minimum.
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "sedd_internal.h"
@@ -1981,7 +1983,7 @@ __global__ void k_validate_offsets(const uint64_t *__restrict__ off, uint64_t n,
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   const uint64_t a = off[i], b = off[i + 1];
-  if (b < a || b - a >= max_doc) atomicOr(bad, 1u);
+  if (b < a || b - a >= max_doc) *bad = 1u;  // every writer stores the same value
 }
 
 __global__ void k_zero_u32(uint32_t *p) { *p = 0; }
@@ -2015,6 +2017,120 @@ __global__ void k_stream_soff(const uint64_t *__restrict__ off, uint64_t n_docs,
 // The default mode of sedd_minhash (word shingles, 61-bit modulus, affine family): validation,
 // coefficients, the signature fill and one launch of k_minhash_stream.  One host wait, for the
 // first and last offset and the validity flag.  With dbg_off the two debug passes run instead.
+// ---- state of the streaming path that calls on different streams and threads may share --------
+//
+// Coefficient sets: the K coefficients of a seed (64-bit values and limb form) with the tables
+// 257^i and the per-length Horner multipliers behind them, written once by k_coeffs and only
+// read afterwards.  A set is created on the stream of the call that first asks for it; a call on
+// another stream waits for the creating kernel through an event until that event has been seen
+// complete.  Probe slots: a small ring of pinned host records that the offset probe and the
+// validation kernel write directly, one per call in flight.
+struct TableSet {
+  int K;
+  uint64_t seed;
+  uint8_t *dev;
+  hipEvent_t ready;
+  bool settled;
+};
+constexpr size_t MAX_TABLE_SETS = 16;
+constexpr uint32_t PROBE_SLOTS = 64;
+struct ProbeSlot {
+  uint64_t off0, offn;
+  uint32_t bad, pad[3];
+};
+static std::mutex g_stream_mutex;
+static std::vector<TableSet> g_table_sets;
+static ProbeSlot *g_probe_ring = nullptr;
+static std::atomic<uint32_t> g_probe_next{0};
+
+struct TablePtrs {
+  uint64_t *coef_a, *coef_b, *qpow;
+  CoefSplit *coef_s;
+  PowSplit *ptab;
+};
+
+static int tables_acquire(int K, uint64_t seed, hipStream_t st, TablePtrs *out) {
+  std::lock_guard<std::mutex> lock(g_stream_mutex);
+  Carver cv;
+  const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
+  const uint64_t o_cs = cv.take<CoefSplit>(K);
+  const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
+  const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
+  auto bind = [&](uint8_t *A) {
+    out->coef_a = (uint64_t *)(A + o_a);
+    out->coef_b = (uint64_t *)(A + o_b);
+    out->coef_s = (CoefSplit *)(A + o_cs);
+    out->qpow = (uint64_t *)(A + o_qpow);
+    out->ptab = (PowSplit *)(A + o_ptab);
+  };
+  for (TableSet &t : g_table_sets) {
+    if (t.K != K || t.seed != seed) continue;
+    if (!t.settled) {
+      if (hipEventQuery(t.ready) == hipSuccess) t.settled = true;
+      else SEDD_HIP(hipStreamWaitEvent(st, t.ready, 0));
+      (void)hipGetLastError();  // hipEventQuery reports "not ready" as an error value
+    }
+    bind(t.dev);
+    return SEDD_OK;
+  }
+  if (g_table_sets.size() >= MAX_TABLE_SETS) {
+    // rare: more distinct (K, seed) pairs than slots; start over once nothing can still read them
+    SEDD_HIP(hipDeviceSynchronize());
+    for (TableSet &t : g_table_sets) {
+      (void)hipFree(t.dev);
+      (void)hipEventDestroy(t.ready);
+    }
+    g_table_sets.clear();
+  }
+  TableSet t;
+  t.K = K;
+  t.seed = seed;
+  t.settled = false;
+  void *p = nullptr;
+  if (hipMalloc(&p, cv.off) != hipSuccess) {
+    (void)hipGetLastError();
+    return SEDD_ENOMEM;
+  }
+  t.dev = (uint8_t *)p;
+  bind(t.dev);
+  hipLaunchKernelGGL(k_coeffs, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, K,
+                     out->coef_a, out->coef_b, out->coef_s, out->qpow, out->ptab);
+  SEDD_LAUNCH_CHECK();
+  SEDD_HIP(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
+  SEDD_HIP(hipEventRecord(t.ready, st));
+  g_table_sets.push_back(t);
+  return SEDD_OK;
+}
+
+static int probe_slot_acquire(ProbeSlot **slot) {
+  {
+    std::lock_guard<std::mutex> lock(g_stream_mutex);
+    if (!g_probe_ring) {
+      void *p = nullptr;
+      if (hipHostMalloc(&p, PROBE_SLOTS * sizeof(ProbeSlot), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        return SEDD_ENOMEM;
+      }
+      g_probe_ring = (ProbeSlot *)p;
+    }
+  }
+  *slot = g_probe_ring + (g_probe_next.fetch_add(1) % PROBE_SLOTS);
+  return SEDD_OK;
+}
+
+// frees the coefficient sets and the probe ring (the device must be idle)
+int release_stream_state() {
+  std::lock_guard<std::mutex> lock(g_stream_mutex);
+  for (TableSet &t : g_table_sets) {
+    (void)hipFree(t.dev);
+    (void)hipEventDestroy(t.ready);
+  }
+  g_table_sets.clear();
+  if (g_probe_ring) (void)hipHostFree(g_probe_ring);
+  g_probe_ring = nullptr;
+  return SEDD_OK;
+}
+
 // host_ends: {doc_offsets[0], doc_offsets[n_docs]} when the caller has the offsets on the host and
 // has validated them there (then nothing waits on the device); nullptr otherwise.
 static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
@@ -2023,38 +2139,27 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
                               const uint64_t *host_ends = nullptr) {
   const bool debug = dbg_off != nullptr;
   const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
-  Carver cv;
-  const uint64_t o_probe = cv.take<uint64_t>(4);
-  const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
-  const uint64_t o_cs = cv.take<CoefSplit>(K);
-  const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
-  const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
-  const uint64_t fixed_bytes = cv.off;
-  uint8_t *A = nullptr;
-  int rc = scratch_ensure(fixed_bytes, &A);
-  if (rc) return rc;
+  int rc;
   uint64_t off0, offn;
   if (host_ends) {
     off0 = host_ends[0];
     offn = host_ends[1];
   } else {
-    void *pin = nullptr;
-    rc = pinned_ensure(64, &pin);
+    // the probe and the validation kernel write straight into a pinned host record
+    ProbeSlot *slot = nullptr;
+    rc = probe_slot_acquire(&slot);
     if (rc) return rc;
-    uint64_t *d_probe = (uint64_t *)(A + o_probe);
-    uint32_t *d_bad = (uint32_t *)(d_probe + 2);
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(1), 0, st, d_bad);
-    SEDD_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, d_probe);
+    slot->off0 = slot->offn = 0;
+    slot->bad = 0;
+    hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, &slot->off0);
     SEDD_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
-                       doc_offsets, n_docs, max_doc, d_bad);
+                       doc_offsets, n_docs, max_doc, &slot->bad);
     SEDD_LAUNCH_CHECK();
-    SEDD_HIP(hipMemcpyAsync(pin, d_probe, 24, hipMemcpyDeviceToHost, st));
     SEDD_HIP(hipStreamSynchronize(st));
-    off0 = ((const uint64_t *)pin)[0];
-    offn = ((const uint64_t *)pin)[1];
-    if (((const uint32_t *)pin)[4]) return SEDD_EINVAL;
+    off0 = slot->off0;
+    offn = slot->offn;
+    if (slot->bad) return SEDD_EINVAL;
   }
   if (offn < off0 || offn > n_bytes) return SEDD_EINVAL;
   if (offn > off0 && !bytes) return SEDD_EINVAL;
@@ -2080,24 +2185,25 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
   const uint64_t n_pieces = offn > off0 ? (sa.frame_end + piece - 1) / piece : 0;
   if (n_pieces >= (uint64_t(1) << 31)) return SEDD_EINVAL;
 
+  TablePtrs tp;
+  rc = tables_acquire((int)K, seed, st, &tp);
+  if (rc) return rc;
+  uint64_t *coef_a = tp.coef_a;
+  CoefSplit *coef_s = tp.coef_s;
+  sa.qpow = tp.qpow;
+  sa.ptab = tp.ptab;
+  // the two debug passes keep their counters in the arena (they are not meant to run concurrently)
+  Carver cv;
   uint64_t o_pc = 0, o_dp = 0, o_dl = 0, o_tmp = 0;
+  uint8_t *A = nullptr;
   if (debug) {
     o_pc = cv.take<uint32_t>(n_pieces + 1);
     o_dp = cv.take<uint32_t>(n_docs);
     o_dl = cv.take<uint32_t>(n_docs);
     o_tmp = cv.take<uint32_t>(scan_tmp_count(n_pieces + 1));
-    rc = scratch_ensure(cv.off, &A);  // may move the arena: nothing in it is live yet
+    rc = scratch_ensure(cv.off, &A);
     if (rc) return rc;
   }
-  uint64_t *coef_a = (uint64_t *)(A + o_a), *coef_b = (uint64_t *)(A + o_b);
-  CoefSplit *coef_s = (CoefSplit *)(A + o_cs);
-  uint64_t *qpow = (uint64_t *)(A + o_qpow);
-  PowSplit *ptab = (PowSplit *)(A + o_ptab);
-  sa.qpow = qpow;
-  sa.ptab = ptab;
-  hipLaunchKernelGGL(k_coeffs, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, (int)K,
-                     coef_a, coef_b, coef_s, qpow, ptab);
-  SEDD_LAUNCH_CHECK();
   const HotConsts hc = {1u << 29, 8u, 1u};
   StreamDebug dbg = {};
 

@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "sedd_internal.h"
@@ -79,8 +80,10 @@ int pinned_ensure(uint64_t bytes, void **ptr) {
 // ---- persistent device counters ------------------------------------------------------------
 
 static unsigned long long *g_stats = nullptr;
+static std::mutex g_small_state_mutex;  // the counters' allocation and the list of timed spans
 
 int stats_ensure(unsigned long long **p) {
+  std::lock_guard<std::mutex> lock(g_small_state_mutex);
   if (!g_stats) {
     void *q = nullptr;
     hipError_t e = hipMalloc(&q, SEDD_STAT_N * sizeof(unsigned long long));
@@ -118,6 +121,7 @@ static hipEvent_t prof_event() {
 
 ProfScope::ProfScope(int label, hipStream_t st) : st_(st), idx_(-1) {
   if (!g_prof_on || label < 0) return;  // a negative label: this scope is not timed
+  std::lock_guard<std::mutex> lock(g_small_state_mutex);
   ProfSpan sp{label, prof_event(), prof_event()};
   if (!sp.e0 || !sp.e1) return;
   (void)hipEventRecord(sp.e0, st);
@@ -125,7 +129,9 @@ ProfScope::ProfScope(int label, hipStream_t st) : st_(st), idx_(-1) {
   idx_ = (int)g_spans.size() - 1;
 }
 ProfScope::~ProfScope() {
-  if (idx_ >= 0) (void)hipEventRecord(g_spans[idx_].e1, st_);
+  if (idx_ < 0) return;
+  std::lock_guard<std::mutex> lock(g_small_state_mutex);
+  if (idx_ < (int)g_spans.size()) (void)hipEventRecord(g_spans[idx_].e1, st_);
 }
 
 // ---- exclusive scan ----------------------------------------------------------------------
@@ -276,7 +282,9 @@ int sedd_release_scratch(void) {
     g_pinned = nullptr;
     g_pinned_bytes = 0;
   }
-  return release_host_feed();
+  int rc = release_host_feed();
+  if (rc) return rc;
+  return release_stream_state();
 }
 
 uint64_t sedd_scratch_bytes(void) { return g_arena_bytes; }
@@ -292,6 +300,7 @@ int sedd_profile_read(double *ms, uint64_t *spans) {
     ms[i] = 0.0;
     spans[i] = 0;
   }
+  std::lock_guard<std::mutex> lock(g_small_state_mutex);
   for (ProfSpan &sp : g_spans) {
     SEDD_HIP(hipEventSynchronize(sp.e1));
     float t = 0.f;

@@ -936,6 +936,44 @@ def test_minhash_from_host_memory_in_chunks(sedd, flags, n):
     assert e.value.code == -1
 
 
+def test_minhash_default_mode_from_four_threads_on_four_streams(sedd):
+    """The default mode keeps no mutable shared scratch: four threads, a stream each, different
+    corpora, K and seeds, several calls per thread in flight together; every result against the
+    oracle.  More (K, seed) pairs than the coefficient cache holds are cycled through first."""
+    import threading
+    say("minhash concurrent")
+    for s_ in range(20):                                    # overflow the cache of coefficient sets
+        data, off = corpus.generate(corpus.config(1).scaled(40))
+        _check_minhash(sedd, data, off, 5, 8, seed=1000 + s_, flags=0)
+    jobs = []
+    for t in range(4):
+        r = corpus.config(1).scaled(2500 + 400 * t, seed=50 + t)
+        data, off = corpus.generate(r)
+        K, seed, n = (64, 128, 200, 256)[t], 7 * t, (5, 3, 5, 2)[t]
+        jobs.append((data, off, n, K, seed, oracle.minhash_sharded(data, off, n, K, seed, 0, procs=NPROC)))
+    errors = []
+
+    def work(t):
+        try:
+            data, off, n, K, seed, want = jobs[t]
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                d_data, d_off = dev(data), dev(off)
+                for rep in range(6):
+                    got = sedd.sedd_minhash(d_data, d_off, n, K, seed, 0, stream=st)
+                    st.synchronize()
+                    if not np.array_equal(host(got), want):
+                        errors.append((t, rep))
+        except Exception as e:                              # surfaced in the main thread
+            errors.append((t, repr(e)))
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+
+
 def test_minhash_rejects_offsets_beyond_the_text(sedd):
     """The binding passes the size of the text: offsets that point past it are refused before
     any kernel follows them."""
