@@ -1,22 +1,21 @@
 // sedd_minhash: shingling, Eq. 1 base hash, K hash functions and per-document minimum.
 //
-// Default mode (word shingles, 61-bit modulus, affine family): k_minhash_stream, one launch that
-// reads the text once; see the comment above that kernel.
+// Word shingles with the affine family (the default 61-bit modulus and the paper's own prime):
+// k_minhash_stream, one launch that reads the text once; see the comment above that kernel.
 //
-// Byte shingles and the two alternative hash-function modes run per chunk of consecutive
-// documents (all on the caller's stream, no host waits inside the loop):
+// Byte shingles and the rolling-family mode run per chunk of consecutive documents (all on the
+// caller's stream, no host waits inside the loop):
 //   1. byte tiles     each non-empty document is cut into 1 KiB tiles aligned to 16-byte
 //                     addresses; a scan over per-document tile counts builds the work list.
-//   2. words          (word mode) one wavefront per byte tile marks token starts from a 16-byte
-//                     vector load per lane and counts them; after a scan a second pass writes
-//                     one record per token (its Eq. 1 hash modulo the paper's prime, or its
-//                     position) and the length.
+//   2. words          (rolling family on word shingles) one wavefront per byte tile marks token
+//                     starts from a 16-byte vector load per lane and counts them; after a scan a
+//                     second pass writes position and length of every token.
 //   3. shingle tiles  per-document shingle counts, scanned into shingle offsets and a second
 //                     work list of tiles of TS shingles.
 //   4. min-hash       one wavefront per shingle tile.  Phase A (lane = shingle): x(s) of Eq. 1
-//                     from the token records or from the tile's bytes with the reuse form of
-//                     Eq. 2, into LDS.  Phase B (lane = hash function): the modular
-//                     multiply-add, truncation to 32 bits and running minimum.
+//                     from the tile's bytes with the reuse form of Eq. 2, into LDS.  Phase B
+//                     (lane = hash function): the modular multiply-add, truncation to 32 bits
+//                     and running minimum.  (Rolling family: lane = function throughout.)
 #include <algorithm>
 #include <atomic>
 #include <mutex>
@@ -53,15 +52,15 @@ struct CoefSplit {
   uint64_t b;
 };
 
-// Token records, structure of arrays: tok_v[i] = Eq. 1 hash of "token 0x20" = W + 32 * 257^len,
-// tok_len[i] = min(len, 255); a token of 255 bytes or more keeps its length in tok_long[i]
-// (written and read only for such tokens).
+// Token records of the rolling-family mode, structure of arrays: pos[i] = position of token i in
+// the chunk frame, len[i] = min(length, 255); a token of 255 bytes or more keeps its length in
+// long_len[i] (written and read only for such tokens).
 struct TokenRecs {
-  uint64_t *v;
+  uint32_t *pos;
   uint8_t *len;
   uint32_t *long_len;
 };
-constexpr uint32_t LONG_TOKEN = 255;
+constexpr uint32_t LONG_TOKEN = 255;  // token lengths from here on take the general shingle hash
 
 
 // Per token length l < QPOW_N, what one Horner step over token records multiplies by:
@@ -81,6 +80,9 @@ __device__ __forceinline__ uint64_t qpow_global(const uint64_t *__restrict__ qpo
 // Section 3.2 quotes p' = 4,294,967 as the modulus of Eq. 1 in the paper's experiments.  p' is
 // not a Mersenne prime, so a product is reduced through an estimate of its quotient.
 constexpr uint32_t PP = 4294967u;
+// a quotient estimate of the hash loops is off by one only for remainders this close to p' (see
+// k_minhash_pp)
+constexpr uint32_t PP_EDGE = 4400;  // > p' (p' + 2) / 2^32 = 4295.0
 
 // t mod p' for t < 2^46.  With T = t >> 14 (< 2^32) and M = floor(2^46 / p'), floor(T M / 2^32)
 // is the quotient or up to 2 below it; the remainder estimate then lies in [0, 3 p') (< 2^24).
@@ -115,20 +117,9 @@ struct PowPP {
   uint32_t pw1, sp;
 };
 
-__device__ __forceinline__ void store_token_pp(const TokenRecs &tr, uint32_t idx, uint32_t w,
-                                               uint32_t len, const PowPP *__restrict__ ptab) {
-  const uint32_t sp = len < (uint32_t)QPOW_N ? ptab[len].sp : mulmod_pp(32u, powmod_pp(257u, len));
-  uint32_t v = w + sp;
-  v = min(v, v - PP);
-  reinterpret_cast<uint32_t *>(tr.v)[idx] = v;  // this mode keeps 32-bit token values
-  tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
-  if (len >= LONG_TOKEN) tr.long_len[idx] = len;
-}
-
-// position record of the rolling-family mode (32-bit values, like the paper-prime records)
 __device__ __forceinline__ void store_token_pos(const TokenRecs &tr, uint32_t idx, uint32_t pos,
                                                 uint32_t len) {
-  reinterpret_cast<uint32_t *>(tr.v)[idx] = pos;
+  tr.pos[idx] = pos;
   tr.len[idx] = (uint8_t)(len < LONG_TOKEN ? len : LONG_TOKEN);
   if (len >= LONG_TOKEN) tr.long_len[idx] = len;
 }
@@ -406,74 +397,40 @@ __device__ __forceinline__ uint64_t horner3_lazy(uint64_t acc, uint32_t D) {
   return (((hi & 0x1FFFFFFFull) << 32) | (uint32_t)lo) + (hi >> 29);
 }
 
-// A token that the tile's wavefront cannot finish from LDS (64 bytes or more, or running past
-// the look-ahead): Eq. 1 byte by byte from global memory, w = sum c_i 257^i.
+// A token that a wavefront cannot finish from the LDS copy of its tile (64 bytes or more, or
+// running past the look-ahead) is walked byte by byte in global memory.
 struct WalkedToken {
-  uint64_t w;
+  uint64_t w;  // Eq. 1 of the token, w = sum c_i 257^i
   uint32_t len;
 };
-__device__ __noinline__ WalkedToken walk_token(const uint8_t *__restrict__ pbase, uint32_t p0,
-                                               uint32_t ve) {
-  uint64_t w = 0, pw = 1;
-  uint32_t l = 0;
-  for (uint32_t p = p0; p < ve; p++) {
-    const uint32_t c = pbase[p];
-    if (is_ws(c)) break;
-    w = addmod(w, mulmod(pw, (uint64_t)c));
-    pw = mul257(pw);
-    l++;
-  }
-  WalkedToken r;
-  r.w = w;
-  r.len = l;
-  return r;
-}
 
-// the same modulo the paper's prime (w in the low word)
-__device__ __noinline__ WalkedToken walk_token_pp(const uint8_t *__restrict__ pbase, uint32_t p0,
+// bytes from position p0 up to the first whitespace byte or the document's end ve
+__device__ __noinline__ uint32_t token_length_far(const uint8_t *__restrict__ pbase, uint32_t p0,
                                                   uint32_t ve) {
-  uint32_t w = 0, pw = 1, l = 0;
-  for (uint32_t p = p0; p < ve; p++) {
-    const uint32_t c = pbase[p];
-    if (is_ws(c)) break;
-    w = red_pp((uint64_t)pw * c + w);
-    pw = mulmod_pp(pw, 257u);
-    l++;
-  }
-  WalkedToken r;
-  r.w = w;
-  r.len = l;
-  return r;
+  uint32_t p = p0;
+  while (p < ve && !is_ws(pbase[p])) p++;
+  return p - p0;
 }
 
-// One wavefront per byte tile.
-// Pass 1 (lane = 16-byte segment): the tile's bytes, plus LOOK bytes of look-ahead, go to LDS
-// together with the bitmap of token bytes; every lane drops the positions of the tokens that
-// start in its segment into LDS at their rank within the tile.
-// Pass 2 (lane = token): the token's length is the run of ones in the bitmap from its position;
-// its Eq. 1 hash is a Horner chain over 3-byte digits read from the LDS copy, last digit first,
-// the same number of steps for the whole wavefront (lanes with shorter tokens feed zero digits
-// first, which leave the accumulator at zero).  Then V = W + 32 * 257^len and the record is
-// stored; consecutive lanes store consecutive records.
 constexpr uint32_t LOOK = 16;
 constexpr uint32_t MAX_TILE_TOKENS = TB / 2 + 2;
-constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token pass 2 finishes from LDS
-
+constexpr uint32_t FAST_TOKEN_MAX = 63;  // longest token finished from LDS
+// text in LDS: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
+// than the wavefront's longest
 constexpr uint32_t SM_TEXT_WORDS = (TB + LOOK + FAST_TOKEN_MAX + 9) / 4 + 2;
 
-// EM selects what a record holds beside the length: the token's Eq. 1 hash modulo the paper's
-// prime as a 32-bit value (EM_PP), or the token's position in the chunk frame as a 32-bit value
-// (EM_POS, for the mode whose functions hash the bytes themselves).  The default mode (61-bit
-// modulus) keeps no token records in memory: see k_minhash_stream.
-enum { EM_PP = 1, EM_POS = 2 };
-template <int EM>
+// Token records of the rolling-family mode, whose functions hash the bytes themselves: position
+// in the chunk frame and length of every token.  One wavefront per byte tile.
+// Pass 1 (lane = 16-byte segment): the bitmap of token bytes of the tile plus LOOK bytes of
+// look-ahead goes to LDS; every lane drops the positions of the tokens that start in its segment
+// into LDS at their rank within the tile.
+// Pass 2 (lane = token): the token's length is the run of ones in the bitmap from its position;
+// consecutive lanes store consecutive records.
+// (The other word-shingle modes keep no token records in memory: see k_minhash_stream.)
 __global__ void __launch_bounds__(TB_LANES)
 k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
              const uint32_t *__restrict__ n_tiles, const uint32_t *__restrict__ wbase,
-             const PowPP *__restrict__ ptab_pp, TokenRecs rec) {
-  // text: tile + look-ahead + slack for the (masked) reads of lanes whose token is shorter
-  // than the wavefront's longest
-  __shared__ uint32_t sm_text[SM_TEXT_WORDS];
+             TokenRecs rec) {
   __shared__ uint32_t sm_bits[TB / 32 + 4];  // token-byte bitmap: tile, look-ahead, zero pad
   __shared__ uint16_t sm_pos[MAX_TILE_TOKENS];
   const uint32_t lane = threadIdx.x;
@@ -483,114 +440,50 @@ k_emit_words(const uint8_t *__restrict__ pbase, const BTile *__restrict__ tiles,
   const BTile bt = tiles[t];
   const uint32_t first_idx = wbase[t];
   if (t >= *n_tiles) return;
+  const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
+  const uint4 q_own = load_raw16(pbase, tile0 + lane * 16, vs, ve);
+  const uint4 q_la = load_raw16(pbase, tile0 + TB, vs, ve);  // wave-uniform: scalar loads
+  const uint32_t prev_byte = load_prev_byte(pbase, tile0, vs, ve);
+  const Segment sg = make_segment(q_own, tile0 + lane * 16, vs, ve);
+  const Segment la = make_segment(q_la, tile0 + TB, vs, ve);
+  const uint32_t starts0 = token_starts(lane, prev_byte, sg.wm);
+
+  // wave_shl:1 (lane l reads lane l + 1; the last lane gets 0)
+  const uint32_t wm_up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sg.wm, 0x130, 0xF, 0xF, false);
+  if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
+  if (lane == 0) {
+    sm_bits[TB / 32] = la.wm;
+    sm_bits[TB / 32 + 1] = 0;
+    sm_bits[TB / 32 + 2] = 0;
+  }
+  const uint32_t cnt = __popc(starts0);
+  const uint32_t inc = wave_inclusive_scan(cnt);
+  const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
   {
-    const uint32_t vs = bt.vs, ve = bt.ve, tile0 = bt.tile0;
-    const uint4 q_own = load_raw16(pbase, tile0 + lane * 16, vs, ve);
-    const uint4 q_la = load_raw16(pbase, tile0 + TB, vs, ve);  // wave-uniform: scalar loads
-    const uint32_t prev_byte = load_prev_byte(pbase, tile0, vs, ve);
-    const Segment sg = make_segment(q_own, tile0 + lane * 16, vs, ve);
-    const Segment la = make_segment(q_la, tile0 + TB, vs, ve);
-    const uint32_t starts0 = token_starts(lane, prev_byte, sg.wm);
+    uint32_t st = starts0, j = inc - cnt;
+    while (st) {
+      const uint32_t bit = __ffs(st) - 1;
+      sm_pos[j++] = (uint16_t)(lane * 16 + bit);
+      st &= st - 1;
+    }
+  }
+  __syncthreads();
 
-    *reinterpret_cast<uint4 *>(&sm_text[lane * 4]) = q_own;
-    // wave_shl:1 (lane l reads lane l + 1; the last lane gets 0)
-    const uint32_t wm_up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)sg.wm, 0x130, 0xF, 0xF, false);
-    if (!(lane & 1)) sm_bits[lane >> 1] = sg.wm | (wm_up << 16);
-    if (lane == 0) {
-      *reinterpret_cast<uint4 *>(&sm_text[TB / 4]) = q_la;
-      sm_bits[TB / 32] = la.wm;
-      sm_bits[TB / 32 + 1] = 0;
-      sm_bits[TB / 32 + 2] = 0;
-    }
-    const uint32_t cnt = __popc(starts0);
-    const uint32_t inc = wave_inclusive_scan(cnt);
-    const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
-    {
-      uint32_t st = starts0, j = inc - cnt;
-      while (st) {
-        const uint32_t bit = __ffs(st) - 1;
-        sm_pos[j++] = (uint16_t)(lane * 16 + bit);
-        st &= st - 1;
-      }
-    }
-    __syncthreads();
-
-    // does the document end inside what the LDS copy covers?
-    const bool doc_ends_in_view = tile0 + TB + LOOK >= ve;
-    for (uint32_t base = 0; base < tot; base += TB_LANES) {
-      const uint32_t j = base + lane;
-      const bool active = j < tot;
-      const uint32_t pos = active ? sm_pos[j] : 0u;
-      // 64 bitmap bits from the token's first byte on
-      const uint32_t dw = pos >> 5, sh = pos & 31;
-      const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
-      const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
-      const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
-      const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
-      const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
-      // the run ends at a real non-token byte (or at the document's end) inside the LDS copy
-      const bool fast =
-          active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
-      const uint32_t flen = fast ? run : 0u;
-      uint64_t acc = 0;
-      uint32_t acc_pp = 0;
-      constexpr uint32_t R3_PP = R3 % PP;
-      // acc <- acc * 257^3 + D in the mode's modulus
-      auto absorb = [&](uint32_t D) {
-        if (EM == EM_PP) acc_pp = red_pp((uint64_t)acc_pp * R3_PP + D);  // < 2^45 + 2^25
-        else acc = horner3_lazy(acc, D);
-      };
-      if (!__any(flen > 8)) {
-        // every token of this pass has at most 8 bytes: one 12-byte read, three digits
-        const uint32_t wd = pos >> 2;
-        const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2];
-        const uint64_t keep = ~0ull >> ((64u - 8u * flen) & 63u);  // flen >= 1 where it matters
-        const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, pos & 3u) & (uint32_t)keep;
-        const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, pos & 3u) & (uint32_t)(keep >> 32);
-        const uint32_t d0 = a0 & 0xFFFFFFu;
-        const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
-        const uint32_t d2 = a1 >> 16;
-        const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
-        const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
-        const uint32_t D2 = d2 + (d2 >> 8);
-        if (EM == EM_PP) {
-          acc_pp = D2;  // < 2^17
-          absorb(D1);
-        } else {
-          acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
-        }
-        absorb(D0);
-      } else {
-        const uint32_t nd = (flen + 2) / 3;
-        uint32_t maxnd = nd;
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
-        maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
-        for (uint32_t k = maxnd; k-- > 0;) {
-          const int rem = (int)flen - (int)(3 * k);  // bytes of the token from digit k on
-          const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
-          const uint32_t m = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
-          const uint32_t off = pos + 3 * k;
-          const uint32_t lo = sm_text[off >> 2], hi = sm_text[(off >> 2) + 1];
-          const uint32_t d = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & m;
-          // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
-          const uint32_t D = d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
-          absorb(D);
-        }
-      }
-      uint64_t w = EM == EM_PP ? (uint64_t)acc_pp : fold61(acc);
-      uint32_t len = flen;
-      if (active && !fast) {
-        const WalkedToken wt = EM == EM_PP ? walk_token_pp(pbase, tile0 + pos, ve)
-                                           : walk_token(pbase, tile0 + pos, ve);
-        w = wt.w;
-        len = wt.len;
-      }
-      if (active) {
-        if (EM == EM_PP) store_token_pp(rec, first_idx + j, (uint32_t)w, len, ptab_pp);
-        else store_token_pos(rec, first_idx + j, tile0 + pos, len);  // EM_POS: only the length is used
-      }
-    }
+  // does the document end inside what the bitmap covers?
+  const bool doc_ends_in_view = tile0 + TB + LOOK >= ve;
+  for (uint32_t j = lane; j < tot; j += TB_LANES) {
+    const uint32_t pos = sm_pos[j];
+    // 64 bitmap bits from the token's first byte on
+    const uint32_t dw = pos >> 5, sh = pos & 31;
+    const uint32_t b0 = sm_bits[dw], b1 = sm_bits[dw + 1], b2 = sm_bits[dw + 2];
+    const uint32_t w_lo = __builtin_amdgcn_alignbit(b1, b0, sh);
+    const uint32_t w_hi = __builtin_amdgcn_alignbit(b2, b1, sh);
+    const uint64_t zeros = ~(((uint64_t)w_hi << 32) | w_lo);
+    const uint32_t run = zeros ? (uint32_t)(__ffsll((unsigned long long)zeros) - 1) : 64u;
+    // the run ends at a real non-token byte (or at the document's end) inside the bitmap
+    const bool seen = run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
+    const uint32_t len = seen ? run : token_length_far(pbase, tile0 + pos, ve);
+    store_token_pos(rec, first_idx + j, tile0 + pos, len);
   }
 }
 
@@ -629,23 +522,17 @@ struct XSource {
   const uint8_t *pbase;   // chunk text frame (byte mode)
   const uint32_t *dv;     // document frame positions (byte mode)
   const uint32_t *sbase;  // shingle offsets per document (byte mode)
-  TokenRecs rec;          // token records (word mode)
   const uint64_t *qpow;   // 257^i, i < QPOW_N
-  const PowPP *ptab_pp;   // Horner multipliers per token length (paper-prime mode), QPOW_N entries
+  const PowPP *ptab_pp;   // powers of 257 modulo the paper's prime, QPOW_N entries
   const uint64_t *given;  // caller-supplied hashes (debug entry), indexed like the shingle stream
   uint32_t n;             // shingle length
 };
-enum { X_WORDS = 0, X_BYTES = 1, X_GIVEN = 2 };
-
-__device__ __forceinline__ uint32_t token_len(const TokenRecs &rec, uint32_t i) {
-  uint32_t l = rec.len[i];
-  if (l == LONG_TOKEN) l = rec.long_len[i];
-  return l;
-}
+// word shingles are hashed by k_minhash_stream from its token ring (or, in the rolling-family mode,
+// by k_minhash_rf_words from the bytes)
+enum { X_BYTES = 1, X_GIVEN = 2 };
 
 // x of shingle i of tile ht, 61-bit modulus: a caller-supplied value, or Horner over the window's
-// bytes from the last to the first.  (Word shingles of this modulus are hashed by
-// k_minhash_stream from its token ring.)
+// bytes from the last to the first
 template <int MODE>
 __device__ __forceinline__ uint64_t shingle_x(const XSource &xsrc, const HTile &ht, uint32_t i) {
   static_assert(MODE == X_GIVEN || MODE == X_BYTES, "word shingles take the streaming kernel");
@@ -837,9 +724,10 @@ k_minhash(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__restr
   }
 }
 
-// ---- the streaming kernel (word shingles, 61-bit modulus) ----------------------------------------
+// ---- the streaming kernel (word shingles, affine family) ------------------------------------------
 //
-// The whole of sedd_minhash in one launch, for the default mode: the text is read from HBM once,
+// The whole of sedd_minhash in one launch, for the default mode and the paper-prime mode (the
+// template argument A holds what depends on the modulus): the text is read from HBM once,
 // nothing but the signatures is written, and there is no work list.  The text (a frame that
 // starts on a 16-byte boundary at or below document 0) is cut into pieces of `piece` bytes; one
 // wavefront owns the tokens that START inside its piece, in document order, and with them the
@@ -870,8 +758,6 @@ struct StreamArgs {
   uint64_t frame_end;     // frame position of the end of the last document
   uint32_t piece;         // bytes per wavefront, a multiple of TB
   uint32_t n;             // shingle length
-  const uint64_t *qpow;   // 257^i, i < QPOW_N
-  const PowSplit *ptab;   // Horner multipliers per token length
 };
 
 // what the kernel does with a shingle hash: evaluate the K functions (production), count, or
@@ -885,73 +771,6 @@ struct StreamDebug {
   uint64_t x_cap;         //           entries of x
   uint64_t x_base;        //           index of this call's first shingle
 };
-
-// Eq. 1 of a token of flen <= FAST_TOKEN_MAX bytes at byte `pos` of the LDS copy of a tile
-// (flen = 0 for an idle lane), lazily reduced: Horner over 3-byte digits, last digit first.
-// Must be called by the whole wavefront.
-__device__ __forceinline__ uint64_t lds_token_hash(const uint32_t *sm_text, uint32_t pos,
-                                                   uint32_t flen) {
-  uint64_t acc;
-  if (!__any(flen > 8)) {
-    // every token of this round has at most 8 bytes: one 12-byte read, three digits
-    const uint32_t wd = pos >> 2;
-    const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2];
-    const uint64_t keep = ~0ull >> ((64u - 8u * flen) & 63u);  // flen >= 1 where it matters
-    const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, pos & 3u) & (uint32_t)keep;
-    const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, pos & 3u) & (uint32_t)(keep >> 32);
-    const uint32_t d0 = a0 & 0xFFFFFFu;
-    const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
-    const uint32_t d2 = a1 >> 16;
-    const uint32_t D0 = d0 + ((d0 >> 8) & 0xFFu) + 513u * (d0 >> 16);
-    const uint32_t D1 = d1 + ((d1 >> 8) & 0xFFu) + 513u * (d1 >> 16);
-    const uint32_t D2 = d2 + (d2 >> 8);
-    acc = (uint64_t)D2 * R3 + D1;  // exact, below 2^42
-    acc = horner3_lazy(acc, D0);
-  } else if (!__any(flen > 16)) {
-    // at most 16 bytes (ordinary prose): one 20-byte read, five digits and a byte, no loop
-    const uint32_t wd = pos >> 2, sh = pos & 3u;
-    const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2], t3 = sm_text[wd + 3],
-                   t4 = sm_text[wd + 4];
-    // bytes 0..7 and 8..15 of the token, those past its end cleared
-    const uint32_t l_lo = min(flen, 8u), l_hi = flen - l_lo;
-    const uint64_t keep_lo = l_lo ? ~0ull >> (64u - 8u * l_lo) : 0ull;
-    const uint64_t keep_hi = l_hi ? ~0ull >> (64u - 8u * l_hi) : 0ull;
-    const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, sh) & (uint32_t)keep_lo;
-    const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, sh) & (uint32_t)(keep_lo >> 32);
-    const uint32_t a2 = __builtin_amdgcn_alignbyte(t3, t2, sh) & (uint32_t)keep_hi;
-    const uint32_t a3 = __builtin_amdgcn_alignbyte(t4, t3, sh) & (uint32_t)(keep_hi >> 32);
-    // three-byte digits: bytes 0-2, 3-5, 6-8, 9-11, 12-14, and byte 15
-    const uint32_t d0 = a0 & 0xFFFFFFu;
-    const uint32_t d1 = __builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu;
-    const uint32_t d2 = __builtin_amdgcn_alignbyte(a2, a1, 2u) & 0xFFFFFFu;
-    const uint32_t d3 = __builtin_amdgcn_alignbyte(a3, a2, 1u) & 0xFFFFFFu;
-    const uint32_t d4 = a3 & 0xFFFFFFu;
-    auto digit = [](uint32_t d) { return d + ((d >> 8) & 0xFFu) + 513u * (d >> 16); };
-    acc = (uint64_t)(a3 >> 24) * R3 + digit(d4);  // exact, below 2^33
-    acc = horner3_lazy(acc, digit(d3));
-    acc = horner3_lazy(acc, digit(d2));
-    acc = horner3_lazy(acc, digit(d1));
-    acc = horner3_lazy(acc, digit(d0));
-  } else {
-    acc = 0;
-    const uint32_t nd = (flen + 2) / 3;
-    uint32_t maxnd = nd;
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
-    maxnd = (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
-    for (uint32_t k = maxnd; k-- > 0;) {
-      const int rem = (int)flen - (int)(3 * k);  // bytes of the token from digit k on
-      const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
-      const uint32_t msk = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
-      const uint32_t o = pos + 3 * k;
-      const uint32_t lo = sm_text[o >> 2], hi = sm_text[(o >> 2) + 1];
-      const uint32_t dg = __builtin_amdgcn_alignbyte(hi, lo, o & 3u) & msk;
-      // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
-      acc = horner3_lazy(acc, dg + ((dg >> 8) & 0xFFu) + 513u * (dg >> 16));
-    }
-  }
-  return acc;
-}
 
 // Eq. 1 of the token that starts at p, byte by byte: up to max_len bytes or the first whitespace
 __device__ __noinline__ WalkedToken walk_token_far(const uint8_t *__restrict__ p, uint64_t max_len) {
@@ -968,91 +787,453 @@ __device__ __noinline__ WalkedToken walk_token_far(const uint8_t *__restrict__ p
   r.len = (uint32_t)l;
   return r;
 }
-
-// x of the shingle made of the ring records first .. first + PER - 1 (ring indices are taken
-// modulo RING); valid if every token is shorter than LONG_TOKEN bytes, *long_tok says if not
-template <int PER>
-__device__ __forceinline__ uint64_t ring_x_unrolled(const uint64_t *ring_v, const uint32_t *ring_len,
-                                                    const PowSplit *__restrict__ ptab, uint32_t first,
-                                                    const HotConsts &hc, bool *long_tok) {
-  uint32_t len[PER];
-  uint64_t V[PER];
-#pragma unroll
-  for (int m = 0; m < PER; m++) {
-    len[m] = ring_len[(first + m) & (RING - 1)];
-    V[m] = ring_v[(first + m) & (RING - 1)];
+// the same modulo the paper's prime (w in the low word)
+__device__ __noinline__ WalkedToken walk_token_far_pp(const uint8_t *__restrict__ p, uint64_t max_len) {
+  uint32_t w = 0, pw = 1;
+  uint64_t l = 0;
+  for (; l < max_len; l++) {
+    const uint32_t c = p[l];
+    if (is_ws(c)) break;
+    w = red_pp((uint64_t)pw * c + w);
+    pw = mulmod_pp(pw, 257u);
   }
-  bool lt = false;
-#pragma unroll
-  for (int m = 0; m < PER; m++) {
-    lt |= len[m] >= LONG_TOKEN;
-    len[m] = min(len[m], LONG_TOKEN);  // keeps the table index in range; the value is redone if long
-  }
-  *long_tok = lt;
-  uint4 e[PER];
-#pragma unroll
-  for (int m = 0; m < PER - 1; m++) e[m] = *reinterpret_cast<const uint4 *>(ptab + len[m]);
-  const uint64_t nsp = ptab[len[PER - 1]].nsp;
-  uint64_t acc = V[PER - 1] + nsp;  // bare last token, < 2^62
-  acc = (acc & P61) + (acc >> 61);
-#pragma unroll
-  for (int m = PER - 2; m >= 0; m--) acc = horner_step_lazy(acc, e[m].x, e[m].y, e[m].z, V[m], hc);
-  return fold61(acc);
+  WalkedToken r;
+  r.w = w;
+  r.len = (uint32_t)l;
+  return r;
 }
 
-// the same for any number of tokens and any token lengths
-__device__ __noinline__ uint64_t ring_x_general(const uint64_t *ring_v, const uint32_t *ring_len,
-                                                const uint64_t *__restrict__ qpow, uint32_t first,
-                                                uint32_t per) {
-  const uint32_t last = first + per - 1;
-  const uint64_t pw = qpow_global(qpow, ring_len[last & (RING - 1)]);
-  const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
-  const uint64_t v_last = ring_v[last & (RING - 1)];
-  uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;
-  for (uint32_t m = last; m-- > first;) {
-    const uint64_t Pm = qpow_global(qpow, ring_len[m & (RING - 1)] + 1);
-    acc = addmod(mulmod(Pm, acc), ring_v[m & (RING - 1)]);
-  }
-  return acc;
+// The digits of a token of at most 16 bytes at byte `pos` of the LDS copy of a tile: bytes 0-2,
+// 3-5, 6-8, 9-11, 12-14 as c0 + 257 c1 + 257^2 c2 each, and byte 15; bytes past flen cleared.
+struct TokenDigits {
+  uint32_t D[5], last;
+};
+__device__ __forceinline__ uint32_t digit257(uint32_t d) {
+  // three bytes c0 + 256 c1 + 65536 c2 -> c0 + 257 c1 + 257^2 c2
+  return d + ((d >> 8) & 0xFFu) + 513u * (d >> 16);
+}
+__device__ __forceinline__ TokenDigits token_digits16(const uint32_t *sm_text, uint32_t pos, uint32_t flen) {
+  const uint32_t wd = pos >> 2, sh = pos & 3u;
+  const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2], t3 = sm_text[wd + 3],
+                 t4 = sm_text[wd + 4];
+  // bytes 0..7 and 8..15 of the token, those past its end cleared
+  const uint32_t l_lo = min(flen, 8u), l_hi = flen - l_lo;
+  const uint64_t keep_lo = l_lo ? ~0ull >> (64u - 8u * l_lo) : 0ull;
+  const uint64_t keep_hi = l_hi ? ~0ull >> (64u - 8u * l_hi) : 0ull;
+  const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, sh) & (uint32_t)keep_lo;
+  const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, sh) & (uint32_t)(keep_lo >> 32);
+  const uint32_t a2 = __builtin_amdgcn_alignbyte(t3, t2, sh) & (uint32_t)keep_hi;
+  const uint32_t a3 = __builtin_amdgcn_alignbyte(t4, t3, sh) & (uint32_t)(keep_hi >> 32);
+  TokenDigits r;
+  r.D[0] = digit257(a0 & 0xFFFFFFu);
+  r.D[1] = digit257(__builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu);
+  r.D[2] = digit257(__builtin_amdgcn_alignbyte(a2, a1, 2u) & 0xFFFFFFu);
+  r.D[3] = digit257(__builtin_amdgcn_alignbyte(a3, a2, 1u) & 0xFFFFFFu);
+  r.D[4] = digit257(a3 & 0xFFFFFFu);
+  r.last = a3 >> 24;
+  return r;
+}
+// the same for at most 8 bytes: one 12-byte read, digits 0..2 (D[2] holds bytes 6-7)
+__device__ __forceinline__ TokenDigits token_digits8(const uint32_t *sm_text, uint32_t pos, uint32_t flen) {
+  const uint32_t wd = pos >> 2;
+  const uint32_t t0 = sm_text[wd], t1 = sm_text[wd + 1], t2 = sm_text[wd + 2];
+  const uint64_t keep = ~0ull >> ((64u - 8u * flen) & 63u);  // flen >= 1 where it matters
+  const uint32_t a0 = __builtin_amdgcn_alignbyte(t1, t0, pos & 3u) & (uint32_t)keep;
+  const uint32_t a1 = __builtin_amdgcn_alignbyte(t2, t1, pos & 3u) & (uint32_t)(keep >> 32);
+  const uint32_t d2 = a1 >> 16;
+  TokenDigits r;
+  r.D[0] = digit257(a0 & 0xFFFFFFu);
+  r.D[1] = digit257(__builtin_amdgcn_alignbyte(a1, a0, 3u) & 0xFFFFFFu);
+  r.D[2] = d2 + (d2 >> 8);
+  r.D[3] = r.D[4] = r.last = 0;
+  return r;
+}
+// digit k (bytes 3k .. 3k+2) of a token of flen bytes at byte `pos`, for the general loop
+__device__ __forceinline__ uint32_t token_digit_at(const uint32_t *sm_text, uint32_t pos, uint32_t flen,
+                                                   uint32_t k) {
+  const int rem = (int)flen - (int)(3 * k);  // bytes of the token from digit k on
+  const uint32_t nbits = (uint32_t)min(max(rem, 0), 3) * 8u;
+  const uint32_t msk = nbits ? (0xFFFFFFFFu >> (32u - nbits)) : 0u;
+  const uint32_t o = pos + 3 * k;
+  const uint32_t lo = sm_text[o >> 2], hi = sm_text[(o >> 2) + 1];
+  return digit257(__builtin_amdgcn_alignbyte(hi, lo, o & 3u) & msk);
+}
+// number of 3-byte digits of the longest token of the round (wave-uniform)
+__device__ __forceinline__ uint32_t max_digits(uint32_t flen) {
+  uint32_t maxnd = (flen + 2) / 3;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) maxnd = max(maxnd, (uint32_t)__shfl_xor(maxnd, o, 64));
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)maxnd);
 }
 
-template <int F, int P, int SM>
+// ---- the two arithmetics of the streaming kernel -----------------------------------------------
+//
+// Everything that depends on the modulus: Eq. 1 of a token, the value of "token 0x20", Eq. 1 of a
+// shingle from ring records, how a round's shingle hashes sit in LDS, and the hash rounds.
+// Arith61 is the default (p = 2^61-1, low 32 bits kept); ArithPP is SEDD_FLAG_PAPER_PRIME.
+
+struct StreamTables {
+  const uint64_t *qpow;    // 257^i, i < QPOW_N                      (Arith61)
+  const PowSplit *ptab;    // Horner multipliers per token length    (Arith61)
+  const uint64_t *coef_a;  // a_k as 64-bit values, for the exact path (Arith61)
+  const CoefSplit *coef_s; // a_k in limb form and b_k               (Arith61)
+  const PowPP *ptab_pp;    // powers per token length                (ArithPP)
+  const CoefPP *coef_pp;   // a'_k, b'_k and their reciprocals       (ArithPP)
+};
+
+struct Arith61 {
+  using Value = uint64_t;  // token values in the ring
+  static constexpr uint32_t SX_WORDS = 64 * 4;  // a round's shingle hashes in limb form
+  template <int F>
+  struct Coefs {
+    uint64_t b[F];
+    uint32_t a0[F], a12[F];
+  };
+  template <int F>
+  static __device__ __forceinline__ void load(Coefs<F> &c, const StreamTables &tb, int K, int kbase, int LW) {
+#pragma unroll
+    for (int j = 0; j < F; j++) {
+      const int k = kbase + LW * j;
+      const CoefSplit s = tb.coef_s[k < K ? k : 0];  // lanes past K compute function 0, store nothing
+      c.a0[j] = s.a0;
+      c.a12[j] = s.a12;
+      c.b[j] = s.b;
+    }
+  }
+  // Eq. 1 of a token of flen <= FAST_TOKEN_MAX bytes in the LDS copy (flen = 0: idle lane);
+  // Horner over 3-byte digits, last digit first.  Must be called by the whole wavefront.
+  static __device__ __forceinline__ Value token_hash(const uint32_t *sm_text, uint32_t pos, uint32_t flen) {
+    uint64_t acc;
+    if (!__any(flen > 8)) {
+      const TokenDigits t = token_digits8(sm_text, pos, flen);
+      acc = (uint64_t)t.D[2] * R3 + t.D[1];  // exact, below 2^42
+      acc = horner3_lazy(acc, t.D[0]);
+    } else if (!__any(flen > 16)) {
+      // at most 16 bytes (ordinary prose): one 20-byte read, five digits and a byte, no loop
+      const TokenDigits t = token_digits16(sm_text, pos, flen);
+      acc = (uint64_t)t.last * R3 + t.D[4];  // exact, below 2^33
+      acc = horner3_lazy(acc, t.D[3]);
+      acc = horner3_lazy(acc, t.D[2]);
+      acc = horner3_lazy(acc, t.D[1]);
+      acc = horner3_lazy(acc, t.D[0]);
+    } else {
+      acc = 0;
+      for (uint32_t k = max_digits(flen); k-- > 0;) acc = horner3_lazy(acc, token_digit_at(sm_text, pos, flen, k));
+    }
+    return fold61(acc);
+  }
+  static __device__ __forceinline__ WalkedToken token_far(const uint8_t *p, uint64_t max_len) {
+    return walk_token_far(p, max_len);
+  }
+  // V = w + 32 * 257^len: the token followed by the joining space
+  static __device__ __forceinline__ Value with_space(Value w, uint32_t len, const StreamTables &tb) {
+    if (len < (uint32_t)QPOW_N) {
+      const uint64_t nsp = tb.ptab[len].nsp;  // w + 32 * 257^len = w - nsp (mod p)
+      return w >= nsp ? w - nsp : w + (P61 - nsp);
+    }
+    const uint64_t pw = powmod(257, len);
+    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // a shift by 5 is a rotation of the residue
+    return addmod(w, sp == P61 ? 0 : sp);
+  }
+  // x of the shingle made of the ring records first .. first + PER - 1 (indices modulo RING); valid
+  // if every token is shorter than LONG_TOKEN bytes, *long_tok says if not
+  template <int PER>
+  static __device__ __forceinline__ Value shingle_unrolled(const Value *ring_v, const uint32_t *ring_len,
+                                                           const StreamTables &tb, uint32_t first,
+                                                           const HotConsts &hc, bool *long_tok) {
+    uint32_t len[PER];
+    uint64_t V[PER];
+#pragma unroll
+    for (int m = 0; m < PER; m++) {
+      len[m] = ring_len[(first + m) & (RING - 1)];
+      V[m] = ring_v[(first + m) & (RING - 1)];
+    }
+    bool lt = false;
+#pragma unroll
+    for (int m = 0; m < PER; m++) {
+      lt |= len[m] >= LONG_TOKEN;
+      len[m] = min(len[m], LONG_TOKEN);  // keeps the table index in range; the value is redone if long
+    }
+    *long_tok = lt;
+    uint4 e[PER];
+#pragma unroll
+    for (int m = 0; m < PER - 1; m++) e[m] = *reinterpret_cast<const uint4 *>(tb.ptab + len[m]);
+    const uint64_t nsp = tb.ptab[len[PER - 1]].nsp;
+    uint64_t acc = V[PER - 1] + nsp;  // bare last token, < 2^62
+    acc = (acc & P61) + (acc >> 61);
+#pragma unroll
+    for (int m = PER - 2; m >= 0; m--) acc = horner_step_lazy(acc, e[m].x, e[m].y, e[m].z, V[m], hc);
+    return fold61(acc);
+  }
+  // the same for any number of tokens and any token lengths
+  static __device__ __noinline__ Value shingle_general(const Value *ring_v, const uint32_t *ring_len,
+                                                       const uint64_t *__restrict__ qpow, uint32_t first,
+                                                       uint32_t per) {
+    const uint32_t last = first + per - 1;
+    const uint64_t pw = qpow_global(qpow, ring_len[last & (RING - 1)]);
+    const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);  // 32 * 257^len (a rotation, never p)
+    const uint64_t v_last = ring_v[last & (RING - 1)];
+    uint64_t acc = v_last >= sp ? v_last - sp : v_last + P61 - sp;
+    for (uint32_t m = last; m-- > first;) {
+      const uint64_t Pm = qpow_global(qpow, ring_len[m & (RING - 1)] + 1);
+      acc = addmod(mulmod(Pm, acc), ring_v[m & (RING - 1)]);
+    }
+    return acc;
+  }
+  static __device__ __forceinline__ Value shingle_any(const Value *ring_v, const uint32_t *ring_len,
+                                                      const StreamTables &tb, uint32_t first, uint32_t per) {
+    return shingle_general(ring_v, ring_len, tb.qpow, first, per);
+  }
+  // shingle i of the round goes to slot i (16 bytes: the limbs the hash loop multiplies by)
+  template <int P>
+  static __device__ __forceinline__ void put(uint32_t *sx, uint32_t i, Value x) {
+    reinterpret_cast<XLimbs *>(sx)[i] = x_limbs(x);
+  }
+  template <int P>
+  static __device__ __forceinline__ void finish(uint32_t *, uint32_t, uint32_t) {}
+  template <int P>
+  static __device__ __forceinline__ uint64_t get(const uint32_t *sx, uint32_t i) {
+    const XLimbs xv = reinterpret_cast<const XLimbs *>(sx)[i];
+    return ((uint64_t)xv.x1 << 31) | xv.x0;
+  }
+  // the K multiply-adds and minima over the cnt shingles of the round (see k_minhash for the
+  // arithmetic); m[] receives the minima, exact
+  template <int F, int P>
+  static __device__ __forceinline__ void round(const uint32_t *sx_raw, uint32_t cnt, uint32_t grp,
+                                               const Coefs<F> &c, const StreamTables &tb, int K, int kbase,
+                                               const HotConsts &hc, unsigned long long *slow_tiles,
+                                               uint32_t (&m)[F]) {
+    constexpr int LW = 64 / P;
+    const XLimbs *sx = reinterpret_cast<const XLimbs *>(sx_raw);
+    uint32_t mr[F], amb = 0;
+#pragma unroll
+    for (int j = 0; j < F; j++) mr[j] = 0xFFFFFFFFu;
+    auto eval = [&](const XLimbs &xv) {
+#pragma unroll
+      for (int j = 0; j < F; j++) {
+        uint64_t N = (uint64_t)c.a0[j] * xv.x1_4;
+        N += (uint64_t)c.a12[j] * xv.x0_2;
+        uint64_t U = (uint64_t)c.a12[j] * xv.x1 + c.b[j];
+        U += (uint64_t)c.a0[j] * xv.x0;
+        const uint64_t Sv = (uint64_t)(uint32_t)N * hc.two29 + U;
+        const uint64_t W = (uint64_t)(uint32_t)(Sv >> 32) * hc.eight;  // hi: S >> 61, lo: bits 32..60
+        const uint32_t h = (uint32_t)Sv + (uint32_t)(N >> 32) + (uint32_t)(W >> 32);
+        amb = max(amb, (uint32_t)W);
+        mr[j] = min(mr[j], h);
+      }
+    };
+    const XLimbs *sxg = sx + grp;  // this half-wave's first shingle
+    const uint32_t steps = cnt / P;
+#pragma unroll(F >= 4 ? 2 : 4)
+    for (uint32_t s = 0; s < steps; s++) eval(sxg[s * P]);
+    if (P == 2 && (cnt & 1)) eval(sx[cnt - 1]);  // both halves: a repeat cannot change a minimum
+    if (__any(amb >= 0xFFFFFFF0u)) {
+      // rare: some evaluation sat within reach of a carry across bit 61; redo the round exactly
+      if (threadIdx.x == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
+#pragma unroll
+      for (int j = 0; j < F; j++) {
+        mr[j] = 0xFFFFFFFFu;
+        const uint64_t a = tb.coef_a[kbase + LW * j < K ? kbase + LW * j : 0];
+        for (uint32_t s = grp; s < cnt; s += P) {
+          const XLimbs xv = sx[s];
+          const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
+          mr[j] = min(mr[j], (uint32_t)addmod(mulmod(a, x), c.b[j]));
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = min(m[j], mr[j]);
+  }
+};
+
+struct ArithPP {
+  using Value = uint32_t;
+  // half-wave g reads row g: shingle i sits at row i % P, column i / P; rows are padded with
+  // repeats of shingle 0 (a repeat cannot change a minimum) to a multiple of 4 entries
+  static constexpr uint32_t ROW_MAX = 64 + 8;
+  static constexpr uint32_t SX_WORDS = 2 * (32 + 8) > ROW_MAX ? 2 * (32 + 8) : ROW_MAX;
+  template <int F>
+  struct Coefs {
+    uint32_t a[F], b[F], ap[F];
+    uint64_t bp[F];
+  };
+  template <int F>
+  static __device__ __forceinline__ void load(Coefs<F> &c, const StreamTables &tb, int K, int kbase, int LW) {
+#pragma unroll
+    for (int j = 0; j < F; j++) {
+      const int k = kbase + LW * j;
+      const uint4 q = *reinterpret_cast<const uint4 *>(tb.coef_pp + (k < K ? k : 0));
+      c.a[j] = q.x;
+      c.b[j] = q.y;
+      c.ap[j] = q.z;
+      c.bp[j] = q.w;
+    }
+  }
+  static __device__ __forceinline__ Value token_hash(const uint32_t *sm_text, uint32_t pos, uint32_t flen) {
+    constexpr uint32_t R3_PP = R3 % PP;
+    // acc <- acc * 257^3 + D modulo p' (the product stays below 2^45 + 2^25)
+    auto absorb = [&](uint32_t acc, uint32_t D) { return red_pp((uint64_t)acc * R3_PP + D); };
+    uint32_t acc;
+    if (!__any(flen > 8)) {
+      const TokenDigits t = token_digits8(sm_text, pos, flen);
+      acc = absorb(absorb(t.D[2], t.D[1]), t.D[0]);  // D[2] < 2^17
+    } else if (!__any(flen > 16)) {
+      const TokenDigits t = token_digits16(sm_text, pos, flen);
+      acc = absorb(absorb(absorb(absorb(absorb(t.last, t.D[4]), t.D[3]), t.D[2]), t.D[1]), t.D[0]);
+    } else {
+      acc = 0;
+      for (uint32_t k = max_digits(flen); k-- > 0;) acc = absorb(acc, token_digit_at(sm_text, pos, flen, k));
+    }
+    return acc;
+  }
+  static __device__ __forceinline__ WalkedToken token_far(const uint8_t *p, uint64_t max_len) {
+    return walk_token_far_pp(p, max_len);
+  }
+  static __device__ __forceinline__ Value with_space(Value w, uint32_t len, const StreamTables &tb) {
+    const uint32_t sp = len < (uint32_t)QPOW_N ? tb.ptab_pp[len].sp : mulmod_pp(32u, powmod_pp(257u, len));
+    const uint32_t v = w + sp;
+    return min(v, v - PP);  // v - p' wraps to a huge value when v < p'
+  }
+  template <int PER>
+  static __device__ __forceinline__ Value shingle_unrolled(const Value *ring_v, const uint32_t *ring_len,
+                                                           const StreamTables &tb, uint32_t first,
+                                                           const HotConsts &, bool *long_tok) {
+    uint32_t len[PER], V[PER];
+#pragma unroll
+    for (int m = 0; m < PER; m++) {
+      len[m] = ring_len[(first + m) & (RING - 1)];
+      V[m] = ring_v[(first + m) & (RING - 1)];
+    }
+    bool lt = false;
+#pragma unroll
+    for (int m = 0; m < PER; m++) {
+      lt |= len[m] >= LONG_TOKEN;
+      len[m] = min(len[m], LONG_TOKEN);
+    }
+    *long_tok = lt;
+    PowPP e[PER];
+#pragma unroll
+    for (int m = 0; m < PER; m++) e[m] = tb.ptab_pp[len[m]];
+    uint32_t acc = V[PER - 1] + (PP - e[PER - 1].sp);  // the bare last token
+    acc = min(acc, acc - PP);
+#pragma unroll
+    for (int m = PER - 2; m >= 0; m--) acc = red_pp((uint64_t)acc * e[m].pw1 + V[m]);
+    return acc;
+  }
+  static __device__ __noinline__ Value shingle_general(const Value *ring_v, const uint32_t *ring_len,
+                                                       const PowPP *__restrict__ ptab, uint32_t first,
+                                                       uint32_t per) {
+    const uint32_t last = first + per - 1;
+    const uint32_t l_last = ring_len[last & (RING - 1)];
+    const uint32_t sp = l_last < (uint32_t)QPOW_N ? ptab[l_last].sp : mulmod_pp(32u, powmod_pp(257u, l_last));
+    uint32_t acc = ring_v[last & (RING - 1)] + (PP - sp);
+    acc = min(acc, acc - PP);
+    for (uint32_t m = last; m-- > first;) {
+      const uint32_t lm = ring_len[m & (RING - 1)];
+      const uint32_t pw1 = lm < (uint32_t)QPOW_N ? ptab[lm].pw1 : powmod_pp(257u, (uint64_t)lm + 1);
+      acc = red_pp((uint64_t)acc * pw1 + ring_v[m & (RING - 1)]);
+    }
+    return acc;
+  }
+  static __device__ __forceinline__ Value shingle_any(const Value *ring_v, const uint32_t *ring_len,
+                                                      const StreamTables &tb, uint32_t first, uint32_t per) {
+    return shingle_general(ring_v, ring_len, tb.ptab_pp, first, per);
+  }
+  template <int P>
+  static __device__ __forceinline__ void put(uint32_t *sx, uint32_t i, Value x) {
+    sx[(i % P) * (64 / P + 8) + i / P] = x;
+  }
+  // pads every row to the longest row rounded up to a multiple of 4 (all lanes call this)
+  template <int P>
+  static __device__ __forceinline__ void finish(uint32_t *sx, uint32_t cnt, uint32_t lane) {
+    const uint32_t cnt0 = (cnt + P - 1) / P, R = (cnt0 + 3) & ~3u;
+    if (lane < 8 * P) {
+      const uint32_t row = lane / 8, j = lane % 8;
+      const uint32_t have = (cnt + P - 1 - row) / P;  // entries of this row
+      if (have + j < R) sx[row * (64 / P + 8) + have + j] = sx[0];
+    }
+  }
+  template <int P>
+  static __device__ __forceinline__ uint64_t get(const uint32_t *sx, uint32_t i) {
+    return sx[(i % P) * (64 / P + 8) + i / P];
+  }
+  // see k_minhash_pp for the arithmetic: quotient estimate, two 24-bit multiply-adds, and the
+  // exact redo of a round whose minimum is within PP_EDGE of p'
+  template <int F, int P>
+  static __device__ __forceinline__ void round(const uint32_t *sx, uint32_t cnt, uint32_t grp,
+                                               const Coefs<F> &c, const StreamTables &, int, int,
+                                               const HotConsts &, unsigned long long *, uint32_t (&m)[F]) {
+    constexpr uint32_t ROW = 64 / P + 8;
+    const uint32_t cnt0 = (cnt + P - 1) / P, R = (cnt0 + 3) & ~3u;
+    uint32_t mr[F];
+#pragma unroll
+    for (int j = 0; j < F; j++) mr[j] = 0xFFFFFFFFu;
+    const int neg_p = -(int)PP;
+    auto eval = [&](uint32_t x) {
+#pragma unroll
+      for (int j = 0; j < F; j++) {
+        const uint32_t q = (uint32_t)(((uint64_t)x * c.ap[j] + c.bp[j]) >> 32);
+        uint32_t sv;
+        asm("v_mad_u32_u24 %0, %2, %3, %4\n\tv_mad_i32_i24 %0, %1, %5, %0"
+            : "=&v"(sv)
+            : "v"(q), "v"(c.a[j]), "v"(x), "v"(c.b[j]), "s"(neg_p));
+        mr[j] = min(mr[j], sv);
+      }
+    };
+    const uint4 *row = reinterpret_cast<const uint4 *>(sx + grp * ROW);
+    const uint32_t steps = R / 4;
+#pragma unroll 2
+    for (uint32_t s4 = 0; s4 < steps; s4++) {
+      const uint4 xv = row[s4];
+      eval(xv.x);
+      eval(xv.y);
+      eval(xv.z);
+      eval(xv.w);
+    }
+    bool redo = false;
+#pragma unroll
+    for (int j = 0; j < F; j++) redo |= mr[j] >= PP - PP_EDGE;
+    if (__any(redo)) {
+      // rare: the plain reduction over this half-wave's row
+#pragma unroll
+      for (int j = 0; j < F; j++) mr[j] = 0xFFFFFFFFu;
+      for (uint32_t i = 0; i < R; i++) {
+        const uint32_t x = sx[grp * ROW + i];
+#pragma unroll
+        for (int j = 0; j < F; j++) mr[j] = min(mr[j], red_pp((uint64_t)c.a[j] * x + c.b[j]));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < F; j++) m[j] = min(m[j], mr[j]);
+  }
+};
+
+template <int F, int P, int SM, typename A>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8, 8)))
-k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
-                 const CoefSplit *__restrict__ coef_split, int K, uint32_t *__restrict__ sig,
-                 HotConsts hc, unsigned long long *__restrict__ slow_tiles, StreamDebug dbg) {
+k_minhash_stream(StreamArgs sa, StreamTables tb, int K, uint32_t *__restrict__ sig, HotConsts hc,
+                 unsigned long long *__restrict__ slow_tiles, StreamDebug dbg) {
+  using Value = typename A::Value;
   __shared__ uint32_t sm_text[SM_TEXT_WORDS];
   __shared__ uint32_t sm_bits[TB / 32 + 4];
   __shared__ uint16_t sm_pos[MAX_TILE_TOKENS];
-  __shared__ uint64_t ring_v[RING];
+  __shared__ Value ring_v[RING];
   __shared__ uint32_t ring_len[RING];
-  __shared__ XLimbs sx[64];
+  __shared__ __attribute__((aligned(16))) uint32_t sx[A::SX_WORDS];
   const uint32_t lane = threadIdx.x;
   const uint64_t P0 = (uint64_t)blockIdx.x * sa.piece;  // frame position of the piece
   const int64_t PE = (int64_t)sa.piece;                 // its end, relative to P0 like all below
   const uint8_t *pbase = sa.frame + P0;
   const uint32_t n = sa.n;
-  const PowSplit *__restrict__ ptab = sa.ptab;
 
   // the lane's hash functions, as in k_minhash
   constexpr int LW = 64 / P;
   const uint32_t grp = lane / LW;
   const int kbase = blockIdx.y * (LW * F) + (lane % LW);
-  uint64_t cb[F];
-  uint32_t a0[F], a12[F], m[F];
+  typename A::template Coefs<F> coefs = {};
+  uint32_t m[F];
 #pragma unroll
-  for (int j = 0; j < F; j++) {
-    a0[j] = a12[j] = 0;
-    cb[j] = 0;
-    m[j] = 0xFFFFFFFFu;
-    if (SM == SM_HASH) {
-      const int k = kbase + LW * j;
-      const CoefSplit c = coef_split[k < K ? k : 0];  // lanes past K compute function 0, store nothing
-      a0[j] = c.a0;
-      a12[j] = c.a12;
-      cb[j] = c.b;
-    }
-  }
+  for (int j = 0; j < F; j++) m[j] = 0xFFFFFFFFu;
+  if (SM == SM_HASH) A::template load<F>(coefs, tb, K, kbase, LW);
 
   // First document that reaches into the piece: the smallest d with off[d+1] + shift > P0, found
   // 64 probes at a time (the last piece ends at or before frame_end, so there is one).
@@ -1090,56 +1271,20 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
     int64_t cur = vs > 0 ? (vs & ~int64_t(15)) : 0;  // tile start, 16-byte aligned
     bool done = false;
 
-    // evaluates the cnt shingle hashes in sx[0 .. cnt)
+    // takes the cnt shingle hashes that lanes 0 .. cnt-1 have put into sx
     auto consume = [&](uint32_t cnt) {
+      A::template finish<P>(sx, cnt, lane);
+      __syncthreads();
       if (SM == SM_COUNT) {
         emitted += cnt;
       } else if (SM == SM_WRITE) {
         if (lane < cnt) {
           const uint64_t at = dbg.x_base + out_base + emitted + lane;
-          const XLimbs xv = sx[lane];
-          if (at < dbg.x_cap) dbg.x[at] = ((uint64_t)xv.x1 << 31) | xv.x0;
+          if (at < dbg.x_cap) dbg.x[at] = A::template get<P>(sx, lane);
         }
         emitted += cnt;
       } else {
-        uint32_t mr[F], amb = 0;
-#pragma unroll
-        for (int j = 0; j < F; j++) mr[j] = 0xFFFFFFFFu;
-        auto eval = [&](const XLimbs &xv) {
-#pragma unroll
-          for (int j = 0; j < F; j++) {
-            uint64_t N = (uint64_t)a0[j] * xv.x1_4;
-            N += (uint64_t)a12[j] * xv.x0_2;
-            uint64_t U = (uint64_t)a12[j] * xv.x1 + cb[j];
-            U += (uint64_t)a0[j] * xv.x0;
-            const uint64_t Sv = (uint64_t)(uint32_t)N * hc.two29 + U;
-            const uint64_t W = (uint64_t)(uint32_t)(Sv >> 32) * hc.eight;  // hi: S >> 61, lo: bits 32..60
-            const uint32_t h = (uint32_t)Sv + (uint32_t)(N >> 32) + (uint32_t)(W >> 32);
-            amb = max(amb, (uint32_t)W);
-            mr[j] = min(mr[j], h);
-          }
-        };
-        const XLimbs *sxg = sx + grp;  // this half-wave's first shingle
-        const uint32_t steps = cnt / P;
-#pragma unroll(F >= 4 ? 2 : 4)
-        for (uint32_t s = 0; s < steps; s++) eval(sxg[s * P]);
-        if (P == 2 && (cnt & 1)) eval(sx[cnt - 1]);  // both halves: a repeat cannot change a minimum
-        if (__any(amb >= 0xFFFFFFF0u)) {
-          // rare: some evaluation sat within reach of a carry across bit 61; redo the round exactly
-          if (lane == 0 && blockIdx.y == 0) atomicAdd(slow_tiles, 1ull);
-#pragma unroll
-          for (int j = 0; j < F; j++) {
-            mr[j] = 0xFFFFFFFFu;
-            const uint64_t a = coef_a[kbase + LW * j < K ? kbase + LW * j : 0];
-            for (uint32_t s = grp; s < cnt; s += P) {
-              const XLimbs xv = sx[s];
-              const uint64_t x = ((uint64_t)xv.x1 << 31) | xv.x0;
-              mr[j] = min(mr[j], (uint32_t)addmod(mulmod(a, x), cb[j]));
-            }
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < F; j++) m[j] = min(m[j], mr[j]);
+        A::template round<F, P>(sx, cnt, grp, coefs, tb, K, kbase, hc, slow_tiles, m);
       }
       nsh += cnt;
     };
@@ -1195,26 +1340,16 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
         const bool fast =
             active && run <= FAST_TOKEN_MAX && (pos + run < TB + LOOK || doc_ends_in_view);
         const uint32_t flen = fast ? run : 0u;
-        uint64_t w = fold61(lds_token_hash(sm_text, pos, flen));
+        Value w = A::token_hash(sm_text, pos, flen);
         uint32_t len = flen;
         if (active && !fast) {
-          const WalkedToken wt = walk_token_far(tp + pos, (uint64_t)(ve - cur - (int64_t)pos));
-          w = wt.w;
+          const WalkedToken wt = A::token_far(tp + pos, (uint64_t)(ve - cur - (int64_t)pos));
+          w = (Value)wt.w;
           len = wt.len;
         }
         if (active) {
-          // V = w + 32 * 257^len: the token followed by the joining space
-          uint64_t v;
-          if (len < (uint32_t)QPOW_N) {
-            const uint64_t nsp = ptab[len].nsp;
-            v = w >= nsp ? w - nsp : w + (P61 - nsp);
-          } else {
-            const uint64_t pw = powmod(257, len);
-            const uint64_t sp = ((pw << 5) & P61) | (pw >> 56);
-            v = addmod(w, sp == P61 ? 0 : sp);
-          }
           const uint32_t ri = (T + lane) & (RING - 1);
-          ring_v[ri] = v;
+          ring_v[ri] = A::with_space(w, len, tb);
           ring_len[ri] = len;
         }
         const uint32_t in_round = min((uint32_t)TB_LANES, tot - base);
@@ -1229,18 +1364,18 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
           if (lane < cnt) {
             const uint32_t first = S_next + lane;
             bool long_tok = false;
-            uint64_t x;
-            if (n == 5) x = ring_x_unrolled<5>(ring_v, ring_len, ptab, first, hc, &long_tok);
-            else if (n == 3) x = ring_x_unrolled<3>(ring_v, ring_len, ptab, first, hc, &long_tok);
-            else if (n == 4) x = ring_x_unrolled<4>(ring_v, ring_len, ptab, first, hc, &long_tok);
-            else if (n == 2) x = ring_x_unrolled<2>(ring_v, ring_len, ptab, first, hc, &long_tok);
-            else if (n == 1) x = ring_x_unrolled<1>(ring_v, ring_len, ptab, first, hc, &long_tok);
+            Value x;
+            if (n == 5) x = A::template shingle_unrolled<5>(ring_v, ring_len, tb, first, hc, &long_tok);
+            else if (n == 3) x = A::template shingle_unrolled<3>(ring_v, ring_len, tb, first, hc, &long_tok);
+            else if (n == 4) x = A::template shingle_unrolled<4>(ring_v, ring_len, tb, first, hc, &long_tok);
+            else if (n == 2) x = A::template shingle_unrolled<2>(ring_v, ring_len, tb, first, hc, &long_tok);
+            else if (n == 1) x = A::template shingle_unrolled<1>(ring_v, ring_len, tb, first, hc, &long_tok);
             else {
               long_tok = true;
               x = 0;
             }
-            if (long_tok) x = ring_x_general(ring_v, ring_len, sa.qpow, first, n);
-            sx[lane] = x_limbs(x);
+            if (long_tok) x = A::shingle_any(ring_v, ring_len, tb, first, n);
+            A::template put<P>(sx, lane, x);
           }
           __syncthreads();
           consume(cnt);
@@ -1266,7 +1401,7 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
         }
       }
       if (!earlier) {
-        if (lane == 0) sx[0] = x_limbs(ring_x_general(ring_v, ring_len, sa.qpow, 0u, T));
+        if (lane == 0) A::template put<P>(sx, 0u, A::shingle_any(ring_v, ring_len, tb, 0u, T));
         __syncthreads();
         consume(1u);
       }
@@ -1300,11 +1435,12 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
   if (SM == SM_COUNT && lane == 0) dbg.piece_count[blockIdx.x] = emitted;
 }
 
-// ---- the hot kernel of the paper-prime mode ----------------------------------------------------
+// ---- the hot kernel of the paper-prime mode (byte shingles and caller-supplied hashes) ---------
 //
 // Same tiling as k_minhash: one wavefront per shingle tile, phase A fills LDS with the tile's
 // x'(s) = Eq. 1 mod p', phase B evaluates h'_k(s) = (a'_k x' + b'_k) mod p' for the lane's
-// functions over the tile.  Per (shingle, function):
+// functions over the tile.  (Word shingles: ArithPP in k_minhash_stream runs the same phase B.)
+// Per (shingle, function):
 //   q = (x ap + bp) >> 32            one 32x32+64 multiply-add; ap, bp are rounded up, so q is
 //                                    the quotient of a x + b by p', or (rarely) one more
 //   s = (a x + b) - q p'             low 32 bits, two 24-bit multiply-adds (a, x, q, p' < 2^24)
@@ -1316,62 +1452,18 @@ k_minhash_stream(StreamArgs sa, const uint64_t *__restrict__ coef_a,
 // redoes its functions over the tile with the plain reduction.  That happens with probability
 // (PP_EDGE / p')^count per function: in practice only for tiles of one or two shingles, where
 // the second pass costs next to nothing.  4 instructions per evaluation.
-constexpr uint32_t PP_EDGE = 4400;  // > p' (p' + 2) / 2^32 = 4295.0
 
-__device__ __forceinline__ uint32_t token_value_pp(const TokenRecs &rec, uint32_t i) {
-  return reinterpret_cast<const uint32_t *>(rec.v)[i];
-}
-
-// x' of shingle i of tile ht (any token lengths; the general form)
+// x' of shingle i of tile ht
 template <int MODE>
 __device__ __forceinline__ uint32_t shingle_x_pp(const XSource &xsrc, const HTile &ht, uint32_t i) {
+  static_assert(MODE == X_GIVEN || MODE == X_BYTES, "word shingles take the streaming kernel");
   if (MODE == X_GIVEN) return (uint32_t)(xsrc.given[ht.x_off + i] % PP);
-  if (MODE == X_BYTES) {
-    const uint32_t d = ht.doc;
-    const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
-    const uint32_t per = min(len, xsrc.n);
-    const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
-    uint32_t acc = 0;
-    for (uint32_t j = per; j-- > 0;) acc = red_pp((uint64_t)acc * 257u + p[j]);
-    return acc;
-  }
-  const TokenRecs &rec = xsrc.rec;
-  const uint32_t first = ht.tok0 + i, last = first + ht.per - 1;
-  const uint32_t l_last = token_len(rec, last);
-  const uint32_t sp = l_last < (uint32_t)QPOW_N ? xsrc.ptab_pp[l_last].sp
-                                                : mulmod_pp(32u, powmod_pp(257u, l_last));
-  uint32_t acc = token_value_pp(rec, last) + (PP - sp);  // the bare last token
-  acc = min(acc, acc - PP);
-  for (uint32_t m = last; m-- > first;) {
-    const uint32_t lm = token_len(rec, m);
-    const uint32_t pw1 = lm < (uint32_t)QPOW_N ? xsrc.ptab_pp[lm].pw1 : powmod_pp(257u, (uint64_t)lm + 1);
-    acc = red_pp((uint64_t)acc * pw1 + token_value_pp(rec, m));
-  }
-  return acc;
-}
-
-// the same for PER tokens shorter than LONG_TOKEN bytes, all loads issued up front
-template <int PER>
-__device__ __forceinline__ uint32_t words_x_pp_unrolled(const TokenRecs &rec,
-                                                        const PowPP *__restrict__ ptab,
-                                                        uint32_t first, bool *long_tok) {
-  uint32_t len[PER], V[PER];
-#pragma unroll
-  for (int m = 0; m < PER; m++) {
-    len[m] = rec.len[first + m];
-    V[m] = token_value_pp(rec, first + m);
-  }
-  PowPP e[PER];
-#pragma unroll
-  for (int m = 0; m < PER; m++) e[m] = ptab[len[m]];
-  bool lt = false;
-#pragma unroll
-  for (int m = 0; m < PER; m++) lt |= len[m] == LONG_TOKEN;
-  *long_tok = lt;
-  uint32_t acc = V[PER - 1] + (PP - e[PER - 1].sp);
-  acc = min(acc, acc - PP);
-#pragma unroll
-  for (int m = PER - 2; m >= 0; m--) acc = red_pp((uint64_t)acc * e[m].pw1 + V[m]);
+  const uint32_t d = ht.doc;
+  const uint32_t vs = xsrc.dv[d], len = xsrc.dv[d + 1] - vs;
+  const uint32_t per = min(len, xsrc.n);
+  const uint8_t *p = xsrc.pbase + vs + (ht.x_off - xsrc.sbase[d]) + i;
+  uint32_t acc = 0;
+  for (uint32_t j = per; j-- > 0;) acc = red_pp((uint64_t)acc * 257u + p[j]);
   return acc;
 }
 
@@ -1389,23 +1481,7 @@ k_minhash_pp(XSource xsrc, const HTile *__restrict__ tiles, const uint32_t *__re
   if (t >= *n_tiles) return;
   const uint32_t d = ht.doc, cnt = ht.cnt;
 
-  if (MODE == X_WORDS) {
-    const TokenRecs &rec = xsrc.rec;
-    const PowPP *__restrict__ ptab = xsrc.ptab_pp;
-    const uint32_t per = ht.per;
-    for (uint32_t i = threadIdx.x; i < cnt; i += 64) {
-      const uint32_t first = ht.tok0 + i;
-      bool long_tok = true;
-      uint32_t acc = 0;
-      if (per == 5) acc = words_x_pp_unrolled<5>(rec, ptab, first, &long_tok);
-      else if (per == 3) acc = words_x_pp_unrolled<3>(rec, ptab, first, &long_tok);
-      else if (per == 4) acc = words_x_pp_unrolled<4>(rec, ptab, first, &long_tok);
-      else if (per == 2) acc = words_x_pp_unrolled<2>(rec, ptab, first, &long_tok);
-      else if (per == 1) acc = words_x_pp_unrolled<1>(rec, ptab, first, &long_tok);
-      if (long_tok) acc = shingle_x_pp<MODE>(xsrc, ht, i);  // also every other shingle length
-      sx[i % P][i / P] = acc;
-    }
-  } else if (MODE == X_BYTES) {
+  if (MODE == X_BYTES) {
     // the tile's bytes are staged in LDS; lane l owns the WPL windows from WPL l on: the last
     // of them by Horner over its bytes, the others by the reuse form of Eq. 1 (Eq. 2 read
     // backwards):  x(i-1) = q (x(i) - c[i+per-1] q^(per-1)) + c[i-1]   (mod p')
@@ -1890,13 +1966,11 @@ static int launch_minhash(int mode, const XSource &xsrc, const HTile *tiles,
     else if (F == 2) LAUNCH(2, 2, MM);         \
     else LAUNCH(4, 2, MM);                     \
   } while (0)
+  if (mode != X_BYTES && mode != X_GIVEN) return SEDD_EINVAL;  // word shingles: k_minhash_stream
   if (coef_pp) {
-    if (mode == X_WORDS) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_WORDS);
-    else if (mode == X_BYTES) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_BYTES);
+    if (mode == X_BYTES) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_BYTES);
     else SEDD_LAUNCH_MH_F(SEDD_LAUNCH_PP, X_GIVEN);
   } else {
-    // word shingles with the 61-bit modulus never come here: k_minhash_stream hashes them
-    if (mode == X_WORDS) return SEDD_EINVAL;
     if (mode == X_BYTES) SEDD_LAUNCH_MH_F(SEDD_LAUNCH_61, X_BYTES);
     else SEDD_LAUNCH_MH_F(SEDD_LAUNCH_61, X_GIVEN);
   }
@@ -2014,20 +2088,18 @@ __global__ void k_stream_soff(const uint64_t *__restrict__ off, uint64_t n_docs,
                        : (uint64_t)piece_base[n_pieces];
 }
 
-// The default mode of sedd_minhash (word shingles, 61-bit modulus, affine family): validation,
-// coefficients, the signature fill and one launch of k_minhash_stream.  One host wait, for the
-// first and last offset and the validity flag.  With dbg_off the two debug passes run instead.
 // ---- state of the streaming path that calls on different streams and threads may share --------
 //
-// Coefficient sets: the K coefficients of a seed (64-bit values and limb form) with the tables
-// 257^i and the per-length Horner multipliers behind them, written once by k_coeffs and only
-// read afterwards.  A set is created on the stream of the call that first asks for it; a call on
+// Coefficient sets: the K coefficients of a seed (64-bit values and limb form, or the paper-prime
+// form) with the tables 257^i and the per-length Horner multipliers behind them, written once by
+// k_coeffs / k_coeffs_pp and only read afterwards.  A set is created on the stream of the call that first asks for it; a call on
 // another stream waits for the creating kernel through an event until that event has been seen
 // complete.  Probe slots: a small ring of pinned host records that the offset probe and the
 // validation kernel write directly, one per call in flight.
 struct TableSet {
   int K;
   uint64_t seed;
+  bool paper;
   uint8_t *dev;
   hipEvent_t ready;
   bool settled;
@@ -2043,28 +2115,34 @@ static std::vector<TableSet> g_table_sets;
 static ProbeSlot *g_probe_ring = nullptr;
 static std::atomic<uint32_t> g_probe_next{0};
 
-struct TablePtrs {
-  uint64_t *coef_a, *coef_b, *qpow;
-  CoefSplit *coef_s;
-  PowSplit *ptab;
-};
-
-static int tables_acquire(int K, uint64_t seed, hipStream_t st, TablePtrs *out) {
+static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, StreamTables *out) {
   std::lock_guard<std::mutex> lock(g_stream_mutex);
   Carver cv;
-  const uint64_t o_a = cv.take<uint64_t>(K), o_b = cv.take<uint64_t>(K);
-  const uint64_t o_cs = cv.take<CoefSplit>(K);
-  const uint64_t o_qpow = cv.take<uint64_t>(QPOW_N);
-  const uint64_t o_ptab = cv.take<PowSplit>(QPOW_N);
+  uint64_t o_a = 0, o_b = 0, o_cs = 0, o_qpow = 0, o_ptab = 0, o_cpp = 0, o_ptpp = 0;
+  if (paper) {
+    o_cpp = cv.take<CoefPP>(K);
+    o_ptpp = cv.take<PowPP>(QPOW_N);
+  } else {
+    o_a = cv.take<uint64_t>(K);
+    o_b = cv.take<uint64_t>(K);
+    o_cs = cv.take<CoefSplit>(K);
+    o_qpow = cv.take<uint64_t>(QPOW_N);
+    o_ptab = cv.take<PowSplit>(QPOW_N);
+  }
+  *out = StreamTables{};
   auto bind = [&](uint8_t *A) {
-    out->coef_a = (uint64_t *)(A + o_a);
-    out->coef_b = (uint64_t *)(A + o_b);
-    out->coef_s = (CoefSplit *)(A + o_cs);
-    out->qpow = (uint64_t *)(A + o_qpow);
-    out->ptab = (PowSplit *)(A + o_ptab);
+    if (paper) {
+      out->coef_pp = (const CoefPP *)(A + o_cpp);
+      out->ptab_pp = (const PowPP *)(A + o_ptpp);
+    } else {
+      out->coef_a = (const uint64_t *)(A + o_a);
+      out->coef_s = (const CoefSplit *)(A + o_cs);
+      out->qpow = (const uint64_t *)(A + o_qpow);
+      out->ptab = (const PowSplit *)(A + o_ptab);
+    }
   };
   for (TableSet &t : g_table_sets) {
-    if (t.K != K || t.seed != seed) continue;
+    if (t.K != K || t.seed != seed || t.paper != paper) continue;
     if (!t.settled) {
       if (hipEventQuery(t.ready) == hipSuccess) t.settled = true;
       else SEDD_HIP(hipStreamWaitEvent(st, t.ready, 0));
@@ -2085,6 +2163,7 @@ static int tables_acquire(int K, uint64_t seed, hipStream_t st, TablePtrs *out) 
   TableSet t;
   t.K = K;
   t.seed = seed;
+  t.paper = paper;
   t.settled = false;
   void *p = nullptr;
   if (hipMalloc(&p, cv.off) != hipSuccess) {
@@ -2093,8 +2172,15 @@ static int tables_acquire(int K, uint64_t seed, hipStream_t st, TablePtrs *out) 
   }
   t.dev = (uint8_t *)p;
   bind(t.dev);
-  hipLaunchKernelGGL(k_coeffs, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, K,
-                     out->coef_a, out->coef_b, out->coef_s, out->qpow, out->ptab);
+  if (paper)
+    hipLaunchKernelGGL(k_coeffs_pp, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, K,
+                       (CoefPP *)(t.dev + o_cpp), (PowPP *)(t.dev + o_ptpp), (uint64_t *)nullptr,
+                       (uint64_t *)nullptr);
+  else
+    hipLaunchKernelGGL(k_coeffs, dim3((std::max(K, QPOW_N) + 255) / 256), dim3(256), 0, st, seed, K,
+                       (uint64_t *)(t.dev + o_a), (uint64_t *)(t.dev + o_b),
+                       (CoefSplit *)(t.dev + o_cs), (uint64_t *)(t.dev + o_qpow),
+                       (PowSplit *)(t.dev + o_ptab));
   SEDD_LAUNCH_CHECK();
   SEDD_HIP(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
   SEDD_HIP(hipEventRecord(t.ready, st));
@@ -2131,12 +2217,16 @@ int release_stream_state() {
   return SEDD_OK;
 }
 
+// Word shingles with the affine family (61-bit modulus, or the paper's prime with `paper`):
+// validation, coefficients, the signature fill and one launch of k_minhash_stream.  One host wait,
+// for the first and last offset and the validity flag.  With dbg_off the two debug passes run
+// instead.
 // host_ends: {doc_offsets[0], doc_offsets[n_docs]} when the caller has the offsets on the host and
 // has validated them there (then nothing waits on the device); nullptr otherwise.
 static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *doc_offsets,
-                              uint64_t n_docs, int32_t n, int32_t K, uint64_t seed, uint32_t *sig,
-                              uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off, hipStream_t st,
-                              const uint64_t *host_ends = nullptr) {
+                              uint64_t n_docs, int32_t n, int32_t K, uint64_t seed, bool paper,
+                              uint32_t *sig, uint64_t *dbg_x, uint64_t dbg_cap, uint64_t *dbg_off,
+                              hipStream_t st, const uint64_t *host_ends = nullptr) {
   const bool debug = dbg_off != nullptr;
   const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);
   int rc;
@@ -2185,13 +2275,9 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
   const uint64_t n_pieces = offn > off0 ? (sa.frame_end + piece - 1) / piece : 0;
   if (n_pieces >= (uint64_t(1) << 31)) return SEDD_EINVAL;
 
-  TablePtrs tp;
-  rc = tables_acquire((int)K, seed, st, &tp);
+  StreamTables tb;
+  rc = tables_acquire((int)K, seed, paper, st, &tb);
   if (rc) return rc;
-  uint64_t *coef_a = tp.coef_a;
-  CoefSplit *coef_s = tp.coef_s;
-  sa.qpow = tp.qpow;
-  sa.ptab = tp.ptab;
   // the two debug passes keep their counters in the arena (they are not meant to run concurrently)
   Carver cv;
   uint64_t o_pc = 0, o_dp = 0, o_dl = 0, o_tmp = 0;
@@ -2218,10 +2304,17 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
     dbg.x_base = 0;
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, pc + n_pieces, (uint64_t)1, 0u);
     SEDD_LAUNCH_CHECK();
+#define SEDD_LAUNCH_STREAM_DBG(SM)                                                                \
+  do {                                                                                           \
+    if (paper)                                                                                   \
+      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM, ArithPP>), dim3((uint32_t)n_pieces), dim3(64), \
+                         0, st, sa, tb, 1, (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg); \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM, Arith61>), dim3((uint32_t)n_pieces), dim3(64), \
+                         0, st, sa, tb, 1, (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg); \
+  } while (0)
     if (n_pieces) {
-      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM_COUNT>), dim3((uint32_t)n_pieces), dim3(64), 0, st,
-                         sa, (const uint64_t *)nullptr, (const CoefSplit *)nullptr, 1,
-                         (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg);
+      SEDD_LAUNCH_STREAM_DBG(SM_COUNT);
       SEDD_LAUNCH_CHECK();
     }
     rc = scan_exclusive_u32(pc, pc, n_pieces + 1, (uint32_t *)(A + o_tmp), st);
@@ -2231,11 +2324,10 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
                        dbg_off);
     SEDD_LAUNCH_CHECK();
     if (dbg_cap && n_pieces) {
-      hipLaunchKernelGGL((k_minhash_stream<1, 1, SM_WRITE>), dim3((uint32_t)n_pieces), dim3(64), 0, st,
-                         sa, (const uint64_t *)nullptr, (const CoefSplit *)nullptr, 1,
-                         (uint32_t *)nullptr, hc, (unsigned long long *)nullptr, dbg);
+      SEDD_LAUNCH_STREAM_DBG(SM_WRITE);
       SEDD_LAUNCH_CHECK();
     }
+#undef SEDD_LAUNCH_STREAM_DBG
     return SEDD_OK;
   }
 
@@ -2256,8 +2348,14 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
   dim3 grid((uint32_t)n_pieces, (uint32_t)((K + per_block - 1) / per_block));
   ProfScope prof(SEDD_PROF_MINHASH, st);
 #define SEDD_LAUNCH_STREAM(FF, HW)                                                               \
-  hipLaunchKernelGGL((k_minhash_stream<FF, HW, SM_HASH>), grid, dim3(64), 0, st, sa, coef_a, coef_s, \
-                     (int)K, sig, hc, stats + SEDD_STAT_SLOW_TILES, dbg)
+  do {                                                                                           \
+    if (paper)                                                                                   \
+      hipLaunchKernelGGL((k_minhash_stream<FF, HW, SM_HASH, ArithPP>), grid, dim3(64), 0, st, sa, tb, \
+                         (int)K, sig, hc, stats + SEDD_STAT_SLOW_TILES, dbg);                    \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_minhash_stream<FF, HW, SM_HASH, Arith61>), grid, dim3(64), 0, st, sa, tb, \
+                         (int)K, sig, hc, stats + SEDD_STAT_SLOW_TILES, dbg);                    \
+  } while (0)
   if (P == 1) SEDD_LAUNCH_STREAM(4, 1);
   else if (F == 1) SEDD_LAUNCH_STREAM(1, 2);
   else if (F == 2) SEDD_LAUNCH_STREAM(2, 2);
@@ -2282,9 +2380,9 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   const int byte_mode = (flags & SEDD_FLAG_BYTE_SHINGLES) ? 1 : 0;
   const bool paper = (flags & SEDD_FLAG_PAPER_PRIME) != 0;
   const bool rolling = (flags & SEDD_FLAG_ROLLING_FAMILY) != 0;
-  if (!byte_mode && !paper && !rolling)
-    return run_minhash_stream(bytes, n_bytes, doc_offsets, n_docs, n, K, seed, sig, dbg_x, dbg_cap,
-                              dbg_off, st);
+  if (!byte_mode && !rolling)
+    return run_minhash_stream(bytes, n_bytes, doc_offsets, n_docs, n, K, seed, paper, sig, dbg_x,
+                              dbg_cap, dbg_off, st);
 
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
@@ -2377,7 +2475,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   const uint64_t o_btb = cv.take<uint32_t>(max_nd + 1);
   const uint64_t o_btd = cv.take<BTile>(byte_mode ? 1 : NBT);
   const uint64_t o_wbase = cv.take<uint32_t>(byte_mode ? 1 : NBT + 1);
-  const uint64_t o_tv = cv.take<uint64_t>(byte_mode ? 1 : NW);
+  const uint64_t o_tv = cv.take<uint32_t>(byte_mode ? 1 : NW);
   const uint64_t o_tl = cv.take<uint8_t>(byte_mode ? 1 : NW);
   const uint64_t o_tx = cv.take<uint32_t>(byte_mode ? 1 : NW);
   const uint64_t o_docw = cv.take<uint32_t>(max_nd + 1);
@@ -2399,7 +2497,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   BTile *btd = (BTile *)(A + o_btd);
   uint32_t *wbase = (uint32_t *)(A + o_wbase);
   TokenRecs rec;
-  rec.v = (uint64_t *)(A + o_tv);
+  rec.pos = (uint32_t *)(A + o_tv);
   rec.len = (uint8_t *)(A + o_tl);
   rec.long_len = (uint32_t *)(A + o_tx);
   uint32_t *docw = (uint32_t *)(A + o_docw), *sbase = (uint32_t *)(A + o_sbase);
@@ -2409,12 +2507,10 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   XSource xsrc;
   xsrc.dv = dv;
   xsrc.sbase = sbase;
-  xsrc.rec = rec;
   xsrc.qpow = qpow;
   xsrc.ptab_pp = ptab_pp;
   xsrc.given = nullptr;
   xsrc.n = (uint32_t)n;
-  const int mode = byte_mode ? X_BYTES : X_WORDS;
 
   {
     int nthr = std::max(K, QPOW_N);
@@ -2474,12 +2570,8 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
       SEDD_LAUNCH_CHECK();
       rc = scan_exclusive_u32(wbase, wbase, nbt + 1, tmp, st);
       if (rc) return rc;
-      if (paper)
-        hipLaunchKernelGGL(k_emit_words<EM_PP>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
-                           btd, btb + nd, wbase, ptab_pp, rec);
-      else
-        hipLaunchKernelGGL(k_emit_words<EM_POS>, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase,
-                           btd, btb + nd, wbase, ptab_pp, rec);
+      hipLaunchKernelGGL(k_emit_words, dim3((uint32_t)nbt), dim3(TB_LANES), 0, st, pbase, btd,
+                         btb + nd, wbase, rec);
       SEDD_LAUNCH_CHECK();
     }
     {
@@ -2501,9 +2593,9 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
 #define SEDD_LAUNCH_DBG(MM, PAPER)                                                              \
   hipLaunchKernelGGL((k_debug_write_x<MM, PAPER>), dim3((uint32_t)nht), dim3(64), 0, st, xsrc, \
                      htd, htb + nd, total, dbg_x, dbg_cap)
-      if (byte_mode && paper) SEDD_LAUNCH_DBG(X_BYTES, true);
-      else if (byte_mode) SEDD_LAUNCH_DBG(X_BYTES, false);
-      else SEDD_LAUNCH_DBG(X_WORDS, true);  // word shingles reach this driver with the paper's prime only
+      if (!byte_mode) return SEDD_EINVAL;  // word shingles: the debug passes of k_minhash_stream
+      if (paper) SEDD_LAUNCH_DBG(X_BYTES, true);
+      else SEDD_LAUNCH_DBG(X_BYTES, false);
 #undef SEDD_LAUNCH_DBG
       SEDD_LAUNCH_CHECK();
       hipLaunchKernelGGL(k_debug_write_offsets, dim3(gdoc), dim3(256), 0, st, sbase, nd, total,
@@ -2514,7 +2606,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
     } else if (rolling) {
       RfArgs ra;
       ra.pbase = pbase;
-      ra.tok_pos = reinterpret_cast<const uint32_t *>(rec.v);
+      ra.tok_pos = rec.pos;
       ra.tok_len = rec.len;
       ra.tok_long = rec.long_len;
       ra.dv = dv;
@@ -2525,7 +2617,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
       rc = launch_minhash_rf(byte_mode, ra, htd, htb + nd, nht, (int)K, sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
     } else {
-      rc = launch_minhash(mode, xsrc, htd, htb + nd, nht, coef_a, coef_s,
+      rc = launch_minhash(X_BYTES, xsrc, htd, htb + nd, nht, coef_a, coef_s,
                           paper ? coef_pp : (const CoefPP *)nullptr, (int)K,
                           sig + c.d0 * (uint64_t)K, st);
       if (rc) return rc;
@@ -2662,7 +2754,7 @@ int sedd_minhash_host_chunked(const uint8_t *host_bytes, const uint64_t *host_do
   int rc = feed_ensure(max_text, max_docs + 1);
   if (rc) return rc;
   HostFeed &f = g_feed;
-  const bool plain = !(flags & (SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_PAPER_PRIME | SEDD_FLAG_ROLLING_FAMILY));
+  const bool streamed = !(flags & (SEDD_FLAG_BYTE_SHINGLES | SEDD_FLAG_ROLLING_FAMILY));
   const size_t n_chunks = cuts.size() - 1;
   bool used[2] = {false, false};
   auto upload = [&](size_t i) -> int {
@@ -2693,9 +2785,10 @@ int sedd_minhash_host_chunked(const uint8_t *host_bytes, const uint64_t *host_do
     // the staged offsets are the caller's, unshifted: the text pointer is moved back instead
     const uint8_t *base = f.text[s] - off[d0];
     const uint64_t ends[2] = {off[d0], off[d1]};
-    if (plain)
+    if (streamed)
       rc = run_minhash_stream(base, off[d1], f.offs[s], d1 - d0, shingle_n, K, seed,
-                              sig + d0 * (uint64_t)K, nullptr, 0, nullptr, st, ends);
+                              (flags & SEDD_FLAG_PAPER_PRIME) != 0, sig + d0 * (uint64_t)K, nullptr, 0,
+                              nullptr, st, ends);
     else
       rc = run_minhash(base, off[d1], f.offs[s], d1 - d0, shingle_n, K, seed, flags,
                        sig + d0 * (uint64_t)K, nullptr, 0, nullptr, st);

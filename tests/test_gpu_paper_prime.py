@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from paper_2501_01046_amd import corpus
-from tests.test_gpu_parity import _edge_corpus, _pack, dev, host, say
+from tests.test_gpu_parity import _edge_corpus, _fuzz_docs, _pack, _piece_edge_docs, dev, host, say
 
 pytestmark = pytest.mark.gpu
 
@@ -184,6 +184,70 @@ def test_minhash_long_documents_split_into_tiles(sedd):
     data, off = corpus.generate(r)
     _check_minhash(sedd, data, off, 5, 128, 1, PAPER, procs=NPROC)
     _check_minhash(sedd, data[: int(off[12])], off[:13], 13, 128, 1, PAPER | BYTES, procs=NPROC)
+
+
+@pytest.mark.parametrize("piece", [1024, 5120, 1 << 20])
+def test_stream_kernel_piece_size_invariance(sedd, piece):
+    """Word shingles of this mode run through the streaming kernel too: shingle hashes in order and
+    signatures against the oracle however the text is cut between wavefronts."""
+    say("paper-prime stream piece", piece)
+    sedd.debug_set_piece_bytes(piece)
+    try:
+        for lead in (0, 1019):
+            docs = _piece_edge_docs() + _fuzz_docs(piece + lead, 60)
+            data, off = _pack(docs, lead)
+            d_data, d_off = dev(data), dev(off)
+            for n in (1, 5, 64):
+                wx, woff = _oracle_x(docs, n, False)
+                x, soff = sedd.debug_shingle_hashes(d_data, d_off, n, PAPER)
+                assert np.array_equal(host(soff), woff), (lead, n)
+                assert np.array_equal(host(x), wx), (lead, n)
+            for n, K in ((5, 128), (3, 256), (1, 40), (64, 32)):
+                want = oracle.minhash(data, off, n, K, 3, PAPER)
+                got = host(sedd.sedd_minhash(d_data, d_off, n, K, 3, PAPER))
+                bad = np.nonzero((got != want).any(axis=1))[0]
+                assert bad.size == 0, (lead, n, K, bad[:5])
+    finally:
+        sedd.debug_set_piece_bytes(0)
+
+
+@pytest.mark.parametrize("max_len", [8, 9, 16, 17, 40])
+def test_stream_kernel_token_length_tiers(sedd, max_len):
+    """Longest word exactly at and next to the limits of the three token-hash paths, all byte
+    values inside the words."""
+    say("paper-prime stream token lengths up to", max_len)
+    rng = np.random.default_rng(100 + max_len)
+    pool = np.array([c for c in range(256) if c not in (9, 10, 11, 12, 13, 32)], dtype=np.uint8)
+    docs = []
+    for _ in range(120):
+        lens = rng.integers(1, max_len + 1, size=int(rng.integers(1, 400)))
+        lens[rng.integers(0, lens.size)] = max_len
+        docs.append(b" ".join(bytes(rng.choice(pool, size=int(l))) for l in lens))
+    data, off = _pack(docs, lead=max_len % 16)
+    wx, woff = _oracle_x(docs, 3, False)
+    x, soff = sedd.debug_shingle_hashes(dev(data), dev(off), 3, PAPER)
+    assert np.array_equal(host(soff), woff) and np.array_equal(host(x), wx)
+    _check_minhash(sedd, data, off, 5, 64, seed=max_len, flags=PAPER, procs=NPROC)
+
+
+@pytest.mark.parametrize("n,K", [(1, 64), (2, 256), (1, 1000)])
+def test_stream_kernel_rounds_of_one_or_two_shingles(sedd, n, K):
+    """The hash loop's quotient estimate is exact only below p' minus a margin; a round whose
+    minimum lies above is redone exactly.  That needs rounds of very few shingles: tens of
+    thousands of documents of one to three short words, about one (document, function) pair in a
+    thousand within the margin."""
+    say("paper-prime stream tiny documents", n, K)
+    rng = np.random.default_rng(n * 1000 + K)
+    n_docs = 30_000 if K <= 256 else 8_000
+    docs = []
+    for _ in range(n_docs):
+        words = [bytes(rng.integers(97, 123, size=int(rng.integers(1, 10)), dtype=np.uint8))
+                 for _ in range(int(rng.integers(1, 4)))]
+        docs.append(b" ".join(words))
+    data, off = _pack(docs, 0)
+    want = _check_minhash(sedd, data, off, n, K, seed=5, flags=PAPER, procs=NPROC)
+    near = int((want >= PP - 4400).sum())
+    assert near >= 20, near          # the case did occur: minima inside the margin
 
 
 def test_modes_alternate_on_the_same_scratch(sedd):
