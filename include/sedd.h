@@ -161,8 +161,8 @@ int sedd_lsh_dense_keys(const uint32_t *sig, uint64_t n_docs, int32_t K, int32_t
  *
  * keys        device, uint64[n_docs*b], document-major, values < 2^61.
  * cluster_id  device, int64[n_docs].       n_docs < 2^31, n_docs*b < 2^32.
- * Cost: the (key, document) records of every band are radix-sorted by the low 24..40 key bits
- * (2^bits >= 16 n_docs: 3 to 5 passes over 12 bytes per record), then every record looks back
+ * Cost: the (key, document) records of every band are radix-sorted by the low 16..32 key bits
+ * (2^bits >= n_docs: 2 to 4 passes over 12 bytes per record), then every record looks back
  * over at most 64 records of its band for its key.  That suffices whenever those bits spread
  * the keys (band keys of sedd_lsh_keys do).  If some record does not find its key or the end of
  * its group within 64 records, the remaining passes up to bit 61 run as well (8 in all) and every

@@ -62,10 +62,10 @@ k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b
 // the whole array already yields band-major positions), then a stable scatter.
 //
 // Grouping does not need a full sort.  Band keys are residues of a polynomial hash, so their low
-// bits are uniform: sorting by the low B bits with 2^B >= 16 n leaves, on average, less than 1/16
+// bits are uniform: sorting by the low B bits with 2^B >= n leaves, on average, less than one
 // foreign record inside a group of records that agree in those bits.  sedd_cluster therefore
-// sorts by B = 24 or 32 bits (3 or 4 passes instead of 8) and the linking kernel walks back over
-// the records that share the low B bits until it meets one with the same full key.
+// sorts by B = 16, 24 or 32 bits (2 to 4 passes instead of 8) and the linking kernel walks back
+// over the records that share the low B bits until it meets one with the same full key.
 
 constexpr int SORT_THREADS = 256;
 constexpr int SORT_ITEMS = 16;
@@ -855,7 +855,8 @@ static int sort_layout(uint64_t n, uint32_t b, SortBufs *sb, int K_sketch = 0) {
 
 // number of low key bits the grouping sort orders by: whole digits with 2^bits >= slack * n where
 // that is possible.  A group of equal low bits then holds about 1 / slack records of other keys.
-// sedd_cluster takes slack 16 (its linker walks over the few strangers); the verified path takes
+// sedd_cluster takes slack 1 (its linker walks over the few strangers, neighbours in memory: a
+// step of the walk costs far less than a radix pass over all records); the verified path takes
 // 4096 so that a group is, almost always, exactly one bucket.
 static int grouping_bits(uint64_t n_docs, uint64_t slack) {
   int bits = 2 * RADIX_BITS;
@@ -924,7 +925,7 @@ static int sort_rest_if_gated(uint64_t n_docs, uint32_t b, int key_bits, SortBuf
 // sedd_cluster on the buffers of `sb` (the caller has checked the arguments)
 static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_t *cluster_id,
                        SortBufs &sb, bool timed, hipStream_t st) {
-  const int bits = grouping_bits(n_docs, 16);
+  const int bits = grouping_bits(n_docs, 1);
   const uint32_t n = (uint32_t)n_docs;
   const uint64_t total = n_docs * (uint64_t)b;
   const uint32_t link_grid = (uint32_t)((total + 255) / 256);
