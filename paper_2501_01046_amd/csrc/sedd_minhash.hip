@@ -2094,7 +2094,9 @@ __global__ void k_stream_soff(const uint64_t *__restrict__ off, uint64_t n_docs,
 // form) with the tables 257^i and the per-length Horner multipliers behind them, written once by
 // k_coeffs / k_coeffs_pp and only read afterwards.  A set is created on the stream of the call that first asks for it; a call on
 // another stream waits for the creating kernel through an event until that event has been seen
-// complete.  Probe slots: a small ring of pinned host records that the offset probe and the
+// complete.  A call holds its set (TablesLease) from the look-up until its kernels are enqueued;
+// when the cache is full, the sets that no call holds are freed after a device synchronisation,
+// so no kernel, enqueued or about to be, can still read them.  Probe slots: a small ring of pinned host records that the offset probe and the
 // validation kernel write directly, one per call in flight.
 struct TableSet {
   int K;
@@ -2103,6 +2105,7 @@ struct TableSet {
   uint8_t *dev;
   hipEvent_t ready;
   bool settled;
+  int users;  // calls between look-up and the launch of their last kernel
 };
 constexpr size_t MAX_TABLE_SETS = 16;
 constexpr uint32_t PROBE_SLOTS = 64;
@@ -2115,7 +2118,23 @@ static std::vector<TableSet> g_table_sets;
 static ProbeSlot *g_probe_ring = nullptr;
 static std::atomic<uint32_t> g_probe_next{0};
 
-static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, StreamTables *out) {
+static void tables_release(const uint8_t *dev) {
+  std::lock_guard<std::mutex> lock(g_stream_mutex);
+  for (TableSet &t : g_table_sets)
+    if (t.dev == dev && t.users > 0) {
+      t.users--;
+      return;
+    }
+}
+struct TablesLease {
+  const uint8_t *dev = nullptr;
+  ~TablesLease() {
+    if (dev) tables_release(dev);
+  }
+};
+
+static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, StreamTables *out,
+                          TablesLease *lease) {
   std::lock_guard<std::mutex> lock(g_stream_mutex);
   Carver cv;
   uint64_t o_a = 0, o_b = 0, o_cs = 0, o_qpow = 0, o_ptab = 0, o_cpp = 0, o_ptpp = 0;
@@ -2149,22 +2168,31 @@ static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, Stre
       (void)hipGetLastError();  // hipEventQuery reports "not ready" as an error value
     }
     bind(t.dev);
+    t.users++;
+    lease->dev = t.dev;
     return SEDD_OK;
   }
   if (g_table_sets.size() >= MAX_TABLE_SETS) {
-    // rare: more distinct (K, seed) pairs than slots; start over once nothing can still read them
+    // rare: more distinct (K, seed, modulus) triples than slots.  Sets that a call still holds
+    // stay; the others go once nothing enqueued can still read them.
     SEDD_HIP(hipDeviceSynchronize());
+    std::vector<TableSet> kept;
     for (TableSet &t : g_table_sets) {
+      if (t.users > 0) {
+        kept.push_back(t);
+        continue;
+      }
       (void)hipFree(t.dev);
       (void)hipEventDestroy(t.ready);
     }
-    g_table_sets.clear();
+    g_table_sets.swap(kept);
   }
   TableSet t;
   t.K = K;
   t.seed = seed;
   t.paper = paper;
   t.settled = false;
+  t.users = 1;
   void *p = nullptr;
   if (hipMalloc(&p, cv.off) != hipSuccess) {
     (void)hipGetLastError();
@@ -2181,10 +2209,17 @@ static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, Stre
                        (uint64_t *)(t.dev + o_a), (uint64_t *)(t.dev + o_b),
                        (CoefSplit *)(t.dev + o_cs), (uint64_t *)(t.dev + o_qpow),
                        (PowSplit *)(t.dev + o_ptab));
-  SEDD_LAUNCH_CHECK();
-  SEDD_HIP(hipEventCreateWithFlags(&t.ready, hipEventDisableTiming));
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&t.ready, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    // an asynchronous error may stem from the launch above: let it finish before the free
+    (void)hipStreamSynchronize(st);
+    (void)hipFree(t.dev);
+    return set_device_error(e, "coefficient set");
+  }
   SEDD_HIP(hipEventRecord(t.ready, st));
   g_table_sets.push_back(t);
+  lease->dev = t.dev;
   return SEDD_OK;
 }
 
@@ -2276,7 +2311,8 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
   if (n_pieces >= (uint64_t(1) << 31)) return SEDD_EINVAL;
 
   StreamTables tb;
-  rc = tables_acquire((int)K, seed, paper, st, &tb);
+  TablesLease lease;  // released when this call has enqueued its kernels
+  rc = tables_acquire((int)K, seed, paper, st, &tb, &lease);
   if (rc) return rc;
   // the two debug passes keep their counters in the arena (they are not meant to run concurrently)
   Carver cv;

@@ -937,9 +937,11 @@ def test_minhash_from_host_memory_in_chunks(sedd, flags, n):
 
 
 def test_minhash_default_mode_from_four_threads_on_four_streams(sedd):
-    """The default mode keeps no mutable shared scratch: four threads, a stream each, different
-    corpora, K and seeds, several calls per thread in flight together; every result against the
-    oracle.  More (K, seed) pairs than the coefficient cache holds are cycled through first."""
+    """Word shingles with the affine family keep no mutable shared scratch: four threads, a stream
+    each, different corpora, K and seeds (one thread in the paper-prime mode), several calls per
+    thread in flight together; every result against the oracle.  More (K, seed) pairs than the
+    coefficient cache holds are cycled through first, and again by one thread while the others
+    are calling, so that sets are evicted while others are in use."""
     import threading
     say("minhash concurrent")
     for s_ in range(20):                                    # overflow the cache of coefficient sets
@@ -949,21 +951,31 @@ def test_minhash_default_mode_from_four_threads_on_four_streams(sedd):
     for t in range(4):
         r = corpus.config(1).scaled(2500 + 400 * t, seed=50 + t)
         data, off = corpus.generate(r)
-        K, seed, n = (64, 128, 200, 256)[t], 7 * t, (5, 3, 5, 2)[t]
-        jobs.append((data, off, n, K, seed, oracle.minhash_sharded(data, off, n, K, seed, 0, procs=NPROC)))
+        K, seed, n, flags = (64, 128, 200, 256)[t], 7 * t, (5, 3, 5, 2)[t], (0, 0, 2, 0)[t]
+        jobs.append((data, off, n, K, seed, flags,
+                     oracle.minhash_sharded(data, off, n, K, seed, flags, procs=NPROC)))
+    small, small_off = corpus.generate(corpus.config(1).scaled(40))
+    small_want = [oracle.minhash(small, small_off, 5, 8, 3000 + s_, 0) for s_ in range(24)]
     errors = []
 
     def work(t):
         try:
-            data, off, n, K, seed, want = jobs[t]
+            data, off, n, K, seed, flags, want = jobs[t]
             st = torch.cuda.Stream()
             with torch.cuda.stream(st):
                 d_data, d_off = dev(data), dev(off)
+                d_small, d_small_off = dev(small), dev(small_off)
                 for rep in range(6):
-                    got = sedd.sedd_minhash(d_data, d_off, n, K, seed, 0, stream=st)
+                    got = sedd.sedd_minhash(d_data, d_off, n, K, seed, flags, stream=st)
                     st.synchronize()
                     if not np.array_equal(host(got), want):
                         errors.append((t, rep))
+                    if t == 0:                              # fresh seeds: the cache overflows meanwhile
+                        for s_ in range(4 * rep, 4 * rep + 4):
+                            g = sedd.sedd_minhash(d_small, d_small_off, 5, 8, 3000 + s_, 0, stream=st)
+                            st.synchronize()
+                            if not np.array_equal(host(g), small_want[s_]):
+                                errors.append((t, rep, "seed", s_))
         except Exception as e:                              # surfaced in the main thread
             errors.append((t, repr(e)))
     threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
