@@ -19,6 +19,7 @@
 #include <algorithm>
 #include <atomic>
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "sedd_internal.h"
@@ -2117,6 +2118,7 @@ static std::mutex g_stream_mutex;
 static std::vector<TableSet> g_table_sets;
 static ProbeSlot *g_probe_ring = nullptr;
 static std::atomic<uint32_t> g_probe_next{0};
+static std::atomic<bool> g_probe_busy[PROBE_SLOTS];  // a call holds its record until it has read it
 
 static void tables_release(const uint8_t *dev) {
   std::lock_guard<std::mutex> lock(g_stream_mutex);
@@ -2235,9 +2237,30 @@ static int probe_slot_acquire(ProbeSlot **slot) {
       g_probe_ring = (ProbeSlot *)p;
     }
   }
-  *slot = g_probe_ring + (g_probe_next.fetch_add(1) % PROBE_SLOTS);
-  return SEDD_OK;
+  // a record nobody holds; with more calls in flight than records, wait for one to come back
+  for (;;) {
+    for (uint32_t tries = 0; tries < PROBE_SLOTS; tries++) {
+      const uint32_t i = g_probe_next.fetch_add(1) % PROBE_SLOTS;
+      if (!g_probe_busy[i].exchange(true)) {
+        *slot = g_probe_ring + i;
+        return SEDD_OK;
+      }
+    }
+    std::this_thread::yield();
+  }
 }
+static void probe_slot_release(ProbeSlot *slot) {
+  if (slot) g_probe_busy[slot - g_probe_ring].store(false);
+}
+struct ProbeLease {
+  ProbeSlot *slot = nullptr;
+  hipStream_t st = nullptr;
+  bool pending = false;  // a kernel that writes the record may still be enqueued
+  ~ProbeLease() {
+    if (pending) (void)hipStreamSynchronize(st);  // an error path: nobody else gets the record before
+    probe_slot_release(slot);
+  }
+};
 
 // frees the coefficient sets and the probe ring (the device must be idle)
 int release_stream_state() {
@@ -2271,17 +2294,21 @@ static int run_minhash_stream(const uint8_t *bytes, uint64_t n_bytes, const uint
     offn = host_ends[1];
   } else {
     // the probe and the validation kernel write straight into a pinned host record
-    ProbeSlot *slot = nullptr;
-    rc = probe_slot_acquire(&slot);
+    ProbeLease held;  // given back when this block has read the record
+    rc = probe_slot_acquire(&held.slot);
     if (rc) return rc;
+    ProbeSlot *slot = held.slot;
+    held.st = st;
     slot->off0 = slot->offn = 0;
     slot->bad = 0;
+    held.pending = true;
     hipLaunchKernelGGL(k_stream_probe, dim3(1), dim3(1), 0, st, doc_offsets, n_docs, &slot->off0);
     SEDD_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_validate_offsets, dim3((uint32_t)((n_docs + 255) / 256)), dim3(256), 0, st,
                        doc_offsets, n_docs, max_doc, &slot->bad);
     SEDD_LAUNCH_CHECK();
     SEDD_HIP(hipStreamSynchronize(st));
+    held.pending = false;
     off0 = slot->off0;
     offn = slot->offn;
     if (slot->bad) return SEDD_EINVAL;
