@@ -15,7 +15,7 @@
  *     Calls enqueue their kernels on it and return; results are ready when the
  *     stream has drained.  sedd_minhash first validates `doc_offsets` with two
  *     small kernels and waits once for the first and last offset and the verdict
- *     (twice with byte shingles or an alternative hash mode, which also plan
+ *     (twice with byte shingles or the rolling-family mode, which also plan
  *     bounded-size chunks); everything after that is enqueued without host waits.
  *   - Return value: SEDD_OK (0) or a negative error code.  On an error no output
  *     is written.  Bad scalars, null or misaligned pointers are found before any
@@ -28,10 +28,11 @@
  *     calls that use it: those must not overlap in time, neither on different
  *     streams nor from different threads.  sedd_release_scratch() frees it.
  *     Calls that do NOT use it may run concurrently from several threads on
- *     several streams: sedd_minhash / sedd_minhash_bounded in the default mode
- *     (word shingles, no mode flag; its coefficient tables are cached per
- *     (K, seed) and read-only), sedd_lsh_keys, sedd_lsh_dense_keys, and
- *     sedd_cluster_ws / sedd_cluster_verified_ws with a workspace per call.
+ *     several streams: sedd_minhash / sedd_minhash_bounded on word shingles
+ *     without SEDD_FLAG_ROLLING_FAMILY (the default mode and the paper-prime
+ *     mode; their coefficient tables are cached per (K, seed, modulus) and
+ *     read-only), sedd_lsh_keys, sedd_lsh_dense_keys, and sedd_cluster_ws /
+ *     sedd_cluster_verified_ws with a workspace per call.
  *   - All arithmetic is exact unsigned integer arithmetic; results do not
  *     depend on launch shape, chunking or timing.
  */
@@ -119,8 +120,8 @@ int sedd_minhash_bounded(const uint8_t *bytes, uint64_t n_bytes, const uint64_t 
  * into one of two device staging buffers while chunk i is hashed on `stream`; the signatures are
  * those of one sedd_minhash call on the whole text.
  * Host memory should be pinned (hipHostMalloc): uploads from pageable memory are correct but do
- * not overlap.  The offsets are validated on the host, so the default hash mode enqueues
- * everything without waiting on the device; the call returns when the last upload has left the
+ * not overlap.  The offsets are validated on the host, so word shingles of the default and the
+ * paper-prime mode enqueue everything without waiting on the device; the call returns when the last upload has left the
  * host buffers (they may then be changed or freed) and `sig` is complete when `stream` drains.
  * The staging buffers (2 x the largest chunk) are kept for later calls; sedd_release_scratch
  * frees them.  Like the scratch arena they are shared: calls must not overlap in time.
