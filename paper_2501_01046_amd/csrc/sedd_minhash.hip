@@ -812,7 +812,7 @@ static int run_minhash(const uint8_t *bytes, uint64_t n_bytes, const uint64_t *d
   // validation and chunk planning on the device; the host sees a handful of numbers
   const uint64_t chunk_bytes =
       g_chunk_bytes_override ? std::min<uint64_t>(g_chunk_bytes_override, uint64_t(1) << 30)
-                             : (byte_mode ? (uint64_t(128) << 20) : (uint64_t(256) << 20));
+                             : (byte_mode ? (uint64_t(1) << 30) : (uint64_t(256) << 20));
   const uint64_t chunk_docs = uint64_t(1) << 22;
   // chunk positions are 32-bit: a chunk is at most chunk_bytes (<= 2^30) plus one document
   const uint64_t max_doc = (uint64_t(1) << 32) - (uint64_t(1) << 30) - (uint64_t(1) << 16);

@@ -5,8 +5,8 @@ The CPU oracle cannot process these corpora whole in test time, so:
   * signatures and band keys are compared bit for bit on a sample the oracle computes: at least
     1 % of the documents of workloads 3 and 5 and 10 % of workload 4 (random runs of consecutive
     documents, a contiguous prefix, every document within 50 of an edge of a streamed 2 GB piece
-    or of one of the 256 MB chunks sedd_minhash cuts a piece into, the longest documents, random
-    single documents, exact copies and their sources);
+    or of a chunk boundary of the chunked paths, the longest documents, random single documents,
+    exact copies and their sources);
   * on the contiguous prefix (200k documents; 20k of workload 4, long documents included) the
     oracle runs the whole path on its own signatures and keys, and the GPU's cluster ids and
     verified cluster ids of the same prefix must equal the oracle's;
@@ -55,8 +55,8 @@ def sedd():
     m.sedd_release_scratch()
 
 
-CHUNK_BYTES_WORDS = 256 << 20     # sedd_minhash's internal chunk size (word / byte shingles)
-CHUNK_BYTES_BYTES = 128 << 20
+CHUNK_BYTES_WORDS = 256 << 20     # chunk size of sedd_minhash's chunked paths (rolling family on words;
+CHUNK_BYTES_BYTES = 1 << 30       # byte shingles); the streaming kernel has no chunks
 CHUNK_DOCS = 1 << 22
 
 
@@ -401,13 +401,18 @@ def test_one_document_above_one_gigabyte(sedd):
     bad = np.nonzero((got != want).any(axis=1))[0]
     assert bad.size == 0, f"documents {bad[:5]} differ"
     del d_data, data
-    # byte shingles (the chunked path): one document of 160 MB, larger than a 128 MB chunk
+    # byte shingles (the chunked path): one document of 160 MB with chunks of 64 MB, so that the
+    # document is longer than a chunk
     docs = small[:50] + [block * (160_000_000 // len(block) + 1)] + small[50:]
     data = np.frombuffer(b"".join(docs), dtype=np.uint8)
     off = np.cumsum([0] + [len(d) for d in docs]).astype(np.uint64)
     want_b = oracle.minhash_sharded(data, off, 13, K, 1, 1, procs=NPROC)
-    got_b = sedd.sedd_minhash(torch.from_numpy(data.copy()).cuda(), torch.from_numpy(off).cuda(),
-                              13, K, 1, 1).cpu().numpy()
+    sedd.debug_set_chunk_bytes(64 << 20)
+    try:
+        got_b = sedd.sedd_minhash(torch.from_numpy(data.copy()).cuda(), torch.from_numpy(off).cuda(),
+                                  13, K, 1, 1).cpu().numpy()
+    finally:
+        sedd.debug_set_chunk_bytes(0)
     assert np.array_equal(got_b, want_b)
 
 
@@ -419,7 +424,7 @@ def test_config2_full_size_paper_prime(sedd):
     sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, r.K, 2, 1 << 62)
     ids, copies = _sample_docs(gen, r, bounds, lengths, n_random=4000, n_longest=6, n_copies=0,
                                seed=22)
-    # documents around the internal 256 MB chunk edges (about 99k documents per chunk)
+    # and documents at regular distances through the corpus
     edge = [d for c in range(1, 10) for d in range(c * 98_000, c * 98_000 + 2_500, 25)]
     ids = np.array(sorted(set(ids.tolist()) | set(edge)), dtype=np.int64)
     want = _oracle_on_sample(gen, ids, r.shingle_n, r.K, 2)
