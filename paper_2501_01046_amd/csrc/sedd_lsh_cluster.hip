@@ -1,5 +1,6 @@
 // sedd_lsh_keys and sedd_cluster: band keys, per-band radix sort, run detection, union-find.
 #include <algorithm>
+#include <cmath>
 
 #include "sedd_internal.h"
 
@@ -536,13 +537,34 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 // Phase 0 runs the tiles (0, tj) of every group, phase 1 the others; a phase-1 tile whose records
 // are all in the component of the group's first record already is skipped, which keeps a large
 // group of alike documents (exact copies, empty documents) linear instead of quadratic.
+//
+// Two kernels share this scheme.  k_v_groups takes the groups whose records fit LDS (document
+// ids, keys and all sketch words of up to group_capacity(KW) records: the dense buckets of
+// Section 3.2 hold a few hundred): one block loads the group once and then runs its tiles from
+// LDS, so a tile touches global memory only for the rare candidate pair.  Groups of up to
+// VG_SMALL_WORDS of LDS take one wavefront each (a dozen tiles at most, nothing to synchronise),
+// larger ones a block of four.  k_v_tiles takes the groups beyond that, staging two tiles of
+// sketches at a time.
+// Unrelated documents differ in about 16 sketch bits per word, so after a few words every pair
+// of a tile is usually ruled out already; k_v_groups accumulates `check_words` words (chosen on
+// the host from K and min_match) for all pairs of a tile, drops the tile if no pair is left, and
+// otherwise finishes the few pairs that are, one by one.  The bound itself is exact either way:
+// popcounts only grow.
 
 constexpr int VT = 64;
 constexpr int VWC = 8;   // sketch words per record staged at a time (256 signature entries)
 constexpr int VTHREADS = 64;
+constexpr uint32_t VG_LDS_WORDS = 12 * 1024;   // k_v_groups with four wavefronts: 48 KiB, three blocks
+                                               // per compute unit (as many as the registers allow)
+constexpr uint32_t VG_SMALL_WORDS = 3 * 1024;  // k_v_groups with one wavefront: 12 KiB
 
 // sketch words per document
 __host__ __device__ static inline uint32_t sketch_words(int K) { return (uint32_t)((K + 31) / 32); }
+// records of a group that k_v_groups can hold: per record KW sketch words, the key, the document
+// id and a flag; whole tiles
+__host__ __device__ static inline uint32_t group_capacity(uint32_t KW, uint32_t lds_words = VG_LDS_WORDS) {
+  return (lds_words / (KW + 4)) & ~uint32_t(VT - 1);
+}
 
 // bits[d * KW + w]: bit i = lowest bit of sig[d * K + 32 w + i] (0 past K).  A wavefront takes 64
 // consecutive entries of one document at a time (one coalesced load, one ballot, two words).
@@ -583,10 +605,10 @@ __device__ __forceinline__ int exact_matches(const uint32_t *__restrict__ sig, u
   return m;
 }
 
-// exclusive prefix sums over the large groups of their phase-0 and phase-1 tile counts
+// exclusive prefix sums over the large groups of their phase-0 and phase-1 tile counts (k_v_tiles)
 __global__ void __launch_bounds__(1024)
 k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ counts,
-               uint64_t big_cap, uint64_t *__restrict__ pre) {
+               uint64_t big_cap, uint32_t lds_capacity, uint64_t *__restrict__ pre) {
   __shared__ uint64_t s_part[1024 / 64];
   __shared__ uint64_t s_carry[2];
   const uint32_t nb = min((uint64_t)counts[2], big_cap);
@@ -596,7 +618,7 @@ k_v_plan_tiles(const BigGroup *__restrict__ big, const uint32_t *__restrict__ co
   for (uint32_t base = 0; base < nb; base += 1024) {
     const uint32_t g = base + threadIdx.x;
     uint64_t v[2] = {0, 0};
-    if (g < nb) {
+    if (g < nb && big[g].size > lds_capacity) {  // the others are k_v_groups' work
       const uint64_t T = (big[g].size + VT - 1) / VT;
       v[0] = T;
       v[1] = T * (T - 1) / 2;
@@ -763,6 +785,153 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
         // a candidate: the full comparison decides (skipped for documents joined already)
         if (uf_find(parent, u) == uf_find(parent, v)) continue;
         if (min_match <= 0 || exact_matches(sig, u, v, K, vec_ok) >= min_match) uf_unite(parent, u, v);
+      }
+  }
+}
+
+// A pair that the sketch words before w_from have not ruled out (d differing bits so far): the
+// remaining words, then the keys, then the full comparison.  Rare, so kept out of line.
+__device__ __noinline__ void group_pair(const uint32_t *__restrict__ sk, uint32_t cap, int KW,
+                                        int w_from, uint32_t d, int max_diff,
+                                        const uint32_t *__restrict__ s_doc,
+                                        const uint64_t *__restrict__ s_key, uint32_t ri, uint32_t cj,
+                                        const uint32_t *__restrict__ sig, int K, int min_match,
+                                        bool vec_ok, uint32_t *parent) {
+  const uint32_t u = s_doc[ri], v = s_doc[cj];
+  if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) return;
+  if (s_key[ri] != s_key[cj]) return;
+  for (int w = w_from; w < KW && (int)d <= max_diff; w++)
+    d += __popc(sk[(size_t)w * cap + ri] ^ sk[(size_t)w * cap + cj]);
+  if ((int)d > max_diff) return;  // the bound rules the pair out
+  // a candidate: the full comparison decides (skipped for documents joined already)
+  if (uf_find(parent, u) == uf_find(parent, v)) return;
+  if (min_match <= 0 || exact_matches(sig, u, v, K, vec_ok) >= min_match) uf_unite(parent, u, v);
+}
+
+// One tile of a group that sits in LDS: the 64 records from row0 on against the 64 from col0 on
+// (row0 <= col0, both multiples of VT).  sk[w * cap + rec] = sketch word w of record rec; records
+// past the group's end have the document id 0xFFFFFFFF and zero sketches.  One wavefront, each
+// lane an 8 x 8 block of pairs.  The first check_words words are accumulated for all pairs; if
+// some pair is still below the bound then, the few that are get finished one by one.
+__device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint32_t cap, int KW,
+                                           int check_words, int max_diff,
+                                           const uint32_t *__restrict__ s_doc,
+                                           const uint64_t *__restrict__ s_key, uint32_t row0,
+                                           uint32_t col0, const uint32_t *__restrict__ sig, int K,
+                                           int min_match, bool vec_ok, uint32_t *parent) {
+  const int lane = threadIdx.x & 63, ty = lane >> 3, tx = lane & 7;  // rows 8 ty .., columns 8 tx ..
+  uint32_t diff[64];  // diff[8 i + j]: sketch bits that differ, row 8 ty + i against column 8 tx + j
+  const uint32_t *rp = sk + row0 + ty * 8, *cp = sk + col0 + tx * 8;
+  auto accumulate = [&](int w, bool first) {
+    const uint4 r0 = *reinterpret_cast<const uint4 *>(rp + (size_t)w * cap);
+    const uint4 r1 = *reinterpret_cast<const uint4 *>(rp + (size_t)w * cap + 4);
+    const uint4 c0 = *reinterpret_cast<const uint4 *>(cp + (size_t)w * cap);
+    const uint4 c1 = *reinterpret_cast<const uint4 *>(cp + (size_t)w * cap + 4);
+    const uint32_t rv[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+    const uint32_t cv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+      for (int j = 0; j < 8; j++)
+        diff[8 * i + j] = (first ? 0u : diff[8 * i + j]) + __popc(rv[i] ^ cv[j]);
+  };
+  accumulate(0, true);
+  for (int w = 1; w < check_words; w++) accumulate(w, false);
+  // the smallest count among the pairs that matter: in a diagonal tile those above the diagonal
+  uint32_t least = 0xFFFFFFFFu;
+  if (row0 == col0) {
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+      for (int j = 0; j < 8; j++)
+        if (ty * 8 + i < tx * 8 + j) least = min(least, diff[8 * i + j]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 64; i++) least = min(least, diff[i]);
+  }
+  if (__all((int)least > max_diff)) return;  // no pair of the tile can reach min_match any more
+  if ((int)least > max_diff) return;         // none of this lane's
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      if ((int)diff[8 * i + j] > max_diff) continue;
+      const uint32_t ri = row0 + ty * 8 + i, cj = col0 + tx * 8 + j;
+      if (row0 == col0 && ri >= cj) continue;  // upper triangle of a diagonal tile
+      group_pair(sk, cap, KW, check_words, diff[8 * i + j], max_diff, s_doc, s_key, ri, cj, sig, K,
+                 min_match, vec_ok, parent);
+    }
+}
+
+// The large groups of more than min_size records that fit LDS_WORDS of LDS (see above): one block
+// of WAVES wavefronts per group at a time.
+template <int WAVES, uint32_t LDS_WORDS>
+__global__ void __launch_bounds__(WAVES * 64)
+k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
+           const uint32_t *__restrict__ sig, const uint32_t *__restrict__ bits, int K, int min_match,
+           int check_words, uint32_t min_size, uint32_t *parent, const BigGroup *__restrict__ big,
+           const uint32_t *__restrict__ counts, uint64_t big_cap) {
+  constexpr uint32_t VG_THREADS = WAVES * 64;
+  __shared__ __attribute__((aligned(16))) uint32_t lds[LDS_WORDS];
+  const int KW = (int)sketch_words(K);
+  const uint32_t cap = group_capacity((uint32_t)KW, LDS_WORDS);
+  // keys first (8-byte aligned), then document ids, flags, sketches [word][record]
+  uint64_t *s_key = reinterpret_cast<uint64_t *>(lds);
+  uint32_t *s_doc = lds + 2 * cap, *s_joined = lds + 3 * cap, *sk = lds + 4 * cap;
+  const uint32_t nb = min((uint64_t)counts[2], big_cap);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
+  const int max_diff = K - min_match;  // a pair whose sketches differ in more bits cannot reach min_match
+  for (uint32_t gi = blockIdx.x; gi < nb; gi += gridDim.x) {
+    const BigGroup g = big[gi];
+    if (g.size > cap || g.size <= min_size) continue;  // another launch's work (uniform over the block)
+    const uint32_t T = (g.size + VT - 1) / VT;
+    __syncthreads();  // the previous group's readers are done
+    // two sweeps, so that the loads of several records are in flight together: ids and keys
+    // first, then the sketches they point to (a thread reads back what it wrote itself)
+#pragma unroll 4
+    for (uint32_t rec = tid; rec < T * VT; rec += VG_THREADS) {
+      uint32_t doc = 0xFFFFFFFFu;
+      uint64_t key = 0;
+      if (rec < g.size) {
+        doc = bd[g.start + rec];
+        key = bk[g.start + rec];
+      }
+      s_doc[rec] = doc;
+      s_key[rec] = key;
+    }
+#pragma unroll 2
+    for (uint32_t rec = tid; rec < T * VT; rec += VG_THREADS) {
+      const uint32_t doc = s_doc[rec];
+      for (int w = 0; w < KW; w++)
+        sk[(size_t)w * cap + rec] = doc != 0xFFFFFFFFu ? bits[(uint64_t)doc * KW + w] : 0u;
+    }
+    __syncthreads();
+    // phase 0: every tile against the group's first tile
+    for (uint32_t tj = wave; tj < T; tj += WAVES)
+      group_tile(sk, cap, KW, check_words, max_diff, s_doc, s_key, 0, tj * VT, sig, K, min_match, vec_ok,
+                 parent);
+    if (T < 2) continue;
+    __syncthreads();
+    // who is in the component of the group's first record by now (a record that joins it later
+    // is merely compared once more)
+    {
+      const uint32_t head_root = uf_find(parent, s_doc[0]);
+      for (uint32_t rec = tid; rec < T * VT; rec += VG_THREADS) {
+        const uint32_t doc = s_doc[rec];
+        s_joined[rec] = (doc == 0xFFFFFFFFu || uf_find(parent, doc) == head_root) ? 1u : 0u;
+      }
+    }
+    __syncthreads();
+    // phase 1: the other tiles, dealt to the wavefronts in turn
+    uint32_t q = 0;
+    for (uint32_t ti = 1; ti < T; ti++)
+      for (uint32_t tj = ti; tj < T; tj++, q++) {
+        if ((q & (WAVES - 1)) != (uint32_t)wave) continue;
+        const bool alike = s_joined[ti * VT + lane] && s_joined[tj * VT + lane];
+        if (__all(alike)) continue;  // nothing left to learn here
+        group_tile(sk, cap, KW, check_words, max_diff, s_doc, s_key, ti * VT, tj * VT, sig, K, min_match,
+                   vec_ok, parent);
       }
   }
 }
@@ -1072,6 +1241,18 @@ static int check_verified_args(const void *keys, const void *sig, uint64_t n_doc
   return SEDD_OK;
 }
 
+// Sketch words that k_v_groups accumulates for every pair of a tile before it looks at the counts.
+// Two unrelated documents differ in Binomial(32, 1/2) bits per word: after w words in about
+// 16 w +- sqrt(8 w).  The first w where four standard deviations below that mean still exceed
+// K - min_match leaves next to no unrelated pair; with a low threshold that is every word.
+static int sketch_check_words(int K, int min_match) {
+  const int KW = (int)sketch_words(K);
+  const double max_diff = (double)K - (double)min_match;
+  for (int w = 1; w < KW; w++)
+    if (16.0 * w - 4.0 * std::sqrt(8.0 * w) > max_diff) return w;
+  return KW;
+}
+
 // sedd_cluster_verified on the buffers of `sb` (the caller has checked the arguments)
 static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
                                 uint32_t b, int32_t min_match, int64_t *cluster_id, SortBufs &sb,
@@ -1117,12 +1298,23 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, b), dim3(SORT_THREADS), 0, st, sb.ka, n,
                      ~uint64_t(0), list1, counts, sb.big, sb.gate, 1);
   SEDD_LAUNCH_CHECK();
-  // large groups: tile plan, then the tiles against each group's first tile, then the rest
+  // large groups: sketches; the groups that fit LDS; for the others the tile plan, then the tiles
+  // against each group's first tile, then the rest
+  const uint32_t KW = sketch_words(K);
   hipLaunchKernelGGL(k_v_plan_tiles, dim3(1), dim3(1024), 0, st, sb.big, counts, sb.big_cap,
-                     sb.tile_pre);
+                     group_capacity(KW), sb.tile_pre);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, sketch_words(K),
-                     counts, sb.sketch);
+  hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, KW, counts,
+                     sb.sketch);
+  SEDD_LAUNCH_CHECK();
+  const int check_words = sketch_check_words((int)K, (int)min_match);
+  hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 24), dim3(64), 0, st, sb.ka, sb.da, sig,
+                     sb.sketch, (int)K, (int)min_match, check_words, 0u, sb.parent, sb.big, counts,
+                     sb.big_cap);
+  SEDD_LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_v_groups<4, VG_LDS_WORDS>), dim3(256 * 6), dim3(256), 0, st, sb.ka, sb.da, sig,
+                     sb.sketch, (int)K, (int)min_match, check_words, group_capacity(KW, VG_SMALL_WORDS),
+                     sb.parent, sb.big, counts, sb.big_cap);
   SEDD_LAUNCH_CHECK();
   for (int phase = 0; phase < 2; phase++) {
     hipLaunchKernelGGL(k_v_tiles, dim3(256 * 24), dim3(VTHREADS), 0, st, phase, sb.ka, sb.da, sig, sb.sketch,
