@@ -601,6 +601,32 @@ def test_cluster_verified_large_buckets_sketch_bound(sedd, K):
             assert np.array_equal(got, oracle.cluster_verified(keys, sg, mm)), (name, mm)
 
 
+@pytest.mark.parametrize("K,sizes", [(256, (65, 255, 256, 257, 300, 1023, 1024, 1025, 1100)),
+                                     (128, (383, 384, 385, 640, 1535, 1536, 1537)),
+                                     (1000, (64, 65, 320, 321, 500))])
+def test_cluster_verified_bucket_sizes_at_the_limits_of_the_three_kernels(sedd, K, sizes):
+    """Buckets of more than 64 documents are compared from LDS by one wavefront, from LDS by four,
+    or tile by tile from memory, depending on how many records fit next to their sketches: bucket
+    sizes at and next to those limits for three signature lengths, with related documents spread
+    over the tiles of every bucket, at thresholds where the sketch check comes early, late and
+    never."""
+    say("verified bucket sizes", K, sizes)
+    rng = np.random.default_rng(K)
+    n = int(sum(sizes))
+    band0 = np.repeat(np.arange(len(sizes), dtype=np.uint64), sizes)
+    rng.shuffle(band0)
+    keys = np.stack([band0 * np.uint64(1_000_003) + np.uint64(17),
+                     rng.integers(0, n // 3, size=n, dtype=np.uint64)], axis=1)
+    _, sig = _proto_case(K + 1, n, K, 2, 3, max(8, n // 40), noise=0.35)
+    d_keys, d_sig = dev(keys), dev(sig)
+    for mm in (oracle.min_match_for(0.8, K), oracle.min_match_for(0.95, K), K // 2, 1):
+        got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+        want = oracle.cluster_verified(keys, sig, mm)
+        assert np.array_equal(got, want), (mm, int((got != want).sum()))
+        if mm == oracle.min_match_for(0.8, K):                 # the buckets do hold related documents
+            assert n // 10 < int((want != np.arange(n)).sum()) < n
+
+
 def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
     """Buckets whose keys differ only above the sorted bits share one sorted group."""
     say("verified low-bit collisions")
