@@ -75,17 +75,24 @@ constexpr int RADIX_BITS = 8;
 constexpr int RADIX = 1 << RADIX_BITS;
 constexpr int KEY_BITS = 61;
 
-// keys[d*b + j] -> bk[j*n + d], bd[j*n + d] = d
+// keys[d*b + j] -> bk[j*n + d], bd[j*n + d] = d.  With `high`: *high is raised if some key has a
+// bit set at or above high_shift (the word must be zero before the launch).
 __global__ void __launch_bounds__(256)
 k_to_band_major(const uint64_t *__restrict__ keys, uint32_t n, uint32_t b,
-                uint64_t *__restrict__ bk, uint32_t *__restrict__ bd) {
+                uint64_t *__restrict__ bk, uint32_t *__restrict__ bd, int high_shift,
+                uint32_t *high) {
   uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
-  if (d >= n) return;
-  const uint64_t *row = keys + (uint64_t)d * b;
-  for (uint32_t j = 0; j < b; j++) {
-    bk[(uint64_t)j * n + d] = row[j];
-    bd[(uint64_t)j * n + d] = d;
+  uint64_t seen = 0;
+  if (d < n) {
+    const uint64_t *row = keys + (uint64_t)d * b;
+    for (uint32_t j = 0; j < b; j++) {
+      const uint64_t key = row[j];
+      seen |= key;
+      bk[(uint64_t)j * n + d] = key;
+      bd[(uint64_t)j * n + d] = d;
+    }
   }
+  if (high && __any((seen >> high_shift) != 0) && (threadIdx.x & 63) == 0) atomicOr(high, 1u);
 }
 
 __global__ void __launch_bounds__(SORT_THREADS)
@@ -956,6 +963,7 @@ struct SortBufs {
   uint64_t *ka, *kb;
   uint32_t *da, *db, *hist, *tmp, *parent;
   uint32_t *gate;      // raised by the linking / marking kernel when the sorted bits are too few
+  uint32_t *high;      // raised by k_to_band_major when some key reaches into the last two digits sorted
   uint32_t *counts;    // verified path: lengths of the follower, outsider and large-group lists
   uint32_t *sketch;    // one-bit signature sketches (verified path): n * sketch_words(K) words
   BigGroup *big;       // capacity big_cap
@@ -985,7 +993,7 @@ static SortPlan plan_sort(uint64_t n, uint32_t b, int K_sketch) {
   pl.o_h = cv.take<uint32_t>(nh);
   pl.o_t = cv.take<uint32_t>(scan_tmp_count(nh));
   pl.o_p = cv.take<uint32_t>(n);
-  pl.o_gate = cv.take<uint32_t>(1);
+  pl.o_gate = cv.take<uint32_t>(2);
   pl.o_counts = cv.take<uint32_t>(4);
   pl.big_cap = K_sketch ? total / BIG_GROUP + 1 : 0;
   pl.o_big = cv.take<BigGroup>(pl.big_cap + 1);
@@ -1004,6 +1012,7 @@ static void bind_sort(const SortPlan &pl, uint8_t *A, SortBufs *sb) {
   sb->tmp = (uint32_t *)(A + pl.o_t);
   sb->parent = (uint32_t *)(A + pl.o_p);
   sb->gate = (uint32_t *)(A + pl.o_gate);
+  sb->high = sb->gate + 1;
   sb->counts = (uint32_t *)(A + pl.o_counts);
   sb->big = (BigGroup *)(A + pl.o_big);
   sb->tile_pre = (uint64_t *)(A + pl.o_pre);
@@ -1073,14 +1082,26 @@ static int sort_passes(uint32_t n, uint32_t b, int shift0, int shift1, SortBufs 
 }
 
 // leaves the records, sorted by the low key_bits bits (whole digits, or KEY_BITS for a full
-// sort), in sb->ka / sb->da; sb->kb / sb->db are free afterwards
+// sort), in sb->ka / sb->da; sb->kb / sb->db are free afterwards.
+// With skip_empty_digits the last two passes run only if some key has a bit set in the digits
+// they sort by (they are enqueued either way and return at once otherwise): keys that are small
+// numbers, like the bucket ids of sedd_lsh_dense_keys, are sorted after the passes that matter.
 static int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key_bits, SortBufs *sb,
-                      hipStream_t st) {
+                      hipStream_t st, bool skip_empty_digits = false) {
   const uint32_t n = (uint32_t)n_docs;
+  const bool split = skip_empty_digits && key_bits >= 3 * RADIX_BITS && key_bits < KEY_BITS;
+  const int always_bits = split ? key_bits - 2 * RADIX_BITS : key_bits;
+  if (split) {
+    hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, sb->high, 1u, 0u,
+                       (const uint32_t *)nullptr);
+    SEDD_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(k_to_band_major, dim3((n + 255) / 256), dim3(256), 0, st, keys, n, b, sb->ka,
-                     sb->da);
+                     sb->da, always_bits, split ? sb->high : (uint32_t *)nullptr);
   SEDD_LAUNCH_CHECK();
-  return sort_passes(n, b, 0, key_bits, sb, nullptr, st);
+  int rc = sort_passes(n, b, 0, always_bits, sb, nullptr, st);
+  if (rc || !split) return rc;
+  return sort_passes(n, b, always_bits, key_bits, sb, sb->high, st);  // two passes: no copy back
 }
 
 // The fallback of the grouping sort: the passes over the key bits it left out, enqueued always,
@@ -1263,7 +1284,7 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   g_last_gate = sb.gate;
   {
     ProfScope prof(SEDD_PROF_SORT, st);
-    rc = sort_bands(keys, n_docs, b, bits, &sb, st);
+    rc = sort_bands(keys, n_docs, b, bits, &sb, st, true);
     if (rc) return rc;
   }
   const uint32_t n = (uint32_t)n_docs;
