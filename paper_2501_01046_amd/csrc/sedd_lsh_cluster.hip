@@ -952,11 +952,15 @@ __global__ void k_copy_sorted(const uint64_t *__restrict__ bk, const uint32_t *_
                               uint64_t total, uint64_t *__restrict__ ok,
                               uint32_t *__restrict__ od, const uint32_t *__restrict__ gate) {
   if (gate && *gate == 0) return;
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < total) {
+  const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
     ok[i] = bk[i];
     od[i] = bd[i];
   }
+}
+// a grid that fills the chip a few times over: a gated launch that has nothing to do costs little
+static uint32_t copy_grid(uint64_t total) {
+  return (uint32_t)std::min<uint64_t>((total + 255) / 256, 256 * 64);
 }
 
 struct SortBufs {
@@ -1068,7 +1072,7 @@ static int sort_passes(uint32_t n, uint32_t b, int shift0, int shift1, SortBufs 
   if (gate) {
     if (src_k != sb->ka) {
       const uint64_t total = (uint64_t)n * b;
-      hipLaunchKernelGGL(k_copy_sorted, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, src_k,
+      hipLaunchKernelGGL(k_copy_sorted, dim3(copy_grid(total)), dim3(256), 0, st, src_k,
                          src_d, total, sb->ka, sb->da, gate);
       SEDD_LAUNCH_CHECK();
     }
@@ -1428,7 +1432,7 @@ int sedd_debug_sort_bands(const uint64_t *keys, uint64_t n_docs, int32_t b,
   rc = sort_bands(keys, n_docs, (uint32_t)b, KEY_BITS, &sb, st);
   if (rc) return rc;
   const uint64_t total = n_docs * (uint64_t)b;
-  hipLaunchKernelGGL(k_copy_sorted, dim3((uint32_t)((total + 255) / 256)), dim3(256), 0, st, sb.ka,
+  hipLaunchKernelGGL(k_copy_sorted, dim3(copy_grid(total)), dim3(256), 0, st, sb.ka,
                      sb.da, total, keys_sorted, docs_sorted, (const uint32_t *)nullptr);
   SEDD_LAUNCH_CHECK();
   return SEDD_OK;
