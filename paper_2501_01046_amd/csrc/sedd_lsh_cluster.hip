@@ -545,32 +545,33 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
 // are all in the component of the group's first record already is skipped, which keeps a large
 // group of alike documents (exact copies, empty documents) linear instead of quadratic.
 //
-// Two kernels share this scheme.  k_v_groups takes the groups whose records fit LDS (document
-// ids, keys and all sketch words of up to group_capacity(KW) records: the dense buckets of
-// Section 3.2 hold a few hundred): one block loads the group once and then runs its tiles from
-// LDS, so a tile touches global memory only for the rare candidate pair.  Groups of up to
-// VG_SMALL_WORDS of LDS take one wavefront each (a dozen tiles at most, nothing to synchronise),
-// larger ones a block of four.  k_v_tiles takes the groups beyond that, staging two tiles of
-// sketches at a time.
+// Two kernels share this scheme.  k_v_groups takes the groups whose records fit LDS: document ids,
+// keys and the first `lds_words` sketch words of every record (the dense buckets of Section 3.2
+// hold a few hundred records).  One block loads the group once and then runs its tiles, 32 x 64
+// pairs each, from LDS, so a tile touches global memory only for the rare pair that survives.
+// Groups that fit VG_SMALL_WORDS of LDS take one wavefront each (a dozen tiles, nothing to
+// synchronise), larger ones a block of four.  k_v_tiles takes the groups beyond that, staging two
+// tiles of 64 records' sketches at a time.
 // Unrelated documents differ in about 16 sketch bits per word, so after a few words every pair
-// of a tile is usually ruled out already; k_v_groups accumulates `check_words` words (chosen on
-// the host from K and min_match) for all pairs of a tile, drops the tile if no pair is left, and
-// otherwise finishes the few pairs that are, one by one.  The bound itself is exact either way:
-// popcounts only grow.
+// of a tile is usually ruled out already.  `lds_words` is that number of words (chosen on the
+// host from K and min_match): k_v_groups accumulates them for all pairs of a tile, drops the tile
+// if no pair is left, and otherwise finishes the few pairs that are, one by one, with the
+// remaining sketch words from memory.  The bound itself is exact either way: popcounts only grow.
 
 constexpr int VT = 64;
 constexpr int VWC = 8;   // sketch words per record staged at a time (256 signature entries)
 constexpr int VTHREADS = 64;
-constexpr uint32_t VG_LDS_WORDS = 12 * 1024;   // k_v_groups with four wavefronts: 48 KiB, three blocks
+constexpr uint32_t VG_LDS_WORDS = 8 * 1024;    // k_v_groups with four wavefronts: 32 KiB, five blocks
                                                // per compute unit (as many as the registers allow)
-constexpr uint32_t VG_SMALL_WORDS = 3 * 1024;  // k_v_groups with one wavefront: 12 KiB
+constexpr uint32_t VG_SMALL_WORDS = 2 * 1024;  // k_v_groups with one wavefront: 8 KiB
 
 // sketch words per document
 __host__ __device__ static inline uint32_t sketch_words(int K) { return (uint32_t)((K + 31) / 32); }
-// records of a group that k_v_groups can hold: per record KW sketch words, the key, the document
-// id and a flag; whole tiles
-__host__ __device__ static inline uint32_t group_capacity(uint32_t KW, uint32_t lds_words = VG_LDS_WORDS) {
-  return (lds_words / (KW + 4)) & ~uint32_t(VT - 1);
+// records of a group that k_v_groups can hold: per record the sketch words it keeps in LDS, the
+// key, the document id and a flag; whole tiles
+__host__ __device__ static inline uint32_t group_capacity(uint32_t sketch_words_in_lds,
+                                                          uint32_t lds_words = VG_LDS_WORDS) {
+  return (lds_words / (sketch_words_in_lds + 4)) & ~uint32_t(VT - 1);
 }
 
 // bits[d * KW + w]: bit i = lowest bit of sig[d * K + 32 w + i] (0 past K).  A wavefront takes 64
@@ -796,77 +797,78 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
   }
 }
 
-// A pair that the sketch words before w_from have not ruled out (d differing bits so far): the
-// remaining words, then the keys, then the full comparison.  Rare, so kept out of line.
-__device__ __noinline__ void group_pair(const uint32_t *__restrict__ sk, uint32_t cap, int KW,
-                                        int w_from, uint32_t d, int max_diff,
-                                        const uint32_t *__restrict__ s_doc,
+// A pair that the sketch words in LDS (the first lds_words of each record) have not ruled out, d
+// differing bits so far: the keys, the remaining sketch words from memory, then the full
+// comparison.  Rare, so kept out of line.
+__device__ __noinline__ void group_pair(const uint32_t *__restrict__ bits, int KW, int lds_words,
+                                        uint32_t d, int max_diff, const uint32_t *__restrict__ s_doc,
                                         const uint64_t *__restrict__ s_key, uint32_t ri, uint32_t cj,
                                         const uint32_t *__restrict__ sig, int K, int min_match,
                                         bool vec_ok, uint32_t *parent) {
   const uint32_t u = s_doc[ri], v = s_doc[cj];
   if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) return;
   if (s_key[ri] != s_key[cj]) return;
-  for (int w = w_from; w < KW && (int)d <= max_diff; w++)
-    d += __popc(sk[(size_t)w * cap + ri] ^ sk[(size_t)w * cap + cj]);
+  const uint32_t *bu = bits + (uint64_t)u * KW, *bv = bits + (uint64_t)v * KW;
+  for (int w = lds_words; w < KW && (int)d <= max_diff; w++) d += __popc(bu[w] ^ bv[w]);
   if ((int)d > max_diff) return;  // the bound rules the pair out
   // a candidate: the full comparison decides (skipped for documents joined already)
   if (uf_find(parent, u) == uf_find(parent, v)) return;
   if (min_match <= 0 || exact_matches(sig, u, v, K, vec_ok) >= min_match) uf_unite(parent, u, v);
 }
 
-// One tile of a group that sits in LDS: the 64 records from row0 on against the 64 from col0 on
-// (row0 <= col0, both multiples of VT).  sk[w * cap + rec] = sketch word w of record rec; records
-// past the group's end have the document id 0xFFFFFFFF and zero sketches.  One wavefront, each
-// lane an 8 x 8 block of pairs.  The first check_words words are accumulated for all pairs; if
-// some pair is still below the bound then, the few that are get finished one by one.
-__device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint32_t cap, int KW,
-                                           int check_words, int max_diff,
+// One tile of a group that sits in LDS: the 32 records from row0 on against the 64 from col0 on
+// (row0 a multiple of 32, col0 of 64, row0 < col0 + 64).  sk[w * cap + rec] = sketch word w of
+// record rec, w < lds_words; slots past the group's end have the document id 0xFFFFFFFF.  One wavefront, each lane a 4 x 8 block of pairs (half the registers of 8 x 8:
+// five wavefronts share a SIMD).  The words in LDS are accumulated for all pairs; if some pair
+// is still below the bound then, the few that are get finished one by one.
+__device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint32_t cap, int lds_words,
+                                           const uint32_t *__restrict__ bits, int KW, int max_diff,
                                            const uint32_t *__restrict__ s_doc,
                                            const uint64_t *__restrict__ s_key, uint32_t row0,
                                            uint32_t col0, const uint32_t *__restrict__ sig, int K,
                                            int min_match, bool vec_ok, uint32_t *parent) {
-  const int lane = threadIdx.x & 63, ty = lane >> 3, tx = lane & 7;  // rows 8 ty .., columns 8 tx ..
-  uint32_t diff[64];  // diff[8 i + j]: sketch bits that differ, row 8 ty + i against column 8 tx + j
-  const uint32_t *rp = sk + row0 + ty * 8, *cp = sk + col0 + tx * 8;
+  const int lane = threadIdx.x & 63, ty = lane >> 3, tx = lane & 7;  // rows 4 ty .., columns 8 tx ..
+  uint32_t diff[32];  // diff[8 i + j]: sketch bits that differ, row 4 ty + i against column 8 tx + j
+  const uint32_t *rp = sk + row0 + ty * 4, *cp = sk + col0 + tx * 8;
   auto accumulate = [&](int w, bool first) {
     const uint4 r0 = *reinterpret_cast<const uint4 *>(rp + (size_t)w * cap);
-    const uint4 r1 = *reinterpret_cast<const uint4 *>(rp + (size_t)w * cap + 4);
     const uint4 c0 = *reinterpret_cast<const uint4 *>(cp + (size_t)w * cap);
     const uint4 c1 = *reinterpret_cast<const uint4 *>(cp + (size_t)w * cap + 4);
-    const uint32_t rv[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+    const uint32_t rv[4] = {r0.x, r0.y, r0.z, r0.w};
     const uint32_t cv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
-    for (int i = 0; i < 8; i++)
+    for (int i = 0; i < 4; i++)
 #pragma unroll
       for (int j = 0; j < 8; j++)
         diff[8 * i + j] = (first ? 0u : diff[8 * i + j]) + __popc(rv[i] ^ cv[j]);
   };
   accumulate(0, true);
-  for (int w = 1; w < check_words; w++) accumulate(w, false);
-  // the smallest count among the pairs that matter: in a diagonal tile those above the diagonal
+  for (int w = 1; w < lds_words; w++) accumulate(w, false);
+  // the smallest count among the pairs that matter: where the rows reach into the columns' range,
+  // those with the row record before the column record
+  const bool diagonal = row0 + 32 > col0;
   uint32_t least = 0xFFFFFFFFu;
-  if (row0 == col0) {
+  if (diagonal) {
 #pragma unroll
-    for (int i = 0; i < 8; i++)
+    for (int i = 0; i < 4; i++)
 #pragma unroll
       for (int j = 0; j < 8; j++)
-        if (ty * 8 + i < tx * 8 + j) least = min(least, diff[8 * i + j]);
+        if (row0 + ty * 4 + i < col0 + tx * 8 + j) least = min(least, diff[8 * i + j]);
   } else {
 #pragma unroll
-    for (int i = 0; i < 64; i++) least = min(least, diff[i]);
+    for (int i = 0; i < 32; i++) least = min(least, diff[i]);
   }
   if (__all((int)least > max_diff)) return;  // no pair of the tile can reach min_match any more
   if ((int)least > max_diff) return;         // none of this lane's
 #pragma unroll
-  for (int i = 0; i < 8; i++)
+  for (int i = 0; i < 4; i++)
 #pragma unroll
     for (int j = 0; j < 8; j++) {
       if ((int)diff[8 * i + j] > max_diff) continue;
-      const uint32_t ri = row0 + ty * 8 + i, cj = col0 + tx * 8 + j;
-      if (row0 == col0 && ri >= cj) continue;  // upper triangle of a diagonal tile
-      group_pair(sk, cap, KW, check_words, diff[8 * i + j], max_diff, s_doc, s_key, ri, cj, sig, K,
-                 min_match, vec_ok, parent);
+      const uint32_t ri = row0 + ty * 4 + i, cj = col0 + tx * 8 + j;
+      if (ri >= cj) continue;  // every pair once: the earlier record is the row
+      group_pair(bits, KW, lds_words, diff[8 * i + j], max_diff, s_doc, s_key, ri, cj, sig, K, min_match,
+                 vec_ok, parent);
     }
 }
 
@@ -876,12 +878,12 @@ template <int WAVES, uint32_t LDS_WORDS>
 __global__ void __launch_bounds__(WAVES * 64)
 k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
            const uint32_t *__restrict__ sig, const uint32_t *__restrict__ bits, int K, int min_match,
-           int check_words, uint32_t min_size, uint32_t *parent, const BigGroup *__restrict__ big,
+           int lds_words, uint32_t min_size, uint32_t *parent, const BigGroup *__restrict__ big,
            const uint32_t *__restrict__ counts, uint64_t big_cap) {
   constexpr uint32_t VG_THREADS = WAVES * 64;
   __shared__ __attribute__((aligned(16))) uint32_t lds[LDS_WORDS];
   const int KW = (int)sketch_words(K);
-  const uint32_t cap = group_capacity((uint32_t)KW, LDS_WORDS);
+  const uint32_t cap = group_capacity((uint32_t)lds_words, LDS_WORDS);
   // keys first (8-byte aligned), then document ids, flags, sketches [word][record]
   uint64_t *s_key = reinterpret_cast<uint64_t *>(lds);
   uint32_t *s_doc = lds + 2 * cap, *s_joined = lds + 3 * cap, *sk = lds + 4 * cap;
@@ -892,7 +894,7 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
   for (uint32_t gi = blockIdx.x; gi < nb; gi += gridDim.x) {
     const BigGroup g = big[gi];
     if (g.size > cap || g.size <= min_size) continue;  // another launch's work (uniform over the block)
-    const uint32_t T = (g.size + VT - 1) / VT;
+    const uint32_t T = (g.size + VT - 1) / VT;  // column blocks of 64 records; row blocks of 32: 2 T
     __syncthreads();  // the previous group's readers are done
     // two sweeps, so that the loads of several records are in flight together: ids and keys
     // first, then the sketches they point to (a thread reads back what it wrote itself)
@@ -910,14 +912,19 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
 #pragma unroll 2
     for (uint32_t rec = tid; rec < T * VT; rec += VG_THREADS) {
       const uint32_t doc = s_doc[rec];
-      for (int w = 0; w < KW; w++)
-        sk[(size_t)w * cap + rec] = doc != 0xFFFFFFFFu ? bits[(uint64_t)doc * KW + w] : 0u;
+      // a slot past the group's end gets scrambled bits, so that the bound rules it out like an
+      // unrelated document instead of keeping its tile alive (its document id says what it is anyway)
+      for (int w = 0; w < lds_words; w++)
+        sk[(size_t)w * cap + rec] =
+            doc != 0xFFFFFFFFu ? bits[(uint64_t)doc * KW + w] : 0x9E3779B9u * (rec * 8u + (uint32_t)w + 1u);
     }
     __syncthreads();
-    // phase 0: every tile against the group's first tile
-    for (uint32_t tj = wave; tj < T; tj += WAVES)
-      group_tile(sk, cap, KW, check_words, max_diff, s_doc, s_key, 0, tj * VT, sig, K, min_match, vec_ok,
-                 parent);
+    // phase 0: the group's first 64 records (two row blocks) against every column block
+    for (uint32_t q = wave; q < 2 * T; q += WAVES) {
+      const uint32_t ri = q & 1, tj = q >> 1;
+      group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, ri * 32, tj * VT, sig, K, min_match,
+                 vec_ok, parent);
+    }
     if (T < 2) continue;
     __syncthreads();
     // who is in the component of the group's first record by now (a record that joins it later
@@ -930,14 +937,15 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
       }
     }
     __syncthreads();
-    // phase 1: the other tiles, dealt to the wavefronts in turn
+    // phase 1: the other tiles (row block ri of 32 records against the column blocks from the one
+    // that holds it on), dealt to the wavefronts in turn
     uint32_t q = 0;
-    for (uint32_t ti = 1; ti < T; ti++)
-      for (uint32_t tj = ti; tj < T; tj++, q++) {
+    for (uint32_t ri = 2; ri < 2 * T; ri++)
+      for (uint32_t tj = ri >> 1; tj < T; tj++, q++) {
         if ((q & (WAVES - 1)) != (uint32_t)wave) continue;
-        const bool alike = s_joined[ti * VT + lane] && s_joined[tj * VT + lane];
+        const bool alike = s_joined[ri * 32 + (lane & 31)] && s_joined[tj * VT + lane];
         if (__all(alike)) continue;  // nothing left to learn here
-        group_tile(sk, cap, KW, check_words, max_diff, s_doc, s_key, ti * VT, tj * VT, sig, K, min_match,
+        group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, ri * 32, tj * VT, sig, K, min_match,
                    vec_ok, parent);
       }
   }
@@ -1326,20 +1334,21 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   // large groups: sketches; the groups that fit LDS; for the others the tile plan, then the tiles
   // against each group's first tile, then the rest
   const uint32_t KW = sketch_words(K);
+  const int check_words = sketch_check_words((int)K, (int)min_match);
   hipLaunchKernelGGL(k_v_plan_tiles, dim3(1), dim3(1024), 0, st, sb.big, counts, sb.big_cap,
-                     group_capacity(KW), sb.tile_pre);
+                     group_capacity((uint32_t)check_words), sb.tile_pre);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, KW, counts,
                      sb.sketch);
   SEDD_LAUNCH_CHECK();
-  const int check_words = sketch_check_words((int)K, (int)min_match);
-  hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 24), dim3(64), 0, st, sb.ka, sb.da, sig,
+  hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 40), dim3(64), 0, st, sb.ka, sb.da, sig,
                      sb.sketch, (int)K, (int)min_match, check_words, 0u, sb.parent, sb.big, counts,
                      sb.big_cap);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_v_groups<4, VG_LDS_WORDS>), dim3(256 * 6), dim3(256), 0, st, sb.ka, sb.da, sig,
-                     sb.sketch, (int)K, (int)min_match, check_words, group_capacity(KW, VG_SMALL_WORDS),
-                     sb.parent, sb.big, counts, sb.big_cap);
+  hipLaunchKernelGGL((k_v_groups<4, VG_LDS_WORDS>), dim3(256 * 10), dim3(256), 0, st, sb.ka, sb.da, sig,
+                     sb.sketch, (int)K, (int)min_match, check_words,
+                     group_capacity((uint32_t)check_words, VG_SMALL_WORDS), sb.parent, sb.big, counts,
+                     sb.big_cap);
   SEDD_LAUNCH_CHECK();
   for (int phase = 0; phase < 2; phase++) {
     hipLaunchKernelGGL(k_v_tiles, dim3(256 * 24), dim3(VTHREADS), 0, st, phase, sb.ka, sb.da, sig, sb.sketch,

@@ -601,15 +601,16 @@ def test_cluster_verified_large_buckets_sketch_bound(sedd, K):
             assert np.array_equal(got, oracle.cluster_verified(keys, sg, mm)), (name, mm)
 
 
-@pytest.mark.parametrize("K,sizes", [(256, (65, 255, 256, 257, 300, 1023, 1024, 1025, 1100)),
-                                     (128, (383, 384, 385, 640, 1535, 1536, 1537)),
-                                     (1000, (64, 65, 320, 321, 500))])
+@pytest.mark.parametrize("K,sizes", [
+    (256, (65, 127, 128, 129, 191, 192, 193, 319, 320, 321, 639, 640, 641, 895, 896, 897, 1100, 1343, 1344, 1345)),
+    (128, (255, 256, 257, 319, 320, 321, 1023, 1024, 1025, 1151, 1152, 1153, 1343, 1344, 1345)),
+    (1000, (64, 65, 191, 192, 193, 383, 384, 385, 500, 895, 896, 897))])
 def test_cluster_verified_bucket_sizes_at_the_limits_of_the_three_kernels(sedd, K, sizes):
     """Buckets of more than 64 documents are compared from LDS by one wavefront, from LDS by four,
-    or tile by tile from memory, depending on how many records fit next to their sketches: bucket
-    sizes at and next to those limits for three signature lengths, with related documents spread
-    over the tiles of every bucket, at thresholds where the sketch check comes early, late and
-    never."""
+    or tile by tile from memory, depending on how many records fit LDS next to the sketch words
+    kept there, which in turn depends on the threshold: bucket sizes at and next to those limits
+    for three signature lengths and the thresholds used below, with related documents spread over
+    the tiles of every bucket."""
     say("verified bucket sizes", K, sizes)
     rng = np.random.default_rng(K)
     n = int(sum(sizes))
