@@ -820,11 +820,14 @@ __device__ __noinline__ void group_pair(const uint32_t *__restrict__ bits, int K
 // (row0 a multiple of 32, col0 of 64, row0 < col0 + 64).  sk[w * cap + rec] = sketch word w of
 // record rec, w < lds_words; slots past the group's end have the document id 0xFFFFFFFF.  One wavefront, each lane a 4 x 8 block of pairs (half the registers of 8 x 8:
 // five wavefronts share a SIMD).  The words in LDS are accumulated for all pairs; if some pair
-// is still below the bound then, the few that are get finished one by one.
+// is still below the bound then, the few that are get finished one by one (s_joined, if given,
+// marks the records known to be in the component of the group's first record: a pair of two such
+// records has nothing to add).
 __device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint32_t cap, int lds_words,
                                            const uint32_t *__restrict__ bits, int KW, int max_diff,
                                            const uint32_t *__restrict__ s_doc,
-                                           const uint64_t *__restrict__ s_key, uint32_t row0,
+                                           const uint64_t *__restrict__ s_key,
+                                           const uint32_t *__restrict__ s_joined, uint32_t row0,
                                            uint32_t col0, const uint32_t *__restrict__ sig, int K,
                                            int min_match, bool vec_ok, uint32_t *parent) {
   const int lane = threadIdx.x & 63, ty = lane >> 3, tx = lane & 7;  // rows 4 ty .., columns 8 tx ..
@@ -867,6 +870,8 @@ __device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint
       if ((int)diff[8 * i + j] > max_diff) continue;
       const uint32_t ri = row0 + ty * 4 + i, cj = col0 + tx * 8 + j;
       if (ri >= cj) continue;  // every pair once: the earlier record is the row
+      // both in the component of the group's first record already (s_joined: phase 1 only)
+      if (s_joined && s_joined[ri] && s_joined[cj]) continue;
       group_pair(bits, KW, lds_words, diff[8 * i + j], max_diff, s_doc, s_key, ri, cj, sig, K, min_match,
                  vec_ok, parent);
     }
@@ -922,8 +927,8 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
     // phase 0: the group's first 64 records (two row blocks) against every column block
     for (uint32_t q = wave; q < 2 * T; q += WAVES) {
       const uint32_t ri = q & 1, tj = q >> 1;
-      group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, ri * 32, tj * VT, sig, K, min_match,
-                 vec_ok, parent);
+      group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, nullptr, ri * 32, tj * VT, sig, K,
+                 min_match, vec_ok, parent);
     }
     if (T < 2) continue;
     __syncthreads();
@@ -945,8 +950,8 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
         if ((q & (WAVES - 1)) != (uint32_t)wave) continue;
         const bool alike = s_joined[ri * 32 + (lane & 31)] && s_joined[tj * VT + lane];
         if (__all(alike)) continue;  // nothing left to learn here
-        group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, ri * 32, tj * VT, sig, K, min_match,
-                   vec_ok, parent);
+        group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, s_joined, ri * 32, tj * VT, sig, K,
+                   min_match, vec_ok, parent);
       }
   }
 }

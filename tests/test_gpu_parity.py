@@ -628,6 +628,39 @@ def test_cluster_verified_bucket_sizes_at_the_limits_of_the_three_kernels(sedd, 
             assert n // 10 < int((want != np.arange(n)).sum()) < n
 
 
+def test_cluster_verified_buckets_of_copies_with_strangers(sedd):
+    """Buckets that are mostly copies of one document with unrelated documents mixed in (and one
+    with two families of copies): the tiles that hold a stranger cannot be skipped, and nearly all
+    of their pairs pass the sketch bound."""
+    say("verified copies with strangers")
+    rng = np.random.default_rng(77)
+    K, sizes = 256, (800, 500, 130, 896)
+    n = int(sum(sizes))
+    band0 = np.repeat(np.arange(len(sizes), dtype=np.uint64), sizes)
+    sig = rng.integers(0, 1 << 32, size=(n, K), dtype=np.uint64).astype(np.uint32)
+    start = 0
+    for gi, s in enumerate(sizes):
+        idx = np.arange(start, start + s)
+        copies = idx[rng.random(s) < 0.85]
+        if gi == 1:                                    # two families
+            half = copies.size // 2
+            sig[copies[:half]] = sig[copies[0]]
+            sig[copies[half:]] = sig[copies[half]]
+        else:
+            sig[copies] = sig[copies[0]]
+        near = copies[rng.random(copies.size) < 0.1]   # some copies with a few entries changed
+        for d in near:
+            sig[d, rng.integers(0, K, size=20)] = rng.integers(0, 1 << 32, size=20, dtype=np.uint64).astype(np.uint32)
+        start += s
+    perm = rng.permutation(n)
+    band0, sig = band0[perm], sig[perm]
+    keys = np.stack([band0 + np.uint64(5), rng.integers(0, n, size=n, dtype=np.uint64)], axis=1)
+    d_keys, d_sig = dev(keys), dev(sig)
+    for mm in (oracle.min_match_for(0.8, K), K, 1):
+        got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+        assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
+
+
 def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
     """Buckets whose keys differ only above the sorted bits share one sorted group."""
     say("verified low-bit collisions")
