@@ -797,17 +797,34 @@ k_v_tiles(int phase, const uint64_t *__restrict__ bk, const uint32_t *__restrict
   }
 }
 
+// Pairs of documents that a block of k_v_groups puts aside (in LDS) while it runs the tiles of a
+// group, and decides together afterwards: one lane finishing a pair on the spot (remaining sketch
+// words, two finds, K entries) keeps its wavefront waiting on a chain of dependent loads, whereas
+// the list is worked off by sixteen lanes per pair, all pairs of the block side by side.
+struct PairList {
+  uint2 *pairs;     // document ids
+  uint32_t *count;  // pairs appended (may exceed cap: those were finished on the spot)
+  uint32_t cap;
+};
+
 // A pair that the sketch words in LDS (the first lds_words of each record) have not ruled out, d
-// differing bits so far: the keys, the remaining sketch words from memory, then the full
-// comparison.  Rare, so kept out of line.
+// differing bits so far: the keys; then either onto the list, or, in place, the remaining
+// sketch words from memory and the full comparison.  Rare, so kept out of line.
 __device__ __noinline__ void group_pair(const uint32_t *__restrict__ bits, int KW, int lds_words,
                                         uint32_t d, int max_diff, const uint32_t *__restrict__ s_doc,
                                         const uint64_t *__restrict__ s_key, uint32_t ri, uint32_t cj,
                                         const uint32_t *__restrict__ sig, int K, int min_match,
-                                        bool vec_ok, uint32_t *parent) {
+                                        bool vec_ok, uint32_t *parent, const PairList *defer) {
   const uint32_t u = s_doc[ri], v = s_doc[cj];
   if (u == 0xFFFFFFFFu || v == 0xFFFFFFFFu) return;
   if (s_key[ri] != s_key[cj]) return;
+  if (defer) {
+    const uint32_t slot = atomicAdd(defer->count, 1u);
+    if (slot < defer->cap) {
+      defer->pairs[slot] = make_uint2(u, v);
+      return;
+    }
+  }
   const uint32_t *bu = bits + (uint64_t)u * KW, *bv = bits + (uint64_t)v * KW;
   for (int w = lds_words; w < KW && (int)d <= max_diff; w++) d += __popc(bu[w] ^ bv[w]);
   if ((int)d > max_diff) return;  // the bound rules the pair out
@@ -829,7 +846,8 @@ __device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint
                                            const uint64_t *__restrict__ s_key,
                                            const uint32_t *__restrict__ s_joined, uint32_t row0,
                                            uint32_t col0, const uint32_t *__restrict__ sig, int K,
-                                           int min_match, bool vec_ok, uint32_t *parent) {
+                                           int min_match, bool vec_ok, uint32_t *parent,
+                                           const PairList *defer) {
   const int lane = threadIdx.x & 63, ty = lane >> 3, tx = lane & 7;  // rows 4 ty .., columns 8 tx ..
   uint32_t diff[32];  // diff[8 i + j]: sketch bits that differ, row 4 ty + i against column 8 tx + j
   const uint32_t *rp = sk + row0 + ty * 4, *cp = sk + col0 + tx * 8;
@@ -873,7 +891,7 @@ __device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint
       // both in the component of the group's first record already (s_joined: phase 1 only)
       if (s_joined && s_joined[ri] && s_joined[cj]) continue;
       group_pair(bits, KW, lds_words, diff[8 * i + j], max_diff, s_doc, s_key, ri, cj, sig, K, min_match,
-                 vec_ok, parent);
+                 vec_ok, parent, defer);
     }
 }
 
@@ -886,7 +904,14 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
            int lds_words, uint32_t min_size, uint32_t *parent, const BigGroup *__restrict__ big,
            const uint32_t *__restrict__ counts, uint64_t big_cap) {
   constexpr uint32_t VG_THREADS = WAVES * 64;
+  constexpr uint32_t LATER_CAP = WAVES * 128;  // pairs a block can put aside per group
   __shared__ __attribute__((aligned(16))) uint32_t lds[LDS_WORDS];
+  __shared__ uint2 s_later[LATER_CAP];
+  __shared__ uint32_t s_later_n;
+  PairList later;
+  later.pairs = s_later;
+  later.count = &s_later_n;
+  later.cap = LATER_CAP;
   const int KW = (int)sketch_words(K);
   const uint32_t cap = group_capacity((uint32_t)lds_words, LDS_WORDS);
   // keys first (8-byte aligned), then document ids, flags, sketches [word][record]
@@ -901,6 +926,7 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
     if (g.size > cap || g.size <= min_size) continue;  // another launch's work (uniform over the block)
     const uint32_t T = (g.size + VT - 1) / VT;  // column blocks of 64 records; row blocks of 32: 2 T
     __syncthreads();  // the previous group's readers are done
+    if (tid == 0) s_later_n = 0;
     // two sweeps, so that the loads of several records are in flight together: ids and keys
     // first, then the sketches they point to (a thread reads back what it wrote itself)
 #pragma unroll 4
@@ -924,11 +950,12 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
             doc != 0xFFFFFFFFu ? bits[(uint64_t)doc * KW + w] : 0x9E3779B9u * (rec * 8u + (uint32_t)w + 1u);
     }
     __syncthreads();
-    // phase 0: the group's first 64 records (two row blocks) against every column block
+    // phase 0: the group's first 64 records (two row blocks) against every column block; pairs
+    // are decided in place, so that phase 1 knows who has joined the first record
     for (uint32_t q = wave; q < 2 * T; q += WAVES) {
       const uint32_t ri = q & 1, tj = q >> 1;
       group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, nullptr, ri * 32, tj * VT, sig, K,
-                 min_match, vec_ok, parent);
+                 min_match, vec_ok, parent, nullptr);
     }
     if (T < 2) continue;
     __syncthreads();
@@ -943,7 +970,7 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
     }
     __syncthreads();
     // phase 1: the other tiles (row block ri of 32 records against the column blocks from the one
-    // that holds it on), dealt to the wavefronts in turn
+    // that holds it on), dealt to the wavefronts in turn; surviving pairs go onto the list
     uint32_t q = 0;
     for (uint32_t ri = 2; ri < 2 * T; ri++)
       for (uint32_t tj = ri >> 1; tj < T; tj++, q++) {
@@ -951,8 +978,25 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
         const bool alike = s_joined[ri * 32 + (lane & 31)] && s_joined[tj * VT + lane];
         if (__all(alike)) continue;  // nothing left to learn here
         group_tile(sk, cap, lds_words, bits, KW, max_diff, s_doc, s_key, s_joined, ri * 32, tj * VT, sig, K,
-                   min_match, vec_ok, parent);
+                   min_match, vec_ok, parent, &later);
       }
+    __syncthreads();
+    // the pairs put aside: sixteen lanes per pair take the sketch bound over all words and, if it
+    // holds, the find and the full comparison
+    {
+      const uint32_t n_later = min(s_later_n, LATER_CAP);
+      const int tl = tid & (TEAM - 1);
+      for (uint32_t e = tid / TEAM; e < n_later; e += VG_THREADS / TEAM) {
+        const uint2 p = s_later[e];
+        const uint32_t *bu = bits + (uint64_t)p.x * KW, *bv = bits + (uint64_t)p.y * KW;
+        uint32_t d = 0;
+        for (int w = tl; w < KW; w += TEAM) d += __popc(bu[w] ^ bv[w]);
+#pragma unroll
+        for (int o = TEAM / 2; o >= 1; o >>= 1) d += __shfl_xor(d, o, TEAM);
+        if ((int)d > max_diff) continue;  // the bound rules the pair out (uniform over the team)
+        team_verify_pair(sig, K, min_match, parent, p.x, p.y, tl);
+      }
+    }
   }
 }
 
