@@ -152,6 +152,4 @@ uint64_t scan_tmp_count(uint64_t n);
 int scan_exclusive_u32(const uint32_t *in, uint32_t *out, uint64_t n, uint32_t *tmp,
                        hipStream_t s, const uint32_t *gate = nullptr);
 
-static inline uint32_t ceil_div_u64(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
-
 }  // namespace sedd

@@ -138,9 +138,6 @@ struct Segment {
   uint32_t w[4];
   uint32_t wm;
 };
-__device__ __forceinline__ uint32_t seg_byte(const Segment &sg, int i) {
-  return (sg.w[i >> 2] >> (8 * (i & 3))) & 0xFFu;
-}
 // 4-bit mask of the bytes of w that are NOT whitespace {09..0D, 20}, by SWAR on the word
 __device__ __forceinline__ uint32_t nonspace_mask4(uint32_t w) {
   const uint32_t lo7 = w & 0x7F7F7F7Fu;
