@@ -661,6 +661,39 @@ def test_cluster_verified_buckets_of_copies_with_strangers(sedd):
         assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_fuzz_cluster_verified(sedd, seed):
+    """Random mixes of bucket sizes (single documents up to buckets beyond what LDS holds), band
+    counts, key magnitudes, signature lengths, noise levels and thresholds; sometimes all sketch
+    bits equal, so that the bound rules nothing out."""
+    say("fuzz verified", seed)
+    rng = np.random.default_rng(seed)
+    for case in range(14):
+        K = int(rng.choice([1, 7, 32, 33, 64, 100, 128, 200, 256, 300, 512, 777, 1024]))
+        b = int(rng.integers(1, 6))
+        sizes = rng.choice([1, 2, 5, 40, 63, 64, 65, 100, 130, 200, 333, 500, 700, 900, 1300],
+                           size=int(rng.integers(1, 8)))
+        n = int(sizes.sum())
+        band0 = np.repeat(np.arange(sizes.size, dtype=np.uint64), sizes)
+        rng.shuffle(band0)
+        keys = np.empty((n, b), dtype=np.uint64)
+        keys[:, 0] = band0 * np.uint64(rng.choice([1, 1 << 20, 1 << 40, 999_983])) + np.uint64(3)
+        for j in range(1, b):
+            keys[:, j] = rng.integers(0, max(1, n // int(rng.choice([1, 3, 50]))), size=n, dtype=np.uint64)
+        protos = max(1, n // int(rng.choice([5, 30, 200])))
+        proto = rng.integers(0, 1 << 32, size=(protos, K), dtype=np.uint64).astype(np.uint32)
+        sig = proto[rng.integers(0, protos, size=n)].copy()
+        flip = rng.random((n, K)) < rng.random((n, 1)) * float(rng.choice([0.0, 0.2, 0.5]))
+        sig[flip] = rng.integers(0, 1 << 32, size=int(flip.sum()), dtype=np.uint64).astype(np.uint32)
+        if rng.random() < 0.3:
+            sig &= np.uint32(0xFFFFFFFE)
+        d_keys, d_sig = dev(keys), dev(sig)
+        for mm in sorted({0, 1, K // 2, oracle.min_match_for(0.8, K), oracle.min_match_for(0.95, K), K, K + 1}):
+            got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+            want = oracle.cluster_verified(keys, sig, mm)
+            assert np.array_equal(got, want), (case, K, b, sizes.tolist(), mm)
+
+
 def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
     """Buckets whose keys differ only above the sorted bits share one sorted group."""
     say("verified low-bit collisions")
