@@ -16,6 +16,7 @@ constexpr uint32_t SORT_TILE = SORT_THREADS * SORT_ITEMS;
 constexpr int RADIX_BITS = 8;
 constexpr int RADIX = 1 << RADIX_BITS;
 constexpr int KEY_BITS = 61;
+constexpr uint32_t XCDS = 8;  // accelerator dies of the chip; consecutive workgroups go to them in turn
 
 // ---- union-find --------------------------------------------------------------------------
 //

@@ -123,7 +123,13 @@ k_radix_scatter(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd
   __shared__ uint32_t s_gbase[RADIX];    // where the tile's run of the digit starts in the output
   __shared__ uint64_t s_key[SORT_TILE];
   __shared__ uint32_t s_doc[SORT_TILE];
-  const uint32_t blk = blockIdx.x, band = blockIdx.y;
+  // Workgroups go to the chip's eight XCDs in turn, each with an L2 of its own.  Tile t and tile
+  // t + 1 of a band write adjoining stretches of every digit's run, so the cache lines where
+  // they meet are completed only if both tiles pass through the same L2: XCD x takes the tiles
+  // [x * per_xcd, (x + 1) * per_xcd) (the grid is padded to 8 * per_xcd).
+  const uint32_t per_xcd = gridDim.x / XCDS;
+  const uint32_t blk = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS, band = blockIdx.y;
+  if (blk >= nblk) return;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t *sk = bk + (uint64_t)band * n;
   const uint32_t *sd = bd + (uint64_t)band * n;
@@ -357,7 +363,8 @@ static int sort_passes(uint32_t n, uint32_t b, int shift0, int shift1, SortBufs 
     SEDD_LAUNCH_CHECK();
     int rc = scan_exclusive_u32(sb->hist, sb->hist, nh, sb->tmp, st, gate);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_radix_scatter, grid, dim3(SORT_THREADS), 0, st, src_k, src_d, n,
+    const dim3 grid_xcd((sb->nblk + XCDS - 1) / XCDS * XCDS, b);  // see k_radix_scatter
+    hipLaunchKernelGGL(k_radix_scatter, grid_xcd, dim3(SORT_THREADS), 0, st, src_k, src_d, n,
                        sb->nblk, shift, sb->hist, dst_k, dst_d, gate);
     SEDD_LAUNCH_CHECK();
     std::swap(src_k, dst_k);
