@@ -69,20 +69,35 @@ k_lsh_dense_keys(const uint32_t *__restrict__ sig, uint64_t n_docs, int K, int b
 
 // keys[d*b + j] -> bk[j*n + d], bd[j*n + d] = d.  With `high`: *high is raised if some key has a
 // bit set at or above high_shift (the word must be zero before the launch).
+// A block moves 64 documents, 32 bands at a time, through LDS: rows of the document-major input
+// are read whole (32 keys = 256 contiguous bytes per document), columns of the band-major output
+// are written 64 documents = 512 contiguous bytes at a time.
+constexpr uint32_t TBM_DOCS = 64, TBM_BANDS = 32;
 __global__ void __launch_bounds__(256)
 k_to_band_major(const uint64_t *__restrict__ keys, uint32_t n, uint32_t b,
                 uint64_t *__restrict__ bk, uint32_t *__restrict__ bd, int high_shift,
                 uint32_t *high) {
-  uint32_t d = blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ uint64_t tile[TBM_DOCS][TBM_BANDS + 1];  // one key of padding per row: no bank conflicts
+  const uint32_t d0 = blockIdx.x * TBM_DOCS, nd = min(TBM_DOCS, n - d0);
   uint64_t seen = 0;
-  if (d < n) {
-    const uint64_t *row = keys + (uint64_t)d * b;
-    for (uint32_t j = 0; j < b; j++) {
-      const uint64_t key = row[j];
+  for (uint32_t j0 = 0; j0 < b; j0 += TBM_BANDS) {
+    const uint32_t nb = min(TBM_BANDS, b - j0);
+    for (uint32_t e = threadIdx.x; e < nd * nb; e += blockDim.x) {
+      const uint32_t doc = e / nb, band = e - doc * nb;
+      const uint64_t key = keys[(uint64_t)(d0 + doc) * b + j0 + band];
       seen |= key;
-      bk[(uint64_t)j * n + d] = key;
-      bd[(uint64_t)j * n + d] = d;
+      tile[doc][band] = key;
     }
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e < nb * TBM_DOCS; e += blockDim.x) {
+      const uint32_t band = e / TBM_DOCS, doc = e % TBM_DOCS;
+      if (doc < nd) {
+        const uint64_t o = (uint64_t)(j0 + band) * n + d0 + doc;
+        bk[o] = tile[doc][band];
+        bd[o] = d0 + doc;
+      }
+    }
+    __syncthreads();
   }
   if (high && __any((seen >> high_shift) != 0) && (threadIdx.x & 63) == 0) atomicOr(high, 1u);
 }
@@ -92,13 +107,23 @@ k_radix_hist(const uint64_t *__restrict__ bk, uint32_t n, uint32_t nblk, int shi
              uint32_t *__restrict__ hist, const uint32_t *__restrict__ gate) {
   __shared__ uint32_t h[RADIX];
   if (gate && *gate == 0) return;  // a pass of the full-key fallback that is not needed
-  const uint32_t blk = blockIdx.x, band = blockIdx.y;
+  // tiles to XCDs as in k_radix_scatter: the counts of 32 consecutive tiles share a cache line
+  const uint32_t per_xcd = gridDim.x / XCDS;
+  const uint32_t blk = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS, band = blockIdx.y;
+  if (blk >= nblk) return;
   h[threadIdx.x] = 0;
   __syncthreads();
   const uint64_t *src = bk + (uint64_t)band * n;
+  uint64_t key[SORT_ITEMS];  // all loads before the first count
+#pragma unroll
   for (int it = 0; it < SORT_ITEMS; it++) {
-    uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
-    if (e < n) atomicAdd(&h[(uint32_t)(src[e] >> shift) & (RADIX - 1)], 1u);
+    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
+    key[it] = e < n ? src[e] : 0;
+  }
+#pragma unroll
+  for (int it = 0; it < SORT_ITEMS; it++) {
+    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
+    if (e < n) atomicAdd(&h[(uint32_t)(key[it] >> shift) & (RADIX - 1)], 1u);
   }
   __syncthreads();
   hist[((uint64_t)band * RADIX + threadIdx.x) * nblk + blk] = h[threadIdx.x];
@@ -357,13 +382,13 @@ static int sort_passes(uint32_t n, uint32_t b, int shift0, int shift1, SortBufs 
   uint64_t *src_k = sb->ka, *dst_k = sb->kb;
   uint32_t *src_d = sb->da, *dst_d = sb->db;
   for (int shift = shift0; shift < shift1; shift += RADIX_BITS) {
-    dim3 grid(sb->nblk, b);
-    hipLaunchKernelGGL(k_radix_hist, grid, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
+    // the grid is padded to a multiple of the number of XCDs (see k_radix_scatter)
+    const dim3 grid_xcd((sb->nblk + XCDS - 1) / XCDS * XCDS, b);
+    hipLaunchKernelGGL(k_radix_hist, grid_xcd, dim3(SORT_THREADS), 0, st, src_k, n, sb->nblk, shift,
                        sb->hist, gate);
     SEDD_LAUNCH_CHECK();
     int rc = scan_exclusive_u32(sb->hist, sb->hist, nh, sb->tmp, st, gate);
     if (rc) return rc;
-    const dim3 grid_xcd((sb->nblk + XCDS - 1) / XCDS * XCDS, b);  // see k_radix_scatter
     hipLaunchKernelGGL(k_radix_scatter, grid_xcd, dim3(SORT_THREADS), 0, st, src_k, src_d, n,
                        sb->nblk, shift, sb->hist, dst_k, dst_d, gate);
     SEDD_LAUNCH_CHECK();
@@ -401,8 +426,8 @@ int sort_bands(const uint64_t *keys, uint64_t n_docs, uint32_t b, int key_bits, 
                        (const uint32_t *)nullptr);
     SEDD_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_to_band_major, dim3((n + 255) / 256), dim3(256), 0, st, keys, n, b, sb->ka,
-                     sb->da, always_bits, split ? sb->high : (uint32_t *)nullptr);
+  hipLaunchKernelGGL(k_to_band_major, dim3((n + TBM_DOCS - 1) / TBM_DOCS), dim3(256), 0, st, keys, n, b,
+                     sb->ka, sb->da, always_bits, split ? sb->high : (uint32_t *)nullptr);
   SEDD_LAUNCH_CHECK();
   int rc = sort_passes(n, b, 0, always_bits, sb, nullptr, st);
   if (rc || !split) return rc;
