@@ -264,12 +264,13 @@ __global__ void k_iota_u32(uint32_t *p, uint32_t n) {
 constexpr uint32_t WALK_CAP = 64;
 __global__ void __launch_bounds__(256)
 k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
-            uint32_t b, uint64_t mask, uint32_t *parent, uint32_t *gate, int retry) {
+            uint64_t mask, uint32_t *parent, uint32_t *gate, int retry) {
   if (retry && *gate == 0) return;
-  uint64_t idx = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // grid: x over the records of a band, y = band
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t idx = (uint64_t)blockIdx.y * n + i;
   bool open = false;
-  if (idx < (uint64_t)n * b) {
-    const uint32_t i = (uint32_t)(idx % n);
+  if (i < n) {
     const uint64_t key = bk[idx];
     for (uint32_t back = 1; back <= i; back++) {
       if (back > WALK_CAP) {
@@ -446,8 +447,7 @@ static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_
                        SortBufs &sb, bool timed, hipStream_t st) {
   const int bits = grouping_bits(n_docs, 1);
   const uint32_t n = (uint32_t)n_docs;
-  const uint64_t total = n_docs * (uint64_t)b;
-  const uint32_t link_grid = (uint32_t)((total + 255) / 256);
+  const dim3 link_grid((n + 255) / 256, b);
   g_last_gate = sb.gate;
   int rc;
   {
@@ -462,7 +462,7 @@ static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_
     hipLaunchKernelGGL(k_fill_small_u32, dim3(1), dim3(64), 0, st, sb.gate, 1u, 0u,
                        (const uint32_t *)nullptr);
     SEDD_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_link_runs, dim3(link_grid), dim3(256), 0, st, sb.ka, sb.da, n, b,
+    hipLaunchKernelGGL(k_link_runs, link_grid, dim3(256), 0, st, sb.ka, sb.da, n,
                        (uint64_t(1) << bits) - 1, sb.parent, sb.gate, 0);
     SEDD_LAUNCH_CHECK();
   }
@@ -473,7 +473,7 @@ static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_
     if (rc) return rc;
   }
   ProfScope prof(timed ? SEDD_PROF_UNION : -1, st);
-  hipLaunchKernelGGL(k_link_runs, dim3(link_grid), dim3(256), 0, st, sb.ka, sb.da, n, b,
+  hipLaunchKernelGGL(k_link_runs, link_grid, dim3(256), 0, st, sb.ka, sb.da, n,
                      ~uint64_t(0), sb.parent, sb.gate, 1);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_write_roots, dim3((n + 255) / 256), dim3(256), 0, st, sb.parent, n,
