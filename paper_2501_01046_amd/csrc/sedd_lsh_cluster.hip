@@ -99,7 +99,11 @@ k_to_band_major(const uint64_t *__restrict__ keys, uint32_t n, uint32_t b,
     }
     __syncthreads();
   }
-  if (high && __any((seen >> high_shift) != 0) && (threadIdx.x & 63) == 0) atomicOr(high, 1u);
+  // every writer stores the same value; a block that already sees the flag up leaves it alone, so
+  // that keys which all reach that high do not queue a write per block on one address
+  if (high && __syncthreads_or((seen >> high_shift) != 0) && threadIdx.x == 0 &&
+      __hip_atomic_load(high, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0)
+    *high = 1u;
 }
 
 __global__ void __launch_bounds__(SORT_THREADS)
