@@ -781,11 +781,11 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, KW, counts,
                      sb.sketch);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 40), dim3(64), 0, st, sb.ka, sb.da, sig,
+  hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 512), dim3(64), 0, st, sb.ka, sb.da, sig,
                      sb.sketch, (int)K, (int)min_match, check_words, 0u, sb.parent, sb.big, counts,
                      sb.big_cap);
   SEDD_LAUNCH_CHECK();
-  hipLaunchKernelGGL((k_v_groups<4, VG_LDS_WORDS>), dim3(256 * 10), dim3(256), 0, st, sb.ka, sb.da, sig,
+  hipLaunchKernelGGL((k_v_groups<4, VG_LDS_WORDS>), dim3(256 * 128), dim3(256), 0, st, sb.ka, sb.da, sig,
                      sb.sketch, (int)K, (int)min_match, check_words,
                      group_capacity((uint32_t)check_words, VG_SMALL_WORDS), sb.parent, sb.big, counts,
                      sb.big_cap);
