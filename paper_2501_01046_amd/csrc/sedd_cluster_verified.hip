@@ -781,6 +781,8 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   hipLaunchKernelGGL(k_sig_sketch, dim3(256 * 16), dim3(256), 0, st, sig, n, (int)K, KW, counts,
                      sb.sketch);
   SEDD_LAUNCH_CHECK();
+  // many more blocks than the chip holds at once: groups differ a lot in work, and the hardware
+  // hands a finished block's place to the next one; a block that finds no group of its launch exits
   hipLaunchKernelGGL((k_v_groups<1, VG_SMALL_WORDS>), dim3(256 * 512), dim3(64), 0, st, sb.ka, sb.da, sig,
                      sb.sketch, (int)K, (int)min_match, check_words, 0u, sb.parent, sb.big, counts,
                      sb.big_cap);
