@@ -16,41 +16,29 @@ namespace sedd {
 //
 // The union graph of "pair in the same bucket with at least min_match equal signature entries"
 // is built without enumerating all pairs of a large bucket whose members are alike:
-//   1. every record that is not the first of its group is compared with the group's first
+//   1. every record that is not the first of its bucket is compared with the bucket's first
 //      record (its head); a verified pair is united, a record that fails becomes an outsider;
-//   2. every outsider is compared with all other records of its group.
+//   2. every outsider is compared with all other records of its bucket.
 // A pair of two non-outsiders is never compared: both are already in the head's component, so
 // the edge could not change any component.  Likewise any pair found in one component is skipped.
 // The components, and so the cluster ids, are exactly those of the exhaustive comparison.
 
 constexpr int TEAM = 16;  // lanes that compare one pair of signatures
 
-// slot for every lane with pred set, taken from *counter by one atomic per wavefront
-__device__ __forceinline__ uint32_t wave_append(bool pred, uint32_t *counter) {
-  const uint64_t m = __ballot(pred);
-  if (m == 0) return 0xFFFFFFFFu;
-  const int lane = threadIdx.x & 63;
-  const int leader = __ffsll((unsigned long long)m) - 1;
-  uint32_t base = 0;
-  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
-  base = __shfl(base, leader, 64);
-  return pred ? base + (uint32_t)__popcll(m & ((uint64_t(1) << lane) - 1)) : 0xFFFFFFFFu;
-}
-
-// Records that are not the first of their group go to list1 (one atomic per block of SORT_TILE
+// Records that are not the first of their bucket go to list1 (one atomic per block of SORT_TILE
 // records), except those that can see, BIG_GROUP records before or after them, a record of their
 // own group: their group is large and is compared tile by tile instead.  The first record of a
 // large group appends the group to `big`.
 __global__ void __launch_bounds__(SORT_THREADS)
 k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
          uint32_t *__restrict__ list1, uint32_t *__restrict__ counts,
-         BigGroup *__restrict__ big, uint32_t *gate, int retry) {
+         BigGroup *__restrict__ big, uint32_t *gate, uint32_t mixed_limit, int retry) {
   __shared__ uint32_t s_base[2];
   if (retry && *gate == 0) return;
   const uint32_t blk = blockIdx.x, band = blockIdx.y;
   const uint64_t *src = bk + (uint64_t)band * n;
   uint32_t flags = 0, heads = 0;  // bit it: item it goes to list1 / is the head of a large group
-  bool mixed = false;  // a large group that holds more than one key: the sorted bits are too few
+  uint32_t mixed = 0;  // records that see another key BIG_GROUP records on inside their own group
 #pragma unroll
   for (int it = 0; it < SORT_ITEMS; it++) {
     const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
@@ -61,17 +49,38 @@ k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
     if (e + BIG_GROUP < n) {
       const uint64_t other = src[e + BIG_GROUP];
       far_after = (other & mask) == low;
-      mixed |= far_after && other != key;
+      mixed += far_after && other != key;
     }
     if (follower) {
       const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
-      if (!far_before && !far_after) flags |= 1u << it;
+      if (!far_before && !far_after) {
+        // small group: listed only if an earlier record of the group has this very key (the
+        // group starts fewer than BIG_GROUP records back, and is nearly always one bucket)
+        bool real = false;
+        for (uint32_t q = e; q > 0 && !real;) {
+          const uint64_t other = src[--q];
+          if ((other & mask) != low) break;
+          real = other == key;
+        }
+        if (real) flags |= 1u << it;
+      }
     } else if (far_after) {
       heads |= 1u << it;
     }
   }
-  // (with mask = all ones a group holds one key, so a retry never raises the gate)
-  if (__any(mixed) && (threadIdx.x & 63) == 0) atomicOr(gate, 1u);
+  // A large group with a stranger or two costs a few comparisons more (every pair test compares
+  // the keys); large groups that are mixtures throughout mean the sorted bits are too few.  The
+  // gate goes up when more than mixed_limit records say so (counts[3]), raised by the wavefront
+  // whose addition crosses the limit.  With mask = all ones a group holds one key: a retry adds nothing.
+  if (__any(mixed != 0)) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mixed += __shfl_xor(mixed, o, 64);
+    if ((threadIdx.x & 63) == 0 &&
+        __hip_atomic_load(gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+      const uint32_t before = atomicAdd(counts + 3, mixed);
+      if (before <= mixed_limit && before + mixed > mixed_limit) atomicOr(gate, 1u);
+    }
+  }
   // both counts through one scan (at most SORT_TILE = 2^12 of either per block) and one atomic
   // each per block
   static_assert(SORT_TILE <= (1u << 15), "two counts share one 32-bit scan");
@@ -169,37 +178,55 @@ __device__ __forceinline__ bool team_verify_pair(const uint32_t *__restrict__ si
   return true;
 }
 
-// step 1: one team per follower record, against the head of its group
-__global__ void __launch_bounds__(256)
+// step 1: one team per follower record, against the head of its bucket.  The outsiders of a block
+// collect in LDS and go to list2 every HP_FLUSH rounds, with one atomic on the list's length per
+// block and flush (one per wavefront and round, all on that one word, took most of the kernel's time).
+constexpr uint32_t HP_THREADS = 256, HP_FLUSH = 32;
+__global__ void __launch_bounds__(HP_THREADS)
 k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
                uint64_t mask_lo, const uint32_t *__restrict__ gate,
                const uint32_t *__restrict__ sig, int K, int min_match,
                uint32_t *parent, const uint32_t *__restrict__ list1, uint32_t *counts,
                uint32_t *__restrict__ list2) {
+  __shared__ uint32_t s_out[HP_FLUSH * (HP_THREADS / TEAM)];  // at most one outsider per team and round
+  __shared__ uint32_t s_n, s_base;
   const uint64_t mask = *gate ? ~uint64_t(0) : mask_lo;  // gate up: the records are fully sorted
   const uint32_t n1 = counts[0];
   const int tl = threadIdx.x & (TEAM - 1);
-  const uint32_t teams = gridDim.x * (blockDim.x / TEAM);
-  // every lane of a wavefront runs the same number of rounds (wave_append is a wave operation)
+  const uint32_t teams = gridDim.x * (HP_THREADS / TEAM);
+  // every thread of a block runs the same number of rounds (the flush is a block operation)
   const uint32_t rounds = (n1 + teams - 1) / teams;
-  uint32_t e = blockIdx.x * (blockDim.x / TEAM) + threadIdx.x / TEAM;
+  if (threadIdx.x == 0) s_n = 0;
+  __syncthreads();
+  uint32_t e = blockIdx.x * (HP_THREADS / TEAM) + threadIdx.x / TEAM;
   for (uint32_t it = 0; it < rounds; it++, e += teams) {
-    bool outsider = false;
-    uint32_t i = 0;
     if (e < n1) {
-      i = list1[e];
+      const uint32_t i = list1[e];
       const uint64_t key = bk[i];
       const uint32_t band0 = (i / n) * n;
       const uint32_t gs = group_lower_bound(bk, mask, band0, i, key & mask);
-      // a group of more than BIG_GROUP records is compared tile by tile (k_v_tiles)
+      // a group of more than BIG_GROUP records is compared tile by tile (k_v_groups, k_v_tiles)
       const bool large = gs + BIG_GROUP < band0 + n && ((bk[gs + BIG_GROUP] ^ key) & mask) == 0;
       bool joined = large;
-      if (!large && bk[gs] == key)
-        joined = team_verify_pair(sig, K, min_match, parent, bd[gs], bd[i], tl);
-      outsider = !joined && tl == 0;
+      if (!large) {
+        uint32_t h = gs;  // the bucket's first record: k_v_mark saw one before i
+        while (bk[h] != key) h++;
+        joined = team_verify_pair(sig, K, min_match, parent, bd[h], bd[i], tl);
+      }
+      if (!joined && tl == 0) s_out[atomicAdd(&s_n, 1u)] = i;
     }
-    const uint32_t slot = wave_append(outsider, counts + 1);
-    if (outsider) list2[slot] = i;
+    if ((it + 1) % HP_FLUSH == 0 || it + 1 == rounds) {
+      __syncthreads();
+      const uint32_t held = s_n;
+      if (held) {  // uniform over the block
+        if (threadIdx.x == 0) s_base = atomicAdd(counts + 1, held);
+        __syncthreads();
+        for (uint32_t k = threadIdx.x; k < held; k += HP_THREADS) list2[s_base + k] = s_out[k];
+        __syncthreads();
+        if (threadIdx.x == 0) s_n = 0;
+        __syncthreads();
+      }
+    }
   }
 }
 
@@ -222,8 +249,9 @@ k_v_outsider_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__
     const uint32_t gs = group_lower_bound(bk, mask, band0, o, key & mask);
     const uint32_t ge = group_upper_bound(bk, mask, o + 1, band0 + n, key & mask);
     const uint32_t v = bd[o];
-    // the head (gs) was this record's partner in step 1
-    for (uint32_t j = gs + 1 + team; j < ge; j += 64 / TEAM) {
+    // the bucket's first record was this record's partner in step 1 (it is the group's first
+    // unless the group holds other keys; then it is merely looked at again)
+    for (uint32_t j = gs + (bk[gs] == key ? 1u : 0u) + team; j < ge; j += 64 / TEAM) {
       if (j == o || bk[j] != key) continue;
       team_verify_pair(sig, K, min_match, parent, bd[j], v, tl);
     }
@@ -732,7 +760,9 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
                                 hipStream_t st) {
   int rc;
   uint32_t *counts = sb.counts;  // list lengths (followers, outsiders, large groups), cleared by every call
-  const int bits = grouping_bits(n_docs, 4096);
+  const int bits = grouping_bits(n_docs, 256);
+  // records of mixed large groups the call puts up with before it sorts by the whole key
+  const uint32_t mixed_limit = (uint32_t)std::min<uint64_t>(n_docs * b / 1024, 0x7FFFFFFFu);
   g_last_gate = sb.gate;
   {
     ProfScope prof(SEDD_PROF_SORT, st);
@@ -754,7 +784,7 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
                        (const uint32_t *)nullptr);
     SEDD_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, b), dim3(SORT_THREADS), 0, st, sb.ka, n, mask,
-                       list1, counts, sb.big, sb.gate, 0);
+                       list1, counts, sb.big, sb.gate, mixed_limit, 0);
     SEDD_LAUNCH_CHECK();
   }
   {
@@ -769,7 +799,7 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
                      (const uint32_t *)sb.gate);
   SEDD_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_v_mark, dim3(sb.nblk, b), dim3(SORT_THREADS), 0, st, sb.ka, n,
-                     ~uint64_t(0), list1, counts, sb.big, sb.gate, 1);
+                     ~uint64_t(0), list1, counts, sb.big, sb.gate, mixed_limit, 1);
   SEDD_LAUNCH_CHECK();
   // large groups: sketches; the groups that fit LDS; for the others the tile plan, then the tiles
   // against each group's first tile, then the rest
@@ -799,7 +829,7 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
   }
   // grids sized to the chip: the kernels stride over lists whose lengths only the device knows
   const uint32_t grid = 256 * 16;
-  hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(256), 0, st, sb.ka, sb.da, n, mask,
+  hipLaunchKernelGGL(k_v_head_pairs, dim3(grid), dim3(HP_THREADS), 0, st, sb.ka, sb.da, n, mask,
                      (const uint32_t *)sb.gate, sig, (int)K, (int)min_match, sb.parent, list1, counts,
                      list2);
   SEDD_LAUNCH_CHECK();

@@ -369,7 +369,7 @@ int sort_layout(uint64_t n, uint32_t b, SortBufs *sb, int K_sketch) {
 // that is possible.  A group of equal low bits then holds about 1 / slack records of other keys.
 // sedd_cluster takes slack 1 (its linker walks over the few strangers, neighbours in memory: a
 // step of the walk costs far less than a radix pass over all records); the verified path takes
-// 4096 so that a group is, almost always, exactly one bucket.
+// 256 so that a group is, nearly always, exactly one bucket.
 int grouping_bits(uint64_t n_docs, uint64_t slack) {
   int bits = 2 * RADIX_BITS;
   while (bits < 56 && (uint64_t(1) << bits) < slack * n_docs) bits += RADIX_BITS;

@@ -694,6 +694,39 @@ def test_fuzz_cluster_verified(sedd, seed):
             assert np.array_equal(got, want), (case, K, b, sizes.tolist(), mm)
 
 
+def test_cluster_verified_large_buckets_with_a_few_strangers_in_their_group(sedd):
+    """Large buckets whose sorted group also holds a few records of another key (equal below the
+    sorted bits): too few to make the call sort by the whole key, so the large-group kernels meet
+    pairs with different keys and must leave them alone."""
+    say("verified strangers in large groups")
+    rng = np.random.default_rng(41)
+    n, K, b = 120_000, 64, 4
+    sizes = (70, 200, 600, 3000)                       # one-wavefront, four-wavefront and tiled groups
+    lo = rng.integers(0, 1 << 61, size=(n, b), dtype=np.uint64) & np.uint64((1 << 61) - 1)
+    sig = rng.integers(0, 1 << 32, size=(n, K), dtype=np.uint64).astype(np.uint32)
+    at = 0
+    for band in range(b):
+        for gi, s in enumerate(sizes):
+            idx = np.arange(at, at + s)
+            at += s
+            key = np.uint64(1000 * band + gi + 1)
+            lo[idx, band] = key
+            fam = idx[rng.random(s) < 0.7]             # a family of near copies inside the bucket
+            sig[fam] = sig[fam[0]]
+            sig[fam[::3], :6] = rng.integers(0, 1 << 32, size=(fam[::3].size, 6), dtype=np.uint64).astype(np.uint32)
+            # strangers: same low bits, another key; two of them copies of the family's document
+            odd = idx[rng.choice(s, size=4, replace=False)]
+            lo[odd, band] = key | np.uint64(1 << 50)
+            sig[odd[:2]] = sig[fam[0]]
+    perm = rng.permutation(n)
+    keys, sig = np.ascontiguousarray(lo[perm]), sig[perm]
+    d_keys, d_sig = dev(keys), dev(sig)
+    for mm in (oracle.min_match_for(0.8, K), K, 0):
+        got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
+        assert sedd.debug_last_regroup() == 0          # the strangers stayed in their groups
+        assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
+
+
 def test_cluster_verified_keys_that_agree_in_their_low_bits(sedd):
     """Buckets whose keys differ only above the sorted bits share one sorted group."""
     say("verified low-bit collisions")
