@@ -266,31 +266,46 @@ __global__ void k_iota_u32(uint32_t *p, uint32_t n) {
 // and a second launch of this kernel (retry = 1, mask = all ones) links the fully sorted records.
 // Links made by the first launch stay valid: it only ever unites records with equal keys.
 constexpr uint32_t WALK_CAP = 64;
+constexpr int LINK_ITEMS = 4;  // records per thread: their keys and left neighbours are loaded together
 __global__ void __launch_bounds__(256)
 k_link_runs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd, uint32_t n,
             uint64_t mask, uint32_t *parent, uint32_t *gate, int retry) {
   if (retry && *gate == 0) return;
-  // grid: x over the records of a band, y = band
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint64_t idx = (uint64_t)blockIdx.y * n + i;
+  // grid: x over the records of a band (256 * LINK_ITEMS per block), y = band
+  const uint64_t band0 = (uint64_t)blockIdx.y * n;
+  const uint32_t i0 = blockIdx.x * (256u * LINK_ITEMS) + threadIdx.x;
+  uint64_t key[LINK_ITEMS], left[LINK_ITEMS];
+#pragma unroll
+  for (int it = 0; it < LINK_ITEMS; it++) {
+    const uint32_t i = i0 + it * 256u;
+    key[it] = i < n ? bk[band0 + i] : 0;
+    left[it] = i < n && i > 0 ? bk[band0 + i - 1] : 0;
+  }
   bool open = false;
-  if (i < n) {
-    const uint64_t key = bk[idx];
+#pragma unroll
+  for (int it = 0; it < LINK_ITEMS; it++) {
+    const uint32_t i = i0 + it * 256u;
+    if (i >= n) continue;
+    const uint64_t idx = band0 + i;
+    uint64_t other = left[it];
     for (uint32_t back = 1; back <= i; back++) {
       if (back > WALK_CAP) {
         open = true;
         break;
       }
-      const uint64_t other = bk[idx - back];
-      if ((other ^ key) & mask) break;
-      if (other == key) {
+      if (back > 1) other = bk[idx - back];
+      if ((other ^ key[it]) & mask) break;
+      if (other == key[it]) {
         uf_unite(parent, bd[idx - back], bd[idx]);
         break;
       }
     }
   }
   // with mask = all ones the first step always ends the walk, so a retry never gets here
-  if (__any(open) && (threadIdx.x & 63) == 0) atomicOr(gate, 1u);
+  // (raised by whoever still sees it down: thousands of atomics on one word would queue up)
+  if (__any(open) && (threadIdx.x & 63) == 0 &&
+      __hip_atomic_load(gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0)
+    atomicOr(gate, 1u);
 }
 
 __global__ void k_write_roots(uint32_t *parent, uint32_t n, int64_t *__restrict__ cluster_id) {
@@ -451,7 +466,7 @@ static int run_cluster(const uint64_t *keys, uint64_t n_docs, uint32_t b, int64_
                        SortBufs &sb, bool timed, hipStream_t st) {
   const int bits = grouping_bits(n_docs, 1);
   const uint32_t n = (uint32_t)n_docs;
-  const dim3 link_grid((n + 255) / 256, b);
+  const dim3 link_grid((n + 256 * LINK_ITEMS - 1) / (256 * LINK_ITEMS), b);
   g_last_gate = sb.gate;
   int rc;
   {
