@@ -39,33 +39,43 @@ k_v_mark(const uint64_t *__restrict__ bk, uint32_t n, uint64_t mask,
   const uint64_t *src = bk + (uint64_t)band * n;
   uint32_t flags = 0, heads = 0;  // bit it: item it goes to list1 / is the head of a large group
   uint32_t mixed = 0;  // records that see another key BIG_GROUP records on inside their own group
+  constexpr int BATCH = 4;  // records whose three loads are issued together
+  static_assert(SORT_ITEMS % BATCH == 0, "whole batches");
 #pragma unroll
-  for (int it = 0; it < SORT_ITEMS; it++) {
-    const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
-    if (e >= n) continue;
-    const uint64_t key = src[e], low = key & mask;
-    const bool follower = e > 0 && (src[e - 1] & mask) == low;
-    bool far_after = false;
-    if (e + BIG_GROUP < n) {
-      const uint64_t other = src[e + BIG_GROUP];
-      far_after = (other & mask) == low;
-      mixed += far_after && other != key;
+  for (int it0 = 0; it0 < SORT_ITEMS; it0 += BATCH) {
+    uint64_t key[BATCH], before[BATCH], after[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; j++) {
+      const uint32_t e = blk * SORT_TILE + (it0 + j) * SORT_THREADS + threadIdx.x;
+      key[j] = e < n ? src[e] : 0;
+      before[j] = e < n && e > 0 ? src[e - 1] : 0;
+      after[j] = e + BIG_GROUP < n ? src[e + BIG_GROUP] : 0;
     }
-    if (follower) {
-      const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
-      if (!far_before && !far_after) {
-        // small group: listed only if an earlier record of the group has this very key (the
-        // group starts fewer than BIG_GROUP records back, and is nearly always one bucket)
-        bool real = false;
-        for (uint32_t q = e; q > 0 && !real;) {
-          const uint64_t other = src[--q];
-          if ((other & mask) != low) break;
-          real = other == key;
+#pragma unroll
+    for (int j = 0; j < BATCH; j++) {
+      const int it = it0 + j;
+      const uint32_t e = blk * SORT_TILE + it * SORT_THREADS + threadIdx.x;
+      if (e >= n) continue;
+      const uint64_t low = key[j] & mask;
+      const bool follower = e > 0 && (before[j] & mask) == low;
+      const bool far_after = e + BIG_GROUP < n && (after[j] & mask) == low;
+      mixed += far_after && after[j] != key[j];
+      if (follower) {
+        const bool far_before = e >= BIG_GROUP && (src[e - BIG_GROUP] & mask) == low;
+        if (!far_before && !far_after) {
+          // small group: listed only if an earlier record of the group has this very key (the
+          // group starts fewer than BIG_GROUP records back, and is nearly always one bucket)
+          bool real = before[j] == key[j];
+          for (uint32_t q = e - 1; q > 0 && !real;) {
+            const uint64_t other = src[--q];
+            if ((other & mask) != low) break;
+            real = other == key[j];
+          }
+          if (real) flags |= 1u << it;
         }
-        if (real) flags |= 1u << it;
+      } else if (far_after) {
+        heads |= 1u << it;
       }
-    } else if (far_after) {
-      heads |= 1u << it;
     }
   }
   // A large group with a stranger or two costs a few comparisons more (every pair test compares
@@ -307,25 +317,47 @@ __host__ __device__ static inline uint32_t group_capacity(uint32_t sketch_words_
   return (lds_words / (sketch_words_in_lds + 4)) & ~uint32_t(VT - 1);
 }
 
-// bits[d * KW + w]: bit i = lowest bit of sig[d * K + 32 w + i] (0 past K).  A wavefront takes 64
-// consecutive entries of one document at a time (one coalesced load, one ballot, two words).
+// bits[d * KW + w]: bit i = lowest bit of sig[d * K + 32 w + i] (0 past K).  A piece is 64
+// consecutive entries of one document: one coalesced load, one ballot, two words.  A wavefront
+// takes SKETCH_BATCH consecutive pieces at a time, all loads first.
 // Does nothing when the call has no large group (counts[2] == 0).
+constexpr int SKETCH_BATCH = 8;
 __global__ void __launch_bounds__(256)
 k_sig_sketch(const uint32_t *__restrict__ sig, uint32_t n, int K, uint32_t KW,
              const uint32_t *__restrict__ counts, uint32_t *__restrict__ bits) {
   if (counts[2] == 0) return;
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t per_doc = (uint32_t)((K + 63) / 64);  // 64-entry pieces per document
+  const uint32_t per_doc = (uint32_t)((K + 63) / 64);  // pieces per document
   const uint64_t pieces = (uint64_t)n * per_doc;
   const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const uint64_t n_waves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
-  for (uint64_t pc = wave; pc < pieces; pc += n_waves) {
-    const uint32_t d = (uint32_t)(pc / per_doc), part = (uint32_t)(pc % per_doc);
-    const uint32_t k = 64 * part + lane;
-    const uint32_t v = k < (uint32_t)K ? sig[(uint64_t)d * K + k] : 0u;
-    const uint64_t m = __ballot(v & 1u);
-    if (lane < 2 && 2 * part + lane < KW)
-      bits[(uint64_t)d * KW + 2 * part + lane] = (uint32_t)(m >> (32 * lane));
+  for (uint64_t pc0 = wave * SKETCH_BATCH; pc0 < pieces; pc0 += n_waves * SKETCH_BATCH) {
+    const uint64_t d0 = pc0 / per_doc;
+    const uint32_t part0 = (uint32_t)(pc0 - d0 * per_doc);
+    uint32_t v[SKETCH_BATCH];
+    uint64_t d = d0;
+    uint32_t part = part0;
+#pragma unroll
+    for (int j = 0; j < SKETCH_BATCH; j++) {
+      const uint32_t k = 64 * part + lane;
+      v[j] = pc0 + j < pieces && k < (uint32_t)K ? sig[d * K + k] : 0u;
+      if (++part == per_doc) {
+        part = 0;
+        d++;
+      }
+    }
+    d = d0;
+    part = part0;
+#pragma unroll
+    for (int j = 0; j < SKETCH_BATCH; j++) {
+      const uint64_t m = __ballot(v[j] & 1u);
+      if (pc0 + j < pieces && lane < 2 && 2 * part + lane < KW)
+        bits[d * KW + 2 * part + lane] = (uint32_t)(m >> (32 * lane));
+      if (++part == per_doc) {
+        part = 0;
+        d++;
+      }
+    }
   }
 }
 
