@@ -213,9 +213,11 @@ int sedd_cluster_static(const uint64_t *keys, uint64_t n_docs, int32_t b, int64_
  * whose lowest bits differ are unequal) and the signatures are compared entry by entry only if
  * the bound reaches min_match.  All of this yields the components of the exhaustive comparison.
  * Scratch: beside the sort buffers, n_docs * ceil(K / 32) * 4 bytes for the sketches.
- * The records are first sorted by the low key bits only (2^bits >= 4096 n_docs); a group of more
- * than 64 records that holds two different keys makes the call sort by the whole key before it
- * compares anything, so buckets are never merged into larger all-pairs blocks than they are.
+ * The records are first sorted by the low key bits only (2^bits >= 256 n_docs); every comparison
+ * also compares the whole keys, so a group that holds a few records of another bucket costs a few
+ * comparisons more.  When more than n_docs * b / 1024 records sit in groups of more than 64 that
+ * hold different keys, the call sorts by the whole key before it compares anything: keys that
+ * agree in their low bits never merge buckets into all-pairs blocks of unbounded size.
  */
 int sedd_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint64_t n_docs, int32_t K,
                           int32_t b, int32_t min_match, int64_t *cluster_id, void *stream);

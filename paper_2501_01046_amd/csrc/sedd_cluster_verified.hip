@@ -820,7 +820,7 @@ static int run_cluster_verified(const uint64_t *keys, const uint32_t *sig, uint6
     SEDD_LAUNCH_CHECK();
   }
   {
-    // only if a large group held more than one key (the sorted bits were too few to separate
+    // only if too many records sat in large groups of mixed keys (the sorted bits were too few to separate
     // the buckets): sort by the rest of the key and mark again, now on whole keys
     ProfScope prof(SEDD_PROF_SORT, st);
     rc = sort_rest_if_gated(n_docs, b, bits, &sb, st);
