@@ -632,17 +632,20 @@ __device__ __forceinline__ void group_tile(const uint32_t *__restrict__ sk, uint
   for (int w = 1; w < lds_words; w++) accumulate(w, false);
   // the smallest count among the pairs that matter: where the rows reach into the columns' range,
   // those with the row record before the column record
-  const bool diagonal = row0 + 32 > col0;
-  uint32_t least = 0xFFFFFFFFu;
+  const bool diagonal = row0 + 32 > col0;  // uniform: one tile in each row of tiles
+  uint32_t least = diff[0];
+#pragma unroll
+  for (int i = 1; i < 32; i++) least = min(least, diff[i]);  // three-way minima: 16 instructions
   if (diagonal) {
+    // (the empty statement keeps this a branch of its own: turned into selects inside the minima
+    // above, it would cost every tile three instructions per pair)
+    asm volatile("");
+    least = 0xFFFFFFFFu;
 #pragma unroll
     for (int i = 0; i < 4; i++)
 #pragma unroll
       for (int j = 0; j < 8; j++)
         if (row0 + ty * 4 + i < col0 + tx * 8 + j) least = min(least, diff[8 * i + j]);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 32; i++) least = min(least, diff[i]);
   }
   if (__all((int)least > max_diff)) return;  // no pair of the tile can reach min_match any more
   if ((int)least > max_diff) return;         // none of this lane's
@@ -683,7 +686,8 @@ k_v_groups(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
   uint64_t *s_key = reinterpret_cast<uint64_t *>(lds);
   uint32_t *s_doc = lds + 2 * cap, *s_joined = lds + 3 * cap, *sk = lds + 4 * cap;
   const uint32_t nb = min((uint64_t)counts[2], big_cap);
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to be
   const bool vec_ok = (K & 3) == 0 && ((uintptr_t)sig & 15) == 0;
   const int max_diff = K - min_match;  // a pair whose sketches differ in more bits cannot reach min_match
   for (uint32_t gi = blockIdx.x; gi < nb; gi += gridDim.x) {
