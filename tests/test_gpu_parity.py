@@ -694,11 +694,13 @@ def test_fuzz_cluster_verified(sedd, seed):
             assert np.array_equal(got, want), (case, K, b, sizes.tolist(), mm)
 
 
-def test_cluster_verified_large_buckets_with_a_few_strangers_in_their_group(sedd):
-    """Large buckets whose sorted group also holds a few records of another key (equal below the
-    sorted bits): too few to make the call sort by the whole key, so the large-group kernels meet
-    pairs with different keys and must leave them alone."""
-    say("verified strangers in large groups")
+@pytest.mark.parametrize("strangers,whole_key_sort", [(4, 0), (60, 1)])
+def test_cluster_verified_large_buckets_with_strangers_in_their_group(sedd, strangers, whole_key_sort):
+    """Large buckets whose sorted group also holds records of another key (equal below the sorted
+    bits).  A few: too few to make the call sort by the whole key, so the large-group kernels
+    meet pairs with different keys and must leave them alone.  Many: the call sorts by the whole
+    key first.  The clusters are the oracle's either way."""
+    say("verified strangers in large groups", strangers)
     rng = np.random.default_rng(41)
     n, K, b = 120_000, 64, 4
     sizes = (70, 200, 600, 3000)                       # one-wavefront, four-wavefront and tiled groups
@@ -715,7 +717,7 @@ def test_cluster_verified_large_buckets_with_a_few_strangers_in_their_group(sedd
             sig[fam] = sig[fam[0]]
             sig[fam[::3], :6] = rng.integers(0, 1 << 32, size=(fam[::3].size, 6), dtype=np.uint64).astype(np.uint32)
             # strangers: same low bits, another key; two of them copies of the family's document
-            odd = idx[rng.choice(s, size=4, replace=False)]
+            odd = idx[rng.choice(s, size=min(strangers, s // 3), replace=False)]
             lo[odd, band] = key | np.uint64(1 << 50)
             sig[odd[:2]] = sig[fam[0]]
     perm = rng.permutation(n)
@@ -723,7 +725,7 @@ def test_cluster_verified_large_buckets_with_a_few_strangers_in_their_group(sedd
     d_keys, d_sig = dev(keys), dev(sig)
     for mm in (oracle.min_match_for(0.8, K), K, 0):
         got = host(sedd.sedd_cluster_verified(d_keys, d_sig, mm))
-        assert sedd.debug_last_regroup() == 0          # the strangers stayed in their groups
+        assert sedd.debug_last_regroup() == whole_key_sort   # 0: the strangers stayed in their groups
         assert np.array_equal(got, oracle.cluster_verified(keys, sig, mm)), mm
 
 
