@@ -47,7 +47,7 @@ extern "C" {
 
 #define SEDD_OK 0
 #define SEDD_EINVAL (-1)  /* bad argument (null pointer, K<1, b*r>K, offsets decreasing, ...) */
-#define SEDD_ENOMEM (-2)  /* device or pinned-host scratch allocation failed */
+#define SEDD_ENOMEM (-2)  /* device or pinned-host allocation failed; sedd_last_device_error() names it */
 #define SEDD_EDEVICE (-3) /* a HIP call failed; sedd_last_device_error() names it */
 #define SEDD_ELIMIT (-4)  /* the input exceeds a fixed limit of the entry point (sedd_cluster_static) */
 
@@ -256,7 +256,7 @@ int sedd_cluster_verified_ws(const uint64_t *keys, const uint32_t *sig, uint64_t
 
 /* Text for an error code (static storage). */
 const char *sedd_strerror(int code);
-/* Text of the HIP error behind the last SEDD_EDEVICE of this thread (static storage). */
+/* Text of the HIP error behind the last SEDD_EDEVICE or SEDD_ENOMEM of this thread (static storage). */
 const char *sedd_last_device_error(void);
 /* Library version, major*10000 + minor*100 + patch. */
 int sedd_version(void);

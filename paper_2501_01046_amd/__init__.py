@@ -55,6 +55,10 @@ def lib():
             raise RuntimeError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2501_01046_amd.build` "
                 "(there is no fallback path)")
+        # torch first: it brings its own HIP runtime, and the library must bind to that one.  Loaded
+        # before torch, the library pulls in the system's runtime instead, torch then finds a runtime
+        # that is not the one it was built with, and allocations fail.
+        import torch  # noqa: F401
         L = C.CDLL(_LIB_PATH)
         u64, i32, u32, vp = C.c_uint64, C.c_int32, C.c_uint32, C.c_void_p
         L.sedd_minhash.restype = C.c_int
@@ -129,8 +133,10 @@ def _check(rc: int, where: str):
     if rc != 0:
         L = lib()
         detail = L.sedd_strerror(rc).decode()
-        if rc == -3:
-            detail += " / " + L.sedd_last_device_error().decode()
+        if rc in (-2, -3):
+            last = L.sedd_last_device_error().decode()
+            if last:
+                detail += " / " + last
         raise SeddError(rc, where, detail)
 
 

@@ -1085,8 +1085,12 @@ static int feed_ensure(uint64_t text_bytes, uint64_t offs_count) {
     const uint64_t tb = std::max(text_bytes, f.text_bytes) + 64, oc = std::max(offs_count, f.offs_count);
     for (int i = 0; i < 2; i++) {
       void *p = nullptr, *q = nullptr;
-      if (hipMalloc(&p, tb) != hipSuccess || hipMalloc(&q, oc * sizeof(uint64_t)) != hipSuccess) {
+      hipError_t e = hipMalloc(&p, tb);
+      if (e == hipSuccess) e = hipMalloc(&q, oc * sizeof(uint64_t));
+      if (e != hipSuccess) {
         (void)hipGetLastError();
+        if (p) (void)hipFree(p);
+        set_device_error(e, "hipMalloc(upload buffers)");
         return SEDD_ENOMEM;
       }
       f.text[i] = (uint8_t *)p;

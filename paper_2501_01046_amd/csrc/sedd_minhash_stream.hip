@@ -856,8 +856,10 @@ static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, Stre
   t.settled = false;
   t.users = 1;
   void *p = nullptr;
-  if (hipMalloc(&p, cv.off) != hipSuccess) {
+  const hipError_t e = hipMalloc(&p, cv.off);
+  if (e != hipSuccess) {
     (void)hipGetLastError();
+    set_device_error(e, "hipMalloc(coefficient tables)");
     return SEDD_ENOMEM;
   }
   t.dev = (uint8_t *)p;
@@ -890,8 +892,10 @@ static int probe_slot_acquire(ProbeSlot **slot) {
     std::lock_guard<std::mutex> lock(g_stream_mutex);
     if (!g_probe_ring) {
       void *p = nullptr;
-      if (hipHostMalloc(&p, PROBE_SLOTS * sizeof(ProbeSlot), hipHostMallocDefault) != hipSuccess) {
+      const hipError_t e = hipHostMalloc(&p, PROBE_SLOTS * sizeof(ProbeSlot), hipHostMallocDefault);
+      if (e != hipSuccess) {
         (void)hipGetLastError();
+        set_device_error(e, "hipHostMalloc(offset probe records)");
         return SEDD_ENOMEM;
       }
       g_probe_ring = (ProbeSlot *)p;

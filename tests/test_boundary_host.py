@@ -198,3 +198,26 @@ def test_workspace_size_and_argument_checks():
     assert L.sedd_cluster_ws(None, u64(0), 16, None, None, u64(0), None) == 0
     assert L.sedd_cluster_verified_ws(FAKE, FAKE, u64(4), 128, 16, 103, FAKE, FAKE, u64(100), None) == -4
     assert L.sedd_cluster_verified_ws(FAKE, None, u64(4), 128, 16, 103, FAKE, FAKE, u64(1 << 20), None) == -1
+
+
+def test_loading_the_library_first_still_leaves_one_hip_runtime_in_the_process():
+    """torch ships a HIP runtime of its own.  A process that loaded libsedd.so before torch held two
+    runtimes (the system's for the library, torch's for the tensors) and the library's first
+    allocation failed on the GPU.  The binding therefore imports torch before it loads the library:
+    in a fresh interpreter that only asks for the library, every libamdhip64 mapped afterwards is
+    one and the same file."""
+    import subprocess
+    import sys
+    code = (
+        "import paper_2501_01046_amd as s\n"
+        "s.lib()\n"
+        "import sys, os\n"
+        "assert 'torch' in sys.modules\n"
+        "paths = {os.path.realpath(l.split()[-1]) for l in open('/proc/self/maps')\n"
+        "         if 'libamdhip64' in l}\n"
+        "print(sorted(paths))\n"
+        "assert len(paths) == 1, paths\n"
+    )
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True,
+                       timeout=600)
+    assert r.returncode == 0, r.stdout + r.stderr
