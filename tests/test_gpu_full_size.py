@@ -416,6 +416,76 @@ def test_one_document_above_one_gigabyte(sedd):
     assert np.array_equal(got_b, want_b)
 
 
+def test_more_than_two_to_the_32_signature_entries(sedd):
+    """9M short documents at K = 512: the signature matrix has 4.6e9 entries (18.4 GB), so every
+    index d * K beyond document 8,388,608 needs more than 32 bits.  Signatures, band keys and
+    dense keys of sampled documents (many of them beyond that point) against the oracle; the
+    verified clusters, which compare whole signature rows, against the planted exact copies."""
+    say("more than 2^32 signature entries")
+    rng = np.random.default_rng(23)
+    n_docs, K, n, L = 9_000_000, 512, 2, 14
+    rows = rng.integers(97, 123, size=(n_docs, L), dtype=np.uint8)
+    rows[:, 3] = 0x20
+    rows[:, 7] = 0x20
+    ids = np.arange(n_docs)
+    for j in range(5):                                  # the document's index, so that no two are alike
+        rows[:, 8 + j] = 97 + (ids // 26 ** j) % 26
+    rows[::7, 3] = 0x61                                 # some documents of two tokens
+    rows[::11, 3] = 0x61
+    rows[::11, 7] = 0x61                                # and of one (fewer tokens than n)
+    # exact copies: document dst repeats src < dst; most of them in the upper range of indices
+    edge = (1 << 32) // K
+    src = np.concatenate([rng.integers(0, n_docs // 2, size=300), rng.integers(edge, n_docs - 10, size=300)])
+    dst = np.concatenate([rng.integers(edge, n_docs, size=300), np.zeros(300, dtype=np.int64)])
+    dst[300:] = src[300:] + rng.integers(1, 10, size=300)
+    keep = np.unique(dst, return_index=True)[1]
+    src, dst = src[keep], dst[keep]
+    ok = ~np.isin(src, dst)                             # no chains: a source is never a copy itself
+    src, dst = src[ok], dst[ok]
+    rows[dst] = rows[src]
+    lens = np.full(n_docs, L, dtype=np.uint64)
+    empty = np.setdiff1d(np.arange(5, n_docs, 999_983), np.concatenate([src, dst]))
+    lens[empty] = 0
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint64)
+    data = np.ascontiguousarray(rows[lens > 0]).reshape(-1)
+    d_data, d_off = torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda()
+    sig = sedd.sedd_minhash(d_data, d_off, n, K)
+    torch.cuda.synchronize()
+    assert sig.numel() > (1 << 32)
+    sample = np.unique(np.concatenate([
+        np.arange(0, 100), np.arange(n_docs - 100, n_docs), np.arange(edge - 100, edge + 100),
+        rng.integers(0, n_docs, size=1500), rng.integers(edge, n_docs, size=1500), src, dst, empty]))
+    s_lens = lens[sample]
+    s_off = np.concatenate([[0], np.cumsum(s_lens)]).astype(np.uint64)
+    s_data = np.ascontiguousarray(rows[sample][s_lens > 0]).reshape(-1)
+    want_sig = oracle.minhash(s_data, s_off, n, K)
+    idx = torch.from_numpy(sample).cuda()
+    got_sig = sig.view(torch.int32)[idx].cpu().numpy().view(np.uint32)   # (no uint32 gather in torch)
+    bad = np.nonzero((got_sig != want_sig).any(axis=1))[0]
+    assert bad.size == 0, f"signatures of documents {sample[bad][:5]} differ"
+    say(f"  signatures of {sample.size} sampled documents ok ({int((sample >= edge).sum())} beyond 2^32 / K)")
+    for b, r in ((64, 8), (4, 8)):
+        keys = sedd.sedd_lsh_keys(sig, b, r)
+        got_keys = keys.view(torch.int64)[idx].cpu().numpy().view(np.uint64)
+        assert np.array_equal(got_keys, oracle.lsh_keys(want_sig, b, r)), (b, r)
+        del keys
+    nb = sedd.dense_bucket_count(n_docs)
+    dkeys = sedd.sedd_lsh_dense_keys(sig, 16, 8, nb)
+    got_dkeys = dkeys.view(torch.int64)[idx].cpu().numpy().view(np.uint64)
+    assert np.array_equal(got_dkeys, oracle.lsh_dense_keys(want_sig, 16, 8, nb))
+    del dkeys
+    # verified clusters at min_match = K: exactly the planted copies (and the empty documents,
+    # whose signatures are all 0xFFFFFFFF, with the first of them)
+    keys = sedd.sedd_lsh_keys(sig, 4, 8)
+    cid = sedd.sedd_cluster_verified(keys, sig, K).cpu().numpy()
+    want = np.arange(n_docs, dtype=np.int64)
+    want[dst] = src
+    want[empty] = empty[0]
+    diff = np.nonzero(cid != want)[0]
+    assert diff.size == 0, f"verified cluster ids differ at {diff[:5]}: {cid[diff[:5]]} vs {want[diff[:5]]}"
+    say(f"  verified clusters: {dst.size} planted copies and {empty.size} empty documents found, nothing else")
+
+
 def test_config2_full_size_paper_prime(sedd):
     """The medium workload with the paper's own modulus (SEDD_FLAG_PAPER_PRIME)."""
     r = corpus.config(2)
