@@ -486,6 +486,56 @@ def test_more_than_two_to_the_32_signature_entries(sedd):
     say(f"  verified clusters: {dst.size} planted copies and {empty.size} empty documents found, nothing else")
 
 
+def test_cluster_close_to_two_to_the_32_records(sedd):
+    """67M documents in 64 bands: 4.288e9 (key, document) records, just below the 2^32 the calls
+    accept, so record indices in the upper bands pass 2^31.  Every key holds its document's index
+    in its high bits (no two documents agree by accident) over 34 random low bits (the sorted
+    bits stay random); copies are planted band by band, most of them in the last bands and the
+    last documents.  sedd_cluster and sedd_cluster_verified must find exactly the planted pairs."""
+    say("cluster close to 2^32 records")
+    n, b, K = 67_000_000, 64, 8
+    assert n * b < (1 << 32) and n * b > (1 << 32) - (1 << 24)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    keys = torch.empty((n, b), dtype=torch.int64, device="cuda")
+    step = 1 << 22
+    for i in range(0, n, step):
+        part = keys[i:i + step]
+        part.random_(0, 1 << 34, generator=gen)
+        part += (torch.arange(i, min(n, i + step), device="cuda", dtype=torch.int64) << 34)[:, None]
+    sig = torch.empty((n, K), dtype=torch.int32, device="cuda")
+    sig.random_(0, (1 << 31) - 1, generator=gen)
+    rng = np.random.default_rng(6)
+    m = 4000
+    src = np.concatenate([rng.integers(0, n - 2000, size=m // 2), rng.integers(n - 200_000, n - 2000, size=m // 2)])
+    dst = src + rng.integers(1, 1000, size=m)
+    keep = np.unique(dst, return_index=True)[1]
+    src, dst = src[keep], dst[keep]
+    ok = ~np.isin(src, dst)
+    src, dst = src[ok], dst[ok]
+    band = np.where(rng.random(src.size) < 0.5, rng.integers(b - 3, b, size=src.size), rng.integers(0, b, size=src.size))
+    t_src, t_dst, t_band = (torch.from_numpy(a).cuda() for a in (src, dst, band))
+    keys[t_dst, t_band] = keys[t_src, t_band]
+    half = src.size // 2                                 # half of the copies also repeat the signature
+    sig[t_dst[:half]] = sig[t_src[:half]]
+    torch.cuda.synchronize()
+    want = torch.arange(n, dtype=torch.int64, device="cuda")
+    want[t_dst] = t_src
+    cid = sedd.sedd_cluster(keys.view(torch.uint64))
+    diff = torch.nonzero(cid != want).flatten()
+    assert diff.numel() == 0, f"cluster ids differ at {diff[:5].tolist()}"
+    say(f"  sedd_cluster: {src.size} planted pairs found, nothing else")
+    del cid
+    want_v = torch.arange(n, dtype=torch.int64, device="cuda")
+    want_v[t_dst[:half]] = t_src[:half]
+    vcid = sedd.sedd_cluster_verified(keys.view(torch.uint64), sig.view(torch.uint32), K)
+    diff = torch.nonzero(vcid != want_v).flatten()
+    assert diff.numel() == 0, f"verified cluster ids differ at {diff[:5].tolist()}"
+    say(f"  sedd_cluster_verified: the {half} pairs with equal signatures found, nothing else")
+    del keys, sig, vcid
+    sedd.sedd_release_scratch()
+
+
 def test_config2_full_size_paper_prime(sedd):
     """The medium workload with the paper's own modulus (SEDD_FLAG_PAPER_PRIME)."""
     r = corpus.config(2)
