@@ -536,6 +536,29 @@ def test_cluster_close_to_two_to_the_32_records(sedd):
     sedd.sedd_release_scratch()
 
 
+def test_one_call_on_more_than_four_gigabytes_of_words(sedd):
+    """850k documents of the 10M-document recipe, 5 GB of text, handed to sedd_minhash in ONE call
+    (the workload itself uses 2 GB pieces): byte positions inside the call pass 2^32.  Sampled
+    documents, and every document within 50 of the 2^32 position, against the oracle."""
+    r = corpus.config(3).scaled(850_000)
+    gen = corpus.Corpus(r)
+    K = 64
+    say("one call on 5 GB of words:", r.n_docs, "documents")
+    smp = Sampler(r.n_docs, seed=8, n_runs=8, run_len=250, prefix=0, n_single=1500,
+                  n_longest_per_piece=2, byte_mode=False)
+    sig, bounds, lengths, total = _stream_minhash(sedd, gen, r, r.shingle_n, K, 0, 1 << 62, sampler=smp)
+    assert len(bounds) == 1 and total > (1 << 32) + (1 << 28)
+    at = int(np.searchsorted(np.cumsum(lengths), 1 << 32))
+    for d in range(at - 50, at + 50):
+        smp.add(gen, d)
+    for d in range(r.n_docs - 50, r.n_docs):
+        smp.add(gen, d)
+    ids, want = _oracle_on_collected(smp, r.shingle_n, K, 0)
+    _check_sampled_signatures(sig, ids, want, K, "5 GB call")
+    say(f"  {total / 1e9:.2f} GB in one call; signatures ok on {ids.size} documents "
+        f"({int((ids > at).sum())} of them beyond byte 2^32)")
+
+
 def test_config2_full_size_paper_prime(sedd):
     """The medium workload with the paper's own modulus (SEDD_FLAG_PAPER_PRIME)."""
     r = corpus.config(2)
