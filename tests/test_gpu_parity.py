@@ -983,6 +983,33 @@ def test_stream_kernel_token_length_tiers(sedd, max_len):
     _check_minhash(sedd, data, off, 5, 64, seed=max_len, flags=0, procs=NPROC)
 
 
+@pytest.mark.parametrize("flags", [0, 2, 4])
+def test_words_longer_than_tiles_and_pieces(sedd, flags):
+    """Words (no whitespace inside) of about one 1 KiB tile, one 8 KiB piece of the streaming
+    kernel, 70 KiB and 3 MB, alone in a document, at its start, in its middle and at its end: the
+    wavefront that owns the word's first byte walks it to its end, the wavefronts whose pieces
+    lie inside it own nothing.  Default, paper-prime and rolling-family mode."""
+    say("words longer than tiles and pieces, flags", flags)
+    rng = np.random.default_rng(64 + flags)
+
+    def word(length):
+        return bytes(rng.integers(33, 127, size=int(length), dtype=np.uint8))
+
+    def filler(k):
+        return b" ".join(word(l) for l in rng.integers(1, 12, size=k))
+
+    docs = []
+    for length in (1007, 1008, 1024, 1025, 8191, 8192, 8193, 70_001, 3_000_000):
+        docs.append(word(length))
+        docs.append(word(length) + b" " + filler(9))
+        docs.append(filler(7) + b"\n" + word(length) + b"\t" + filler(300))
+        docs.append(filler(40) + b" " + word(length))
+        docs.append(word(length) + b" " + word(length + 1))
+    data, off = _pack(docs, lead=3)
+    for n, K in ((1, 8), (5, 40)):
+        _check_minhash(sedd, data, off, n, K, seed=7, flags=flags, procs=NPROC)
+
+
 def _token_with_hash(x, rng):
     """A whitespace-free byte string whose Eq. 1 value is x: random high digits, then the base-257
     expansion of what is left, retried until every digit is a usable byte."""
