@@ -212,16 +212,42 @@ k_v_head_pairs(const uint64_t *__restrict__ bk, const uint32_t *__restrict__ bd,
   for (uint32_t it = 0; it < rounds; it++, e += teams) {
     if (e < n1) {
       const uint32_t i = list1[e];
-      const uint64_t key = bk[i];
+      const uint64_t key = bk[i], low = key & mask;
       const uint32_t band0 = (i / n) * n;
-      const uint32_t gs = group_lower_bound(bk, mask, band0, i, key & mask);
-      // a group of more than BIG_GROUP records is compared tile by tile (k_v_groups, k_v_tiles)
-      const bool large = gs + BIG_GROUP < band0 + n && ((bk[gs + BIG_GROUP] ^ key) & mask) == 0;
-      bool joined = large;
-      if (!large) {
-        uint32_t h = gs;  // the bucket's first record: k_v_mark saw one before i
-        while (bk[h] != key) h++;
-        joined = team_verify_pair(sig, K, min_match, parent, bd[h], bd[i], tl);
+      const uint64_t band_end = (uint64_t)band0 + n;
+      // One round of loads settles nearly every follower: lane t of the team takes the record
+      // t + 1 places before i (key and document), and the record BIG_GROUP places after that one.
+      const bool in_band = i >= band0 + 1u + (uint32_t)tl;
+      const uint32_t back = i - 1u - (uint32_t)tl;
+      const uint64_t far = (uint64_t)back + BIG_GROUP;
+      const uint64_t k_back = in_band ? bk[back] : ~key;  // ~key: another group, another key
+      const uint64_t k_far = in_band && far < band_end ? bk[far] : ~key;
+      const uint32_t d_back = in_band ? bd[back] : 0u;
+      const uint32_t d_i = bd[i];
+      const uint32_t team_shift = threadIdx.x & 48u;  // the team's lanes inside the wavefront's ballot
+      const uint32_t same = (uint32_t)(__ballot((k_back & mask) == low) >> team_shift) & 0xFFFFu;
+      const uint32_t equal = (uint32_t)(__ballot(k_back == key) >> team_shift) & 0xFFFFu;
+      const uint32_t c = (uint32_t)__ffs((int)~same) - 1u;  // records of the group right before i (16: or more)
+      bool joined;
+      if (c < (uint32_t)TEAM) {  // (c >= 1: k_v_mark lists records that follow one of their group)
+        // the group starts at i - c; more than BIG_GROUP records: compared by k_v_groups / k_v_tiles
+        const uint64_t k_over = __shfl(k_far, (int)c - 1, TEAM);  // the record at group start + BIG_GROUP
+        joined = (k_over & mask) == low;
+        if (!joined) {
+          const uint32_t eq = equal & ((1u << c) - 1u);  // the bucket's records before i
+          if (eq) {
+            const int first = 31 - __clz((int)eq);  // the bucket's first record is the farthest back
+            joined = team_verify_pair(sig, K, min_match, parent, __shfl(d_back, first, TEAM), d_i, tl);
+          }
+        }
+      } else {
+        const uint32_t gs = group_lower_bound(bk, mask, band0, i, low);
+        joined = gs + BIG_GROUP < band_end && ((bk[gs + BIG_GROUP] ^ key) & mask) == 0;
+        if (!joined) {
+          uint32_t h = gs;  // the bucket's first record: k_v_mark saw one before i
+          while (bk[h] != key) h++;
+          joined = team_verify_pair(sig, K, min_match, parent, bd[h], d_i, tl);
+        }
       }
       if (!joined && tl == 0) s_out[atomicAdd(&s_n, 1u)] = i;
     }

@@ -856,7 +856,7 @@ static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, Stre
   t.settled = false;
   t.users = 1;
   void *p = nullptr;
-  const hipError_t e = hipMalloc(&p, cv.off);
+  hipError_t e = hipMalloc(&p, cv.off);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     set_device_error(e, "hipMalloc(coefficient tables)");
@@ -873,7 +873,7 @@ static int tables_acquire(int K, uint64_t seed, bool paper, hipStream_t st, Stre
                        (uint64_t *)(t.dev + o_a), (uint64_t *)(t.dev + o_b),
                        (CoefSplit *)(t.dev + o_cs), (uint64_t *)(t.dev + o_qpow),
                        (PowSplit *)(t.dev + o_ptab));
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e == hipSuccess) e = hipEventCreateWithFlags(&t.ready, hipEventDisableTiming);
   if (e != hipSuccess) {
     // an asynchronous error may stem from the launch above: let it finish before the free
